@@ -1,0 +1,173 @@
+/*
+ * CPU oracle: Philox4x32-R block function and the attention-dropout keep-mask.
+ *
+ * TEST INFRASTRUCTURE ONLY.  Nothing on the product path may call, link or
+ * import this file; it exists so that the HIP kernels can be compared, bit for
+ * bit, with a slow and obviously correct scalar implementation.  It shares no
+ * code, header, table or constant generator with the HIP path.
+ *
+ * What it follows:
+ *  - The paper (Sec. 2.3) names Philox, a counter-based generator built on
+ *    wide multiplies, and cites the Philox publication (Salmon, Moraes, Dror,
+ *    Shaw, "Parallel random numbers: as easy as 1, 2, 3", SC'11) for the round
+ *    function; the constants and the round below are those of that
+ *    publication's Philox-4x32 and are pinned by its known-answer vectors.
+ *  - The paper (Sec. 6.1, Sec. 7.2) says the stand-alone RNG kernel stores one
+ *    bit per element of the B x nH x SQ x SQ score matrix.  The paper does not
+ *    say how (seed, offset, element) map to (counter, key, output word); the
+ *    map used here is a reading, written out in oracle_dropout_mask().
+ *
+ * Parity pins (tests marked "not gpu"): known-answer vectors for R = 10 and
+ * R = 7, the C++26 engine's specified 10000th output, threshold closed forms,
+ * kept-fraction within 4 sigma, offset splitting, monotonicity in p, and an
+ * independent big-integer Python evaluation of the same definitions.
+ * Statistical quality of Philox itself: parity unpinned (taken from the cited
+ * publication).
+ */
+#include <stdint.h>
+#include <stddef.h>
+#include <string.h>
+
+/* Multipliers and Weyl key increments of Philox-4x32 (Philox publication). */
+#define PHILOX_M0 0xD2511F53u
+#define PHILOX_M1 0xCD9E8D57u
+#define PHILOX_W0 0x9E3779B9u
+#define PHILOX_W1 0xBB67AE85u
+
+/* One Philox-4x32 block: `rounds` rounds on counter c[0..3] with key k[0..1].
+ * Round: p0 = M0*c0, p1 = M1*c2 (64-bit products);
+ *        c <- ( hi(p1)^c1^k0, lo(p1), hi(p0)^c3^k1, lo(p0) );
+ * the key is advanced by (W0, W1) between rounds. */
+void oracle_philox4x32(const uint32_t ctr[4], const uint32_t key[2], int rounds,
+                       uint32_t out[4])
+{
+    uint32_t c0 = ctr[0], c1 = ctr[1], c2 = ctr[2], c3 = ctr[3];
+    uint32_t k0 = key[0], k1 = key[1];
+    for (int r = 0; r < rounds; ++r) {
+        uint64_t p0 = (uint64_t)PHILOX_M0 * (uint64_t)c0;
+        uint64_t p1 = (uint64_t)PHILOX_M1 * (uint64_t)c2;
+        uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
+        uint32_t n1 = (uint32_t)p1;
+        uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+        uint32_t n3 = (uint32_t)p0;
+        c0 = n0; c1 = n1; c2 = n2; c3 = n3;
+        k0 += PHILOX_W0;
+        k1 += PHILOX_W1;
+    }
+    out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+/* The (seed, call index) -> (counter, key) map of this build:
+ * key = (lo32(seed), hi32(seed)); counter = (lo32(n), hi32(n), 0, 0) where n is
+ * the 64-bit call index (arithmetic mod 2^64). */
+static void philox_call(uint64_t seed, uint64_t n, int rounds, uint32_t out[4])
+{
+    uint32_t ctr[4] = { (uint32_t)n, (uint32_t)(n >> 32), 0u, 0u };
+    uint32_t key[2] = { (uint32_t)seed, (uint32_t)(seed >> 32) };
+    oracle_philox4x32(ctr, key, rounds, out);
+}
+
+/* Raw stream: out[4*i .. 4*i+3] = Philox(seed, first_counter + i). */
+void oracle_philox_raw(uint64_t seed, uint64_t first_counter, uint64_t ncalls,
+                       int rounds, uint32_t *out)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < (int64_t)ncalls; ++i)
+        philox_call(seed, first_counter + (uint64_t)i, rounds, out + 4 * (size_t)i);
+}
+
+/* Keep threshold: an element is kept iff its 32-bit random word x satisfies
+ * x < T with T = floor((1 - p) * 2^32), evaluated in IEEE double from the
+ * float argument p.  T is returned as a 64-bit value because p = 0 gives
+ * T = 2^32 (every element kept).  Returns 0 on success, -1 if p is outside
+ * [0, 1) or NaN. */
+int oracle_keep_threshold(float p, uint64_t *T)
+{
+    if (!(p >= 0.0f) || !(p < 1.0f)) return -1;
+    double t = (1.0 - (double)p) * 4294967296.0;
+    *T = (uint64_t)t; /* t >= 0: truncation is floor */
+    return 0;
+}
+
+uint64_t oracle_mask_words(int B, int H, int S)
+{
+    uint64_t W = ((uint64_t)S + 63u) / 64u;
+    return (uint64_t)B * (uint64_t)H * (uint64_t)S * W;
+}
+
+/* Number of Philox calls one mask consumes: 64 lanes per group of 4 words. */
+uint64_t oracle_mask_philox_calls(int B, int H, int S)
+{
+    uint64_t words = oracle_mask_words(B, H, S);
+    return 64u * ((words + 3u) / 4u);
+}
+
+/* Keep-mask for a B x H x S x S score matrix (paper Sec. 6.1 / 7.2: one bit
+ * per element, B*nH*SQ^2 bits).
+ *
+ * Layout: each score row (b, h, i) occupies W = ceil(S/64) consecutive 64-bit
+ * words; word index w = ((b*H + h)*S + i)*W + cb; bit l (LSB first) of word w
+ * is column j = 64*cb + l.  Bits with j >= S are 0.  Bit = 1 means keep.
+ *
+ * Random words: words are taken in groups of four, g = w / 4, r = w % 4.
+ * Lane l of group g makes Philox call number n = offset + 64*g + l (mod 2^64)
+ * with `rounds` rounds; output word r of that call decides bit l of mask word
+ * 4*g + r.  `offset` counts Philox calls.
+ *
+ * Returns 0, or -1 for invalid arguments (out untouched). */
+int oracle_dropout_mask_rounds(uint64_t seed, uint64_t offset, int B, int H, int S,
+                               float p, int rounds, uint64_t *out)
+{
+    uint64_t T;
+    if (B <= 0 || H <= 0 || S <= 0 || rounds <= 0 || out == NULL) return -1;
+    if (oracle_keep_threshold(p, &T) != 0) return -1;
+    const uint64_t W = ((uint64_t)S + 63u) / 64u;
+    const uint64_t words = oracle_mask_words(B, H, S);
+    const uint64_t groups = (words + 3u) / 4u;
+
+#pragma omp parallel for schedule(static)
+    for (int64_t gi = 0; gi < (int64_t)groups; ++gi) {
+        const uint64_t g = (uint64_t)gi;
+        uint64_t acc[4] = { 0, 0, 0, 0 };
+        for (unsigned l = 0; l < 64; ++l) {
+            uint32_t x[4];
+            philox_call(seed, offset + 64u * g + l, rounds, x);
+            for (unsigned r = 0; r < 4; ++r) {
+                const uint64_t w = 4u * g + r;
+                if (w >= words) continue;
+                const uint64_t j = 64u * (w % W) + l; /* column of this bit */
+                if (j < (uint64_t)S && (uint64_t)x[r] < T)
+                    acc[r] |= (uint64_t)1 << l;
+            }
+        }
+        for (unsigned r = 0; r < 4; ++r) {
+            const uint64_t w = 4u * g + r;
+            if (w < words) out[w] = acc[r];
+        }
+    }
+    return 0;
+}
+
+int oracle_dropout_mask(uint64_t seed, uint64_t offset, int B, int H, int S,
+                        float p, uint64_t *out)
+{
+    return oracle_dropout_mask_rounds(seed, offset, B, H, S, p, 10, out);
+}
+
+/* Number of set bits in a word array (kept-fraction tests and timing sink). */
+uint64_t oracle_popcount_words(const uint64_t *w, uint64_t n)
+{
+    uint64_t total = 0;
+#pragma omp parallel for reduction(+ : total) schedule(static)
+    for (int64_t i = 0; i < (int64_t)n; ++i)
+        total += (uint64_t)__builtin_popcountll(w[i]);
+    return total;
+}
+
+/* Number of threads the OpenMP loops above use (reported beside timings). */
+#ifdef _OPENMP
+#include <omp.h>
+int oracle_num_threads(void) { return omp_get_max_threads(); }
+#else
+int oracle_num_threads(void) { return 1; }
+#endif

@@ -1,0 +1,244 @@
+"""Pins for the float64 oracle of GEMM, attention with dropout, rounding and the block (CPU only)."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import dense as D
+from oracle import numerics as N
+from oracle import philox as P
+
+
+# ----------------------------------------------------------------------------- rounding
+def test_bf16_round_all_codes_round_trip_and_match_library():
+    codes = np.arange(65536, dtype=np.uint32) << 16
+    vals = codes.view(np.float32)
+    finite = np.isfinite(vals)
+    assert np.array_equal(N.bf16_round(vals[finite]).view(np.uint32), codes[finite])
+    rng = np.random.default_rng(0)
+    x = np.concatenate([rng.standard_normal(200000).astype(np.float32) * 3.0,
+                        rng.integers(0, 2**32, 200000, dtype=np.uint32).view(np.float32)])
+    x = x[np.isfinite(x)]
+    lib = torch.from_numpy(x).to(torch.bfloat16).to(torch.float32).numpy()   # library second opinion
+    got = N.bf16_round(x)
+    both_finite = np.isfinite(lib)
+    assert np.array_equal(got[both_finite], lib[both_finite])
+
+
+def test_bf16_round_ties_to_even():
+    one = np.float32(1.0)
+    ulp = np.float32(2.0 ** -7)                      # bf16 spacing in [1, 2)
+    assert N.bf16_round(np.float32(1.0 + 0.5 * ulp))[()] == one                # tie -> even (1.0)
+    assert N.bf16_round(np.float32(1.0 + 1.5 * ulp))[()] == np.float32(1.0 + 2 * ulp)   # tie -> even
+    assert N.bf16_round(np.float32(1.0 + 0.5 * ulp + 2.0 ** -20))[()] == np.float32(1.0 + ulp)
+    assert N.bf16_round(np.float32(-(1.0 + 0.5 * ulp)))[()] == -one
+
+
+def test_e4m3_table_against_format_facts_and_library():
+    t = N.e4m3_decode_table()
+    assert t[0x7E] == 448.0 and t[0xFE] == -448.0
+    assert math.isnan(t[0x7F]) and math.isnan(t[0xFF])
+    assert t[0x01] == 2.0 ** -9 and t[0x08] == 2.0 ** -6 and t[0x38] == 1.0 and t[0x00] == 0.0
+    lib = torch.arange(256, dtype=torch.int32).to(torch.uint8).view(torch.float8_e4m3fn).to(torch.float32).numpy()
+    ok = ~np.isnan(t)
+    assert np.array_equal(t[ok], lib[ok].astype(np.float64)) and np.isnan(lib[~ok]).all()
+
+
+def test_e4m3_encode_round_trip_ties_saturation_and_library():
+    t = N.e4m3_decode_table()
+    for code in range(256):
+        if not math.isnan(t[code]) and code != 0x80:
+            assert N.e4m3_encode(np.array([t[code]]))[0] == code
+    # ties: halfway between 1.0 (0x38, even) and 1.125 (0x39) -> 0x38; between 1.125 and 1.25 (0x3A) -> 0x3A
+    assert N.e4m3_encode(np.array([1.0625]))[0] == 0x38
+    assert N.e4m3_encode(np.array([1.1875]))[0] == 0x3A
+    assert N.e4m3_encode(np.array([1e6, -1e6, 460.0]))[:].tolist() == [0x7E, 0xFE, 0x7E]
+    rng = np.random.default_rng(3)
+    x = (rng.standard_normal(100000) * 50).astype(np.float32)
+    x = x[np.abs(x) <= 448]
+    lib = torch.from_numpy(x).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+    got = N.e4m3_encode(x)
+    nz = (got & 0x7F) != 0                        # sign of zero results is not compared
+    assert np.array_equal(got[nz], lib[nz])
+    assert np.all((lib[~nz] & 0x7F) == 0)
+
+
+def test_e4m3_quantise_scale():
+    x = np.array([0.5, -3.0, 1.5])
+    codes, s = N.e4m3_quantise(x)
+    assert abs(s - 3.0 / 448.0) < 1e-9 and codes[1] == 0xFE
+
+
+# ----------------------------------------------------------------------------- GEMM
+def test_gemm_against_loops_library_and_one_hot():
+    rng = np.random.default_rng(5)
+    A = rng.standard_normal((7, 13))
+    Bm = rng.standard_normal((13, 5))
+    C = D.gemm(A, Bm)
+    for m in range(7):
+        for n in range(5):
+            assert abs(C[m, n] - sum(A[m, k] * Bm[k, n] for k in range(13))) < 1e-12
+    assert np.allclose(C, torch.from_numpy(A).matmul(torch.from_numpy(Bm)).numpy(), atol=1e-12)
+    assert np.allclose(D.gemm(A, Bm.T.copy(), transB=True), C, atol=1e-13)
+    # one-hot operands copy rows / columns exactly; a transposed-operand mistake fails here
+    E = np.zeros((3, 7)); E[0, 4] = 1; E[1, 0] = 1; E[2, 6] = 1
+    assert np.array_equal(D.gemm(E, A), A[[4, 0, 6], :])
+    e = D.gemm_entries(A, Bm, [1, 6], [2, 4])
+    assert np.allclose(e, [C[1, 2], C[6, 4]], atol=1e-13)
+
+
+# ----------------------------------------------------------------------------- attention
+def _tiny_inputs(seed=0, B=1, S=12, H=4, Hkv=2, d=8):
+    rng = np.random.default_rng(seed)
+    return (rng.standard_normal((B, S, H, d)), rng.standard_normal((B, S, Hkv, d)),
+            rng.standard_normal((B, S, Hkv, d)))
+
+
+@pytest.mark.parametrize("causal", [False, True])
+def test_attention_vectorised_matches_scalar_loops(causal):
+    Q, K, V = _tiny_inputs()
+    B, S, H, _ = Q.shape
+    keep = P.unpack_keep(P.dropout_mask(9, 0, B, H, S, 0.3), S)
+    a = D.attention_dropout(Q, K, V, keep, 0.3, causal=causal)
+    b = D.attention_dropout_loops(Q, K, V, keep, 0.3, causal=causal)
+    assert np.allclose(a, b, atol=1e-12)
+    rows = [0, 5, 11]
+    assert np.allclose(D.attention_dropout(Q, K, V, keep, 0.3, causal=causal, rows=rows), a[:, rows], atol=1e-13)
+
+
+@pytest.mark.parametrize("causal", [False, True])
+def test_attention_p0_equals_library_sdpa(causal):
+    Q, K, V = _tiny_inputs(1, B=2, S=17, H=4, Hkv=4, d=16)
+    o = D.attention_dropout(Q, K, V, None, 0.0, causal=causal)
+    tq, tk, tv = [torch.from_numpy(x).permute(0, 2, 1, 3) for x in (Q, K, V)]
+    ref = torch.nn.functional.scaled_dot_product_attention(tq, tk, tv, is_causal=causal)
+    assert np.allclose(o, ref.permute(0, 2, 1, 3).numpy(), atol=1e-12)
+    # all-ones keep with p = 0 is the same thing
+    keep = np.ones((2, 4, 17, 17), dtype=bool)
+    assert np.allclose(D.attention_dropout(Q, K, V, keep, 0.0, causal=causal), o, atol=1e-15)
+
+
+def test_attention_gqa_head_mapping():
+    Q, K, V = _tiny_inputs(2, H=4, Hkv=2)
+    o = D.attention_dropout(Q, K, V, None, 0.0)
+    Kf = np.repeat(K, 2, axis=2)     # expand kv heads: query head h uses kv head h // 2
+    Vf = np.repeat(V, 2, axis=2)
+    assert np.allclose(o, D.attention_dropout(Q, Kf, Vf, None, 0.0), atol=1e-15)
+
+
+def test_attention_constant_v_gives_kept_softmax_mass():
+    # V == c  =>  O row = c * (sum of kept softmax probabilities) / (1 - p)
+    Q, K, V = _tiny_inputs(3, S=20, H=2, Hkv=2)
+    V[:] = 2.5
+    B, S, H, d = Q.shape
+    p = 0.4
+    keep = P.unpack_keep(P.dropout_mask(4, 0, B, H, S, p), S)
+    o = D.attention_dropout(Q, K, V, keep, p)
+    for h in range(H):
+        s = Q[0, :, h] @ K[0, :, h].T / math.sqrt(d)
+        Pm = np.exp(s - s.max(1, keepdims=True)); Pm /= Pm.sum(1, keepdims=True)
+        mass = (Pm * keep[0, h]).sum(1)
+        assert np.allclose(o[0, :, h, :], (2.5 * mass / (1 - float(np.float32(p))))[:, None], atol=1e-12)
+
+
+def test_attention_s1_and_fully_dropped_row():
+    Q, K, V = _tiny_inputs(4, S=1, H=2, Hkv=2)
+    keep = np.array([True, False]).reshape(1, 2, 1, 1)
+    o = D.attention_dropout(Q, K, V, keep, 0.5)
+    assert np.allclose(o[0, 0, 0], V[0, 0, 0] * 2.0) and np.all(o[0, 0, 1] == 0.0)
+
+
+def test_attention_dropout_is_unbiased():
+    Q, K, V = _tiny_inputs(5, S=16, H=1, Hkv=1, d=4)
+    p = 0.25
+    base = D.attention_dropout(Q, K, V, None, 0.0)
+    n, acc = 600, np.zeros_like(base)
+    for seed in range(n):
+        keep = P.unpack_keep(P.dropout_mask(seed, 0, 1, 1, 16, p), 16)
+        acc += D.attention_dropout(Q, K, V, keep, p)
+    # per-element std of one draw is below max|V| * sqrt(p/(1-p)); 5 sigma of the mean
+    bound = 5 * np.abs(V).max() * math.sqrt(p / (1 - p)) / math.sqrt(n)
+    assert np.max(np.abs(acc / n - base)) < bound
+
+
+# ----------------------------------------------------------------------------- block pieces
+def test_rmsnorm_closed_form_and_rope_properties():
+    c, eps = 3.0, 1e-5
+    w = np.linspace(0.5, 2.0, 8)
+    y = D.rmsnorm(np.full((2, 8), c), w, eps)
+    assert np.allclose(y, w * c / math.sqrt(c * c + eps), atol=1e-14)
+    rng = np.random.default_rng(6)
+    x = rng.standard_normal((1, 9, 2, 8))
+    r = D.rope(x, 500000.0)
+    assert np.allclose(r[:, 0], x[:, 0], atol=1e-15)                       # position 0 is the identity
+    assert np.allclose(np.linalg.norm(r, axis=-1), np.linalg.norm(x, axis=-1), atol=1e-12)
+    # relative-position property: <rope(q)@s1, rope(k)@s2> depends only on s1 - s2
+    q = np.broadcast_to(rng.standard_normal(8), (1, 9, 1, 8))
+    k = np.broadcast_to(rng.standard_normal(8), (1, 9, 1, 8))
+    rq, rk = D.rope(q, 10000.0), D.rope(k, 10000.0)
+    assert abs(np.dot(rq[0, 5, 0], rk[0, 2, 0]) - np.dot(rq[0, 8, 0], rk[0, 5, 0])) < 1e-12
+    # explicit pair rotation for one element: pair t = 1 of token s = 3, d = 8
+    ang = 3 * 10000.0 ** (-2.0 / 8)
+    xe, xo = q[0, 3, 0, 2], q[0, 3, 0, 3]
+    assert abs(rq[0, 3, 0, 2] - (xe * math.cos(ang) - xo * math.sin(ang))) < 1e-13
+    assert abs(rq[0, 3, 0, 3] - (xe * math.sin(ang) + xo * math.cos(ang))) < 1e-13
+
+
+def _block_setup(seed=7, B=1, S=10, H=4, Hkv=2, d=8, hidden=32, ffn=48):
+    rng = np.random.default_rng(seed)
+    w = dict(norm1=rng.uniform(0.5, 1.5, hidden), norm2=rng.uniform(0.5, 1.5, hidden),
+             wqkv=rng.standard_normal(((H + 2 * Hkv) * d, hidden)) * 0.2,
+             wo=rng.standard_normal((hidden, H * d)) * 0.2,
+             wg=rng.standard_normal((ffn, hidden)) * 0.2, wu=rng.standard_normal((ffn, hidden)) * 0.2,
+             wd=rng.standard_normal((hidden, ffn)) * 0.2)
+    cfg = dict(H=H, Hkv=Hkv, d=d, eps=1e-5, rope_theta=500000.0, p=0.1, causal=False)
+    x = rng.standard_normal((B, S, hidden))
+    return x, w, cfg
+
+
+def test_block_zero_output_projections_give_identity():
+    x, w, cfg = _block_setup()
+    w["wo"][:] = 0; w["wd"][:] = 0
+    keep = P.unpack_keep(P.dropout_mask(1, 0, 1, 4, 10, 0.1), 10)
+    assert np.array_equal(D.block_forward(x, w, cfg, keep), x)
+
+
+def test_block_matches_library_composition_without_dropout():
+    x, w, cfg = _block_setup(8)
+    cfg["p"] = 0.0
+    for causal in (False, True):
+        cfg["causal"] = causal
+        y = D.block_forward(x, w, cfg, None)
+        # independent composition with torch float64 ops
+        tx = torch.from_numpy(x)
+        def rms(t, g): return t * torch.rsqrt((t * t).mean(-1, keepdim=True) + cfg["eps"]) * torch.from_numpy(g)
+        h1 = rms(tx, w["norm1"])
+        qkv = h1 @ torch.from_numpy(w["wqkv"]).T
+        H, Hkv, d = cfg["H"], cfg["Hkv"], cfg["d"]
+        q, k, v = qkv.split([H * d, Hkv * d, Hkv * d], dim=-1)
+        def rope(t, nh):
+            t = t.reshape(1, -1, nh, d // 2, 2)
+            S = t.shape[1]
+            inv = cfg["rope_theta"] ** (-torch.arange(0, d, 2, dtype=torch.float64) / d)
+            ang = torch.arange(S, dtype=torch.float64)[:, None] * inv[None, :]
+            z = torch.view_as_complex(t.contiguous()) * torch.polar(torch.ones_like(ang), ang)[None, :, None, :]
+            return torch.view_as_real(z).reshape(1, S, nh, d)
+        q = rope(q, H).permute(0, 2, 1, 3)
+        k = rope(k, Hkv).permute(0, 2, 1, 3).repeat_interleave(H // Hkv, dim=1)
+        v = v.reshape(1, -1, Hkv, d).permute(0, 2, 1, 3).repeat_interleave(H // Hkv, dim=1)
+        a = torch.nn.functional.scaled_dot_product_attention(q, k, v, is_causal=causal)
+        a = a.permute(0, 2, 1, 3).reshape(1, -1, H * d)
+        x2 = tx + a @ torch.from_numpy(w["wo"]).T
+        h2 = rms(x2, w["norm2"])
+        ref = x2 + (torch.nn.functional.silu(h2 @ torch.from_numpy(w["wg"]).T) * (h2 @ torch.from_numpy(w["wu"]).T)) \
+            @ torch.from_numpy(w["wd"]).T
+        assert np.allclose(y, ref.numpy(), atol=1e-11)
+
+
+def test_block_row_subset_matches_full():
+    x, w, cfg = _block_setup(9)
+    keep = P.unpack_keep(P.dropout_mask(2, 0, 1, 4, 10, 0.1), 10)
+    full = D.block_forward(x, w, cfg, keep)
+    rows = [0, 3, 9]
+    assert np.allclose(D.block_forward(x, w, cfg, keep, rows=rows), full[:, rows], atol=1e-13)

@@ -1,0 +1,216 @@
+/*
+ * rov - RNG/GEMM overlap for attention dropout on MI355X (gfx950).
+ *
+ * C ABI of the hot path of "Reducing the Cost of Dropout in Flash-Attention by
+ * Hiding RNG with GEMM" (arXiv 2410.07531): a stand-alone Philox kernel writes
+ * the dropout keep-mask to HBM on a side stream while dense GEMMs run, and a
+ * flash-attention forward consumes the mask (paper Sec. 1, Sec. 6.1).
+ *
+ * Conventions shared by every entry point
+ *  - Return value: ROV_OK (0) or a negative ROV_ERR_* code.  On error nothing is
+ *    enqueued and outputs are untouched.  After ROV_ERR_HIP, rov_last_hip_error()
+ *    returns the hipError_t value of the failing runtime call.
+ *  - Every data pointer is a DEVICE pointer owned by the caller, valid until
+ *    the work enqueued on `stream` has completed.  The library allocates no
+ *    device memory and never synchronises the device: calls are asynchronous
+ *    on the given stream.  `stream` is a hipStream_t passed as void* (NULL =
+ *    the default stream).  Descriptor structs themselves live in HOST memory
+ *    and are read before the call returns.
+ *  - dtype codes: ROV_F32 = 0, ROV_BF16 = 1, ROV_FP8_E4M3 = 2 (OCP e4m3).
+ */
+#ifndef ROV_H
+#define ROV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define ROV_OK 0
+#define ROV_ERR_INVALID (-1)      /* null pointer, size <= 0, p outside [0,1), bad enum, misalignment */
+#define ROV_ERR_UNSUPPORTED (-2)  /* valid but not implemented shape / dtype combination */
+#define ROV_ERR_HIP (-3)          /* a HIP runtime call failed */
+#define ROV_ERR_WORKSPACE (-4)    /* workspace too small */
+
+#define ROV_F32 0
+#define ROV_BF16 1
+#define ROV_FP8_E4M3 2
+
+#define ROV_SCHED_SEQUENTIAL 0    /* GEMMs, RNG kernel, attention: one stream (paper Sec. 6.1, baseline) */
+#define ROV_SCHED_FUSED 1         /* GEMMs, attention with in-kernel Philox (paper Sec. 6.1, fusion) */
+#define ROV_SCHED_OVERLAP 2       /* RNG on a side stream beside the GEMMs, joined before attention */
+
+/* hipError_t of the last failing HIP call made by this library on the calling thread (0 if none). */
+int rov_last_hip_error(void);
+
+/* Static version string. */
+const char *rov_version(void);
+
+/* ---------------------------------------------------------------- mask geometry
+ * The keep-mask of a B x H x S x S score matrix (paper Sec. 7.2: B*nH*SQ^2 bits)
+ * is an array of 64-bit words, row-major [B][H][S][W] with W = ceil(S/64);
+ * bit l (LSB first) of word (b,h,i,cb) belongs to column j = 64*cb + l; bits
+ * with j >= S are 0; a set bit means "keep".
+ * rov_mask_words         = B*H*S*W (0 if any argument is <= 0).
+ * rov_mask_philox_calls  = 64*ceil(words/4): how far one mask advances the
+ *                          Philox call counter; the next mask (next layer, next
+ *                          step) uses offset + this value. */
+uint64_t rov_mask_words(int B, int H, int S);
+uint64_t rov_mask_philox_calls(int B, int H, int S);
+
+/* ---------------------------------------------------------------- Philox
+ * Philox-4x32 block function (the generator the paper uses, Sec. 2.3; round
+ * function and constants from the publication it cites).  Call number n (64-bit,
+ * wrapping) under a 64-bit seed uses counter (lo32(n), hi32(n), 0, 0) and key
+ * (lo32(seed), hi32(seed)).
+ *
+ * Test hook: out[4*i .. 4*i+3] = Philox(seed, first_counter + i), i < ncalls.
+ * out: device, 16-byte aligned, 4*ncalls uint32.  rounds in [1, 16].
+ * ncalls == 0 is a no-op returning ROV_OK. */
+int rov_philox_raw(uint64_t seed, uint64_t first_counter, uint64_t ncalls, int rounds,
+                   uint32_t *out, void *stream);
+
+/* Stand-alone RNG kernel (paper Sec. 6.1: "stores bits representing random
+ * numbers in HBM for later use by the Attention kernel").
+ * Mask words are taken in groups of four (g = w / 4, r = w % 4).  Lane l of
+ * group g makes Philox-4x32-10 call number offset + 64*g + l; output word r of
+ * that call, x, decides bit l of mask word 4*g + r: keep iff x < T with
+ * T = floor((1 - p) * 2^32) computed in double from the float p.
+ * out: device, 8-byte aligned, rov_mask_words(B,H,S) uint64, fully overwritten.
+ * Requires B,H,S > 0 and 0 <= p < 1 (p == 0 keeps everything). */
+int rov_dropout_mask_generate(uint64_t seed, uint64_t offset, int B, int H, int S, float p,
+                              uint64_t *out, void *stream);
+
+/* Same with a selectable round count (paper Sec. 5.2 studies 3, 5 and 7 rounds).
+ * rounds in {3, 5, 7, 10}. */
+int rov_dropout_mask_generate_rounds(uint64_t seed, uint64_t offset, int B, int H, int S, float p,
+                                     int rounds, uint64_t *out, void *stream);
+
+/* Launch-shape control for the RNG kernel, used by the overlap experiments
+ * (paper Sec. 6.2: the RNG kernel must fit beside a GEMM that owns most of each
+ * compute unit).  max_workgroups <= 0 restores the default (enough workgroups
+ * to fill the device).  Process-wide; returns the previous value. */
+int rov_set_rng_max_workgroups(int max_workgroups);
+
+/* Diagnostic: VALU issue cost of the instruction kinds the RNG kernel is made of
+ * (paper Table 1 bounds the RNG kernel by "Issue stage" and "ALU pipe"; the
+ * ceiling this build prices the kernel against is derived from these measured
+ * costs).  Launches `workgroups` x 256 threads; each lane runs 8 independent
+ * chains x 4 x iters operations of `kind`:
+ *   0 = 32x32->64 multiply plus one add, 1 = low-half multiply, 2 = high-half
+ *   multiply, 3 = three-input xor, 4 = add, 5 = compare-to-ballot plus lane write
+ *   plus one add.
+ * out: device, 2 uint64 per wave (4*workgroups waves): elapsed shader-clock
+ * ticks of the loop as read by s_memtime, and a checksum. */
+int rov_valu_probe(int kind, int iters, int workgroups, uint64_t *out, void *stream);
+
+/* ---------------------------------------------------------------- GEMM
+ * C[M,N] = scaleA*scaleB * sum_k A[m,k] * Bm[k,n], fp32 accumulation (paper
+ * Table 1, GEMM column; the QKV / PROJ / FC1 / FC2 layers of Sec. 3.2).
+ * A: row-major [M,K].  Bm: row-major [K,N] if transB == 0, row-major [N,K]
+ * (K contiguous, the layout of a weight matrix) if transB != 0.
+ * C: row-major [M,N]; fp32 for ROV_F32, bf16 for ROV_BF16 and ROV_FP8_E4M3.
+ * scaleA, scaleB: per-tensor dequantisation scales (use 1.0f for fp32/bf16).
+ * Pointers 16-byte aligned.  Shape limits are reported as ROV_ERR_UNSUPPORTED. */
+int rov_gemm(const void *A, const void *Bm, void *C, int M, int N, int K, int dtype, int transB,
+             float scaleA, float scaleB, void *stream);
+
+/* ---------------------------------------------------------------- attention
+ * O = dropout(softmax(Q K^T / sqrt(d))) V, dropout applied to the softmax
+ * output (paper Sec. 2.2), kept probabilities scaled by 1/(1-p); the softmax
+ * normaliser runs over all admissible columns.  Query head h uses key/value
+ * head h / (H / Hkv).  causal != 0: column j admissible for row i iff j <= i.
+ * Element (b, s, h, t) of tensor X lives at X[b*strides[3x] + s*strides[3x+1] +
+ * h*strides[3x+2] + t] with x = 0 (Q), 1 (K), 2 (V), 3 (O); strides in elements;
+ * the head dimension is contiguous.
+ * mask != NULL: keep-mask words as written by rov_dropout_mask_generate for the
+ *               same (B,H,S) - the paper's "attention with element dropping".
+ * mask == NULL and p > 0: the fused variant (paper Sec. 6.1, fusion): the kernel
+ *               generates the same Philox bits itself from (seed, offset).
+ * p == 0 disables dropout (mask, seed, offset ignored). */
+int rov_attention_fwd_dropout(const void *Q, const void *K, const void *V, void *O,
+                              int B, int H, int Hkv, int S, int d, const int64_t strides[12],
+                              int dtype, int causal, float p, const uint64_t *mask,
+                              uint64_t seed, uint64_t offset, void *stream);
+
+/* ---------------------------------------------------------------- schedules
+ * One "layer step" of the paper's silicon experiment (Sec. 6.1): n_gemms
+ * independent GEMMs, the RNG kernel, then attention with dropout, arranged by
+ * `schedule`:
+ *   ROV_SCHED_SEQUENTIAL: GEMMs -> RNG -> attention(mask), all on main_stream.
+ *   ROV_SCHED_FUSED:      GEMMs -> attention(fused Philox) on main_stream.
+ *   ROV_SCHED_OVERLAP:    RNG on side_stream concurrently with the GEMMs on
+ *                         main_stream; attention(mask) on main_stream after both.
+ * mask: device buffer of rov_mask_words(B,H,S) words (unused for FUSED, may be
+ * NULL there).  side_stream must differ from main_stream for OVERLAP. */
+typedef struct rov_gemm_desc {
+    const void *A;
+    const void *Bm;
+    void *C;
+    int M, N, K;
+    int dtype;
+    int transB;
+    float scaleA, scaleB;
+} rov_gemm_desc;
+
+typedef struct rov_attn_desc {
+    const void *Q;
+    const void *K;
+    const void *V;
+    void *O;
+    int B, H, Hkv, S, d;
+    int64_t strides[12];
+    int dtype;
+    int causal;
+    float p;
+} rov_attn_desc;
+
+int rov_layer_step(int schedule, const rov_gemm_desc *gemms, int n_gemms, const rov_attn_desc *attn,
+                   uint64_t seed, uint64_t offset, uint64_t *mask, void *main_stream,
+                   void *side_stream);
+
+/* ---------------------------------------------------------------- transformer block
+ * Llama-style block forward (paper Fig. 2 / Sec. 3.2 block with RMSNorm, rotary
+ * embedding, grouped-query attention, SwiGLU):
+ *   h1 = RMSNorm(x)*norm1; [q|k|v] = h1 Wqkv^T; RoPE(q,k); a = attention_dropout(q,k,v);
+ *   x2 = x + a Wo^T; h2 = RMSNorm(x2)*norm2; y = x2 + (silu(h2 Wg^T) * (h2 Wu^T)) Wd^T.
+ * Weights are row-major [out_features, in_features], dtype = cfg->dtype (bf16).
+ * x, y: [B, S, hidden].  The mask used by this block's attention is generated
+ * from (seed, offset); with ROV_SCHED_OVERLAP it is generated on side_stream
+ * while the block's first GEMM runs, and when `next_mask` is non-NULL the mask
+ * of the following layer (offset + rov_mask_philox_calls) is generated into it
+ * beside this block's remaining GEMMs (paper Sec. 1: RNG hidden behind the GEMM
+ * layers between the previous and the current attention).
+ * workspace: device scratch of at least rov_block_workspace_bytes() bytes. */
+typedef struct rov_block_cfg {
+    int H, Hkv, d, hidden, ffn;
+    int dtype;
+    int causal;
+    float p;
+    float eps;
+    float rope_theta;
+} rov_block_cfg;
+
+typedef struct rov_block_weights {
+    const void *norm1;   /* [hidden] */
+    const void *norm2;   /* [hidden] */
+    const void *wqkv;    /* [(H + 2*Hkv)*d, hidden] */
+    const void *wo;      /* [hidden, H*d] */
+    const void *wg;      /* [ffn, hidden] */
+    const void *wu;      /* [ffn, hidden] */
+    const void *wd;      /* [hidden, ffn] */
+} rov_block_weights;
+
+size_t rov_block_workspace_bytes(const rov_block_cfg *cfg, int B, int S, int schedule);
+
+int rov_block_forward(const rov_block_weights *w, const void *x, void *y, int B, int S,
+                      const rov_block_cfg *cfg, int schedule, uint64_t seed, uint64_t offset,
+                      int mask_ready, uint64_t *mask, uint64_t *next_mask,
+                      void *workspace, size_t workspace_bytes, void *main_stream, void *side_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ROV_H */

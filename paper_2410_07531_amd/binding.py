@@ -1,0 +1,218 @@
+"""Thin ctypes binding over librov.so: argument marshalling only.
+
+Every function takes torch tensors (device memory) and streams as plumbing and
+forwards raw pointers to the C ABI declared in include/rov.h.  There is no CPU
+fallback: if the library is missing or a call fails, an exception is raised.
+"""
+import ctypes
+import os
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "librov.so")
+
+OK, ERR_INVALID, ERR_UNSUPPORTED, ERR_HIP, ERR_WORKSPACE = 0, -1, -2, -3, -4
+F32, BF16, FP8_E4M3 = 0, 1, 2
+SCHED_SEQUENTIAL, SCHED_FUSED, SCHED_OVERLAP = 0, 1, 2
+
+_ERR_NAMES = {ERR_INVALID: "ROV_ERR_INVALID", ERR_UNSUPPORTED: "ROV_ERR_UNSUPPORTED",
+              ERR_HIP: "ROV_ERR_HIP", ERR_WORKSPACE: "ROV_ERR_WORKSPACE"}
+
+
+class RovError(RuntimeError):
+    def __init__(self, code, what):
+        self.code = code
+        super().__init__("%s failed: %s (%d)" % (what, _ERR_NAMES.get(code, "?"), code))
+
+
+class GemmDesc(ctypes.Structure):
+    _fields_ = [("A", ctypes.c_void_p), ("Bm", ctypes.c_void_p), ("C", ctypes.c_void_p),
+                ("M", ctypes.c_int), ("N", ctypes.c_int), ("K", ctypes.c_int),
+                ("dtype", ctypes.c_int), ("transB", ctypes.c_int),
+                ("scaleA", ctypes.c_float), ("scaleB", ctypes.c_float)]
+
+
+class AttnDesc(ctypes.Structure):
+    _fields_ = [("Q", ctypes.c_void_p), ("K", ctypes.c_void_p), ("V", ctypes.c_void_p),
+                ("O", ctypes.c_void_p),
+                ("B", ctypes.c_int), ("H", ctypes.c_int), ("Hkv", ctypes.c_int),
+                ("S", ctypes.c_int), ("d", ctypes.c_int),
+                ("strides", ctypes.c_int64 * 12),
+                ("dtype", ctypes.c_int), ("causal", ctypes.c_int), ("p", ctypes.c_float)]
+
+
+class BlockCfg(ctypes.Structure):
+    _fields_ = [("H", ctypes.c_int), ("Hkv", ctypes.c_int), ("d", ctypes.c_int),
+                ("hidden", ctypes.c_int), ("ffn", ctypes.c_int), ("dtype", ctypes.c_int),
+                ("causal", ctypes.c_int), ("p", ctypes.c_float), ("eps", ctypes.c_float),
+                ("rope_theta", ctypes.c_float)]
+
+
+class BlockWeights(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_void_p) for n in ("norm1", "norm2", "wqkv", "wo", "wg", "wu", "wd")]
+
+
+# name -> (restype, argtypes); also the list of symbols the header declares
+_u64, _i, _f, _p = ctypes.c_uint64, ctypes.c_int, ctypes.c_float, ctypes.c_void_p
+SIGNATURES = {
+    "rov_last_hip_error": (_i, []),
+    "rov_version": (ctypes.c_char_p, []),
+    "rov_mask_words": (_u64, [_i, _i, _i]),
+    "rov_mask_philox_calls": (_u64, [_i, _i, _i]),
+    "rov_philox_raw": (_i, [_u64, _u64, _u64, _i, _p, _p]),
+    "rov_dropout_mask_generate": (_i, [_u64, _u64, _i, _i, _i, _f, _p, _p]),
+    "rov_dropout_mask_generate_rounds": (_i, [_u64, _u64, _i, _i, _i, _f, _i, _p, _p]),
+    "rov_set_rng_max_workgroups": (_i, [_i]),
+    "rov_valu_probe": (_i, [_i, _i, _i, _p, _p]),
+    "rov_gemm": (_i, [_p, _p, _p, _i, _i, _i, _i, _i, _f, _f, _p]),
+    "rov_attention_fwd_dropout": (_i, [_p, _p, _p, _p, _i, _i, _i, _i, _i,
+                                       ctypes.POINTER(ctypes.c_int64), _i, _i, _f, _p, _u64, _u64, _p]),
+    "rov_layer_step": (_i, [_i, ctypes.POINTER(GemmDesc), _i, ctypes.POINTER(AttnDesc), _u64, _u64,
+                            _p, _p, _p]),
+    "rov_block_workspace_bytes": (ctypes.c_size_t, [ctypes.POINTER(BlockCfg), _i, _i, _i]),
+    "rov_block_forward": (_i, [ctypes.POINTER(BlockWeights), _p, _p, _i, _i, ctypes.POINTER(BlockCfg),
+                               _i, _u64, _u64, _i, _p, _p, _p, ctypes.c_size_t, _p, _p]),
+}
+
+_lib = None
+
+
+def load():
+    """Load librov.so (after torch, so that both share one HIP runtime)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError("librov.so is not built: run `python -c 'import __graft_entry__ as g; g.build()'`")
+    try:
+        import torch  # noqa: F401  (loads libamdhip64 first)
+    except ImportError:
+        pass
+    L = ctypes.CDLL(LIB_PATH)
+    for name, (res, args) in SIGNATURES.items():
+        fn = getattr(L, name)
+        fn.restype = res
+        fn.argtypes = args
+    _lib = L
+    return L
+
+
+def _check(code, what):
+    if code != OK:
+        raise RovError(code, what)
+
+
+def _stream_ptr(stream):
+    if stream is None:
+        import torch
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+def _dtype_code(t):
+    import torch
+    if t.dtype == torch.float32:
+        return F32
+    if t.dtype == torch.bfloat16:
+        return BF16
+    if t.dtype in (torch.float8_e4m3fn, torch.uint8):
+        return FP8_E4M3
+    raise TypeError("unsupported dtype %s" % t.dtype)
+
+
+def mask_words(B, H, S):
+    return int(load().rov_mask_words(B, H, S))
+
+
+def mask_philox_calls(B, H, S):
+    return int(load().rov_mask_philox_calls(B, H, S))
+
+
+def set_rng_max_workgroups(n):
+    return int(load().rov_set_rng_max_workgroups(int(n)))
+
+
+def philox_raw(seed, first_counter, ncalls, rounds=10, out=None, stream=None):
+    """int32-viewed uint32 [ncalls, 4] tensor of raw Philox words (test hook)."""
+    import torch
+    if out is None:
+        out = torch.empty((int(ncalls), 4), dtype=torch.int32, device="cuda")
+    _check(load().rov_philox_raw(seed & (2**64 - 1), first_counter & (2**64 - 1), int(ncalls), int(rounds),
+                                 ctypes.c_void_p(out.data_ptr()), _stream_ptr(stream)), "rov_philox_raw")
+    return out
+
+
+def dropout_mask_generate(seed, offset, B, H, S, p, out=None, rounds=None, stream=None):
+    """Keep-mask words as an int64 tensor [B, H, S, ceil(S/64)] (bit patterns of uint64)."""
+    import torch
+    W = (S + 63) // 64
+    if out is None:
+        out = torch.empty((B, H, S, W), dtype=torch.int64, device="cuda")
+    L = load()
+    if rounds is None:
+        rc = L.rov_dropout_mask_generate(seed & (2**64 - 1), offset & (2**64 - 1), B, H, S, p,
+                                         ctypes.c_void_p(out.data_ptr()), _stream_ptr(stream))
+    else:
+        rc = L.rov_dropout_mask_generate_rounds(seed & (2**64 - 1), offset & (2**64 - 1), B, H, S, p, int(rounds),
+                                                ctypes.c_void_p(out.data_ptr()), _stream_ptr(stream))
+    _check(rc, "rov_dropout_mask_generate")
+    return out
+
+
+def gemm(A, Bm, C=None, transB=True, scaleA=1.0, scaleB=1.0, stream=None):
+    """C = scaleA*scaleB * A @ (Bm^T if transB else Bm)."""
+    import torch
+    M, K = A.shape
+    N = Bm.shape[0] if transB else Bm.shape[1]
+    code = _dtype_code(A)
+    if C is None:
+        C = torch.empty((M, N), dtype=torch.float32 if code == F32 else torch.bfloat16, device=A.device)
+    _check(load().rov_gemm(ctypes.c_void_p(A.data_ptr()), ctypes.c_void_p(Bm.data_ptr()),
+                           ctypes.c_void_p(C.data_ptr()), M, N, K, code, int(bool(transB)),
+                           float(scaleA), float(scaleB), _stream_ptr(stream)), "rov_gemm")
+    return C
+
+
+def _strides12(Q, K, V, O):
+    arr = (ctypes.c_int64 * 12)()
+    for x, t in enumerate((Q, K, V, O)):
+        assert t.stride(3) == 1, "head dimension must be contiguous"
+        arr[3 * x + 0], arr[3 * x + 1], arr[3 * x + 2] = t.stride(0), t.stride(1), t.stride(2)
+    return arr
+
+
+def attention_fwd_dropout(Q, K, V, p, mask=None, seed=0, offset=0, causal=False, O=None, stream=None):
+    """Q [B,S,H,d], K/V [B,S,Hkv,d] -> O [B,S,H,d]; mask=None with p>0 selects the fused variant."""
+    import torch
+    B, S, H, d = Q.shape
+    Hkv = K.shape[2]
+    if O is None:
+        O = torch.empty_like(Q)
+    strides = _strides12(Q, K, V, O)
+    mptr = ctypes.c_void_p(mask.data_ptr()) if mask is not None else ctypes.c_void_p(0)
+    _check(load().rov_attention_fwd_dropout(
+        ctypes.c_void_p(Q.data_ptr()), ctypes.c_void_p(K.data_ptr()), ctypes.c_void_p(V.data_ptr()),
+        ctypes.c_void_p(O.data_ptr()), B, H, Hkv, S, d, strides, _dtype_code(Q), int(bool(causal)), float(p),
+        mptr, seed & (2**64 - 1), offset & (2**64 - 1), _stream_ptr(stream)), "rov_attention_fwd_dropout")
+    return O
+
+
+def make_gemm_desc(A, Bm, C, transB=True, scaleA=1.0, scaleB=1.0):
+    M, K = A.shape
+    N = Bm.shape[0] if transB else Bm.shape[1]
+    return GemmDesc(A.data_ptr(), Bm.data_ptr(), C.data_ptr(), M, N, K, _dtype_code(A), int(bool(transB)),
+                    float(scaleA), float(scaleB))
+
+
+def make_attn_desc(Q, K, V, O, p, causal=False):
+    B, S, H, d = Q.shape
+    desc = AttnDesc(Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(), B, H, K.shape[2], S, d,
+                    _strides12(Q, K, V, O), _dtype_code(Q), int(bool(causal)), float(p))
+    return desc
+
+
+def layer_step(schedule, gemm_descs, attn_desc, seed, offset, mask, main_stream, side_stream):
+    arr = (GemmDesc * len(gemm_descs))(*gemm_descs)
+    mptr = ctypes.c_void_p(mask.data_ptr()) if mask is not None else ctypes.c_void_p(0)
+    _check(load().rov_layer_step(int(schedule), arr, len(gemm_descs), ctypes.byref(attn_desc),
+                                 seed & (2**64 - 1), offset & (2**64 - 1), mptr,
+                                 _stream_ptr(main_stream), _stream_ptr(side_stream)), "rov_layer_step")

@@ -1,0 +1,186 @@
+// Stand-alone RNG kernel: Philox-4x32 keep-mask written to HBM (paper Sec. 6.1,
+// scenario 2 of the dropout kernel; storage B*nH*SQ^2 bits, Sec. 7.2), plus the
+// raw-stream test hook.
+//
+// Shape of the work on gfx950: the kernel reads nothing and is bound by VALU
+// issue (20 wide multiplies per call, Table 1 "ALU pipe"/"Issue stage").  One
+// wave owns a chunk of 64 consecutive mask words = 16 groups of 4 words.  For
+// each group every lane makes one Philox call; the four compares of its output
+// words are, as 64-lane ballots, exactly the four mask words of the group.
+// Each ballot is dropped into the lane that will store it (v_writelane), and
+// after 16 groups the wave issues one fully coalesced 512-byte store.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <atomic>
+
+#include "philox_device.h"
+#include "rov_internal.h"
+
+namespace rov {
+
+namespace {
+
+constexpr int kWavesPerBlock = 4;
+constexpr int kGroupsPerChunk = 16;   // 16 groups x 4 words = 64 words = one 8-byte store per lane
+
+std::atomic<int> g_rng_max_workgroups{0};
+
+// One chunk: 16 groups -> 64 mask words, word 4*gi + r parked in lane 4*gi + r of (vhi:vlo).
+template <int R, bool RAGGED, bool CARRY>
+__device__ __forceinline__ void mask_chunk(uint64_t base, uint32_t lane, uint32_t k0, uint32_t k1,
+                                           uint32_t t_minus_1, uint32_t W, uint32_t cb,
+                                           uint64_t tail_mask, uint32_t& vlo, uint32_t& vhi) {
+#pragma unroll 2
+    for (int gi = 0; gi < kGroupsPerChunk; ++gi) {
+        uint64_t b[4];
+        philox_group_ballots<R, CARRY>(base + 64u * (uint64_t)gi, lane, k0, k1, t_minus_1, b);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            uint64_t bits = b[r];
+            if (RAGGED) {
+                if (cb == W - 1u) bits &= tail_mask;   // columns >= S stay 0
+                cb = (cb + 1u == W) ? 0u : cb + 1u;
+            }
+            const uint32_t dst = 4u * (uint32_t)gi + (uint32_t)r;
+            vlo = write_lane((uint32_t)bits, dst, vlo);
+            vhi = write_lane((uint32_t)(bits >> 32), dst, vhi);
+        }
+    }
+}
+
+template <int R, bool RAGGED>
+__global__ __launch_bounds__(kWavesPerBlock * 64) void mask_kernel(
+    uint64_t* __restrict__ out, uint64_t words, uint64_t nchunks, uint64_t offset, uint32_t k0,
+    uint32_t k1, uint32_t t_minus_1, uint32_t W, uint64_t tail_mask) {
+    const uint32_t lane = threadIdx.x & 63u;
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const uint64_t stride = (uint64_t)gridDim.x * kWavesPerBlock;
+    for (uint64_t chunk = (uint64_t)blockIdx.x * kWavesPerBlock + wave; chunk < nchunks;
+         chunk += stride) {
+        uint32_t vlo = 0u, vhi = 0u;
+        uint32_t cb = 0u;   // column block of the chunk's first word (ragged rows only)
+        if (RAGGED) cb = (uint32_t)((chunk * 64u) % W);
+        // first call number of the chunk; its 1024 calls are base .. base + 1023
+        const uint64_t base = offset + 64u * kGroupsPerChunk * chunk;
+        if ((uint32_t)base <= 0xFFFFFFFFu - (64u * kGroupsPerChunk - 1u)) {
+            mask_chunk<R, RAGGED, false>(base, lane, k0, k1, t_minus_1, W, cb, tail_mask, vlo, vhi);
+        } else {
+            mask_chunk<R, RAGGED, true>(base, lane, k0, k1, t_minus_1, W, cb, tail_mask, vlo, vhi);
+        }
+        const uint64_t widx = chunk * 64u + lane;
+        if (widx < words) out[widx] = ((uint64_t)vhi << 32) | vlo;
+    }
+}
+
+__global__ __launch_bounds__(256) void raw_kernel(uint32_t* __restrict__ out, uint64_t ncalls,
+                                                  uint64_t first, uint32_t k0, uint32_t k1,
+                                                  int rounds) {
+    const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
+    for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < ncalls; i += stride) {
+        const uint64_t n = first + i;
+        uint32_t x[4];
+        philox4x32_dyn(rounds, (uint32_t)n, (uint32_t)(n >> 32), 0u, 0u, k0, k1, x);
+        reinterpret_cast<uint4*>(out)[i] = make_uint4(x[0], x[1], x[2], x[3]);
+    }
+}
+
+template <int R>
+int launch_mask_r(uint64_t* out, uint64_t words, uint64_t offset, uint32_t k0, uint32_t k1,
+                  uint32_t t_minus_1, int S, hipStream_t stream) {
+    const uint32_t W = (uint32_t)(((uint64_t)S + 63u) / 64u);
+    const uint64_t nchunks = (words + 63u) / 64u;
+    uint64_t blocks = (nchunks + kWavesPerBlock - 1) / kWavesPerBlock;
+    int cap = g_rng_max_workgroups.load();
+    if (cap <= 0) cap = device_cu_count() * 64;
+    if (blocks > (uint64_t)cap) blocks = (uint64_t)cap;
+    const int rem = S & 63;
+    const dim3 grid((unsigned)blocks), block(kWavesPerBlock * 64);
+    if (rem == 0) {
+        hipLaunchKernelGGL((mask_kernel<R, false>), grid, block, 0, stream, out, words, nchunks,
+                           offset, k0, k1, t_minus_1, W, ~0ull);
+    } else {
+        const uint64_t tail_mask = (1ull << rem) - 1ull;
+        hipLaunchKernelGGL((mask_kernel<R, true>), grid, block, 0, stream, out, words, nchunks,
+                           offset, k0, k1, t_minus_1, W, tail_mask);
+    }
+    ROV_LAUNCH_CHECK();
+    return ROV_OK;
+}
+
+}  // namespace
+
+bool keep_threshold_minus_1(float p, uint32_t* t_minus_1) {
+    if (!(p >= 0.0f) || !(p < 1.0f)) return false;
+    const double t = (1.0 - (double)p) * 4294967296.0;
+    const uint64_t T = (uint64_t)t;   // floor; 256 <= T <= 2^32 for float p in [0,1)
+    *t_minus_1 = (uint32_t)(T - 1u);
+    return true;
+}
+
+int launch_mask(uint64_t seed, uint64_t offset, int B, int H, int S, float p, int rounds,
+                uint64_t* out, hipStream_t stream) {
+    if (B <= 0 || H <= 0 || S <= 0 || out == nullptr) return ROV_ERR_INVALID;
+    if (!aligned(out, 8)) return ROV_ERR_INVALID;
+    uint32_t tm1;
+    if (!keep_threshold_minus_1(p, &tm1)) return ROV_ERR_INVALID;
+    const uint64_t W = ((uint64_t)S + 63u) / 64u;
+    // words = B*H*S*W; refuse anything that cannot be a real buffer (> 2^40 words)
+    const long double wd = (long double)B * H * S * W;
+    if (wd > 1099511627776.0L) return ROV_ERR_UNSUPPORTED;
+    const uint64_t words = (uint64_t)B * (uint64_t)H * (uint64_t)S * W;
+    const uint32_t k0 = (uint32_t)seed, k1 = (uint32_t)(seed >> 32);
+    switch (rounds) {
+        case 10: return launch_mask_r<10>(out, words, offset, k0, k1, tm1, S, stream);
+        case 7: return launch_mask_r<7>(out, words, offset, k0, k1, tm1, S, stream);
+        case 5: return launch_mask_r<5>(out, words, offset, k0, k1, tm1, S, stream);
+        case 3: return launch_mask_r<3>(out, words, offset, k0, k1, tm1, S, stream);
+        default: return ROV_ERR_INVALID;
+    }
+}
+
+}  // namespace rov
+
+extern "C" {
+
+uint64_t rov_mask_words(int B, int H, int S) {
+    if (B <= 0 || H <= 0 || S <= 0) return 0;
+    const uint64_t W = ((uint64_t)S + 63u) / 64u;
+    return (uint64_t)B * (uint64_t)H * (uint64_t)S * W;
+}
+
+uint64_t rov_mask_philox_calls(int B, int H, int S) {
+    const uint64_t words = rov_mask_words(B, H, S);
+    return 64u * ((words + 3u) / 4u);
+}
+
+int rov_set_rng_max_workgroups(int max_workgroups) {
+    return rov::g_rng_max_workgroups.exchange(max_workgroups > 0 ? max_workgroups : 0);
+}
+
+int rov_philox_raw(uint64_t seed, uint64_t first_counter, uint64_t ncalls, int rounds,
+                   uint32_t* out, void* stream) {
+    if (rounds < 1 || rounds > 16) return ROV_ERR_INVALID;
+    if (ncalls == 0) return ROV_OK;
+    if (out == nullptr || !rov::aligned(out, 16)) return ROV_ERR_INVALID;
+    if (ncalls > (1ull << 40)) return ROV_ERR_UNSUPPORTED;
+    uint64_t blocks = (ncalls + 255u) / 256u;
+    const uint64_t cap = (uint64_t)rov::device_cu_count() * 64u;
+    if (blocks > cap) blocks = cap;
+    hipLaunchKernelGGL(rov::raw_kernel, dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)stream,
+                       out, ncalls, first_counter, (uint32_t)seed, (uint32_t)(seed >> 32), rounds);
+    ROV_LAUNCH_CHECK();
+    return ROV_OK;
+}
+
+int rov_dropout_mask_generate(uint64_t seed, uint64_t offset, int B, int H, int S, float p,
+                              uint64_t* out, void* stream) {
+    return rov::launch_mask(seed, offset, B, H, S, p, 10, out, (hipStream_t)stream);
+}
+
+int rov_dropout_mask_generate_rounds(uint64_t seed, uint64_t offset, int B, int H, int S, float p,
+                                     int rounds, uint64_t* out, void* stream) {
+    return rov::launch_mask(seed, offset, B, H, S, p, rounds, out, (hipStream_t)stream);
+}
+
+}  // extern "C"

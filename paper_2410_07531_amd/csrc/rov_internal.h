@@ -1,0 +1,40 @@
+// Internal helpers shared by the translation units of librov (host side).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include "rov.h"
+
+namespace rov {
+
+// Records the failing hipError_t for rov_last_hip_error() and yields ROV_ERR_HIP.
+int record_hip_error(hipError_t e);
+
+#define ROV_HIP_TRY(expr)                                        \
+    do {                                                         \
+        hipError_t rov_e_ = (expr);                              \
+        if (rov_e_ != hipSuccess) return ::rov::record_hip_error(rov_e_); \
+    } while (0)
+
+// Launch check: hipGetLastError after a kernel launch.
+#define ROV_LAUNCH_CHECK() ROV_HIP_TRY(hipGetLastError())
+
+inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+
+// Number of compute units of the current device (cached per process).
+int device_cu_count();
+
+// Keep threshold minus one: an element is kept iff x <= t_minus_1 (== x < T,
+// T = floor((1-p)*2^32) in double, T in [256, 2^32]).  Returns false if p is
+// outside [0,1) or NaN.
+bool keep_threshold_minus_1(float p, uint32_t* t_minus_1);
+
+// Launchers used across translation units (all asynchronous on `stream`).
+int launch_mask(uint64_t seed, uint64_t offset, int B, int H, int S, float p, int rounds,
+                uint64_t* out, hipStream_t stream);
+int launch_gemm(const void* A, const void* Bm, void* C, int M, int N, int K, int dtype, int transB,
+                float scaleA, float scaleB, hipStream_t stream);
+int launch_attention(const void* Q, const void* K, const void* V, void* O, int B, int H, int Hkv,
+                     int S, int d, const int64_t strides[12], int dtype, int causal, float p,
+                     const uint64_t* mask, uint64_t seed, uint64_t offset, hipStream_t stream);
+
+}  // namespace rov

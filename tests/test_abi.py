@@ -1,0 +1,52 @@
+"""The C-ABI library loads and exports every symbol include/rov.h declares (no GPU needed)."""
+import ctypes
+import os
+import re
+
+from paper_2410_07531_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "rov.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(rov_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_header_symbols_are_exported_and_bound():
+    names = _declared()
+    assert "rov_dropout_mask_generate" in names and "rov_gemm" in names
+    assert os.path.exists(binding.LIB_PATH), "build the library first (__graft_entry__.build())"
+    lib = ctypes.CDLL(binding.LIB_PATH)
+    for n in names:
+        assert hasattr(lib, n), "librov.so does not export %s" % n
+    assert sorted(binding.SIGNATURES) == names
+
+
+def test_host_only_entry_points():
+    L = binding.load()
+    assert L.rov_version().startswith(b"rov")
+    assert binding.mask_words(1, 2, 128) == 512
+    assert binding.mask_words(1, 1, 70) == 140
+    assert binding.mask_words(0, 1, 70) == 0
+    assert binding.mask_philox_calls(1, 2, 128) == 64 * 128
+    assert binding.mask_philox_calls(1, 1, 70) == 64 * 35
+    assert binding.mask_philox_calls(1, 1, 1) == 64
+    assert L.rov_last_hip_error() == 0
+
+
+def test_no_oracle_on_the_product_path():
+    # the package must never import the oracle (and the oracle never the package)
+    pkg = os.path.join(ROOT, "paper_2410_07531_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".h", ".cpp")):
+                src = open(os.path.join(dirpath, f)).read()
+                assert not re.search(r"^\s*(from|import)\s+oracle\b", src, flags=re.M), f
+                assert "liboracle" not in src and "philox_oracle" not in src, f
+    for f in os.listdir(os.path.join(ROOT, "oracle")):
+        if f.endswith((".py", ".c")):
+            src = open(os.path.join(ROOT, "oracle", f)).read()
+            assert not re.search(r"^\s*(from|import)\s+paper_2410_07531_amd\b", src, flags=re.M), f
+            assert "librov" not in src, f

@@ -1,10 +1,329 @@
-// GEMM (placeholder until the MFMA kernel lands): reports ROV_ERR_UNSUPPORTED.
+// GEMM for the QKV / PROJ / FC1 / FC2 layers that the RNG kernel hides behind
+// (paper Sec. 3.2, Table 1 GEMM column: MMA-bound, L2 read bandwidth second).
+//
+// bf16 fast path (A [M,K] and weights [N,K], both K-contiguous):
+//   - workgroup tile 256 x 256, K step 64, 4 waves in a 2 x 2 grid, each wave
+//     owning a 128 x 128 block as 4 x 4 MFMA 32x32x16 tiles (256 fp32
+//     accumulators per lane);
+//   - tiles go from global memory straight into LDS (global_load_lds, 16 bytes
+//     per lane), two 64 KiB stages; a wave's 64 lanes always fill 1 KiB of
+//     consecutive LDS, so the bank swizzle (16-byte chunk index XOR row%8) is
+//     applied on the global-address side;
+//   - the MFMA is issued with the weight fragment as first operand, so each
+//     lane ends up with 4 consecutive output columns and stores 8 bytes at once;
+//   - workgroup ids are remapped so that the workgroups that land on one XCD
+//     (one L2) cover a compact block of output tiles.
+// The register budget is capped below the full file so that RNG waves can be
+// co-resident on every SIMD (the paper's carve-out, Sec. 6.2).
+//
+// Everything else (fp32, [K,N] weights, K not a multiple of 64) takes a small
+// LDS-tiled VALU kernel that is correct for any shape.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
 #include "rov_internal.h"
+
 namespace rov {
-int launch_gemm(const void*, const void*, void*, int, int, int, int, int, float, float, hipStream_t) {
-    return ROV_ERR_UNSUPPORTED;
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+__device__ __forceinline__ uint16_t f32_to_bf16_bits(float f) {
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (uint16_t)((u >> 16) | 0x0040u);   // quiet NaN
+    u += 0x7FFFu + ((u >> 16) & 1u);   // round to nearest, ties to even
+    return (uint16_t)(u >> 16);
 }
+
+__device__ __forceinline__ float bf16_bits_to_f32(uint16_t b) {
+    return __uint_as_float((uint32_t)b << 16);
+}
+
+// ------------------------------------------------------------------ generic kernel
+// 64 x 64 output tile, 16 x 16 threads, 4 x 4 outputs per thread, K step 16, fp32 FMA.
+template <typename T>
+__device__ __forceinline__ float load_as_f32(const T* p);
+template <>
+__device__ __forceinline__ float load_as_f32<float>(const float* p) { return *p; }
+template <>
+__device__ __forceinline__ float load_as_f32<uint16_t>(const uint16_t* p) { return bf16_bits_to_f32(*p); }
+
+template <typename T>
+__device__ __forceinline__ void store_from_f32(T* p, float v);
+template <>
+__device__ __forceinline__ void store_from_f32<float>(float* p, float v) { *p = v; }
+template <>
+__device__ __forceinline__ void store_from_f32<uint16_t>(uint16_t* p, float v) { *p = f32_to_bf16_bits(v); }
+
+template <typename T, bool TRANSB>
+__global__ __launch_bounds__(256) void gemm_generic_kernel(const T* __restrict__ A,
+                                                           const T* __restrict__ Bm,
+                                                           T* __restrict__ C, int M, int N, int K,
+                                                           float alpha) {
+    __shared__ float As[16][64 + 1];
+    __shared__ float Bs[16][64 + 1];
+    const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
+    const int m0 = blockIdx.y * 64, n0 = blockIdx.x * 64;
+    float acc[4][4] = {};
+    for (int k0 = 0; k0 < K; k0 += 16) {
+        for (int e = threadIdx.x; e < 64 * 16; e += 256) {
+            const int r = e >> 4, kk = e & 15;          // A: row r, k kk (k fastest in memory)
+            const int m = m0 + r, k = k0 + kk;
+            As[kk][r] = (m < M && k < K) ? load_as_f32(A + (size_t)m * K + k) : 0.0f;
+            if (TRANSB) {
+                const int n = n0 + r;
+                Bs[kk][r] = (n < N && k < K) ? load_as_f32(Bm + (size_t)n * K + k) : 0.0f;
+            }
+        }
+        if (!TRANSB) {
+            for (int e = threadIdx.x; e < 64 * 16; e += 256) {
+                const int kk = e >> 6, c = e & 63;      // B: k kk, column c (n fastest in memory)
+                const int k = k0 + kk, n = n0 + c;
+                Bs[kk][c] = (n < N && k < K) ? load_as_f32(Bm + (size_t)k * N + n) : 0.0f;
+            }
+        }
+        __syncthreads();
+#pragma unroll
+        for (int kk = 0; kk < 16; ++kk) {
+            float a[4], b[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) a[i] = As[kk][ty * 4 + i];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) b[j] = Bs[kk][tx * 4 + j];
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) acc[i][j] = __builtin_fmaf(a[i], b[j], acc[i][j]);
+        }
+        __syncthreads();
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int m = m0 + ty * 4 + i, n = n0 + tx * 4 + j;
+            if (m < M && n < N) store_from_f32(C + (size_t)m * N + n, alpha * acc[i][j]);
+        }
+}
+
+// ------------------------------------------------------------------ bf16 MFMA kernel
+constexpr int BM = 256, BN = 256, BK = 64;
+constexpr int kStageBytes = (BM + BN) * BK * 2;     // 64 KiB: A tile then W tile
+constexpr int kRowBytes = BK * 2;                   // 128 bytes per tile row
+
+typedef const __attribute__((address_space(1))) void* gptr_t;
+typedef __attribute__((address_space(3))) void* lptr_t;
+
+// One operand tile (256 rows x 64 k) from global to LDS.  Wave w copies row
+// blocks w, w+4, ... (8 rows each); within a block lane L fills physical chunk
+// L%8 of row L/8, which holds logical chunk (L%8) ^ (row%8).
+__device__ __forceinline__ void load_tile(const uint16_t* __restrict__ src, int ld, int row0,
+                                          int max_row, int k0, char* lds_tile, int wave, int lane) {
+    const int rl = lane >> 3;                        // row within the 8-row block
+    const int chunk = (lane & 7) ^ rl;               // logical 16-byte chunk this lane fetches
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const int blk = wave + 4 * i;                // 0..31
+        int row = row0 + blk * 8 + rl;
+        row = row < max_row ? row : max_row;         // clamp: rows past the edge are never stored
+        const uint16_t* g = src + (size_t)row * ld + k0 + chunk * 8;
+        __builtin_amdgcn_global_load_lds((gptr_t)g, (lptr_t)(lds_tile + blk * 8 * kRowBytes), 16, 0, 0);
+    }
+}
+
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+
+// Reads one accumulator value where it is needed.  The "a" constraint keeps the value in its
+// accumulation register until this point; without it the register allocator copies all 256
+// accumulators to ordinary VGPRs at the loop exit and the kernel needs the whole register file,
+// leaving no room for co-resident RNG waves.
+__device__ __forceinline__ float acc_read(float v) {
+    float r;
+    asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(r) : "a"(v));
+    return r;
+}
+
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+    f32x2 v = {lo, hi};
+    bf16x2 h = __builtin_convertvector(v, bf16x2);   // v_cvt_pk_bf16_f32: nearest, ties to even
+    return *reinterpret_cast<uint32_t*>(&h);
+}
+
+__global__ __launch_bounds__(256, 1) void gemm_bf16_tn_kernel(const uint16_t* __restrict__ A,
+                                                              const uint16_t* __restrict__ Wt,
+                                                              uint16_t* __restrict__ C, int M, int N,
+                                                              int K, float alpha, int tiles_m,
+                                                              int tiles_n) {
+    extern __shared__ __attribute__((aligned(1024))) char lds[];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int wm = wave >> 1, wn = wave & 1;
+
+    // XCD-aware tile id: workgroup ids are dealt round-robin to the 8 XCDs; give each XCD a
+    // contiguous range of logical tiles, ordered in bands of 8 tile-rows with the row fastest.
+    const int T = tiles_m * tiles_n;
+    int id;
+    {
+        const int pid = blockIdx.x, per = T >> 3, rem = T & 7;
+        const int xcd = pid & 7, loc = pid >> 3;
+        id = xcd < rem ? xcd * (per + 1) + loc : rem * (per + 1) + (xcd - rem) * per + loc;
+    }
+    constexpr int GM = 8;
+    const int band = id / (GM * tiles_n);
+    const int band_rows = (tiles_m - band * GM) < GM ? (tiles_m - band * GM) : GM;
+    const int in_band = id - band * GM * tiles_n;
+    const int tm = band * GM + in_band % band_rows;
+    const int tn = in_band / band_rows;
+    const int m0 = tm * BM, n0 = tn * BN;
+
+    f32x16 acc[4][4];   // [weight-row block j][activation-row block i]
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[j][i][e] = 0.0f;
+
+    // per-lane fragment addressing: row = base + lane%32, k-chunk = 2*kk + lane/32, swizzled by row%8
+    const int frow = lane & 31;
+    const int fhalf = lane >> 5;
+    const int swz = lane & 7;
+    int foff[4];
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) foff[kk] = frow * kRowBytes + (((2 * kk + fhalf) ^ swz) << 4);
+    const int a_base = (wm * 128) * kRowBytes;
+    const int w_base = BM * kRowBytes + (wn * 128) * kRowBytes;
+
+    bf16x8 af[2][4], wf[2][4];   // fragments of the current and the next k-step
+    auto read_frags = [&](int buf, const char* stage, int kk) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            af[buf][i] = *reinterpret_cast<const bf16x8*>(stage + a_base + i * 32 * kRowBytes + foff[kk]);
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            wf[buf][j] = *reinterpret_cast<const bf16x8*>(stage + w_base + j * 32 * kRowBytes + foff[kk]);
+    };
+
+    const int nk = K / BK;
+    load_tile(A, K, m0, M - 1, 0, lds, wave, lane);
+    load_tile(Wt, K, n0, N - 1, 0, lds + BM * kRowBytes, wave, lane);
+    __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
+    __syncthreads();
+    if (nk > 1) {
+        load_tile(A, K, m0, M - 1, BK, lds + kStageBytes, wave, lane);
+        load_tile(Wt, K, n0, N - 1, BK, lds + kStageBytes + BM * kRowBytes, wave, lane);
+    }
+    read_frags(0, lds, 0);
+
+    for (int kt = 0; kt < nk; ++kt) {
+        const char* cur = lds + (kt & 1) * kStageBytes;
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+            if (kk < 3) {
+                read_frags((kk + 1) & 1, cur, kk + 1);
+            } else if (kt + 1 < nk) {
+                // tile boundary: the next stage must have landed for every wave, and every wave
+                // must be done reading this stage before it is refilled
+                __builtin_amdgcn_s_waitcnt(0x0070);   // vmcnt(0) lgkmcnt(0)
+                __syncthreads();
+                if (kt + 2 < nk) {
+                    char* refill = lds + (kt & 1) * kStageBytes;
+                    load_tile(A, K, m0, M - 1, (kt + 2) * BK, refill, wave, lane);
+                    load_tile(Wt, K, n0, N - 1, (kt + 2) * BK, refill + BM * kRowBytes, wave, lane);
+                }
+                read_frags(0, lds + ((kt + 1) & 1) * kStageBytes, 0);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    acc[j][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[kk & 1][j], af[kk & 1][i],
+                                                                        acc[j][i], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
+
+    // D'[r][c] = C[m = c][n = r]: lane holds column c = lane%32 (an activation row) and, for
+    // register e, weight row 8*(e/4) + 4*(lane/32) + e%4: four consecutive n per e/4.
+    // N is a multiple of 4 here, so a group of four columns is inside or outside as a whole.
+    const int mrow = lane & 31;
+    const int nsub = (lane >> 5) * 4;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int m = m0 + wm * 128 + i * 32 + mrow;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            // keep the accumulator read-out block by block: a hoisted read-out of all 256
+            // values would double the kernel's register footprint
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int n = n0 + wn * 128 + j * 32 + q * 8 + nsub;
+                uint2 v;
+                v.x = pack_bf16x2(alpha * acc_read(acc[j][i][q * 4 + 0]), alpha * acc_read(acc[j][i][q * 4 + 1]));
+                v.y = pack_bf16x2(alpha * acc_read(acc[j][i][q * 4 + 2]), alpha * acc_read(acc[j][i][q * 4 + 3]));
+                if (m < M && n < N) *reinterpret_cast<uint2*>(C + (size_t)m * N + n) = v;
+            }
+        }
+    }
+}
+
+}  // namespace
+
+int launch_gemm(const void* A, const void* Bm, void* C, int M, int N, int K, int dtype, int transB,
+                float scaleA, float scaleB, hipStream_t stream) {
+    if (A == nullptr || Bm == nullptr || C == nullptr || M <= 0 || N <= 0 || K <= 0)
+        return ROV_ERR_INVALID;
+    if (!aligned(A, 16) || !aligned(Bm, 16) || !aligned(C, 16)) return ROV_ERR_INVALID;
+    if (dtype != ROV_F32 && dtype != ROV_BF16 && dtype != ROV_FP8_E4M3) return ROV_ERR_INVALID;
+    if (dtype == ROV_FP8_E4M3) return ROV_ERR_UNSUPPORTED;
+    const float alpha = scaleA * scaleB;
+    const bool tb = transB != 0;
+
+    if (dtype == ROV_BF16 && tb && (K % BK) == 0 && (N % 4) == 0) {
+        const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
+        const long long T = (long long)tiles_m * tiles_n;
+        if (T > 0x7FFFFFFFLL) return ROV_ERR_UNSUPPORTED;
+        static bool attr_set = false;
+        if (!attr_set) {
+            ROV_HIP_TRY(hipFuncSetAttribute((const void*)gemm_bf16_tn_kernel,
+                                            hipFuncAttributeMaxDynamicSharedMemorySize,
+                                            2 * kStageBytes));
+            attr_set = true;
+        }
+        hipLaunchKernelGGL(gemm_bf16_tn_kernel, dim3((unsigned)T), dim3(256), 2 * kStageBytes, stream,
+                           (const uint16_t*)A, (const uint16_t*)Bm, (uint16_t*)C, M, N, K, alpha,
+                           tiles_m, tiles_n);
+        ROV_LAUNCH_CHECK();
+        return ROV_OK;
+    }
+
+    const dim3 grid((unsigned)((N + 63) / 64), (unsigned)((M + 63) / 64)), block(256);
+    if (grid.y > 65535u) return ROV_ERR_UNSUPPORTED;
+    if (dtype == ROV_F32) {
+        if (tb)
+            hipLaunchKernelGGL((gemm_generic_kernel<float, true>), grid, block, 0, stream,
+                               (const float*)A, (const float*)Bm, (float*)C, M, N, K, alpha);
+        else
+            hipLaunchKernelGGL((gemm_generic_kernel<float, false>), grid, block, 0, stream,
+                               (const float*)A, (const float*)Bm, (float*)C, M, N, K, alpha);
+    } else {
+        if (tb)
+            hipLaunchKernelGGL((gemm_generic_kernel<uint16_t, true>), grid, block, 0, stream,
+                               (const uint16_t*)A, (const uint16_t*)Bm, (uint16_t*)C, M, N, K, alpha);
+        else
+            hipLaunchKernelGGL((gemm_generic_kernel<uint16_t, false>), grid, block, 0, stream,
+                               (const uint16_t*)A, (const uint16_t*)Bm, (uint16_t*)C, M, N, K, alpha);
+    }
+    ROV_LAUNCH_CHECK();
+    return ROV_OK;
+}
+
 }  // namespace rov
+
 extern "C" int rov_gemm(const void* A, const void* Bm, void* C, int M, int N, int K, int dtype,
                         int transB, float scaleA, float scaleB, void* stream) {
     return rov::launch_gemm(A, Bm, C, M, N, K, dtype, transB, scaleA, scaleB, (hipStream_t)stream);

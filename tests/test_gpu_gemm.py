@@ -1,0 +1,116 @@
+"""GPU parity: rov_gemm vs the float64 oracle on the same dtype-rounded inputs.
+
+Tolerance (stated for this path): max|gpu - ref| / max|ref| <= 2e-2 for bf16 with fp32
+accumulation; the arithmetic predicts about 2^-9 (one bf16 rounding of the result), so a tighter
+sanity bound of 6e-3 is asserted too.  fp32: 1e-5 of the output scale.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import dense as OD
+from paper_2410_07531_amd import binding as rov
+from paper_2410_07531_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+BF16_TOL = 2e-2
+BF16_EXPECTED = 6e-3
+
+
+def _to_dev(x, dtype):
+    return torch.from_numpy(x).to(dtype).cuda()
+
+
+def _f64(t):
+    return t.float().cpu().numpy().astype(np.float64)
+
+
+def _rel_err(got, ref):
+    return float(np.max(np.abs(got - ref)) / np.max(np.abs(ref)))
+
+
+@pytest.mark.parametrize("M,N,K,transB", [
+    (256, 256, 64, True),        # one tile, one k-step
+    (256, 256, 128, True),       # two k-steps (both LDS stages)
+    (512, 768, 448, True),       # several tiles, odd number of k-steps
+    (300, 520, 192, True),       # ragged M and N (N % 4 == 0): MFMA kernel with clamped edges
+    (1, 4, 64, True),            # degenerate sizes on the MFMA path
+    (77, 130, 100, True),        # N % 4 != 0, K % 64 != 0: generic kernel
+    (130, 96, 72, False),        # [K, N] weights: generic kernel
+])
+def test_gemm_bf16_matches_oracle(M, N, K, transB):
+    print("gemm bf16", M, N, K, transB, flush=True)
+    rng = np.random.default_rng(M * 131 + N * 17 + K)
+    a, w = wl.gemm_operands(rng, M, K, N)
+    A = _to_dev(a, torch.bfloat16)
+    W = _to_dev(w if transB else np.ascontiguousarray(w.T), torch.bfloat16)
+    C = rov.gemm(A, W, transB=transB)
+    torch.cuda.synchronize()
+    ref = OD.gemm(_f64(A), _f64(W), transB=transB)
+    err = _rel_err(_f64(C), ref)
+    assert err <= BF16_TOL and err <= BF16_EXPECTED, err
+
+
+def test_gemm_bf16_scale_and_one_hot():
+    # alpha = scaleA*scaleB is applied; one-hot activations copy weight rows exactly (bf16 in, bf16 out)
+    rng = np.random.default_rng(3)
+    _, w = wl.gemm_operands(rng, 256, 128, 256)
+    W = _to_dev(w, torch.bfloat16)
+    A = torch.zeros((256, 128), dtype=torch.bfloat16, device="cuda")
+    idx = torch.arange(256, device="cuda") % 128
+    A[torch.arange(256, device="cuda"), idx] = 1.0
+    C = rov.gemm(A, W, transB=True)
+    assert torch.equal(C, W[:, idx.cpu()].T.contiguous().cuda() if False else W.T[idx])
+    C2 = rov.gemm(A, W, transB=True, scaleA=0.5, scaleB=4.0)
+    assert torch.equal(C2.float(), 2.0 * C.float())
+
+
+def test_gemm_fp32_tiny_workload():
+    c = wl.CONFIGS[0]
+    _, M, K, N = c["gemms"][0]
+    a = wl.rng_for(0).standard_normal((M, K), dtype=np.float32)
+    b = wl.rng_for(0).standard_normal((K, N), dtype=np.float32)
+    for transB in (False, True):
+        A, Bm = _to_dev(a, torch.float32), _to_dev(b if not transB else np.ascontiguousarray(b.T), torch.float32)
+        C = rov.gemm(A, Bm, transB=transB)
+        ref = OD.gemm(a.astype(np.float64), b.astype(np.float64))
+        assert _rel_err(_f64(C), ref) <= 1e-5
+
+
+def test_gemm_bf16_llama8b_ffn_up_sampled():
+    # full-size second workload (2048 x 4096 x 14336) in the configuration the benchmark times;
+    # the oracle evaluates 64 sampled rows in full and 4096 single entries
+    _, M, K, N = wl.CONFIGS[1]["gemms"][0]
+    print("gemm cfg2", M, K, N, flush=True)
+    rng = wl.rng_for(1)
+    a, w = wl.gemm_operands(rng, M, K, N)
+    A, W = _to_dev(a, torch.bfloat16), _to_dev(w, torch.bfloat16)
+    C = rov.gemm(A, W, transB=True)
+    torch.cuda.synchronize()
+    Ah, Wh, Ch = _f64(A), _f64(W), _f64(C)
+    srng = np.random.default_rng(7)
+    rows = np.sort(srng.choice(M, 64, replace=False))
+    rows[0], rows[-1] = 0, M - 1
+    ref_rows = OD.gemm(Ah[rows], Wh, transB=True)
+    scale = float(np.max(np.abs(ref_rows)))
+    err = float(np.max(np.abs(Ch[rows] - ref_rows)) / scale)
+    assert err <= BF16_TOL and err <= BF16_EXPECTED, err
+    rr, cc = srng.integers(0, M, 4096), srng.integers(0, N, 4096)
+    ent = OD.gemm_entries(Ah, Wh, rr, cc, transB=True)
+    assert float(np.max(np.abs(Ch[rr, cc] - ent)) / scale) <= BF16_EXPECTED
+
+
+def test_gemm_error_paths():
+    import ctypes
+    L = rov.load()
+    A = torch.zeros((64, 64), dtype=torch.bfloat16, device="cuda")
+    C = torch.full((64, 64), 7.0, dtype=torch.bfloat16, device="cuda")
+    s = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+    p = lambda t: ctypes.c_void_p(t.data_ptr())
+    assert L.rov_gemm(p(A), p(A), p(C), 0, 64, 64, rov.BF16, 1, 1.0, 1.0, s) == rov.ERR_INVALID
+    assert L.rov_gemm(ctypes.c_void_p(0), p(A), p(C), 64, 64, 64, rov.BF16, 1, 1.0, 1.0, s) == rov.ERR_INVALID
+    assert L.rov_gemm(p(A), p(A), p(C), 64, 64, 64, 9, 1, 1.0, 1.0, s) == rov.ERR_INVALID
+    assert L.rov_gemm(ctypes.c_void_p(A.data_ptr() + 2), p(A), p(C), 32, 32, 32, rov.BF16, 1, 1.0, 1.0, s) == rov.ERR_INVALID
+    torch.cuda.synchronize()
+    assert bool((C == 7.0).all())

@@ -1,12 +1,586 @@
-// Attention (placeholder until the kernel lands): reports ROV_ERR_UNSUPPORTED.
+// Flash-attention forward with dropout after softmax (paper Sec. 2.2, Sec. 6.1).
+//
+// Three ways to get the keep bits, all giving the same bits:
+//   MODE_NONE  p == 0, no dropout;
+//   MODE_MASK  the paper's "attention with element dropping": keep-mask words written
+//              earlier by the stand-alone RNG kernel are loaded one KV tile ahead, so the
+//              loads sit under the Q K^T matrix multiply (Sec. 6.1);
+//   MODE_FUSED the paper's fusion baseline: the kernel runs Philox itself.
+//
+// bf16 kernel, head dimension 64 or 128, on the matrix cores.  Everything is
+// computed transposed, S^T = K Q^T and O^T = V^T P^T with MFMA 32x32x16, because
+// then one lane owns one query column: the softmax statistics, the rescale of
+// O and the mask word are per-lane scalars and only the row maximum needs one
+// exchange between the two half-waves.  The S^T accumulator registers are, as
+// they stand, the P^T operand of the second product if the 16 keys of a k-step
+// are taken in the order the accumulator holds them; V is written to LDS
+// transposed ([dv][key]) so that this key order is two 8-byte reads per lane.
+//
+// A wave owns NQ*32 query rows and walks the keys 64 at a time; 4 waves per
+// workgroup share each K / V tile through LDS (K straight from global memory
+// with global_load_lds, V through registers because of the transpose).
+//
+// Any other case (fp32, other head dimensions) takes a small one-wave-per-row
+// kernel that is correct for every shape.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "philox_device.h"
 #include "rov_internal.h"
+
 namespace rov {
-int launch_attention(const void*, const void*, const void*, void*, int, int, int, int, int,
-                     const int64_t*, int, int, float, const uint64_t*, uint64_t, uint64_t,
-                     hipStream_t) {
-    return ROV_ERR_UNSUPPORTED;
+namespace {
+
+enum { MODE_NONE = 0, MODE_MASK = 1, MODE_FUSED = 2 };
+
+struct AttnParams {
+    const void* Q;
+    const void* K;
+    const void* V;
+    void* O;
+    const uint64_t* mask;
+    int64_t sq[3], sk[3], sv[3], so[3];   // element strides (batch, token, head)
+    int B, H, Hkv, S, d;
+    int W;                                // mask words per row
+    int causal;
+    float scale_log2;                     // log2(e) / sqrt(d)
+    float inv_keep;                       // 1 / (1 - p)
+    uint64_t offset;                      // Philox call offset (fused)
+    uint32_t k0, k1;                      // Philox key (fused)
+    uint32_t t_minus_1;                   // keep iff x <= t_minus_1 (fused)
+};
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef const __attribute__((address_space(1))) void* gptr_t;
+typedef __attribute__((address_space(3))) void* lptr_t;
+
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+    f32x2 v = {lo, hi};
+    bf16x2 h = __builtin_convertvector(v, bf16x2);
+    return *reinterpret_cast<uint32_t*>(&h);
 }
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+constexpr int BKV = 64;   // keys per tile = one mask word per query row
+
+template <int D>
+struct Tile {
+    static constexpr int kKRow = D * 2;                // bytes per K row in LDS
+    static constexpr int kKBytes = BKV * kKRow;
+    static constexpr int kVPitch = BKV * 2 + 8;        // bytes per V^T row ([dv][key]), padded
+    static constexpr int kVBytes = D * kVPitch;
+    static constexpr int kStage = kKBytes + kVBytes;
+    static constexpr int kChunks = D / 8;              // 16-byte chunks per K row
+};
+
+// K tile: global -> LDS directly.  One wave instruction fills 1 KiB = 1024 / kKRow rows; lane
+// L lands on physical chunk L % kChunks of its row and therefore fetches logical chunk
+// (L % kChunks) ^ (row % 8).
+template <int D>
+__device__ __forceinline__ void load_k_tile(const uint16_t* __restrict__ Kp, int64_t tok_stride,
+                                            int kv0, int S, char* lds_k, int wave, int lane) {
+    constexpr int kChunks = Tile<D>::kChunks;
+    constexpr int kRowsPerInst = 64 / kChunks;                 // 4 (D = 128) or 8 (D = 64)
+    constexpr int kInst = BKV / kRowsPerInst;                  // 16 or 8 per tile
+    const int rl = lane / kChunks;
+    const int pc = lane % kChunks;
+#pragma unroll
+    for (int i = 0; i < kInst / 4; ++i) {
+        const int inst = wave + 4 * i;
+        const int row = inst * kRowsPerInst + rl;              // 0..63
+        int key = kv0 + row;
+        key = key < S ? key : S - 1;
+        const int chunk = pc ^ (row & 7);
+        const uint16_t* g = Kp + (int64_t)key * tok_stride + chunk * 8;
+        __builtin_amdgcn_global_load_lds((gptr_t)g, (lptr_t)(lds_k + inst * 1024), 16, 0, 0);
+    }
+}
+
+// V tile: 16-byte global loads into registers (thread t: key t % 64, chunks t/64 + 4*i) ...
+template <int D>
+__device__ __forceinline__ void load_v_regs(const uint16_t* __restrict__ Vp, int64_t tok_stride,
+                                            int kv0, int S, uint4 (&regs)[D / 32]) {
+    int key = kv0 + (threadIdx.x & 63);
+    key = key < S ? key : S - 1;
+    const int c0 = threadIdx.x >> 6;
+#pragma unroll
+    for (int i = 0; i < D / 32; ++i) {
+        const int chunk = c0 + 4 * i;
+        regs[i] = *reinterpret_cast<const uint4*>(Vp + (int64_t)key * tok_stride + chunk * 8);
+    }
+}
+
+// ... and from registers to LDS transposed: V^T[dv][key].
+template <int D>
+__device__ __forceinline__ void store_v_transposed(const uint4 (&regs)[D / 32], char* lds_v) {
+    const int key = threadIdx.x & 63;
+    const int c0 = threadIdx.x >> 6;
+#pragma unroll
+    for (int i = 0; i < D / 32; ++i) {
+        const int dv0 = (c0 + 4 * i) * 8;
+        const uint32_t w[4] = {regs[i].x, regs[i].y, regs[i].z, regs[i].w};
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const uint16_t v = (uint16_t)(w[e >> 1] >> ((e & 1) * 16));
+            *reinterpret_cast<uint16_t*>(lds_v + (dv0 + e) * Tile<D>::kVPitch + key * 2) = v;
+        }
+    }
+}
+
+template <int D, int NQ, int MODE>
+__global__ __launch_bounds__(256) void attn_bf16_kernel(const AttnParams p) {
+    using T = Tile<D>;
+    constexpr int KS = D / 16;    // k-steps of the first product
+    constexpr int DVT = D / 32;   // dv tiles of the second product
+    extern __shared__ __attribute__((aligned(1024))) char lds[];
+
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int ql = lane & 31;     // query column within a 32-wide tile
+    const int half = lane >> 5;
+    const int S = p.S;
+    const int b = blockIdx.z, h = blockIdx.y;
+    const int hk = h / (p.H / p.Hkv);
+    // heaviest query blocks first when causal
+    const int qblk = p.causal ? (int)(gridDim.x - 1 - blockIdx.x) : (int)blockIdx.x;
+    const int q0 = qblk * (128 * NQ) + wave * (32 * NQ);
+
+    const uint16_t* Qp = (const uint16_t*)p.Q + b * p.sq[0] + h * p.sq[2];
+    const uint16_t* Kp = (const uint16_t*)p.K + b * p.sk[0] + hk * p.sk[2];
+    const uint16_t* Vp = (const uint16_t*)p.V + b * p.sv[0] + hk * p.sv[2];
+    uint16_t* Op = (uint16_t*)p.O + b * p.so[0] + h * p.so[2];
+
+    // Q fragments (second operand of K Q^T): lane holds query ql, features 16*ks + 8*half .. +7
+    bf16x8 qf[NQ][KS];
+    int qrow[NQ];
+#pragma unroll
+    for (int n = 0; n < NQ; ++n) {
+        int q = q0 + 32 * n + ql;
+        qrow[n] = q;
+        q = q < S ? q : S - 1;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks)
+            qf[n][ks] = *reinterpret_cast<const bf16x8*>(Qp + (int64_t)q * p.sq[1] + 16 * ks + 8 * half);
+    }
+
+    f32x16 o[DVT][NQ];
+#pragma unroll
+    for (int t = 0; t < DVT; ++t)
+#pragma unroll
+        for (int n = 0; n < NQ; ++n)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) o[t][n][e] = 0.0f;
+    float m_run[NQ], l_run[NQ];
+#pragma unroll
+    for (int n = 0; n < NQ; ++n) { m_run[n] = -INFINITY; l_run[n] = 0.0f; }
+
+    // number of KV tiles this workgroup walks (causal: up to its last query row)
+    const int q_last = min(qblk * (128 * NQ) + 128 * NQ, S) - 1;
+    const int kv_end = p.causal ? min(S, q_last + 1) : S;
+    const int ntiles = (kv_end + BKV - 1) / BKV;
+
+    // mask words: row-major [b][h][row][W]
+    const uint64_t* mrow[NQ];
+    uint2 mword[NQ], mnext[NQ];
+    if (MODE == MODE_MASK) {
+#pragma unroll
+        for (int n = 0; n < NQ; ++n) {
+            const int q = qrow[n] < S ? qrow[n] : S - 1;
+            mrow[n] = p.mask + (((int64_t)b * p.H + h) * S + q) * p.W;
+            mnext[n] = *reinterpret_cast<const uint2*>(mrow[n]);
+        }
+    }
+    // fused: cached keep words of 4 consecutive KV tiles for this lane's query rows
+    uint32_t fw[NQ][8] = {};
+
+    uint4 vregs[D / 32];
+    load_k_tile<D>(Kp, p.sk[1], 0, S, lds, wave, lane);
+    load_v_regs<D>(Vp, p.sv[1], 0, S, vregs);
+    store_v_transposed<D>(vregs, lds + T::kKBytes);
+
+    const int kswz = ql & 7;
+
+    for (int jt = 0; jt < ntiles; ++jt) {
+        const int kv0 = jt * BKV;
+        char* cur = lds + (jt & 1) * T::kStage;
+        char* nxt = lds + ((jt + 1) & 1) * T::kStage;
+        __builtin_amdgcn_s_waitcnt(0x0070);   // vmcnt(0) lgkmcnt(0): own K loads and V^T writes done
+        __syncthreads();
+        const bool has_next = jt + 1 < ntiles;
+        if (has_next) {
+            load_k_tile<D>(Kp, p.sk[1], kv0 + BKV, S, nxt, wave, lane);
+            load_v_regs<D>(Vp, p.sv[1], kv0 + BKV, S, vregs);
+        }
+        if (MODE == MODE_MASK) {
+#pragma unroll
+            for (int n = 0; n < NQ; ++n) {
+                mword[n] = mnext[n];
+                if (has_next) mnext[n] = *reinterpret_cast<const uint2*>(mrow[n] + (jt + 1));
+            }
+        }
+        if (MODE == MODE_FUSED) {
+            // Every 4th tile: regenerate the keep words of columns [256*(jt/4), +256) for the
+            // wave's rows.  Word w = row*W + cb sits in Philox group w/4; when W % 4 == 0 a
+            // group is exactly the 4 words of one row that the next 4 tiles need.  Otherwise a
+            // group is recomputed per tile and only word w%4 is used.
+            const bool aligned4 = (p.W & 3) == 0;
+            if (!aligned4 || (jt & 3) == 0) {
+#pragma unroll
+                for (int n = 0; n < NQ; ++n) {
+                    for (int r = 0; r < 32; ++r) {
+                        int row = q0 + 32 * n + r;
+                        row = row < S ? row : S - 1;
+                        const uint64_t w = (((uint64_t)b * p.H + h) * S + row) * p.W + (uint64_t)jt;
+                        const uint64_t base = p.offset + 64u * (w >> 2);
+                        uint64_t bal[4];
+                        if ((uint32_t)base <= 0xFFFFFFFFu - 63u)
+                            philox_group_ballots<10, false>(base, lane, p.k0, p.k1, p.t_minus_1, bal);
+                        else
+                            philox_group_ballots<10, true>(base, lane, p.k0, p.k1, p.t_minus_1, bal);
+                        if (aligned4) {
+#pragma unroll
+                            for (int c = 0; c < 4; ++c) {
+                                fw[n][2 * c] = write_lane((uint32_t)bal[c], r, fw[n][2 * c]);
+                                fw[n][2 * c] = write_lane((uint32_t)bal[c], r + 32, fw[n][2 * c]);
+                                fw[n][2 * c + 1] = write_lane((uint32_t)(bal[c] >> 32), r, fw[n][2 * c + 1]);
+                                fw[n][2 * c + 1] = write_lane((uint32_t)(bal[c] >> 32), r + 32, fw[n][2 * c + 1]);
+                            }
+                        } else {
+                            const uint32_t sel = (uint32_t)(w & 3u);
+                            const uint64_t bw = sel == 0 ? bal[0] : sel == 1 ? bal[1] : sel == 2 ? bal[2] : bal[3];
+                            fw[n][0] = write_lane((uint32_t)bw, r, fw[n][0]);
+                            fw[n][0] = write_lane((uint32_t)bw, r + 32, fw[n][0]);
+                            fw[n][1] = write_lane((uint32_t)(bw >> 32), r, fw[n][1]);
+                            fw[n][1] = write_lane((uint32_t)(bw >> 32), r + 32, fw[n][1]);
+                        }
+                    }
+                }
+            }
+#pragma unroll
+            for (int n = 0; n < NQ; ++n) {
+                if (aligned4) {
+                    const int c = jt & 3;
+                    mword[n].x = c == 0 ? fw[n][0] : c == 1 ? fw[n][2] : c == 2 ? fw[n][4] : fw[n][6];
+                    mword[n].y = c == 0 ? fw[n][1] : c == 1 ? fw[n][3] : c == 2 ? fw[n][5] : fw[n][7];
+                } else {
+                    mword[n].x = fw[n][0];
+                    mword[n].y = fw[n][1];
+                }
+            }
+        }
+
+        // ---- S^T = K Q^T for 64 keys x NQ*32 queries
+        f32x16 s[2][NQ];
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int n = 0; n < NQ; ++n)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) s[t][n][e] = 0.0f;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+                const int row = 32 * t + ql;
+                const bf16x8 kf = *reinterpret_cast<const bf16x8*>(
+                    cur + row * T::kKRow + (((2 * ks + half) ^ kswz) << 4));
+#pragma unroll
+                for (int n = 0; n < NQ; ++n)
+                    s[t][n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[n][ks], s[t][n], 0, 0, 0);
+            }
+        }
+
+        // ---- online softmax, dropout, P^T fragments
+        bf16x8 pf[NQ][4];
+        const bool tail = kv0 + BKV > S;
+        const bool diag = p.causal && (kv0 + BKV - 1 > q0);   // some key of the tile may exceed a query
+#pragma unroll
+        for (int n = 0; n < NQ; ++n) {
+            float mx = -INFINITY;
+#pragma unroll
+            for (int t = 0; t < 2; ++t)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    float v = s[t][n][e] * p.scale_log2;
+                    if (tail || diag) {
+                        const int key = kv0 + 32 * t + 8 * (e >> 2) + 4 * half + (e & 3);
+                        const bool ok = key < S && (!p.causal || key <= qrow[n]);
+                        v = ok ? v : -INFINITY;
+                    }
+                    s[t][n][e] = v;
+                    mx = fmaxf(mx, v);
+                }
+            mx = fmaxf(mx, __shfl_xor(mx, 32));
+            const float m_new = fmaxf(m_run[n], mx);
+            const float m_safe = m_new == -INFINITY ? 0.0f : m_new;
+            const float alpha = fast_exp2(m_run[n] - m_safe);
+            m_run[n] = m_new;
+            float sum = 0.0f;
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+                uint32_t bits = 0xFFFFFFFFu;
+                if (MODE != MODE_NONE) bits = (t == 0 ? mword[n].x : mword[n].y) >> (4 * half);
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    float pe = fast_exp2(s[t][n][e] - m_safe);
+                    sum += pe;   // the normaliser counts dropped entries too
+                    if (MODE != MODE_NONE) {
+                        const uint32_t bit = (bits >> (8 * (e >> 2) + (e & 3))) & 1u;
+                        pe = bit ? pe : 0.0f;
+                    }
+                    s[t][n][e] = pe;
+                }
+            }
+            l_run[n] = l_run[n] * alpha + sum;
+#pragma unroll
+            for (int t = 0; t < DVT; ++t)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) o[t][n][e] *= alpha;
+            // k-step u = 2*t + v of the second product takes registers 8*v .. 8*v+7 of tile t
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int t = u >> 1, v8 = (u & 1) * 8;
+                uint32_t w[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) w[e] = pack_bf16x2(s[t][n][v8 + 2 * e], s[t][n][v8 + 2 * e + 1]);
+                pf[n][u] = *reinterpret_cast<bf16x8*>(w);
+            }
+        }
+
+        // ---- O^T += V^T P^T
+        const char* vt = cur + T::kKBytes;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+#pragma unroll
+            for (int t = 0; t < DVT; ++t) {
+                const char* rowp = vt + (32 * t + ql) * T::kVPitch + (16 * u + 4 * half) * 2;
+                const bf16x4 lo = *reinterpret_cast<const bf16x4*>(rowp);
+                const bf16x4 hi = *reinterpret_cast<const bf16x4*>(rowp + 16);
+                const bf16x8 vf = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+#pragma unroll
+                for (int n = 0; n < NQ; ++n)
+                    o[t][n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[n][u], o[t][n], 0, 0, 0);
+            }
+        }
+
+        if (has_next) store_v_transposed<D>(vregs, nxt + T::kKBytes);
+    }
+
+    // ---- normalise, scale kept entries by 1/(1-p), store O (lane: query ql, 4 consecutive dv per e/4)
+#pragma unroll
+    for (int n = 0; n < NQ; ++n) {
+        const float l = l_run[n] + __shfl_xor(l_run[n], 32);
+        const float f = l > 0.0f ? p.inv_keep / l : 0.0f;
+        if (qrow[n] < S) {
+            uint16_t* orow = Op + (int64_t)qrow[n] * p.so[1];
+#pragma unroll
+            for (int t = 0; t < DVT; ++t)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    uint2 v;
+                    v.x = pack_bf16x2(o[t][n][4 * g + 0] * f, o[t][n][4 * g + 1] * f);
+                    v.y = pack_bf16x2(o[t][n][4 * g + 2] * f, o[t][n][4 * g + 3] * f);
+                    *reinterpret_cast<uint2*>(orow + 32 * t + 8 * g + 4 * half) = v;
+                }
+        }
+    }
+}
+
+// ------------------------------------------------------------------ generic kernel
+// One wave per query row, keys in chunks of 256 with an online softmax; any dtype / head
+// dimension up to 256.  Correct for every shape; used for fp32 and odd head dimensions.
+template <typename TT>
+__device__ __forceinline__ float ld(const TT* p);
+template <>
+__device__ __forceinline__ float ld<float>(const float* p) { return *p; }
+template <>
+__device__ __forceinline__ float ld<uint16_t>(const uint16_t* p) { return __uint_as_float((uint32_t)*p << 16); }
+template <typename TT>
+__device__ __forceinline__ void st(TT* p, float v);
+template <>
+__device__ __forceinline__ void st<float>(float* p, float v) { *p = v; }
+template <>
+__device__ __forceinline__ void st<uint16_t>(uint16_t* p, float v) {
+    *p = (uint16_t)(pack_bf16x2(v, 0.0f) & 0xFFFFu);
+}
+
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+    for (int s = 32; s > 0; s >>= 1) v = fmaxf(v, __shfl_xor(v, s));
+    return v;
+}
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int s = 32; s > 0; s >>= 1) v += __shfl_xor(v, s);
+    return v;
+}
+
+template <typename TT, int MODE>
+__global__ __launch_bounds__(256) void attn_generic_kernel(const AttnParams p) {
+    __shared__ float qs[4][256];
+    __shared__ float ps[4][256];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int row = blockIdx.x * 4 + wave;
+    const int b = blockIdx.z, h = blockIdx.y;
+    const int hk = h / (p.H / p.Hkv);
+    const int S = p.S, d = p.d;
+    if (row >= S) return;   // whole wave leaves; no block-wide barrier below
+    const TT* Qp = (const TT*)p.Q + b * p.sq[0] + h * p.sq[2] + (int64_t)row * p.sq[1];
+    const TT* Kp = (const TT*)p.K + b * p.sk[0] + hk * p.sk[2];
+    const TT* Vp = (const TT*)p.V + b * p.sv[0] + hk * p.sv[2];
+    TT* Op = (TT*)p.O + b * p.so[0] + h * p.so[2] + (int64_t)row * p.so[1];
+    for (int t = lane; t < d; t += 64) qs[wave][t] = ld(Qp + t);
+    __builtin_amdgcn_wave_barrier();
+    float acc[4] = {0.f, 0.f, 0.f, 0.f};   // output features lane, lane+64, lane+128, lane+192
+    float m_run = -INFINITY, l_run = 0.0f;
+    const int kv_end = p.causal ? row + 1 : S;
+    const uint64_t wrow = (((uint64_t)b * p.H + h) * S + row) * p.W;
+    for (int c0 = 0; c0 < kv_end; c0 += 256) {
+        float sc[4];
+        float mx = -INFINITY;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int key = c0 + lane + 64 * i;
+            float v = -INFINITY;
+            if (key < kv_end) {
+                const TT* kr = Kp + (int64_t)key * p.sk[1];
+                float dot = 0.0f;
+                for (int t = 0; t < d; ++t) dot = __builtin_fmaf(qs[wave][t], ld(kr + t), dot);
+                v = dot * p.scale_log2;
+            }
+            sc[i] = v;
+            mx = fmaxf(mx, v);
+        }
+        mx = wave_max(mx);
+        const float m_new = fmaxf(m_run, mx);
+        const float alpha = fast_exp2(m_run - m_new);   // chunk 0 always has an admissible key
+        m_run = m_new;
+        float sum = 0.0f;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int key = c0 + lane + 64 * i;
+            float pe = 0.0f;
+            if (key < kv_end) {
+                pe = fast_exp2(sc[i] - m_new);
+                sum += pe;
+                bool keep = true;
+                if (MODE == MODE_MASK) {
+                    keep = (p.mask[wrow + (key >> 6)] >> (key & 63)) & 1ull;
+                } else if (MODE == MODE_FUSED) {
+                    const uint64_t w = wrow + (uint64_t)(key >> 6);
+                    const uint64_t ncall = p.offset + 64u * (w >> 2) + (uint64_t)(key & 63);
+                    uint32_t x[4];
+                    philox4x32<10>((uint32_t)ncall, (uint32_t)(ncall >> 32), 0u, 0u, p.k0, p.k1, x);
+                    const uint32_t sel = (uint32_t)(w & 3u);
+                    const uint32_t xv = sel == 0 ? x[0] : sel == 1 ? x[1] : sel == 2 ? x[2] : x[3];
+                    keep = xv <= p.t_minus_1;
+                }
+                pe = keep ? pe : 0.0f;
+            }
+            ps[wave][lane + 64 * i] = pe;
+        }
+        l_run = l_run * alpha + wave_sum(sum);
+        __builtin_amdgcn_wave_barrier();
+        const int nkeys = min(256, kv_end - c0);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int t = lane + 64 * j;
+            if (t < d) {
+                float a = acc[j] * alpha;
+                for (int kk = 0; kk < nkeys; ++kk)
+                    a = __builtin_fmaf(ps[wave][kk], ld(Vp + (int64_t)(c0 + kk) * p.sv[1] + t), a);
+                acc[j] = a;
+            }
+        }
+        __builtin_amdgcn_wave_barrier();
+    }
+    const float f = l_run > 0.0f ? p.inv_keep / l_run : 0.0f;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int t = lane + 64 * j;
+        if (t < d) st(Op + t, acc[j] * f);
+    }
+}
+
+template <int D, int NQ>
+int launch_bf16(const AttnParams& prm, int mode, hipStream_t stream) {
+    const int bq = 128 * NQ;
+    const dim3 grid((unsigned)((prm.S + bq - 1) / bq), (unsigned)prm.H, (unsigned)prm.B), block(256);
+    const int lds_bytes = 2 * Tile<D>::kStage;
+    void (*kern)(const AttnParams) = mode == MODE_NONE   ? attn_bf16_kernel<D, NQ, MODE_NONE>
+                                     : mode == MODE_MASK ? attn_bf16_kernel<D, NQ, MODE_MASK>
+                                                         : attn_bf16_kernel<D, NQ, MODE_FUSED>;
+    ROV_HIP_TRY(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    lds_bytes));
+    hipLaunchKernelGGL(kern, grid, block, lds_bytes, stream, prm);
+    ROV_LAUNCH_CHECK();
+    return ROV_OK;
+}
+
+template <typename TT>
+int launch_generic(const AttnParams& prm, int mode, hipStream_t stream) {
+    const dim3 grid((unsigned)((prm.S + 3) / 4), (unsigned)prm.H, (unsigned)prm.B), block(256);
+    if (mode == MODE_NONE)
+        hipLaunchKernelGGL((attn_generic_kernel<TT, MODE_NONE>), grid, block, 0, stream, prm);
+    else if (mode == MODE_MASK)
+        hipLaunchKernelGGL((attn_generic_kernel<TT, MODE_MASK>), grid, block, 0, stream, prm);
+    else
+        hipLaunchKernelGGL((attn_generic_kernel<TT, MODE_FUSED>), grid, block, 0, stream, prm);
+    ROV_LAUNCH_CHECK();
+    return ROV_OK;
+}
+
+}  // namespace
+
+int launch_attention(const void* Q, const void* K, const void* V, void* O, int B, int H, int Hkv,
+                     int S, int d, const int64_t strides[12], int dtype, int causal, float p,
+                     const uint64_t* mask, uint64_t seed, uint64_t offset, hipStream_t stream) {
+    if (Q == nullptr || K == nullptr || V == nullptr || O == nullptr || strides == nullptr)
+        return ROV_ERR_INVALID;
+    if (B <= 0 || H <= 0 || Hkv <= 0 || S <= 0 || d <= 0 || (H % Hkv) != 0) return ROV_ERR_INVALID;
+    if (dtype != ROV_F32 && dtype != ROV_BF16) return dtype == ROV_FP8_E4M3 ? ROV_ERR_UNSUPPORTED : ROV_ERR_INVALID;
+    uint32_t tm1 = 0xFFFFFFFFu;
+    if (!keep_threshold_minus_1(p, &tm1)) return ROV_ERR_INVALID;
+    if (B > 65535 || H > 65535) return ROV_ERR_UNSUPPORTED;
+    if (d > 256) return ROV_ERR_UNSUPPORTED;
+    if (mask != nullptr && !aligned(mask, 8)) return ROV_ERR_INVALID;
+
+    AttnParams prm;
+    prm.Q = Q; prm.K = K; prm.V = V; prm.O = O; prm.mask = mask;
+    for (int i = 0; i < 3; ++i) {
+        prm.sq[i] = strides[i]; prm.sk[i] = strides[3 + i];
+        prm.sv[i] = strides[6 + i]; prm.so[i] = strides[9 + i];
+    }
+    prm.B = B; prm.H = H; prm.Hkv = Hkv; prm.S = S; prm.d = d;
+    prm.W = (S + 63) / 64;
+    prm.causal = causal != 0;
+    prm.scale_log2 = 1.4426950408889634f / sqrtf((float)d);
+    prm.inv_keep = p > 0.0f ? 1.0f / (1.0f - p) : 1.0f;
+    prm.offset = offset;
+    prm.k0 = (uint32_t)seed; prm.k1 = (uint32_t)(seed >> 32);
+    prm.t_minus_1 = tm1;
+    const int mode = p == 0.0f ? MODE_NONE : (mask != nullptr ? MODE_MASK : MODE_FUSED);
+
+    if (dtype == ROV_BF16 && (d == 64 || d == 128)) {
+        // 16-byte vector access needs 8-element alignment of every row start
+        bool ok = aligned(Q, 16) && aligned(K, 16) && aligned(V, 16) && aligned(O, 8);
+        for (int i = 0; i < 12; ++i) ok = ok && (strides[i] % 8) == 0;
+        if (ok) {
+            if (d == 128) return launch_bf16<128, 2>(prm, mode, stream);
+            return launch_bf16<64, 2>(prm, mode, stream);
+        }
+    }
+    if (dtype == ROV_BF16) return launch_generic<uint16_t>(prm, mode, stream);
+    return launch_generic<float>(prm, mode, stream);
+}
+
 }  // namespace rov
+
 extern "C" int rov_attention_fwd_dropout(const void* Q, const void* K, const void* V, void* O, int B,
                                          int H, int Hkv, int S, int d, const int64_t strides[12],
                                          int dtype, int causal, float p, const uint64_t* mask,

@@ -176,14 +176,26 @@ int rov_layer_step(int schedule, const rov_gemm_desc *gemms, int n_gemms, const 
  * embedding, grouped-query attention, SwiGLU):
  *   h1 = RMSNorm(x)*norm1; [q|k|v] = h1 Wqkv^T; RoPE(q,k); a = attention_dropout(q,k,v);
  *   x2 = x + a Wo^T; h2 = RMSNorm(x2)*norm2; y = x2 + (silu(h2 Wg^T) * (h2 Wu^T)) Wd^T.
- * Weights are row-major [out_features, in_features], dtype = cfg->dtype (bf16).
- * x, y: [B, S, hidden].  The mask used by this block's attention is generated
- * from (seed, offset); with ROV_SCHED_OVERLAP it is generated on side_stream
- * while the block's first GEMM runs, and when `next_mask` is non-NULL the mask
- * of the following layer (offset + rov_mask_philox_calls) is generated into it
- * beside this block's remaining GEMMs (paper Sec. 1: RNG hidden behind the GEMM
- * layers between the previous and the current attention).
- * workspace: device scratch of at least rov_block_workspace_bytes() bytes. */
+ * RoPE rotates the adjacent pair (2t, 2t+1) of token position s by s*theta^(-2t/d).
+ * Weights are row-major [out_features, in_features], bf16 (cfg->dtype must be
+ * ROV_BF16; d must be 64 or 128; hidden and ffn multiples of 64).  x, y: bf16
+ * [B, S, hidden].
+ *
+ * This block's attention uses the mask of (seed, offset), p = cfg->p:
+ *   SEQUENTIAL  mask_ready == 0: the RNG kernel runs on main_stream between the
+ *               QKV GEMM and attention.  mask_ready != 0: `mask` already holds it.
+ *   FUSED       no mask buffer; attention generates the bits itself.
+ *   OVERLAP     mask_ready == 0: the RNG kernel runs on side_stream beside the QKV
+ *               GEMM and is joined before attention.  mask_ready != 0: `mask`
+ *               already holds it (written during the previous block).  If
+ *               next_mask != NULL, the mask of the following layer (offset +
+ *               rov_mask_philox_calls(B,H,S)) is generated into it on side_stream
+ *               beside this block's PROJ / FC1 / FC2 GEMMs and joined at the end
+ *               (paper Sec. 1: RNG hidden behind the GEMM layers between the
+ *               previous and the current attention).  next_mask must be NULL for
+ *               the other schedules and must differ from mask.
+ * workspace: device scratch, 256-byte aligned, at least
+ * rov_block_workspace_bytes() bytes; contents undefined afterwards. */
 typedef struct rov_block_cfg {
     int H, Hkv, d, hidden, ffn;
     int dtype;

@@ -216,3 +216,29 @@ def layer_step(schedule, gemm_descs, attn_desc, seed, offset, mask, main_stream,
     _check(load().rov_layer_step(int(schedule), arr, len(gemm_descs), ctypes.byref(attn_desc),
                                  seed & (2**64 - 1), offset & (2**64 - 1), mptr,
                                  _stream_ptr(main_stream), _stream_ptr(side_stream)), "rov_layer_step")
+
+
+def block_workspace_bytes(cfg, B, S, schedule):
+    return int(load().rov_block_workspace_bytes(ctypes.byref(cfg), B, S, int(schedule)))
+
+
+def make_block_cfg(H, Hkv, d, hidden, ffn, p, causal=False, eps=1e-5, rope_theta=500000.0, dtype=BF16):
+    return BlockCfg(H, Hkv, d, hidden, ffn, dtype, int(bool(causal)), float(p), float(eps), float(rope_theta))
+
+
+def make_block_weights(w):
+    """w: dict of device tensors norm1, norm2, wqkv, wo, wg, wu, wd."""
+    return BlockWeights(*[w[n].data_ptr() for n in ("norm1", "norm2", "wqkv", "wo", "wg", "wu", "wd")])
+
+
+def block_forward(weights, x, y, cfg, schedule, seed, offset, mask, workspace, main_stream, side_stream,
+                  mask_ready=False, next_mask=None):
+    B, S, _ = x.shape
+    mptr = ctypes.c_void_p(mask.data_ptr()) if mask is not None else ctypes.c_void_p(0)
+    nptr = ctypes.c_void_p(next_mask.data_ptr()) if next_mask is not None else ctypes.c_void_p(0)
+    _check(load().rov_block_forward(ctypes.byref(weights), ctypes.c_void_p(x.data_ptr()),
+                                    ctypes.c_void_p(y.data_ptr()), B, S, ctypes.byref(cfg), int(schedule),
+                                    seed & (2**64 - 1), offset & (2**64 - 1), int(bool(mask_ready)), mptr, nptr,
+                                    ctypes.c_void_p(workspace.data_ptr()), workspace.numel() * workspace.element_size(),
+                                    _stream_ptr(main_stream), _stream_ptr(side_stream)), "rov_block_forward")
+    return y

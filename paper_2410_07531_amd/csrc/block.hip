@@ -1,0 +1,151 @@
+// Row-wise glue of the transformer block (paper Fig. 2: the LayerNorm and
+// element-wise layers "require minimal runtime"; here RMSNorm, rotary embedding
+// and the SwiGLU product of a Llama-style block).  All bf16 in / bf16 out with
+// fp32 arithmetic, 16-byte vector accesses, one pass over the data each.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "rov_internal.h"
+
+namespace rov {
+namespace {
+
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ uint32_t pack2(float lo, float hi) {
+    f32x2 v = {lo, hi};
+    bf16x2 h = __builtin_convertvector(v, bf16x2);
+    return *reinterpret_cast<uint32_t*>(&h);
+}
+__device__ __forceinline__ float lo_f(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float hi_f(uint32_t w) { return __uint_as_float(w & 0xFFFF0000u); }
+
+// y[row] = x[row] / sqrt(mean(x[row]^2) + eps) * weight ; one workgroup per row, n % 8 == 0.
+__global__ __launch_bounds__(256) void rmsnorm_kernel(const uint16_t* __restrict__ x,
+                                                      const uint16_t* __restrict__ weight,
+                                                      uint16_t* __restrict__ y, int n, float eps) {
+    __shared__ float red[4];
+    const uint16_t* xr = x + (size_t)blockIdx.x * n;
+    uint16_t* yr = y + (size_t)blockIdx.x * n;
+    float ss = 0.0f;
+    for (int c = threadIdx.x * 8; c < n; c += 256 * 8) {
+        const uint4 v = *reinterpret_cast<const uint4*>(xr + c);
+        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const float a = lo_f(w[i]), b = hi_f(w[i]);
+            ss = __builtin_fmaf(a, a, ss);
+            ss = __builtin_fmaf(b, b, ss);
+        }
+    }
+#pragma unroll
+    for (int s = 32; s > 0; s >>= 1) ss += __shfl_xor(ss, s);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = ss;
+    __syncthreads();
+    const float tot = red[0] + red[1] + red[2] + red[3];
+    const float inv = 1.0f / sqrtf(tot / (float)n + eps);
+    for (int c = threadIdx.x * 8; c < n; c += 256 * 8) {
+        const uint4 v = *reinterpret_cast<const uint4*>(xr + c);
+        const uint4 g = *reinterpret_cast<const uint4*>(weight + c);
+        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+        const uint32_t gw[4] = {g.x, g.y, g.z, g.w};
+        uint32_t o[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            o[i] = pack2(lo_f(w[i]) * inv * lo_f(gw[i]), hi_f(w[i]) * inv * hi_f(gw[i]));
+        *reinterpret_cast<uint4*>(yr + c) = make_uint4(o[0], o[1], o[2], o[3]);
+    }
+}
+
+// Rotary embedding in place on the first `nheads` heads of each token row of a
+// [tokens, row_elems] buffer: pair (2t, 2t+1) of token position s is rotated by
+// s * theta^(-2t/d).  The angle is formed and reduced modulo 2*pi in double so
+// that long sequences keep fp32-accurate sines.
+__global__ __launch_bounds__(256) void rope_kernel(uint16_t* __restrict__ buf, int64_t row_elems,
+                                                   int S, int nheads, int d, double log2_theta,
+                                                   int64_t total_quads) {
+    // one thread handles 4 pairs (8 elements, 16 bytes)
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= total_quads) return;
+    const int quads_per_head = d / 8;
+    const int qd = (int)(idx % quads_per_head);
+    const int64_t rest = idx / quads_per_head;
+    const int head = (int)(rest % nheads);
+    const int64_t token = rest / nheads;
+    const int pos = (int)(token % S);
+    uint16_t* ptr = buf + token * row_elems + (int64_t)head * d + qd * 8;
+    const uint4 v = *reinterpret_cast<const uint4*>(ptr);
+    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+    uint32_t o[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int t = qd * 4 + i;
+        const double inv_freq = exp2(-2.0 * (double)t / (double)d * log2_theta);
+        double ang = (double)pos * inv_freq;
+        ang -= 6.283185307179586476925 * rint(ang * 0.15915494309189533577);
+        float sn, cs;
+        sincosf((float)ang, &sn, &cs);
+        const float xe = lo_f(w[i]), xo = hi_f(w[i]);
+        o[i] = pack2(xe * cs - xo * sn, xe * sn + xo * cs);
+    }
+    *reinterpret_cast<uint4*>(ptr) = make_uint4(o[0], o[1], o[2], o[3]);
+}
+
+// act = silu(g) * u, element-wise; n8 = number of 8-element groups.
+__global__ __launch_bounds__(256) void swiglu_kernel(const uint16_t* __restrict__ g,
+                                                     const uint16_t* __restrict__ u,
+                                                     uint16_t* __restrict__ act, int64_t n8) {
+    const int64_t stride = (int64_t)gridDim.x * 256;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n8; i += stride) {
+        const uint4 gv = reinterpret_cast<const uint4*>(g)[i];
+        const uint4 uv = reinterpret_cast<const uint4*>(u)[i];
+        const uint32_t gw[4] = {gv.x, gv.y, gv.z, gv.w};
+        const uint32_t uw[4] = {uv.x, uv.y, uv.z, uv.w};
+        uint32_t o[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const float a = lo_f(gw[k]), b = hi_f(gw[k]);
+            const float sa = a / (1.0f + __expf(-a)), sb = b / (1.0f + __expf(-b));
+            o[k] = pack2(sa * lo_f(uw[k]), sb * hi_f(uw[k]));
+        }
+        reinterpret_cast<uint4*>(act)[i] = make_uint4(o[0], o[1], o[2], o[3]);
+    }
+}
+
+}  // namespace
+
+int launch_rmsnorm(const void* x, const void* weight, void* y, int64_t rows, int n, float eps,
+                   hipStream_t stream) {
+    if (rows <= 0 || n <= 0 || (n % 8) != 0 || rows > 0x7FFFFFFF) return ROV_ERR_UNSUPPORTED;
+    hipLaunchKernelGGL(rmsnorm_kernel, dim3((unsigned)rows), dim3(256), 0, stream,
+                       (const uint16_t*)x, (const uint16_t*)weight, (uint16_t*)y, n, eps);
+    ROV_LAUNCH_CHECK();
+    return ROV_OK;
+}
+
+int launch_rope(void* buf, int64_t tokens, int64_t row_elems, int S, int nheads, int d, float theta,
+                hipStream_t stream) {
+    if (tokens <= 0 || nheads <= 0 || (d % 8) != 0 || theta <= 0.0f) return ROV_ERR_UNSUPPORTED;
+    const int64_t quads = tokens * nheads * (d / 8);
+    const int64_t blocks = (quads + 255) / 256;
+    if (blocks > 0x7FFFFFFF) return ROV_ERR_UNSUPPORTED;
+    hipLaunchKernelGGL(rope_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, (uint16_t*)buf,
+                       row_elems, S, nheads, d, log2((double)theta), quads);
+    ROV_LAUNCH_CHECK();
+    return ROV_OK;
+}
+
+int launch_swiglu(const void* g, const void* u, void* act, int64_t n, hipStream_t stream) {
+    if (n <= 0 || (n % 8) != 0) return ROV_ERR_UNSUPPORTED;
+    const int64_t n8 = n / 8;
+    int64_t blocks = (n8 + 255) / 256;
+    const int64_t cap = (int64_t)device_cu_count() * 32;
+    if (blocks > cap) blocks = cap;
+    hipLaunchKernelGGL(swiglu_kernel, dim3((unsigned)blocks), dim3(256), 0, stream,
+                       (const uint16_t*)g, (const uint16_t*)u, (uint16_t*)act, n8);
+    ROV_LAUNCH_CHECK();
+    return ROV_OK;
+}
+
+}  // namespace rov

@@ -153,8 +153,9 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
 
 __global__ __launch_bounds__(256, 1) void gemm_bf16_tn_kernel(const uint16_t* __restrict__ A,
                                                               const uint16_t* __restrict__ Wt,
-                                                              uint16_t* __restrict__ C, int M, int N,
-                                                              int K, float alpha, int tiles_m,
+                                                              uint16_t* __restrict__ C,
+                                                              const uint16_t* __restrict__ R, int M,
+                                                              int N, int K, float alpha, int tiles_m,
                                                               int tiles_n) {
     extern __shared__ __attribute__((aligned(1024))) char lds[];
     const int lane = threadIdx.x & 63;
@@ -262,10 +263,23 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_tn_kernel(const uint16_t* __
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
                 const int n = n0 + wn * 128 + j * 32 + q * 8 + nsub;
-                uint2 v;
-                v.x = pack_bf16x2(alpha * acc_read(acc[j][i][q * 4 + 0]), alpha * acc_read(acc[j][i][q * 4 + 1]));
-                v.y = pack_bf16x2(alpha * acc_read(acc[j][i][q * 4 + 2]), alpha * acc_read(acc[j][i][q * 4 + 3]));
-                if (m < M && n < N) *reinterpret_cast<uint2*>(C + (size_t)m * N + n) = v;
+                float c0 = alpha * acc_read(acc[j][i][q * 4 + 0]);
+                float c1 = alpha * acc_read(acc[j][i][q * 4 + 1]);
+                float c2 = alpha * acc_read(acc[j][i][q * 4 + 2]);
+                float c3 = alpha * acc_read(acc[j][i][q * 4 + 3]);
+                if (m < M && n < N) {
+                    if (R != nullptr) {   // fused residual add (wave-uniform branch)
+                        const uint2 r = *reinterpret_cast<const uint2*>(R + (size_t)m * N + n);
+                        c0 += __uint_as_float(r.x << 16);
+                        c1 += __uint_as_float(r.x & 0xFFFF0000u);
+                        c2 += __uint_as_float(r.y << 16);
+                        c3 += __uint_as_float(r.y & 0xFFFF0000u);
+                    }
+                    uint2 v;
+                    v.x = pack_bf16x2(c0, c1);
+                    v.y = pack_bf16x2(c2, c3);
+                    *reinterpret_cast<uint2*>(C + (size_t)m * N + n) = v;
+                }
             }
         }
     }
@@ -275,6 +289,11 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_tn_kernel(const uint16_t* __
 
 int launch_gemm(const void* A, const void* Bm, void* C, int M, int N, int K, int dtype, int transB,
                 float scaleA, float scaleB, hipStream_t stream) {
+    return launch_gemm_residual(A, Bm, C, nullptr, M, N, K, dtype, transB, scaleA, scaleB, stream);
+}
+
+int launch_gemm_residual(const void* A, const void* Bm, void* C, const void* R, int M, int N, int K,
+                         int dtype, int transB, float scaleA, float scaleB, hipStream_t stream) {
     if (A == nullptr || Bm == nullptr || C == nullptr || M <= 0 || N <= 0 || K <= 0)
         return ROV_ERR_INVALID;
     if (!aligned(A, 16) || !aligned(Bm, 16) || !aligned(C, 16)) return ROV_ERR_INVALID;
@@ -295,12 +314,13 @@ int launch_gemm(const void* A, const void* Bm, void* C, int M, int N, int K, int
             attr_set = true;
         }
         hipLaunchKernelGGL(gemm_bf16_tn_kernel, dim3((unsigned)T), dim3(256), 2 * kStageBytes, stream,
-                           (const uint16_t*)A, (const uint16_t*)Bm, (uint16_t*)C, M, N, K, alpha,
-                           tiles_m, tiles_n);
+                           (const uint16_t*)A, (const uint16_t*)Bm, (uint16_t*)C, (const uint16_t*)R,
+                           M, N, K, alpha, tiles_m, tiles_n);
         ROV_LAUNCH_CHECK();
         return ROV_OK;
     }
 
+    if (R != nullptr) return ROV_ERR_UNSUPPORTED;   // the residual epilogue exists on the MFMA path only
     const dim3 grid((unsigned)((N + 63) / 64), (unsigned)((M + 63) / 64)), block(256);
     if (grid.y > 65535u) return ROV_ERR_UNSUPPORTED;
     if (dtype == ROV_F32) {

@@ -1,12 +1,272 @@
-// Schedules (placeholder).
+// The three schedules of the paper's silicon experiment (Sec. 6.1) and the
+// transformer-block forward built on them.
+//
+//   sequential: GEMM(s) -> RNG kernel -> attention(mask), one stream;
+//   fused:      GEMM(s) -> attention with in-kernel Philox, one stream;
+//   overlap:    RNG kernel on a side stream while the GEMM(s) run on the main
+//               stream; attention(mask) on the main stream after both.
+//
+// Streams and events only: every kernel is launched by the launchers of the
+// other translation units.  Two events (fork, join) per process are reused by
+// every call; a stream-wait captures the event's state at the time of the call,
+// so re-recording them for the next call is safe.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <mutex>
+
 #include "rov_internal.h"
-extern "C" int rov_layer_step(int, const rov_gemm_desc*, int, const rov_attn_desc*, uint64_t,
-                              uint64_t, uint64_t*, void*, void*) {
-    return ROV_ERR_UNSUPPORTED;
+
+namespace rov {
+namespace {
+
+struct Events {
+    hipEvent_t fork = nullptr, join = nullptr;
+    bool ok = false;
+};
+
+int get_events(Events** out) {
+    static Events ev;
+    static std::mutex mu;
+    std::lock_guard<std::mutex> lock(mu);
+    if (!ev.ok) {
+        ROV_HIP_TRY(hipEventCreateWithFlags(&ev.fork, hipEventDisableTiming));
+        ROV_HIP_TRY(hipEventCreateWithFlags(&ev.join, hipEventDisableTiming));
+        ev.ok = true;
+    }
+    *out = &ev;
+    return ROV_OK;
 }
-extern "C" size_t rov_block_workspace_bytes(const rov_block_cfg*, int, int, int) { return 0; }
-extern "C" int rov_block_forward(const rov_block_weights*, const void*, void*, int, int,
-                                 const rov_block_cfg*, int, uint64_t, uint64_t, int, uint64_t*,
-                                 uint64_t*, void*, size_t, void*, void*) {
-    return ROV_ERR_UNSUPPORTED;
+
+bool valid_schedule(int s) {
+    return s == ROV_SCHED_SEQUENTIAL || s == ROV_SCHED_FUSED || s == ROV_SCHED_OVERLAP;
+}
+
+int check_gemm_desc(const rov_gemm_desc& g) {
+    if (g.A == nullptr || g.Bm == nullptr || g.C == nullptr || g.M <= 0 || g.N <= 0 || g.K <= 0)
+        return ROV_ERR_INVALID;
+    if (!aligned(g.A, 16) || !aligned(g.Bm, 16) || !aligned(g.C, 16)) return ROV_ERR_INVALID;
+    if (g.dtype != ROV_F32 && g.dtype != ROV_BF16)
+        return g.dtype == ROV_FP8_E4M3 ? ROV_ERR_UNSUPPORTED : ROV_ERR_INVALID;
+    return ROV_OK;
+}
+
+int check_attn_desc(const rov_attn_desc& a) {
+    if (a.Q == nullptr || a.K == nullptr || a.V == nullptr || a.O == nullptr) return ROV_ERR_INVALID;
+    if (a.B <= 0 || a.H <= 0 || a.Hkv <= 0 || a.S <= 0 || a.d <= 0 || (a.H % a.Hkv) != 0)
+        return ROV_ERR_INVALID;
+    if (a.dtype != ROV_F32 && a.dtype != ROV_BF16)
+        return a.dtype == ROV_FP8_E4M3 ? ROV_ERR_UNSUPPORTED : ROV_ERR_INVALID;
+    if (!(a.p >= 0.0f) || !(a.p < 1.0f)) return ROV_ERR_INVALID;
+    if (a.d > 256 || a.B > 65535 || a.H > 65535) return ROV_ERR_UNSUPPORTED;
+    return ROV_OK;
+}
+
+size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+struct BlockLayout {
+    size_t h, qkv, att, x2, g, u, total;
+};
+
+bool block_layout(const rov_block_cfg* c, int B, int S, BlockLayout* L) {
+    if (c == nullptr || B <= 0 || S <= 0 || c->H <= 0 || c->Hkv <= 0 || c->d <= 0 ||
+        c->hidden <= 0 || c->ffn <= 0)
+        return false;
+    const size_t T = (size_t)B * (size_t)S;
+    size_t off = 0;
+    auto take = [&](size_t elems) {
+        const size_t at = off;
+        off = align_up(off + elems * 2, 256);
+        return at;
+    };
+    L->h = take(T * c->hidden);
+    L->qkv = take(T * (size_t)(c->H + 2 * c->Hkv) * c->d);
+    L->att = take(T * (size_t)c->H * c->d);
+    L->x2 = take(T * c->hidden);
+    L->g = take(T * c->ffn);
+    L->u = take(T * c->ffn);
+    L->total = off;
+    return true;
+}
+
+}  // namespace
+}  // namespace rov
+
+extern "C" int rov_layer_step(int schedule, const rov_gemm_desc* gemms, int n_gemms,
+                              const rov_attn_desc* attn, uint64_t seed, uint64_t offset,
+                              uint64_t* mask, void* main_stream, void* side_stream) {
+    using namespace rov;
+    if (!valid_schedule(schedule) || attn == nullptr || n_gemms < 0 || (n_gemms > 0 && gemms == nullptr))
+        return ROV_ERR_INVALID;
+    for (int i = 0; i < n_gemms; ++i) {
+        const int rc = check_gemm_desc(gemms[i]);
+        if (rc != ROV_OK) return rc;
+    }
+    {
+        const int rc = check_attn_desc(*attn);
+        if (rc != ROV_OK) return rc;
+    }
+    const bool dropout = attn->p > 0.0f;
+    const bool need_mask = dropout && schedule != ROV_SCHED_FUSED;
+    if (need_mask && (mask == nullptr || !aligned(mask, 8))) return ROV_ERR_INVALID;
+    if (schedule == ROV_SCHED_OVERLAP && main_stream == side_stream) return ROV_ERR_INVALID;
+    hipStream_t ms = (hipStream_t)main_stream, ss = (hipStream_t)side_stream;
+
+    Events* ev = nullptr;
+    if (schedule == ROV_SCHED_OVERLAP && need_mask) {
+        const int rc = get_events(&ev);
+        if (rc != ROV_OK) return rc;
+        // the mask buffer may still be read by work already queued on the main stream
+        ROV_HIP_TRY(hipEventRecord(ev->fork, ms));
+        ROV_HIP_TRY(hipStreamWaitEvent(ss, ev->fork, 0));
+    }
+    auto run_gemms = [&](hipStream_t st) {
+        for (int i = 0; i < n_gemms; ++i) {
+            const rov_gemm_desc& g = gemms[i];
+            const int rc = launch_gemm(g.A, g.Bm, g.C, g.M, g.N, g.K, g.dtype, g.transB, g.scaleA,
+                                       g.scaleB, st);
+            if (rc != ROV_OK) return rc;
+        }
+        return (int)ROV_OK;
+    };
+    int rc = ROV_OK;
+    if (schedule == ROV_SCHED_OVERLAP && need_mask) {
+        // GEMMs first so that their workgroups claim each compute unit's LDS and most of its
+        // registers; the RNG workgroups then fill the space left over (paper Sec. 6.2)
+        if (n_gemms > 0) {
+            const rov_gemm_desc& g = gemms[0];
+            rc = launch_gemm(g.A, g.Bm, g.C, g.M, g.N, g.K, g.dtype, g.transB, g.scaleA, g.scaleB, ms);
+            if (rc != ROV_OK) return rc;
+        }
+        rc = launch_mask(seed, offset, attn->B, attn->H, attn->S, attn->p, 10, mask, ss);
+        if (rc != ROV_OK) return rc;
+        ROV_HIP_TRY(hipEventRecord(ev->join, ss));
+        for (int i = 1; i < n_gemms; ++i) {
+            const rov_gemm_desc& g = gemms[i];
+            rc = launch_gemm(g.A, g.Bm, g.C, g.M, g.N, g.K, g.dtype, g.transB, g.scaleA, g.scaleB, ms);
+            if (rc != ROV_OK) return rc;
+        }
+        ROV_HIP_TRY(hipStreamWaitEvent(ms, ev->join, 0));
+    } else {
+        rc = run_gemms(ms);
+        if (rc != ROV_OK) return rc;
+        if (need_mask) {
+            rc = launch_mask(seed, offset, attn->B, attn->H, attn->S, attn->p, 10, mask, ms);
+            if (rc != ROV_OK) return rc;
+        }
+    }
+    return launch_attention(attn->Q, attn->K, attn->V, attn->O, attn->B, attn->H, attn->Hkv, attn->S,
+                            attn->d, attn->strides, attn->dtype, attn->causal, attn->p,
+                            need_mask ? mask : nullptr, seed, offset, ms);
+}
+
+extern "C" size_t rov_block_workspace_bytes(const rov_block_cfg* cfg, int B, int S, int schedule) {
+    (void)schedule;
+    rov::BlockLayout L;
+    if (!rov::block_layout(cfg, B, S, &L)) return 0;
+    return L.total;
+}
+
+extern "C" int rov_block_forward(const rov_block_weights* w, const void* x, void* y, int B, int S,
+                                 const rov_block_cfg* cfg, int schedule, uint64_t seed,
+                                 uint64_t offset, int mask_ready, uint64_t* mask,
+                                 uint64_t* next_mask, void* workspace, size_t workspace_bytes,
+                                 void* main_stream, void* side_stream) {
+    using namespace rov;
+    BlockLayout L;
+    if (w == nullptr || x == nullptr || y == nullptr || !valid_schedule(schedule) ||
+        !block_layout(cfg, B, S, &L))
+        return ROV_ERR_INVALID;
+    if (w->norm1 == nullptr || w->norm2 == nullptr || w->wqkv == nullptr || w->wo == nullptr ||
+        w->wg == nullptr || w->wu == nullptr || w->wd == nullptr)
+        return ROV_ERR_INVALID;
+    if ((cfg->H % cfg->Hkv) != 0 || !(cfg->p >= 0.0f) || !(cfg->p < 1.0f) || !(cfg->eps > 0.0f) ||
+        !(cfg->rope_theta > 0.0f))
+        return ROV_ERR_INVALID;
+    if (cfg->dtype != ROV_BF16)
+        return (cfg->dtype == ROV_F32 || cfg->dtype == ROV_FP8_E4M3) ? ROV_ERR_UNSUPPORTED : ROV_ERR_INVALID;
+    if ((cfg->d != 64 && cfg->d != 128) || (cfg->hidden % 64) != 0 || (cfg->ffn % 64) != 0)
+        return ROV_ERR_UNSUPPORTED;
+    if (workspace == nullptr || !aligned(workspace, 256)) return ROV_ERR_INVALID;
+    if (workspace_bytes < L.total) return ROV_ERR_WORKSPACE;
+    const bool dropout = cfg->p > 0.0f;
+    const bool use_mask = dropout && schedule != ROV_SCHED_FUSED;
+    if (use_mask && (mask == nullptr || !aligned(mask, 8))) return ROV_ERR_INVALID;
+    if (next_mask != nullptr && (!aligned(next_mask, 8) || next_mask == mask)) return ROV_ERR_INVALID;
+    const bool overlap = schedule == ROV_SCHED_OVERLAP && dropout;
+    if (overlap && main_stream == side_stream) return ROV_ERR_INVALID;
+    if (!overlap && next_mask != nullptr) return ROV_ERR_INVALID;   // only the overlap schedule runs ahead
+    hipStream_t ms = (hipStream_t)main_stream, ss = (hipStream_t)side_stream;
+
+    char* ws = (char*)workspace;
+    void* h = ws + L.h;
+    void* qkv = ws + L.qkv;
+    void* att = ws + L.att;
+    void* x2 = ws + L.x2;
+    void* g = ws + L.g;
+    void* u = ws + L.u;
+    const int64_t T = (int64_t)B * S;
+    if (T > 0x7FFFFFFF) return ROV_ERR_UNSUPPORTED;
+    const int H = cfg->H, Hkv = cfg->Hkv, d = cfg->d, hidden = cfg->hidden, ffn = cfg->ffn;
+    const int qkv_n = (H + 2 * Hkv) * d;
+    Events* ev = nullptr;
+    int rc = ROV_OK;
+    if (overlap) {
+        rc = get_events(&ev);
+        if (rc != ROV_OK) return rc;
+    }
+#define ROV_STEP(expr)            \
+    do {                          \
+        rc = (expr);              \
+        if (rc != ROV_OK) return rc; \
+    } while (0)
+
+    // this block's own mask, if nobody produced it yet
+    if (use_mask && !mask_ready && overlap) {
+        ROV_HIP_TRY(hipEventRecord(ev->fork, ms));
+        ROV_HIP_TRY(hipStreamWaitEvent(ss, ev->fork, 0));
+    }
+    ROV_STEP(launch_rmsnorm(x, w->norm1, h, T, hidden, cfg->eps, ms));
+    ROV_STEP(launch_gemm(h, w->wqkv, qkv, (int)T, qkv_n, hidden, ROV_BF16, 1, 1.0f, 1.0f, ms));
+    if (use_mask && !mask_ready) {
+        if (overlap) {
+            ROV_STEP(launch_mask(seed, offset, B, H, S, cfg->p, 10, mask, ss));
+            ROV_HIP_TRY(hipEventRecord(ev->join, ss));
+        } else {
+            ROV_STEP(launch_mask(seed, offset, B, H, S, cfg->p, 10, mask, ms));
+        }
+    }
+    ROV_STEP(launch_rope(qkv, T, qkv_n, S, H + Hkv, d, cfg->rope_theta, ms));   // q heads then k heads
+    if (use_mask && !mask_ready && overlap) ROV_HIP_TRY(hipStreamWaitEvent(ms, ev->join, 0));
+
+    const uint16_t* qp = (const uint16_t*)qkv;
+    const int64_t strides[12] = {
+        (int64_t)S * qkv_n, qkv_n, d,      // Q
+        (int64_t)S * qkv_n, qkv_n, d,      // K
+        (int64_t)S * qkv_n, qkv_n, d,      // V
+        (int64_t)S * H * d, (int64_t)H * d, d};   // O
+    ROV_STEP(launch_attention(qp, qp + (int64_t)H * d, qp + (int64_t)(H + Hkv) * d, att, B, H, Hkv, S, d,
+                              strides, ROV_BF16, cfg->causal, cfg->p, use_mask ? mask : nullptr, seed,
+                              offset, ms));
+
+    // the next layer's mask runs beside this block's remaining GEMMs (it would compete with
+    // attention for VALU issue, so it starts once attention is done)
+    if (overlap && next_mask != nullptr) {
+        ROV_HIP_TRY(hipEventRecord(ev->fork, ms));
+        ROV_HIP_TRY(hipStreamWaitEvent(ss, ev->fork, 0));
+    }
+    ROV_STEP(launch_gemm_residual(att, w->wo, x2, x, (int)T, hidden, H * d, ROV_BF16, 1, 1.0f, 1.0f, ms));
+    if (overlap && next_mask != nullptr) {
+        ROV_STEP(launch_mask(seed, offset + rov_mask_philox_calls(B, H, S), B, H, S, cfg->p, 10,
+                             next_mask, ss));
+        ROV_HIP_TRY(hipEventRecord(ev->join, ss));
+    }
+    ROV_STEP(launch_rmsnorm(x2, w->norm2, h, T, hidden, cfg->eps, ms));
+    ROV_STEP(launch_gemm(h, w->wg, g, (int)T, ffn, hidden, ROV_BF16, 1, 1.0f, 1.0f, ms));
+    ROV_STEP(launch_gemm(h, w->wu, u, (int)T, ffn, hidden, ROV_BF16, 1, 1.0f, 1.0f, ms));
+    ROV_STEP(launch_swiglu(g, u, g, T * ffn, ms));
+    ROV_STEP(launch_gemm_residual(g, w->wd, y, x2, (int)T, hidden, ffn, ROV_BF16, 1, 1.0f, 1.0f, ms));
+    if (overlap && next_mask != nullptr) ROV_HIP_TRY(hipStreamWaitEvent(ms, ev->join, 0));
+#undef ROV_STEP
+    return ROV_OK;
 }

@@ -1,0 +1,151 @@
+"""GPU parity for the schedules and the transformer block.
+
+The three schedules must give the same attention output bit for bit (same mask bits, same
+kernels' arithmetic), and each matches the oracle within the bf16 bar (2e-2 of the output scale).
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import dense as OD
+from oracle import philox as OP
+from paper_2410_07531_amd import binding as rov
+from paper_2410_07531_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+
+def _f64(t):
+    return t.float().cpu().numpy().astype(np.float64)
+
+
+def _dev(x, dtype=torch.bfloat16):
+    return torch.from_numpy(x).to(dtype).cuda()
+
+
+@pytest.mark.parametrize("dtype,B,S,H,Hkv,d,gemm", [
+    (torch.float32, 1, 128, 2, 2, 64, (256, 256, 256)),        # tiny workload
+    (torch.bfloat16, 1, 512, 4, 2, 128, (512, 256, 768)),
+])
+def test_layer_step_three_schedules(dtype, B, S, H, Hkv, d, gemm):
+    rng = np.random.default_rng(11)
+    q, k, v = wl.qkv(rng, B, S, H, Hkv, d)
+    Q, K, V = _dev(q, dtype), _dev(k, dtype), _dev(v, dtype)
+    M, Kd, N = gemm
+    a, w = wl.gemm_operands(rng, M, Kd, N)
+    A, W = _dev(a, dtype), _dev(w, dtype)
+    p, seed, offset = 0.1, wl.SEED, wl.OFFSET
+    main, side = torch.cuda.Stream(), torch.cuda.Stream()
+    outs, cs = [], []
+    for sched in (rov.SCHED_SEQUENTIAL, rov.SCHED_FUSED, rov.SCHED_OVERLAP):
+        print("layer_step", dtype, sched, flush=True)
+        O = torch.zeros_like(Q)
+        C = torch.zeros((M, N), dtype=torch.float32 if dtype == torch.float32 else torch.bfloat16, device="cuda")
+        mask = torch.full((B, H, S, (S + 63) // 64), 0x2AAAAAAAAAAAAAAA, dtype=torch.int64, device="cuda")  # poison
+        torch.cuda.synchronize()
+        gd = [rov.make_gemm_desc(A, W, C)]
+        ad = rov.make_attn_desc(Q, K, V, O, p)
+        for _ in range(2):   # twice: the second pass reuses the events and the mask buffer
+            rov.layer_step(sched, gd, ad, seed, offset, None if sched == rov.SCHED_FUSED else mask, main, side)
+        torch.cuda.synchronize()
+        outs.append(O)
+        cs.append(C)
+        if sched != rov.SCHED_FUSED:
+            assert np.array_equal(mask.cpu().numpy().view(np.uint64), OP.dropout_mask(seed, offset, B, H, S, p))
+    assert torch.equal(outs[0], outs[1]) and torch.equal(outs[0], outs[2])
+    assert torch.equal(cs[0], cs[1]) and torch.equal(cs[0], cs[2])
+    keep = OP.unpack_keep(OP.dropout_mask(seed, offset, B, H, S, p), S)
+    ref = OD.attention_dropout(_f64(Q), _f64(K), _f64(V), keep, p)
+    tol = 2e-2 if dtype == torch.bfloat16 else 1e-4
+    assert np.max(np.abs(_f64(outs[0]) - ref)) / np.max(np.abs(ref)) <= tol
+    refc = OD.gemm(_f64(A), _f64(W), transB=True)
+    assert np.max(np.abs(_f64(cs[0]) - refc)) / np.max(np.abs(refc)) <= (6e-3 if dtype == torch.bfloat16 else 1e-5)
+
+
+def test_layer_step_invalid_arguments():
+    Q = torch.zeros((1, 64, 2, 64), dtype=torch.bfloat16, device="cuda")
+    O = torch.zeros_like(Q)
+    ad = rov.make_attn_desc(Q, Q, Q, O, 0.1)
+    s = torch.cuda.Stream()
+    with pytest.raises(rov.RovError):
+        rov.layer_step(rov.SCHED_OVERLAP, [], ad, 1, 0, None, s, torch.cuda.Stream())      # mask missing
+    mask = torch.zeros((1, 2, 64, 1), dtype=torch.int64, device="cuda")
+    with pytest.raises(rov.RovError):
+        rov.layer_step(rov.SCHED_OVERLAP, [], ad, 1, 0, mask, s, s)                        # same stream
+    with pytest.raises(rov.RovError):
+        rov.layer_step(7, [], ad, 1, 0, mask, s, torch.cuda.Stream())
+
+
+def _block_setup(B, S, H, Hkv, d, hidden, ffn, seed):
+    rng = np.random.default_rng(seed)
+    w = wl.block_weights(rng, H, Hkv, d, hidden, ffn)
+    # non-trivial norm weights so that a dropped scale would show
+    w["norm1"] = (1.0 + 0.1 * rng.standard_normal(hidden)).astype(np.float32)
+    w["norm2"] = (1.0 + 0.1 * rng.standard_normal(hidden)).astype(np.float32)
+    for kname in ("wqkv", "wo", "wg", "wu", "wd"):
+        w[kname] = w[kname] * np.float32(3.0)     # sd 0.06: keeps every stage's contribution visible
+    x = wl.block_input(rng, B, S, hidden)
+    wd = {k_: _dev(v_) for k_, v_ in w.items()}
+    return _dev(x), wd
+
+
+@pytest.mark.parametrize("causal", [False, True])
+def test_block_forward_three_schedules_match_oracle(causal):
+    B, S, H, Hkv, d, hidden, ffn = 1, 256, 4, 2, 128, 512, 1024
+    p, seed, offset = 0.1, wl.SEED, 640
+    x, wd = _block_setup(B, S, H, Hkv, d, hidden, ffn, 21)
+    cfg = rov.make_block_cfg(H, Hkv, d, hidden, ffn, p, causal=causal)
+    weights = rov.make_block_weights(wd)
+    ws = torch.empty(rov.block_workspace_bytes(cfg, B, S, 0), dtype=torch.uint8, device="cuda")
+    main, side = torch.cuda.Stream(), torch.cuda.Stream()
+    W = (S + 63) // 64
+    ys = {}
+    for name, sched, ready in (("seq", rov.SCHED_SEQUENTIAL, False), ("fused", rov.SCHED_FUSED, False),
+                               ("ovl_first", rov.SCHED_OVERLAP, False), ("ovl_steady", rov.SCHED_OVERLAP, True)):
+        print("block", name, causal, flush=True)
+        y = torch.zeros_like(x)
+        mask = torch.zeros((B, H, S, W), dtype=torch.int64, device="cuda")
+        nxt = torch.zeros_like(mask) if name == "ovl_steady" else None
+        if ready:
+            rov.dropout_mask_generate(seed, offset, B, H, S, p, out=mask)
+        torch.cuda.synchronize()
+        rov.block_forward(weights, x, y, cfg, sched, seed, offset, None if sched == rov.SCHED_FUSED else mask,
+                          ws, main, side, mask_ready=ready, next_mask=nxt)
+        torch.cuda.synchronize()
+        ys[name] = y
+        if nxt is not None:
+            exp = OP.dropout_mask(seed, offset + OP.mask_philox_calls(B, H, S), B, H, S, p)
+            assert np.array_equal(nxt.cpu().numpy().view(np.uint64), exp)
+    for name in ("fused", "ovl_first", "ovl_steady"):
+        assert torch.equal(ys["seq"], ys[name]), name
+    keep = OP.unpack_keep(OP.dropout_mask(seed, offset, B, H, S, p), S)
+    ocfg = dict(H=H, Hkv=Hkv, d=d, eps=1e-5, rope_theta=500000.0, p=p, causal=causal)
+    ref = OD.block_forward(_f64(x), {k_: _f64(v_) for k_, v_ in wd.items()}, ocfg, keep)
+    got = _f64(ys["seq"])
+    assert np.max(np.abs(got - ref)) / np.max(np.abs(ref)) <= 2e-2
+    # the block is not the identity: the residual branches are visible at this tolerance
+    assert np.max(np.abs(ref - _f64(x))) / np.max(np.abs(ref)) > 0.1
+
+
+def test_block_workspace_and_argument_errors():
+    B, S, H, Hkv, d, hidden, ffn = 1, 64, 2, 2, 64, 128, 256
+    x, wd = _block_setup(B, S, H, Hkv, d, hidden, ffn, 3)
+    cfg = rov.make_block_cfg(H, Hkv, d, hidden, ffn, 0.1)
+    weights = rov.make_block_weights(wd)
+    need = rov.block_workspace_bytes(cfg, B, S, 0)
+    T = B * S
+    assert need >= 2 * T * (2 * hidden + (H + 2 * Hkv) * d + H * d + 2 * ffn)
+    ws = torch.empty(need - 256, dtype=torch.uint8, device="cuda")
+    y = torch.full_like(x, 5.0)
+    mask = torch.zeros((B, H, S, 1), dtype=torch.int64, device="cuda")
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    with pytest.raises(rov.RovError) as e:
+        rov.block_forward(weights, x, y, cfg, rov.SCHED_SEQUENTIAL, 1, 0, mask, ws, s1, s2)
+    assert e.value.code == rov.ERR_WORKSPACE
+    ws = torch.empty(need, dtype=torch.uint8, device="cuda")
+    with pytest.raises(rov.RovError):
+        rov.block_forward(weights, x, y, cfg, rov.SCHED_SEQUENTIAL, 1, 0, None, ws, s1, s2)     # mask missing
+    with pytest.raises(rov.RovError):
+        rov.block_forward(weights, x, y, cfg, rov.SCHED_SEQUENTIAL, 1, 0, mask, ws, s1, s2, next_mask=mask.clone())
+    torch.cuda.synchronize()
+    assert bool((y == 5.0).all())

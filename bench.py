@@ -1,0 +1,328 @@
+#!/usr/bin/env python3
+"""Benchmark of the RNG/GEMM-overlap hot path on one MI355X.
+
+A "step" is one pass of the whole hot path on the Llama-3-8B-shaped single layer (B=1, H=32,
+d=128, S=2048, p=0.1, bf16): the Philox4x32-10 keep-mask (32 x 2048 x 2048 bits) generated on
+a side stream while the FFN-up GEMM (2048 x 4096 x 14336) runs, joined, then flash-attention
+forward that drops with that mask (`rov_layer_step`, overlap schedule).  Inputs are synthetic
+(seeded N(0,1) activations, N(0,0.02) weights) and already resident in HBM.
+
+One JSON line is printed: whole-step mask throughput as `value`, the roofline of the dominant
+kernel of the step (the GEMM, measured with HIP events inside the timed region through the
+library's kernel trace), the CPU oracle timed on this machine's host cores on a bounded sample, and
+the per-kernel / per-schedule numbers (stand-alone RNG Gbit/s and its VALU roofline, GEMM alone
+vs beside the RNG, hidden fraction, sequential / fused / overlap step and block times).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0       # MI355X dense bf16 MFMA
+PEAK_INT32_TOPS = 78.6          # 256 CU x 4 SIMD x 32 lanes/clk x 2.4 GHz (= fp32 FMA issue rate, 157.3 / 2)
+INT32_OPS_PER_CALL = 84         # 20 wide multiplies (lo+hi = 2 results each), 40 two-input xors, 4 compares
+
+
+def median_ms(fn, warm, iters, sync, ev_pair, inner=10):
+    """Median over `iters` batches of the per-call time of `inner` back-to-back calls (HIP events on
+    the current stream), so that launch latency after an idle queue is not billed to the kernel."""
+    for _ in range(warm):
+        fn()
+    sync()
+    ts = []
+    for _ in range(iters):
+        a, b = ev_pair()
+        a.record()
+        for _ in range(inner):
+            fn()
+        b.record()
+        b.synchronize()
+        ts.append(a.elapsed_time(b) / inner)
+    return float(np.median(ts))
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--no-block", action="store_true", help="skip the config-5 block timings")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline")
+    ap.add_argument("--kernels-only", action="store_true",
+                    help="for profilers: launch a 1 GiB device copy (counter calibration), then the RNG, GEMM and "
+                         "attention kernels of the workload alone and the overlap step, 5 times each; no JSON")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build measures one GPU only (the path has no cross-GPU step); run with --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2410_07531_amd import binding as rov
+    from paper_2410_07531_amd import workloads as wl
+
+    rov.load()
+    torch.cuda.set_device(0)
+    dev = "cuda"
+    sync = torch.cuda.synchronize
+    main_s, side_s = torch.cuda.Stream(), torch.cuda.Stream()
+
+    def ev_pair():
+        return torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+
+    # ------------------------------------------------------------------ workload (configs[1])
+    ci = 1
+    c = wl.CONFIGS[ci]
+    B, H, Hkv, S, d, p = c["B"], c["H"], c["Hkv"], c["S"], c["d"], c["p"]
+    _, M, K, N = c["gemms"][0]
+    rng = wl.rng_for(ci)
+    q, k, v = wl.qkv(rng, B, S, H, Hkv, d)
+    a, w = wl.gemm_operands(rng, M, K, N)
+    bf = torch.bfloat16
+    Q, Kt, V = [torch.from_numpy(x).to(bf).to(dev) for x in (q, k, v)]
+    A, Wt = torch.from_numpy(a).to(bf).to(dev), torch.from_numpy(w).to(bf).to(dev)
+    O = torch.empty_like(Q)
+    C = torch.empty((M, N), dtype=bf, device=dev)
+    mask = torch.empty((B, H, S, S // 64), dtype=torch.int64, device=dev)
+    nbits = B * H * S * S
+    ncalls = nbits // 4
+    gemm_flops = 2.0 * M * N * K
+    attn_flops = 4.0 * B * H * S * S * d
+    gd = [rov.make_gemm_desc(A, Wt, C)]
+    ad = rov.make_attn_desc(Q, Kt, V, O, p)
+
+    def step(sched):
+        rov.layer_step(sched, gd, ad, wl.SEED, wl.OFFSET, None if sched == rov.SCHED_FUSED else mask, main_s, side_s)
+
+    if args.kernels_only:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        with torch.cuda.stream(main_s):
+            for _ in range(5):
+                dst.copy_(src)                                     # reads 1 GiB, writes 1 GiB
+            for _ in range(5):
+                rov.dropout_mask_generate(wl.SEED, 0, B, H, S, p, out=mask, stream=main_s)
+            for _ in range(5):
+                rov.gemm(A, Wt, C=C, stream=main_s)
+            for _ in range(5):
+                rov.attention_fwd_dropout(Q, Kt, V, p, mask=mask, O=O, stream=main_s)
+            for _ in range(5):
+                rov.attention_fwd_dropout(Q, Kt, V, p, seed=wl.SEED, offset=0, O=O, stream=main_s)
+        for _ in range(5):
+            step(rov.SCHED_OVERLAP)
+        sync()
+        print("kernels-only run done", file=sys.stderr)
+        return
+
+    # ------------------------------------------------------------------ timed region (overlap schedule)
+    for _ in range(args.warmup):
+        step(rov.SCHED_OVERLAP)
+    sync()
+    rov.trace_enable(True)
+    rov.trace_read()
+    sync()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step(rov.SCHED_OVERLAP)
+    sync()
+    t1 = time.perf_counter()
+    rov.trace_enable(False)
+    trace = rov.trace_read()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    by_kind = {}
+    for kind, ms in trace:
+        by_kind.setdefault(kind, []).append(ms)
+    gemm_in_step = float(np.mean(by_kind[rov.TRACE_GEMM]))
+    rng_in_step = float(np.mean(by_kind[rov.TRACE_RNG]))
+    attn_in_step = float(np.mean(by_kind[rov.TRACE_ATTENTION]))
+
+    # ------------------------------------------------------------------ per-kernel and per-schedule numbers
+    with torch.cuda.stream(main_s):
+        t_rng = median_ms(lambda: rov.dropout_mask_generate(wl.SEED, 0, B, H, S, p, out=mask, stream=main_s),
+                          5, 10, sync, ev_pair)
+        t_gemm = median_ms(lambda: rov.gemm(A, Wt, C=C, stream=main_s), 5, 10, sync, ev_pair)
+        t_attn_none = median_ms(lambda: rov.attention_fwd_dropout(Q, Kt, V, 0.0, O=O, stream=main_s), 3, 10, sync, ev_pair)
+        t_attn_mask = median_ms(lambda: rov.attention_fwd_dropout(Q, Kt, V, p, mask=mask, O=O, stream=main_s),
+                                3, 10, sync, ev_pair)
+        t_attn_fused = median_ms(lambda: rov.attention_fwd_dropout(Q, Kt, V, p, seed=wl.SEED, offset=0, O=O,
+                                                                  stream=main_s), 3, 10, sync, ev_pair)
+
+        # the overlap schedule's first phase on its own: fork, GEMM || RNG (same small persistent RNG
+        # grid as the library's overlap schedules use), join
+        k_ovl = rov.set_rng_overlap_workgroups_per_cu(0)
+        rov.set_rng_overlap_workgroups_per_cu(k_ovl)
+        n_cu = torch.cuda.get_device_properties(0).multi_processor_count
+
+        def gemm_beside_rng():
+            fork = torch.cuda.Event()
+            fork.record(main_s)
+            side_s.wait_event(fork)
+            rov.gemm(A, Wt, C=C, stream=main_s)
+            rov.dropout_mask_generate(wl.SEED, 0, B, H, S, p, out=mask, stream=side_s)
+            join = torch.cuda.Event()
+            join.record(side_s)
+            main_s.wait_event(join)
+
+        rov.set_rng_max_workgroups(n_cu * k_ovl)
+        t_pair = median_ms(gemm_beside_rng, 5, 10, sync, ev_pair)
+        rov.set_rng_max_workgroups(0)
+        t_seq = median_ms(lambda: step(rov.SCHED_SEQUENTIAL), 5, 10, sync, ev_pair)
+        t_fus = median_ms(lambda: step(rov.SCHED_FUSED), 5, 10, sync, ev_pair)
+        t_ovl = median_ms(lambda: step(rov.SCHED_OVERLAP), 5, 10, sync, ev_pair)
+    hidden = 1.0 - (t_pair - t_gemm) / t_rng
+    gemm_slowdown = gemm_in_step / t_gemm - 1.0
+
+    extras = {
+        "rng_alone": {"ms": t_rng, "gbit_s": nbits / t_rng / 1e6, "gcalls_s": ncalls / t_rng / 1e6,
+                      "roofline": {"bound": "alu", "achieved": ncalls * INT32_OPS_PER_CALL / t_rng / 1e9,
+                                   "peak": PEAK_INT32_TOPS, "unit": "Tint32op/s",
+                                   "frac": ncalls * INT32_OPS_PER_CALL / t_rng / 1e9 / PEAK_INT32_TOPS,
+                                   "traffic": None}},
+        "gemm_alone": {"ms": t_gemm, "tflops": gemm_flops / t_gemm / 1e9,
+                       "mfma_frac": gemm_flops / t_gemm / 1e9 / PEAK_BF16_TFLOPS},
+        "gemm_in_overlap_step": {"ms": gemm_in_step, "tflops": gemm_flops / gemm_in_step / 1e9,
+                                 "mfma_frac": gemm_flops / gemm_in_step / 1e9 / PEAK_BF16_TFLOPS,
+                                 "slowdown_vs_alone": gemm_slowdown},
+        "rng_in_overlap_step": {"ms": rng_in_step, "slowdown_vs_alone": rng_in_step / t_rng - 1.0},
+        "gemm_beside_rng_region_ms": t_pair,
+        "rng_overlap_workgroups_per_cu": k_ovl,
+        "rng_hidden_fraction": hidden,
+        "attention": {"none_ms": t_attn_none, "mask_ms": t_attn_mask, "fused_ms": t_attn_fused,
+                      "in_step_ms": attn_in_step,
+                      "none_tflops": attn_flops / t_attn_none / 1e9, "mask_tflops": attn_flops / t_attn_mask / 1e9,
+                      "fused_tflops": attn_flops / t_attn_fused / 1e9,
+                      "dropping_overhead": t_attn_mask / t_attn_none - 1.0},
+        "layer_step_ms": {"sequential": t_seq, "fused": t_fus, "overlap": t_ovl},
+        "layer_speedup_overlap_vs_sequential": t_seq / t_ovl,
+        "layer_speedup_overlap_vs_fused": t_fus / t_ovl,
+    }
+
+    # ------------------------------------------------------------------ transformer block (configs[4])
+    if not args.no_block:
+        del Q, Kt, V, O, A, Wt, C
+        torch.cuda.empty_cache()
+        extras["block_llama3_8b_s16k"] = bench_block(torch, rov, wl, main_s, side_s, sync, ev_pair)
+
+    # ------------------------------------------------------------------ CPU oracle on a bounded sample
+    cpu = None
+    if not args.no_cpu:
+        cpu = cpu_baseline(wl, ci, q, k, v, a, w, nbits)
+
+    out = {
+        "metric": "RNG mask Gbit/s + Transformer-block speedup: overlap vs sequential/fused",
+        "value": nbits / ms_per_step / 1e6,
+        "unit": "Gbit/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": "llama3_8b_s2k: B=1 H=32 d=128 S=2048 p=0.1 mask 32x2048x2048 bits; "
+                               "GEMM 2048x4096x14336 bf16; overlap schedule (RNG on side stream || GEMM, join, "
+                               "attention with mask)",
+                   "schedule": "overlap", "seed": wl.SEED, "offset": wl.OFFSET},
+        "roofline": {"bound": "mfma", "kernel": "gemm_bf16_tn_kernel (inside the overlap step, RNG co-running)",
+                     "achieved": gemm_flops / gemm_in_step / 1e9, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                     "frac": gemm_flops / gemm_in_step / 1e9 / PEAK_BF16_TFLOPS, "traffic": None},
+        "cpu_baseline": cpu,
+        "extras": extras,
+    }
+    print(json.dumps(out))
+
+
+def bench_block(torch, rov, wl, main_s, side_s, sync, ev_pair):
+    ci = 4
+    c = wl.CONFIGS[ci]
+    B, H, Hkv, S, d, p, hidden, ffn = c["B"], c["H"], c["Hkv"], c["S"], c["d"], c["p"], c["hidden"], c["ffn"]
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(1000 + ci)
+    bf = torch.bfloat16
+
+    def randn(*shape, sd=1.0):
+        return (torch.randn(*shape, device="cuda", generator=gen) * sd).to(bf)
+
+    wts = dict(norm1=torch.ones(hidden, device="cuda", dtype=bf), norm2=torch.ones(hidden, device="cuda", dtype=bf),
+               wqkv=randn((H + 2 * Hkv) * d, hidden, sd=0.02), wo=randn(hidden, H * d, sd=0.02),
+               wg=randn(ffn, hidden, sd=0.02), wu=randn(ffn, hidden, sd=0.02), wd=randn(hidden, ffn, sd=0.02))
+    x = randn(B, S, hidden)
+    y = torch.empty_like(x)
+    res = {}
+    for causal in (False, True):
+        cfg = rov.make_block_cfg(H, Hkv, d, hidden, ffn, p, causal=causal)
+        weights = rov.make_block_weights(wts)
+        ws = torch.empty(rov.block_workspace_bytes(cfg, B, S, 0), dtype=torch.uint8, device="cuda")
+        m0 = torch.empty((B, H, S, S // 64), dtype=torch.int64, device="cuda")
+        m1 = torch.empty_like(m0)
+        off1 = rov.mask_philox_calls(B, H, S)
+        rov.dropout_mask_generate(wl.SEED, 0, B, H, S, p, out=m0)
+        sync()
+        layer = [0]
+
+        def seq():
+            rov.block_forward(weights, x, y, cfg, rov.SCHED_SEQUENTIAL, wl.SEED, 0, m0, ws, main_s, side_s)
+
+        def fus():
+            rov.block_forward(weights, x, y, cfg, rov.SCHED_FUSED, wl.SEED, 0, None, ws, main_s, side_s)
+
+        def ovl():   # steady state: this layer's mask was produced during the previous call
+            cur, nxt = (m0, m1) if layer[0] % 2 == 0 else (m1, m0)
+            rov.block_forward(weights, x, y, cfg, rov.SCHED_OVERLAP, wl.SEED, layer[0] * off1, cur, ws,
+                              main_s, side_s, mask_ready=True, next_mask=nxt)
+            layer[0] += 1
+
+        with torch.cuda.stream(main_s):
+            t_seq = median_ms(seq, 2, 5, sync, ev_pair, inner=2)
+            t_fus = median_ms(fus, 2, 5, sync, ev_pair, inner=2)
+            t_ovl = median_ms(ovl, 2, 5, sync, ev_pair, inner=2)
+        res["causal" if causal else "noncausal"] = {
+            "sequential_ms": t_seq, "fused_ms": t_fus, "overlap_ms": t_ovl,
+            "speedup_overlap_vs_sequential": t_seq / t_ovl, "speedup_overlap_vs_fused": t_fus / t_ovl}
+        del ws, m0, m1
+        torch.cuda.empty_cache()
+    return res
+
+
+def cpu_baseline(wl, ci, q, k, v, a, w, nbits):
+    """The oracle as it stands, timed on this machine's host cores on a bounded sample of the step."""
+    import torch
+    from oracle import dense as OD
+    from oracle import numerics as ON
+    from oracle import philox as OP
+    c = wl.CONFIGS[ci]
+    B, H, S, p = c["B"], c["H"], c["S"], c["p"]
+    t0 = time.perf_counter()
+    words = OP.dropout_mask(wl.SEED, wl.OFFSET, B, H, S, p)          # full mask
+    t_mask = time.perf_counter() - t0
+    rows_g = 32
+    ar = ON.bf16_round(a[:rows_g]).astype(np.float64)
+    wr = ON.bf16_round(w).astype(np.float64)
+    t0 = time.perf_counter()
+    OD.gemm(ar, wr, transB=True)
+    t_gemm = (time.perf_counter() - t0) * (a.shape[0] / rows_g)
+    rows_a = wl.sample_rows(S, 16)
+    keep = OP.unpack_keep(words, S)
+    qr, kr, vr = [ON.bf16_round(x).astype(np.float64) for x in (q, k, v)]
+    t0 = time.perf_counter()
+    OD.attention_dropout(qr, kr, vr, keep, p, rows=rows_a)
+    t_attn = (time.perf_counter() - t0) * (S / len(rows_a))
+    total = t_mask + t_gemm + t_attn
+    return {"value": nbits / total / 1e9, "unit": "Gbit/s", "cores": max(OP.num_threads(), torch.get_num_threads()),
+            "kind": "oracle",
+            "sample": "mask in full (%.3f s, %.2f Gbit/s); GEMM on %d of %d rows and attention on %d of %d query "
+                      "rows of every head, each extrapolated by row count (GEMM %.1f s, attention %.1f s for the "
+                      "full step)" % (t_mask, nbits / t_mask / 1e9, rows_g, a.shape[0], len(rows_a), S, t_gemm, t_attn),
+            "mask_only_gbit_s": nbits / t_mask / 1e9}
+
+
+if __name__ == "__main__":
+    main()

@@ -94,6 +94,12 @@ int rov_dropout_mask_generate_rounds(uint64_t seed, uint64_t offset, int B, int 
  * to fill the device).  Process-wide; returns the previous value. */
 int rov_set_rng_max_workgroups(int max_workgroups);
 
+/* Size of the persistent RNG grid that the overlap schedules launch beside a
+ * GEMM, in workgroups (4 waves, one per SIMD) per compute unit.  Small enough
+ * that a GEMM workgroup still fits on every compute unit whichever kernel
+ * arrives first.  n <= 0 restores the default (2).  Returns the previous value. */
+int rov_set_rng_overlap_workgroups_per_cu(int n);
+
 /* Diagnostic: VALU issue cost of the instruction kinds the RNG kernel is made of
  * (paper Table 1 bounds the RNG kernel by "Issue stage" and "ALU pipe"; the
  * ceiling this build prices the kernel against is derived from these measured
@@ -170,6 +176,23 @@ typedef struct rov_attn_desc {
 int rov_layer_step(int schedule, const rov_gemm_desc *gemms, int n_gemms, const rov_attn_desc *attn,
                    uint64_t seed, uint64_t offset, uint64_t *mask, void *main_stream,
                    void *side_stream);
+
+/* ---------------------------------------------------------------- kernel tracing
+ * Per-kernel timing of what rov_layer_step and rov_block_forward launch (the
+ * paper times each kernel of the sequence after warm-up, Sec. 6.1).  While
+ * enabled, every kernel launched by those two entry points is bracketed by
+ * timing events on its own stream.  rov_trace_read waits for the recorded
+ * events (HOST-side wait on them only), writes up to max_records (kind,
+ * milliseconds) pairs in launch order into the HOST arrays, stores the count in
+ * *n_records and clears the log.  Kinds: ROV_TRACE_GEMM, _RNG, _ATTENTION,
+ * _GLUE (RMSNorm / RoPE / SwiGLU).  At most 16384 records are kept between reads.
+ * rov_trace_enable returns the previous setting. */
+#define ROV_TRACE_GEMM 0
+#define ROV_TRACE_RNG 1
+#define ROV_TRACE_ATTENTION 2
+#define ROV_TRACE_GLUE 3
+int rov_trace_enable(int on);
+int rov_trace_read(int *kinds, float *ms, int max_records, int *n_records);
 
 /* ---------------------------------------------------------------- transformer block
  * Llama-style block forward (paper Fig. 2 / Sec. 3.2 block with RMSNorm, rotary

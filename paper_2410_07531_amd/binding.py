@@ -62,6 +62,10 @@ SIGNATURES = {
     "rov_dropout_mask_generate": (_i, [_u64, _u64, _i, _i, _i, _f, _p, _p]),
     "rov_dropout_mask_generate_rounds": (_i, [_u64, _u64, _i, _i, _i, _f, _i, _p, _p]),
     "rov_set_rng_max_workgroups": (_i, [_i]),
+    "rov_set_rng_overlap_workgroups_per_cu": (_i, [_i]),
+    "rov_trace_enable": (_i, [_i]),
+    "rov_trace_read": (_i, [ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_float), _i,
+                            ctypes.POINTER(ctypes.c_int)]),
     "rov_valu_probe": (_i, [_i, _i, _i, _p, _p]),
     "rov_gemm": (_i, [_p, _p, _p, _i, _i, _i, _i, _i, _f, _f, _p]),
     "rov_attention_fwd_dropout": (_i, [_p, _p, _p, _p, _i, _i, _i, _i, _i,
@@ -129,6 +133,10 @@ def mask_philox_calls(B, H, S):
 
 def set_rng_max_workgroups(n):
     return int(load().rov_set_rng_max_workgroups(int(n)))
+
+
+def set_rng_overlap_workgroups_per_cu(n):
+    return int(load().rov_set_rng_overlap_workgroups_per_cu(int(n)))
 
 
 def philox_raw(seed, first_counter, ncalls, rounds=10, out=None, stream=None):
@@ -242,3 +250,19 @@ def block_forward(weights, x, y, cfg, schedule, seed, offset, mask, workspace, m
                                     ctypes.c_void_p(workspace.data_ptr()), workspace.numel() * workspace.element_size(),
                                     _stream_ptr(main_stream), _stream_ptr(side_stream)), "rov_block_forward")
     return y
+
+
+TRACE_GEMM, TRACE_RNG, TRACE_ATTENTION, TRACE_GLUE = 0, 1, 2, 3
+
+
+def trace_enable(on):
+    return int(load().rov_trace_enable(int(bool(on))))
+
+
+def trace_read(max_records=16384):
+    """List of (kind, milliseconds) in launch order; waits for the traced kernels to finish."""
+    kinds = (ctypes.c_int * max_records)()
+    ms = (ctypes.c_float * max_records)()
+    n = ctypes.c_int(0)
+    _check(load().rov_trace_read(kinds, ms, max_records, ctypes.byref(n)), "rov_trace_read")
+    return [(int(kinds[i]), float(ms[i])) for i in range(n.value)]

@@ -2,6 +2,8 @@
 #include <hip/hip_runtime.h>
 
 #include <atomic>
+#include <mutex>
+#include <vector>
 
 #include "rov_internal.h"
 
@@ -32,9 +34,67 @@ int device_cu_count() {
     return n;
 }
 
+// ---- kernel tracing: timing events around the launches made by the schedules
+namespace {
+struct TraceRec {
+    int kind;
+    hipEvent_t a, b;
+};
+std::mutex g_trace_mu;
+std::vector<TraceRec> g_trace_pool;     // events are created once and reused
+size_t g_trace_used = 0;
+std::atomic<int> g_trace_on{0};
+constexpr size_t kTraceMax = 16384;
+}  // namespace
+
+int trace_begin(int kind, hipStream_t st) {
+    if (!g_trace_on.load()) return -1;
+    std::lock_guard<std::mutex> lock(g_trace_mu);
+    if (g_trace_used >= kTraceMax) return -1;
+    if (g_trace_used == g_trace_pool.size()) {
+        TraceRec r{kind, nullptr, nullptr};
+        if (hipEventCreate(&r.a) != hipSuccess) return -1;
+        if (hipEventCreate(&r.b) != hipSuccess) { (void)hipEventDestroy(r.a); return -1; }
+        g_trace_pool.push_back(r);
+    }
+    const int slot = (int)g_trace_used++;
+    g_trace_pool[slot].kind = kind;
+    (void)hipEventRecord(g_trace_pool[slot].a, st);
+    return slot;
+}
+
+void trace_end(int slot, hipStream_t st) {
+    if (slot < 0) return;
+    std::lock_guard<std::mutex> lock(g_trace_mu);
+    (void)hipEventRecord(g_trace_pool[slot].b, st);
+}
+
 }  // namespace rov
 
 extern "C" {
+
+int rov_trace_enable(int on) { return rov::g_trace_on.exchange(on ? 1 : 0); }
+
+int rov_trace_read(int* kinds, float* ms, int max_records, int* n_records) {
+    if (n_records == nullptr || max_records < 0 || (max_records > 0 && (kinds == nullptr || ms == nullptr)))
+        return ROV_ERR_INVALID;
+    std::lock_guard<std::mutex> lock(rov::g_trace_mu);
+    int n = 0;
+    for (size_t i = 0; i < rov::g_trace_used; ++i) {
+        const rov::TraceRec& r = rov::g_trace_pool[i];
+        ROV_HIP_TRY(hipEventSynchronize(r.b));
+        float t = 0.0f;
+        ROV_HIP_TRY(hipEventElapsedTime(&t, r.a, r.b));
+        if (n < max_records) {
+            kinds[n] = r.kind;
+            ms[n] = t;
+            ++n;
+        }
+    }
+    rov::g_trace_used = 0;
+    *n_records = n;
+    return ROV_OK;
+}
 
 int rov_last_hip_error(void) { return rov::t_last_hip_error; }
 

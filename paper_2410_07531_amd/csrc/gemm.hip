@@ -158,6 +158,9 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_tn_kernel(const uint16_t* __
                                                               int N, int K, float alpha, int tiles_m,
                                                               int tiles_n) {
     extern __shared__ __attribute__((aligned(1024))) char lds[];
+    // Co-resident RNG waves only need the VALU issue slots this kernel leaves idle; raise this
+    // wave's issue priority so that they never delay its MFMA / LDS instruction stream.
+    __builtin_amdgcn_s_setprio(3);
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int wm = wave >> 1, wn = wave & 1;

@@ -25,6 +25,7 @@ constexpr int kWavesPerBlock = 4;
 constexpr int kGroupsPerChunk = 16;   // 16 groups x 4 words = 64 words = one 8-byte store per lane
 
 std::atomic<int> g_rng_max_workgroups{0};
+std::atomic<int> g_rng_overlap_wgs_per_cu{2};
 
 // One chunk: 16 groups -> 64 mask words, word 4*gi + r parked in lane 4*gi + r of (vhi:vlo).
 template <int R, bool RAGGED, bool CARRY>
@@ -87,12 +88,17 @@ __global__ __launch_bounds__(256) void raw_kernel(uint32_t* __restrict__ out, ui
 
 template <int R>
 int launch_mask_r(uint64_t* out, uint64_t words, uint64_t offset, uint32_t k0, uint32_t k1,
-                  uint32_t t_minus_1, int S, hipStream_t stream) {
+                  uint32_t t_minus_1, int S, bool coresident, hipStream_t stream) {
     const uint32_t W = (uint32_t)(((uint64_t)S + 63u) / 64u);
     const uint64_t nchunks = (words + 63u) / 64u;
     uint64_t blocks = (nchunks + kWavesPerBlock - 1) / kWavesPerBlock;
     int cap = g_rng_max_workgroups.load();
-    if (cap <= 0) cap = device_cu_count() * 64;
+    if (cap <= 0) {
+        // alone: enough workgroups to fill every SIMD's wave slots several times over;
+        // beside a GEMM: a persistent grid of a few workgroups per compute unit, so that the
+        // GEMM's workgroup (most of the registers, most of the LDS) always still fits
+        cap = coresident ? device_cu_count() * g_rng_overlap_wgs_per_cu.load() : device_cu_count() * 64;
+    }
     if (blocks > (uint64_t)cap) blocks = (uint64_t)cap;
     const int rem = S & 63;
     const dim3 grid((unsigned)blocks), block(kWavesPerBlock * 64);
@@ -119,7 +125,7 @@ bool keep_threshold_minus_1(float p, uint32_t* t_minus_1) {
 }
 
 int launch_mask(uint64_t seed, uint64_t offset, int B, int H, int S, float p, int rounds,
-                uint64_t* out, hipStream_t stream) {
+                uint64_t* out, hipStream_t stream, bool coresident) {
     if (B <= 0 || H <= 0 || S <= 0 || out == nullptr) return ROV_ERR_INVALID;
     if (!aligned(out, 8)) return ROV_ERR_INVALID;
     uint32_t tm1;
@@ -131,10 +137,10 @@ int launch_mask(uint64_t seed, uint64_t offset, int B, int H, int S, float p, in
     const uint64_t words = (uint64_t)B * (uint64_t)H * (uint64_t)S * W;
     const uint32_t k0 = (uint32_t)seed, k1 = (uint32_t)(seed >> 32);
     switch (rounds) {
-        case 10: return launch_mask_r<10>(out, words, offset, k0, k1, tm1, S, stream);
-        case 7: return launch_mask_r<7>(out, words, offset, k0, k1, tm1, S, stream);
-        case 5: return launch_mask_r<5>(out, words, offset, k0, k1, tm1, S, stream);
-        case 3: return launch_mask_r<3>(out, words, offset, k0, k1, tm1, S, stream);
+        case 10: return launch_mask_r<10>(out, words, offset, k0, k1, tm1, S, coresident, stream);
+        case 7: return launch_mask_r<7>(out, words, offset, k0, k1, tm1, S, coresident, stream);
+        case 5: return launch_mask_r<5>(out, words, offset, k0, k1, tm1, S, coresident, stream);
+        case 3: return launch_mask_r<3>(out, words, offset, k0, k1, tm1, S, coresident, stream);
         default: return ROV_ERR_INVALID;
     }
 }
@@ -152,6 +158,10 @@ uint64_t rov_mask_words(int B, int H, int S) {
 uint64_t rov_mask_philox_calls(int B, int H, int S) {
     const uint64_t words = rov_mask_words(B, H, S);
     return 64u * ((words + 3u) / 4u);
+}
+
+int rov_set_rng_overlap_workgroups_per_cu(int n) {
+    return rov::g_rng_overlap_wgs_per_cu.exchange(n > 0 ? n : 2);
 }
 
 int rov_set_rng_max_workgroups(int max_workgroups) {

@@ -28,9 +28,15 @@ int device_cu_count();
 // outside [0,1) or NaN.
 bool keep_threshold_minus_1(float p, uint32_t* t_minus_1);
 
+// Kernel tracing (rov_trace_enable / rov_trace_read): trace_begin records a timing event on
+// `st` and returns a slot (or -1 when tracing is off); trace_end records the closing event.
+int trace_begin(int kind, hipStream_t st);
+void trace_end(int slot, hipStream_t st);
+
 // Launchers used across translation units (all asynchronous on `stream`).
+// coresident: launch a small persistent grid meant to run beside a GEMM (overlap schedule).
 int launch_mask(uint64_t seed, uint64_t offset, int B, int H, int S, float p, int rounds,
-                uint64_t* out, hipStream_t stream);
+                uint64_t* out, hipStream_t stream, bool coresident = false);
 int launch_gemm(const void* A, const void* Bm, void* C, int M, int N, int K, int dtype, int transB,
                 float scaleA, float scaleB, hipStream_t stream);
 // C = alpha * A W^T + R (R: bf16 [M,N] or nullptr); bf16 MFMA path only when R is given.

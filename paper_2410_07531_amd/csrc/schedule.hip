@@ -62,6 +62,28 @@ int check_attn_desc(const rov_attn_desc& a) {
     return ROV_OK;
 }
 
+// Runs one launcher call bracketed by trace events on its stream.
+template <typename F>
+int traced(int kind, hipStream_t st, F&& launch) {
+    const int slot = trace_begin(kind, st);
+    const int rc = launch();
+    trace_end(slot, st);
+    return rc;
+}
+
+int t_gemm(const void* A, const void* Bm, void* C, const void* R, int M, int N, int K, int dtype,
+           int transB, float sa, float sb, hipStream_t st) {
+    return traced(ROV_TRACE_GEMM, st, [&] {
+        return launch_gemm_residual(A, Bm, C, R, M, N, K, dtype, transB, sa, sb, st);
+    });
+}
+
+int t_mask(uint64_t seed, uint64_t offset, int B, int H, int S, float p, uint64_t* out, hipStream_t st,
+           bool coresident = false) {
+    return traced(ROV_TRACE_RNG, st,
+                  [&] { return launch_mask(seed, offset, B, H, S, p, 10, out, st, coresident); });
+}
+
 size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 struct BlockLayout {
@@ -123,8 +145,8 @@ extern "C" int rov_layer_step(int schedule, const rov_gemm_desc* gemms, int n_ge
     auto run_gemms = [&](hipStream_t st) {
         for (int i = 0; i < n_gemms; ++i) {
             const rov_gemm_desc& g = gemms[i];
-            const int rc = launch_gemm(g.A, g.Bm, g.C, g.M, g.N, g.K, g.dtype, g.transB, g.scaleA,
-                                       g.scaleB, st);
+            const int rc = t_gemm(g.A, g.Bm, g.C, nullptr, g.M, g.N, g.K, g.dtype, g.transB, g.scaleA,
+                                  g.scaleB, st);
             if (rc != ROV_OK) return rc;
         }
         return (int)ROV_OK;
@@ -135,15 +157,15 @@ extern "C" int rov_layer_step(int schedule, const rov_gemm_desc* gemms, int n_ge
         // registers; the RNG workgroups then fill the space left over (paper Sec. 6.2)
         if (n_gemms > 0) {
             const rov_gemm_desc& g = gemms[0];
-            rc = launch_gemm(g.A, g.Bm, g.C, g.M, g.N, g.K, g.dtype, g.transB, g.scaleA, g.scaleB, ms);
+            rc = t_gemm(g.A, g.Bm, g.C, nullptr, g.M, g.N, g.K, g.dtype, g.transB, g.scaleA, g.scaleB, ms);
             if (rc != ROV_OK) return rc;
         }
-        rc = launch_mask(seed, offset, attn->B, attn->H, attn->S, attn->p, 10, mask, ss);
+        rc = t_mask(seed, offset, attn->B, attn->H, attn->S, attn->p, mask, ss, true);
         if (rc != ROV_OK) return rc;
         ROV_HIP_TRY(hipEventRecord(ev->join, ss));
         for (int i = 1; i < n_gemms; ++i) {
             const rov_gemm_desc& g = gemms[i];
-            rc = launch_gemm(g.A, g.Bm, g.C, g.M, g.N, g.K, g.dtype, g.transB, g.scaleA, g.scaleB, ms);
+            rc = t_gemm(g.A, g.Bm, g.C, nullptr, g.M, g.N, g.K, g.dtype, g.transB, g.scaleA, g.scaleB, ms);
             if (rc != ROV_OK) return rc;
         }
         ROV_HIP_TRY(hipStreamWaitEvent(ms, ev->join, 0));
@@ -151,13 +173,15 @@ extern "C" int rov_layer_step(int schedule, const rov_gemm_desc* gemms, int n_ge
         rc = run_gemms(ms);
         if (rc != ROV_OK) return rc;
         if (need_mask) {
-            rc = launch_mask(seed, offset, attn->B, attn->H, attn->S, attn->p, 10, mask, ms);
+            rc = t_mask(seed, offset, attn->B, attn->H, attn->S, attn->p, mask, ms);
             if (rc != ROV_OK) return rc;
         }
     }
-    return launch_attention(attn->Q, attn->K, attn->V, attn->O, attn->B, attn->H, attn->Hkv, attn->S,
-                            attn->d, attn->strides, attn->dtype, attn->causal, attn->p,
-                            need_mask ? mask : nullptr, seed, offset, ms);
+    return traced(ROV_TRACE_ATTENTION, ms, [&] {
+        return launch_attention(attn->Q, attn->K, attn->V, attn->O, attn->B, attn->H, attn->Hkv,
+                                attn->S, attn->d, attn->strides, attn->dtype, attn->causal, attn->p,
+                                need_mask ? mask : nullptr, seed, offset, ms);
+    });
 }
 
 extern "C" size_t rov_block_workspace_bytes(const rov_block_cfg* cfg, int B, int S, int schedule) {
@@ -226,17 +250,19 @@ extern "C" int rov_block_forward(const rov_block_weights* w, const void* x, void
         ROV_HIP_TRY(hipEventRecord(ev->fork, ms));
         ROV_HIP_TRY(hipStreamWaitEvent(ss, ev->fork, 0));
     }
-    ROV_STEP(launch_rmsnorm(x, w->norm1, h, T, hidden, cfg->eps, ms));
-    ROV_STEP(launch_gemm(h, w->wqkv, qkv, (int)T, qkv_n, hidden, ROV_BF16, 1, 1.0f, 1.0f, ms));
+    ROV_STEP(traced(ROV_TRACE_GLUE, ms, [&] { return launch_rmsnorm(x, w->norm1, h, T, hidden, cfg->eps, ms); }));
+    ROV_STEP(t_gemm(h, w->wqkv, qkv, nullptr, (int)T, qkv_n, hidden, ROV_BF16, 1, 1.0f, 1.0f, ms));
     if (use_mask && !mask_ready) {
         if (overlap) {
-            ROV_STEP(launch_mask(seed, offset, B, H, S, cfg->p, 10, mask, ss));
+            ROV_STEP(t_mask(seed, offset, B, H, S, cfg->p, mask, ss, true));
             ROV_HIP_TRY(hipEventRecord(ev->join, ss));
         } else {
-            ROV_STEP(launch_mask(seed, offset, B, H, S, cfg->p, 10, mask, ms));
+            ROV_STEP(t_mask(seed, offset, B, H, S, cfg->p, mask, ms));
         }
     }
-    ROV_STEP(launch_rope(qkv, T, qkv_n, S, H + Hkv, d, cfg->rope_theta, ms));   // q heads then k heads
+    ROV_STEP(traced(ROV_TRACE_GLUE, ms, [&] {   // q heads then k heads
+        return launch_rope(qkv, T, qkv_n, S, H + Hkv, d, cfg->rope_theta, ms);
+    }));
     if (use_mask && !mask_ready && overlap) ROV_HIP_TRY(hipStreamWaitEvent(ms, ev->join, 0));
 
     const uint16_t* qp = (const uint16_t*)qkv;
@@ -245,9 +271,11 @@ extern "C" int rov_block_forward(const rov_block_weights* w, const void* x, void
         (int64_t)S * qkv_n, qkv_n, d,      // K
         (int64_t)S * qkv_n, qkv_n, d,      // V
         (int64_t)S * H * d, (int64_t)H * d, d};   // O
-    ROV_STEP(launch_attention(qp, qp + (int64_t)H * d, qp + (int64_t)(H + Hkv) * d, att, B, H, Hkv, S, d,
-                              strides, ROV_BF16, cfg->causal, cfg->p, use_mask ? mask : nullptr, seed,
-                              offset, ms));
+    ROV_STEP(traced(ROV_TRACE_ATTENTION, ms, [&] {
+        return launch_attention(qp, qp + (int64_t)H * d, qp + (int64_t)(H + Hkv) * d, att, B, H, Hkv, S,
+                                d, strides, ROV_BF16, cfg->causal, cfg->p, use_mask ? mask : nullptr,
+                                seed, offset, ms);
+    }));
 
     // the next layer's mask runs beside this block's remaining GEMMs (it would compete with
     // attention for VALU issue, so it starts once attention is done)
@@ -255,17 +283,16 @@ extern "C" int rov_block_forward(const rov_block_weights* w, const void* x, void
         ROV_HIP_TRY(hipEventRecord(ev->fork, ms));
         ROV_HIP_TRY(hipStreamWaitEvent(ss, ev->fork, 0));
     }
-    ROV_STEP(launch_gemm_residual(att, w->wo, x2, x, (int)T, hidden, H * d, ROV_BF16, 1, 1.0f, 1.0f, ms));
+    ROV_STEP(t_gemm(att, w->wo, x2, x, (int)T, hidden, H * d, ROV_BF16, 1, 1.0f, 1.0f, ms));
     if (overlap && next_mask != nullptr) {
-        ROV_STEP(launch_mask(seed, offset + rov_mask_philox_calls(B, H, S), B, H, S, cfg->p, 10,
-                             next_mask, ss));
+        ROV_STEP(t_mask(seed, offset + rov_mask_philox_calls(B, H, S), B, H, S, cfg->p, next_mask, ss, true));
         ROV_HIP_TRY(hipEventRecord(ev->join, ss));
     }
-    ROV_STEP(launch_rmsnorm(x2, w->norm2, h, T, hidden, cfg->eps, ms));
-    ROV_STEP(launch_gemm(h, w->wg, g, (int)T, ffn, hidden, ROV_BF16, 1, 1.0f, 1.0f, ms));
-    ROV_STEP(launch_gemm(h, w->wu, u, (int)T, ffn, hidden, ROV_BF16, 1, 1.0f, 1.0f, ms));
-    ROV_STEP(launch_swiglu(g, u, g, T * ffn, ms));
-    ROV_STEP(launch_gemm_residual(g, w->wd, y, x2, (int)T, hidden, ffn, ROV_BF16, 1, 1.0f, 1.0f, ms));
+    ROV_STEP(traced(ROV_TRACE_GLUE, ms, [&] { return launch_rmsnorm(x2, w->norm2, h, T, hidden, cfg->eps, ms); }));
+    ROV_STEP(t_gemm(h, w->wg, g, nullptr, (int)T, ffn, hidden, ROV_BF16, 1, 1.0f, 1.0f, ms));
+    ROV_STEP(t_gemm(h, w->wu, u, nullptr, (int)T, ffn, hidden, ROV_BF16, 1, 1.0f, 1.0f, ms));
+    ROV_STEP(traced(ROV_TRACE_GLUE, ms, [&] { return launch_swiglu(g, u, g, T * ffn, ms); }));
+    ROV_STEP(t_gemm(g, w->wd, y, x2, (int)T, hidden, ffn, ROV_BF16, 1, 1.0f, 1.0f, ms));
     if (overlap && next_mask != nullptr) ROV_HIP_TRY(hipStreamWaitEvent(ms, ev->join, 0));
 #undef ROV_STEP
     return ROV_OK;

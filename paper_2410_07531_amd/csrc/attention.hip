@@ -42,6 +42,7 @@ struct AttnParams {
     int64_t sq[3], sk[3], sv[3], so[3];   // element strides (batch, token, head)
     int B, H, Hkv, S, d;
     int W;                                // mask words per row
+    int nq;                               // query blocks per (batch, head)
     int causal;
     float scale_log2;                     // log2(e) / sqrt(d)
     float inv_keep;                       // 1 / (1 - p)
@@ -144,10 +145,24 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(const AttnParams p) {
     const int ql = lane & 31;     // query column within a 32-wide tile
     const int half = lane >> 5;
     const int S = p.S;
-    const int b = blockIdx.z, h = blockIdx.y;
+    // Workgroup ids are dealt round-robin to the 8 XCDs.  All query blocks of one (batch, head)
+    // go to the same XCD, so its K and V are fetched into one L2 only; within an XCD the order
+    // is query block first, then head, so co-resident workgroups walk the same K/V in step.
+    int qblk, bh;
+    {
+        const int pid = blockIdx.x, G = p.B * p.H, nq = p.nq;
+        if ((G & 7) == 0) {
+            const int xcd = pid & 7, j = pid >> 3, gpx = G >> 3;
+            qblk = j / gpx;
+            bh = (j % gpx) * 8 + xcd;
+        } else {
+            qblk = pid / G;
+            bh = pid % G;
+        }
+        if (p.causal) qblk = nq - 1 - qblk;   // heaviest query blocks first
+    }
+    const int b = bh / p.H, h = bh % p.H;
     const int hk = h / (p.H / p.Hkv);
-    // heaviest query blocks first when causal
-    const int qblk = p.causal ? (int)(gridDim.x - 1 - blockIdx.x) : (int)blockIdx.x;
     const int q0 = qblk * (128 * NQ) + wave * (32 * NQ);
 
     const uint16_t* Qp = (const uint16_t*)p.Q + b * p.sq[0] + h * p.sq[2];
@@ -184,19 +199,46 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(const AttnParams p) {
     const int kv_end = p.causal ? min(S, q_last + 1) : S;
     const int ntiles = (kv_end + BKV - 1) / BKV;
 
-    // mask words: row-major [b][h][row][W]
+    // Keep words.  MODE_MASK: one 8-byte word per query row and KV tile, loaded one tile
+    // ahead.  MODE_FUSED: when W % 4 == 0 the words of 4 consecutive KV tiles of a row are one
+    // Philox group; the wave generates them with the group/ballot routine of the stand-alone
+    // RNG kernel into LDS, [2 buffers][NQ*32 rows][4 words].  Otherwise one word per row and
+    // tile is generated.
+    constexpr int kMaskBuf = NQ * 32 * 32;                       // bytes per buffer per wave
+    char* mlds = lds + 2 * T::kStage + wave * (2 * kMaskBuf);
+    const bool aligned4 = (p.W & 3) == 0;
+    const uint64_t row0_words = (((uint64_t)b * p.H + h) * S) * (uint64_t)p.W;   // first word of row 0
     const uint64_t* mrow[NQ];
     uint2 mword[NQ], mnext[NQ];
-    if (MODE == MODE_MASK) {
 #pragma unroll
-        for (int n = 0; n < NQ; ++n) {
-            const int q = qrow[n] < S ? qrow[n] : S - 1;
-            mrow[n] = p.mask + (((int64_t)b * p.H + h) * S + q) * p.W;
-            mnext[n] = *reinterpret_cast<const uint2*>(mrow[n]);
-        }
+    for (int n = 0; n < NQ; ++n) {
+        const int q = qrow[n] < S ? qrow[n] : S - 1;
+        mrow[n] = p.mask + row0_words + (uint64_t)q * p.W;
+        mword[n] = make_uint2(0xFFFFFFFFu, 0xFFFFFFFFu);
+        if (MODE == MODE_MASK) mnext[n] = *reinterpret_cast<const uint2*>(mrow[n]);
     }
-    // fused: cached keep words of 4 consecutive KV tiles for this lane's query rows
-    uint32_t fw[NQ][8] = {};
+    // In-kernel generation of the same group: 16 rows at a time, word r of row gi parked in
+    // lane 4*gi + r, then one 8-byte LDS store per lane (same layout as the DMA).
+    auto mask_generate = [&](int group, int buf) {
+#pragma unroll 1
+        for (int c = 0; c < NQ * 2; ++c) {
+            uint32_t vlo = 0u, vhi = 0u;
+#pragma unroll 4
+            for (int gi = 0; gi < 16; ++gi) {
+                int row = q0 + 16 * c + gi;
+                row = row < S ? row : S - 1;
+                const uint64_t w = row0_words + (uint64_t)row * p.W + 4u * (uint64_t)group;
+                uint64_t bal[4];
+                philox_group_ballots<10, true>(p.offset + 64u * (w >> 2), lane, p.k0, p.k1, p.t_minus_1, bal);
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    vlo = write_lane((uint32_t)bal[r], 4u * gi + r, vlo);
+                    vhi = write_lane((uint32_t)(bal[r] >> 32), 4u * gi + r, vhi);
+                }
+            }
+            *reinterpret_cast<uint2*>(mlds + buf * kMaskBuf + (64 * c + lane) * 8) = make_uint2(vlo, vhi);
+        }
+    };
 
     uint4 vregs[D / 32];
     load_k_tile<D>(Kp, p.sk[1], 0, S, lds, wave, lane);
@@ -209,7 +251,7 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(const AttnParams p) {
         const int kv0 = jt * BKV;
         char* cur = lds + (jt & 1) * T::kStage;
         char* nxt = lds + ((jt + 1) & 1) * T::kStage;
-        __builtin_amdgcn_s_waitcnt(0x0070);   // vmcnt(0) lgkmcnt(0): own K loads and V^T writes done
+        __builtin_amdgcn_s_waitcnt(0x0070);   // vmcnt(0) lgkmcnt(0): own K / mask loads and V^T writes done
         __syncthreads();
         const bool has_next = jt + 1 < ntiles;
         if (has_next) {
@@ -217,6 +259,7 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(const AttnParams p) {
             load_v_regs<D>(Vp, p.sv[1], kv0 + BKV, S, vregs);
         }
         if (MODE == MODE_MASK) {
+            // this tile's words were requested one tile ago, under the previous Q K^T product
 #pragma unroll
             for (int n = 0; n < NQ; ++n) {
                 mword[n] = mnext[n];
@@ -224,53 +267,36 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(const AttnParams p) {
             }
         }
         if (MODE == MODE_FUSED) {
-            // Every 4th tile: regenerate the keep words of columns [256*(jt/4), +256) for the
-            // wave's rows.  Word w = row*W + cb sits in Philox group w/4; when W % 4 == 0 a
-            // group is exactly the 4 words of one row that the next 4 tiles need.  Otherwise a
-            // group is recomputed per tile and only word w%4 is used.
-            const bool aligned4 = (p.W & 3) == 0;
-            if (!aligned4 || (jt & 3) == 0) {
+            const int group = jt >> 2, gbuf = group & 1;
+            if (aligned4) {
+                if ((jt & 3) == 0) mask_generate(group, gbuf);
 #pragma unroll
-                for (int n = 0; n < NQ; ++n) {
-                    for (int r = 0; r < 32; ++r) {
-                        int row = q0 + 32 * n + r;
+                for (int n = 0; n < NQ; ++n)
+                    mword[n] = *reinterpret_cast<const uint2*>(mlds + gbuf * kMaskBuf +
+                                                               (32 * n + ql) * 32 + (jt & 3) * 8);
+            } else {
+                // one word per row and tile: the group holding word row*W + jt, its word w % 4
+#pragma unroll 1
+                for (int c = 0; c < NQ * 2; ++c) {
+                    uint32_t vlo = 0u, vhi = 0u;
+#pragma unroll 2
+                    for (int gi = 0; gi < 16; ++gi) {
+                        int row = q0 + 16 * c + gi;
                         row = row < S ? row : S - 1;
-                        const uint64_t w = (((uint64_t)b * p.H + h) * S + row) * p.W + (uint64_t)jt;
-                        const uint64_t base = p.offset + 64u * (w >> 2);
+                        const uint64_t w = row0_words + (uint64_t)row * p.W + (uint64_t)jt;
                         uint64_t bal[4];
-                        if ((uint32_t)base <= 0xFFFFFFFFu - 63u)
-                            philox_group_ballots<10, false>(base, lane, p.k0, p.k1, p.t_minus_1, bal);
-                        else
-                            philox_group_ballots<10, true>(base, lane, p.k0, p.k1, p.t_minus_1, bal);
-                        if (aligned4) {
-#pragma unroll
-                            for (int c = 0; c < 4; ++c) {
-                                fw[n][2 * c] = write_lane((uint32_t)bal[c], r, fw[n][2 * c]);
-                                fw[n][2 * c] = write_lane((uint32_t)bal[c], r + 32, fw[n][2 * c]);
-                                fw[n][2 * c + 1] = write_lane((uint32_t)(bal[c] >> 32), r, fw[n][2 * c + 1]);
-                                fw[n][2 * c + 1] = write_lane((uint32_t)(bal[c] >> 32), r + 32, fw[n][2 * c + 1]);
-                            }
-                        } else {
-                            const uint32_t sel = (uint32_t)(w & 3u);
-                            const uint64_t bw = sel == 0 ? bal[0] : sel == 1 ? bal[1] : sel == 2 ? bal[2] : bal[3];
-                            fw[n][0] = write_lane((uint32_t)bw, r, fw[n][0]);
-                            fw[n][0] = write_lane((uint32_t)bw, r + 32, fw[n][0]);
-                            fw[n][1] = write_lane((uint32_t)(bw >> 32), r, fw[n][1]);
-                            fw[n][1] = write_lane((uint32_t)(bw >> 32), r + 32, fw[n][1]);
-                        }
+                        philox_group_ballots<10, true>(p.offset + 64u * (w >> 2), lane, p.k0, p.k1,
+                                                       p.t_minus_1, bal);
+                        const uint32_t sel = (uint32_t)(w & 3u);
+                        const uint64_t bw = sel == 0 ? bal[0] : sel == 1 ? bal[1] : sel == 2 ? bal[2] : bal[3];
+                        vlo = write_lane((uint32_t)bw, (uint32_t)gi, vlo);
+                        vhi = write_lane((uint32_t)(bw >> 32), (uint32_t)gi, vhi);
                     }
+                    if (lane < 16) *reinterpret_cast<uint2*>(mlds + (16 * c + lane) * 8) = make_uint2(vlo, vhi);
                 }
-            }
 #pragma unroll
-            for (int n = 0; n < NQ; ++n) {
-                if (aligned4) {
-                    const int c = jt & 3;
-                    mword[n].x = c == 0 ? fw[n][0] : c == 1 ? fw[n][2] : c == 2 ? fw[n][4] : fw[n][6];
-                    mword[n].y = c == 0 ? fw[n][1] : c == 1 ? fw[n][3] : c == 2 ? fw[n][5] : fw[n][7];
-                } else {
-                    mword[n].x = fw[n][0];
-                    mword[n].y = fw[n][1];
-                }
+                for (int n = 0; n < NQ; ++n)
+                    mword[n] = *reinterpret_cast<const uint2*>(mlds + (32 * n + ql) * 8);
             }
         }
 
@@ -330,8 +356,9 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(const AttnParams p) {
                     float pe = fast_exp2(s[t][n][e] - m_safe);
                     sum += pe;   // the normaliser counts dropped entries too
                     if (MODE != MODE_NONE) {
-                        const uint32_t bit = (bits >> (8 * (e >> 2) + (e & 3))) & 1u;
-                        pe = bit ? pe : 0.0f;
+                        // sign-extended 1-bit field -> all-ones / zero mask, then one AND
+                        const int keep = __builtin_amdgcn_sbfe((int)bits, 8 * (e >> 2) + (e & 3), 1);
+                        pe = __uint_as_float(__float_as_uint(pe) & (uint32_t)keep);
                     }
                     s[t][n][e] = pe;
                 }
@@ -510,14 +537,18 @@ __global__ __launch_bounds__(256) void attn_generic_kernel(const AttnParams p) {
 template <int D, int NQ>
 int launch_bf16(const AttnParams& prm, int mode, hipStream_t stream) {
     const int bq = 128 * NQ;
-    const dim3 grid((unsigned)((prm.S + bq - 1) / bq), (unsigned)prm.H, (unsigned)prm.B), block(256);
-    const int lds_bytes = 2 * Tile<D>::kStage;
+    AttnParams prm2 = prm;
+    prm2.nq = (prm.S + bq - 1) / bq;
+    const long long nblocks = (long long)prm2.nq * prm.H * prm.B;
+    if (nblocks > 0x7FFFFFFFLL) return ROV_ERR_UNSUPPORTED;
+    const dim3 grid((unsigned)nblocks), block(256);
+    const int lds_bytes = 2 * Tile<D>::kStage + 4 * 2 * (NQ * 32 * 32);   // K/V stages + per-wave keep words
     void (*kern)(const AttnParams) = mode == MODE_NONE   ? attn_bf16_kernel<D, NQ, MODE_NONE>
                                      : mode == MODE_MASK ? attn_bf16_kernel<D, NQ, MODE_MASK>
                                                          : attn_bf16_kernel<D, NQ, MODE_FUSED>;
     ROV_HIP_TRY(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
                                     lds_bytes));
-    hipLaunchKernelGGL(kern, grid, block, lds_bytes, stream, prm);
+    hipLaunchKernelGGL(kern, grid, block, lds_bytes, stream, prm2);
     ROV_LAUNCH_CHECK();
     return ROV_OK;
 }

@@ -107,7 +107,8 @@ int rov_set_rng_overlap_workgroups_per_cu(int n);
  * chains x 4 x iters operations of `kind`:
  *   0 = 32x32->64 multiply plus one add, 1 = low-half multiply, 2 = high-half
  *   multiply, 3 = three-input xor, 4 = add, 5 = compare-to-ballot plus lane write
- *   plus one add.
+ *   plus one add, 6 = MFMA 32x32x16 bf16 (32 independent issues per iteration,
+ *   i.e. 32 * 32768 flop per wave per iteration: the matrix-core rate under load).
  * out: device, 2 uint64 per wave (4*workgroups waves): elapsed shader-clock
  * ticks of the loop as read by s_memtime, and a checksum. */
 int rov_valu_probe(int kind, int iters, int workgroups, uint64_t *out, void *stream);

@@ -16,8 +16,13 @@
 // The register budget is capped below the full file so that RNG waves can be
 // co-resident on every SIMD (the paper's carve-out, Sec. 6.2).
 //
-// Everything else (fp32, [K,N] weights, K not a multiple of 64) takes a small
-// LDS-tiled VALU kernel that is correct for any shape.
+// fp8 (OCP e4m3) uses the same kernel: a tile row is 128 bytes either way (64
+// bf16 or 128 fp8 values), and each 16-byte fragment feeds two MFMA 32x32x16
+// fp8 instructions (which 8 of the 16 k-values a half-wave supplies is the same
+// for both operands, so the sum is unchanged).
+//
+// Everything else (fp32, [K,N] weights, K not a multiple of the tile depth)
+// takes a small LDS-tiled VALU kernel that is correct for any shape.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -49,6 +54,18 @@ __device__ __forceinline__ float load_as_f32<float>(const float* p) { return *p;
 template <>
 __device__ __forceinline__ float load_as_f32<uint16_t>(const uint16_t* p) { return bf16_bits_to_f32(*p); }
 
+// OCP e4m3: 1 sign, 4 exponent bits (bias 7), 3 mantissa bits; 0x7F / 0xFF are NaN; no infinities.
+__device__ __forceinline__ float e4m3_to_f32(uint8_t c) {
+    const uint32_t e = (c >> 3) & 0xFu, m = c & 0x7u;
+    float v;
+    if (e == 0xFu && m == 0x7u) v = __uint_as_float(0x7FC00000u);
+    else if (e == 0u) v = (float)m * 0.001953125f;                       // m/8 * 2^-6
+    else v = __uint_as_float(((e + 120u) << 23) | (m << 20));            // (1 + m/8) * 2^(e-7)
+    return (c & 0x80u) ? -v : v;
+}
+template <>
+__device__ __forceinline__ float load_as_f32<uint8_t>(const uint8_t* p) { return e4m3_to_f32(*p); }
+
 template <typename T>
 __device__ __forceinline__ void store_from_f32(T* p, float v);
 template <>
@@ -56,10 +73,10 @@ __device__ __forceinline__ void store_from_f32<float>(float* p, float v) { *p = 
 template <>
 __device__ __forceinline__ void store_from_f32<uint16_t>(uint16_t* p, float v) { *p = f32_to_bf16_bits(v); }
 
-template <typename T, bool TRANSB>
+template <typename T, typename TO, bool TRANSB>
 __global__ __launch_bounds__(256) void gemm_generic_kernel(const T* __restrict__ A,
                                                            const T* __restrict__ Bm,
-                                                           T* __restrict__ C, int M, int N, int K,
+                                                           TO* __restrict__ C, int M, int N, int K,
                                                            float alpha) {
     __shared__ float As[16][64 + 1];
     __shared__ float Bs[16][64 + 1];
@@ -107,19 +124,21 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(const T* __restrict__
         }
 }
 
-// ------------------------------------------------------------------ bf16 MFMA kernel
-constexpr int BM = 256, BN = 256, BK = 64;
-constexpr int kStageBytes = (BM + BN) * BK * 2;     // 64 KiB: A tile then W tile
-constexpr int kRowBytes = BK * 2;                   // 128 bytes per tile row
+// ------------------------------------------------------------------ MFMA kernel (bf16 / fp8)
+constexpr int BM = 256, BN = 256;
+constexpr int kRowBytes = 128;                      // one tile row: 64 bf16 or 128 fp8 values
+constexpr int kStageBytes = (BM + BN) * kRowBytes;  // 64 KiB: A tile then W tile
 
 typedef const __attribute__((address_space(1))) void* gptr_t;
 typedef __attribute__((address_space(3))) void* lptr_t;
+typedef int i32x4 __attribute__((ext_vector_type(4)));
 
-// One operand tile (256 rows x 64 k) from global to LDS.  Wave w copies row
+// One operand tile (256 rows x 128 bytes of k) from global to LDS.  Wave w copies row
 // blocks w, w+4, ... (8 rows each); within a block lane L fills physical chunk
 // L%8 of row L/8, which holds logical chunk (L%8) ^ (row%8).
-__device__ __forceinline__ void load_tile(const uint16_t* __restrict__ src, int ld, int row0,
-                                          int max_row, int k0, char* lds_tile, int wave, int lane) {
+__device__ __forceinline__ void load_tile(const char* __restrict__ src, size_t ld_bytes, int row0,
+                                          int max_row, size_t k0_bytes, char* lds_tile, int wave,
+                                          int lane) {
     const int rl = lane >> 3;                        // row within the 8-row block
     const int chunk = (lane & 7) ^ rl;               // logical 16-byte chunk this lane fetches
 #pragma unroll
@@ -127,7 +146,7 @@ __device__ __forceinline__ void load_tile(const uint16_t* __restrict__ src, int 
         const int blk = wave + 4 * i;                // 0..31
         int row = row0 + blk * 8 + rl;
         row = row < max_row ? row : max_row;         // clamp: rows past the edge are never stored
-        const uint16_t* g = src + (size_t)row * ld + k0 + chunk * 8;
+        const char* g = src + (size_t)row * ld_bytes + k0_bytes + chunk * 16;
         __builtin_amdgcn_global_load_lds((gptr_t)g, (lptr_t)(lds_tile + blk * 8 * kRowBytes), 16, 0, 0);
     }
 }
@@ -151,12 +170,13 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
     return *reinterpret_cast<uint32_t*>(&h);
 }
 
-__global__ __launch_bounds__(256, 1) void gemm_bf16_tn_kernel(const uint16_t* __restrict__ A,
-                                                              const uint16_t* __restrict__ Wt,
-                                                              uint16_t* __restrict__ C,
-                                                              const uint16_t* __restrict__ R, int M,
-                                                              int N, int K, float alpha, int tiles_m,
-                                                              int tiles_n) {
+// ESZ: bytes per input element (2 = bf16, 1 = fp8 e4m3).  Output and residual are bf16.
+template <int ESZ>
+__global__ __launch_bounds__(256, 1) void gemm_tn_kernel(const char* __restrict__ A,
+                                                         const char* __restrict__ Wt,
+                                                         uint16_t* __restrict__ C,
+                                                         const uint16_t* __restrict__ R, int M, int N,
+                                                         int K, float alpha, int tiles_m, int tiles_n) {
     extern __shared__ __attribute__((aligned(1024))) char lds[];
     // Co-resident RNG waves only need the VALU issue slots this kernel leaves idle; raise this
     // wave's issue priority so that they never delay its MFMA / LDS instruction stream.
@@ -200,24 +220,25 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_tn_kernel(const uint16_t* __
     const int a_base = (wm * 128) * kRowBytes;
     const int w_base = BM * kRowBytes + (wn * 128) * kRowBytes;
 
-    bf16x8 af[2][4], wf[2][4];   // fragments of the current and the next k-step
+    i32x4 af[2][4], wf[2][4];   // 16-byte fragments of the current and the next k-step
     auto read_frags = [&](int buf, const char* stage, int kk) {
 #pragma unroll
         for (int i = 0; i < 4; ++i)
-            af[buf][i] = *reinterpret_cast<const bf16x8*>(stage + a_base + i * 32 * kRowBytes + foff[kk]);
+            af[buf][i] = *reinterpret_cast<const i32x4*>(stage + a_base + i * 32 * kRowBytes + foff[kk]);
 #pragma unroll
         for (int j = 0; j < 4; ++j)
-            wf[buf][j] = *reinterpret_cast<const bf16x8*>(stage + w_base + j * 32 * kRowBytes + foff[kk]);
+            wf[buf][j] = *reinterpret_cast<const i32x4*>(stage + w_base + j * 32 * kRowBytes + foff[kk]);
     };
 
-    const int nk = K / BK;
-    load_tile(A, K, m0, M - 1, 0, lds, wave, lane);
-    load_tile(Wt, K, n0, N - 1, 0, lds + BM * kRowBytes, wave, lane);
+    const size_t ld_bytes = (size_t)K * ESZ;
+    const int nk = (int)(ld_bytes / kRowBytes);
+    load_tile(A, ld_bytes, m0, M - 1, 0, lds, wave, lane);
+    load_tile(Wt, ld_bytes, n0, N - 1, 0, lds + BM * kRowBytes, wave, lane);
     __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
     __syncthreads();
     if (nk > 1) {
-        load_tile(A, K, m0, M - 1, BK, lds + kStageBytes, wave, lane);
-        load_tile(Wt, K, n0, N - 1, BK, lds + kStageBytes + BM * kRowBytes, wave, lane);
+        load_tile(A, ld_bytes, m0, M - 1, kRowBytes, lds + kStageBytes, wave, lane);
+        load_tile(Wt, ld_bytes, n0, N - 1, kRowBytes, lds + kStageBytes + BM * kRowBytes, wave, lane);
     }
     read_frags(0, lds, 0);
 
@@ -234,18 +255,34 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_tn_kernel(const uint16_t* __
                 __syncthreads();
                 if (kt + 2 < nk) {
                     char* refill = lds + (kt & 1) * kStageBytes;
-                    load_tile(A, K, m0, M - 1, (kt + 2) * BK, refill, wave, lane);
-                    load_tile(Wt, K, n0, N - 1, (kt + 2) * BK, refill + BM * kRowBytes, wave, lane);
+                    load_tile(A, ld_bytes, m0, M - 1, (size_t)(kt + 2) * kRowBytes, refill, wave, lane);
+                    load_tile(Wt, ld_bytes, n0, N - 1, (size_t)(kt + 2) * kRowBytes, refill + BM * kRowBytes,
+                              wave, lane);
                 }
                 read_frags(0, lds + ((kt + 1) & 1) * kStageBytes, 0);
             }
             __builtin_amdgcn_sched_barrier(0);
+            if (ESZ == 2) {
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
+                for (int j = 0; j < 4; ++j)
 #pragma unroll
-                for (int i = 0; i < 4; ++i)
-                    acc[j][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[kk & 1][j], af[kk & 1][i],
-                                                                        acc[j][i], 0, 0, 0);
+                    for (int i = 0; i < 4; ++i)
+                        acc[j][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                            __builtin_bit_cast(bf16x8, wf[kk & 1][j]), __builtin_bit_cast(bf16x8, af[kk & 1][i]),
+                            acc[j][i], 0, 0, 0);
+            } else {
+#pragma unroll
+                for (int hf = 0; hf < 2; ++hf)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j)
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) {
+                            const i32x4 wv = wf[kk & 1][j], av = af[kk & 1][i];
+                            const long wl = ((long)(uint32_t)wv[2 * hf]) | ((long)wv[2 * hf + 1] << 32);
+                            const long al = ((long)(uint32_t)av[2 * hf]) | ((long)av[2 * hf + 1] << 32);
+                            acc[j][i] = __builtin_amdgcn_mfma_f32_32x32x16_fp8_fp8(wl, al, acc[j][i], 0, 0, 0);
+                        }
+            }
             __builtin_amdgcn_sched_barrier(0);
         }
     }
@@ -301,24 +338,24 @@ int launch_gemm_residual(const void* A, const void* Bm, void* C, const void* R, 
         return ROV_ERR_INVALID;
     if (!aligned(A, 16) || !aligned(Bm, 16) || !aligned(C, 16)) return ROV_ERR_INVALID;
     if (dtype != ROV_F32 && dtype != ROV_BF16 && dtype != ROV_FP8_E4M3) return ROV_ERR_INVALID;
-    if (dtype == ROV_FP8_E4M3) return ROV_ERR_UNSUPPORTED;
     const float alpha = scaleA * scaleB;
     const bool tb = transB != 0;
+    const int esz = dtype == ROV_BF16 ? 2 : 1;
 
-    if (dtype == ROV_BF16 && tb && (K % BK) == 0 && (N % 4) == 0) {
+    if (dtype != ROV_F32 && tb && ((size_t)K * esz) % kRowBytes == 0 && (N % 4) == 0) {
         const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
         const long long T = (long long)tiles_m * tiles_n;
         if (T > 0x7FFFFFFFLL) return ROV_ERR_UNSUPPORTED;
-        static bool attr_set = false;
-        if (!attr_set) {
-            ROV_HIP_TRY(hipFuncSetAttribute((const void*)gemm_bf16_tn_kernel,
-                                            hipFuncAttributeMaxDynamicSharedMemorySize,
+        auto kern = esz == 2 ? gemm_tn_kernel<2> : gemm_tn_kernel<1>;
+        static bool attr_set[2] = {false, false};
+        if (!attr_set[esz - 1]) {
+            ROV_HIP_TRY(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
                                             2 * kStageBytes));
-            attr_set = true;
+            attr_set[esz - 1] = true;
         }
-        hipLaunchKernelGGL(gemm_bf16_tn_kernel, dim3((unsigned)T), dim3(256), 2 * kStageBytes, stream,
-                           (const uint16_t*)A, (const uint16_t*)Bm, (uint16_t*)C, (const uint16_t*)R,
-                           M, N, K, alpha, tiles_m, tiles_n);
+        hipLaunchKernelGGL(kern, dim3((unsigned)T), dim3(256), 2 * kStageBytes, stream, (const char*)A,
+                           (const char*)Bm, (uint16_t*)C, (const uint16_t*)R, M, N, K, alpha, tiles_m,
+                           tiles_n);
         ROV_LAUNCH_CHECK();
         return ROV_OK;
     }
@@ -328,18 +365,25 @@ int launch_gemm_residual(const void* A, const void* Bm, void* C, const void* R, 
     if (grid.y > 65535u) return ROV_ERR_UNSUPPORTED;
     if (dtype == ROV_F32) {
         if (tb)
-            hipLaunchKernelGGL((gemm_generic_kernel<float, true>), grid, block, 0, stream,
+            hipLaunchKernelGGL((gemm_generic_kernel<float, float, true>), grid, block, 0, stream,
                                (const float*)A, (const float*)Bm, (float*)C, M, N, K, alpha);
         else
-            hipLaunchKernelGGL((gemm_generic_kernel<float, false>), grid, block, 0, stream,
+            hipLaunchKernelGGL((gemm_generic_kernel<float, float, false>), grid, block, 0, stream,
                                (const float*)A, (const float*)Bm, (float*)C, M, N, K, alpha);
+    } else if (dtype == ROV_BF16) {
+        if (tb)
+            hipLaunchKernelGGL((gemm_generic_kernel<uint16_t, uint16_t, true>), grid, block, 0, stream,
+                               (const uint16_t*)A, (const uint16_t*)Bm, (uint16_t*)C, M, N, K, alpha);
+        else
+            hipLaunchKernelGGL((gemm_generic_kernel<uint16_t, uint16_t, false>), grid, block, 0, stream,
+                               (const uint16_t*)A, (const uint16_t*)Bm, (uint16_t*)C, M, N, K, alpha);
     } else {
         if (tb)
-            hipLaunchKernelGGL((gemm_generic_kernel<uint16_t, true>), grid, block, 0, stream,
-                               (const uint16_t*)A, (const uint16_t*)Bm, (uint16_t*)C, M, N, K, alpha);
+            hipLaunchKernelGGL((gemm_generic_kernel<uint8_t, uint16_t, true>), grid, block, 0, stream,
+                               (const uint8_t*)A, (const uint8_t*)Bm, (uint16_t*)C, M, N, K, alpha);
         else
-            hipLaunchKernelGGL((gemm_generic_kernel<uint16_t, false>), grid, block, 0, stream,
-                               (const uint16_t*)A, (const uint16_t*)Bm, (uint16_t*)C, M, N, K, alpha);
+            hipLaunchKernelGGL((gemm_generic_kernel<uint8_t, uint16_t, false>), grid, block, 0, stream,
+                               (const uint8_t*)A, (const uint8_t*)Bm, (uint16_t*)C, M, N, K, alpha);
     }
     ROV_LAUNCH_CHECK();
     return ROV_OK;

@@ -64,12 +64,50 @@ __global__ __launch_bounds__(256) void probe_kernel(uint64_t* __restrict__ out, 
     }
 }
 
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+// kind 6: back-to-back independent MFMA 32x32x16 bf16 (4 accumulators per wave, no memory
+// traffic): the matrix-core rate this device sustains, i.e. the clock it holds under MFMA load.
+__global__ __launch_bounds__(256) void probe_mfma_kernel(uint64_t* __restrict__ out, int iters, uint32_t s) {
+    bf16x8 a, b;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        a[i] = (__bf16)(float)((threadIdx.x + i) & 3);
+        b[i] = (__bf16)(float)((threadIdx.x * 3 + i + s) & 3);
+    }
+    f32x16 acc[4];
+#pragma unroll
+    for (int c = 0; c < 4; ++c)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[c][e] = 0.0f;
+    const uint64_t t0 = __builtin_readcyclecounter();
+    for (int i = 0; i < iters; ++i) {
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+#pragma unroll
+            for (int c = 0; c < 4; ++c)
+                acc[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[c], 0, 0, 0);
+    }
+    const uint64_t t1 = __builtin_readcyclecounter();
+    float sum = 0.0f;
+#pragma unroll
+    for (int c = 0; c < 4; ++c)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) sum += acc[c][e];
+    if ((threadIdx.x & 63u) == 0u) {
+        const uint64_t wave = ((uint64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+        out[2 * wave] = t1 - t0;
+        out[2 * wave + 1] = (uint64_t)__float_as_uint(sum);
+    }
+}
+
 }  // namespace
 }  // namespace rov
 
 // Diagnostic entry point (declared in rov.h).
 extern "C" int rov_valu_probe(int kind, int iters, int workgroups, uint64_t* out, void* stream) {
-    if (kind < 0 || kind > 5 || iters <= 0 || workgroups <= 0 || out == nullptr) return ROV_ERR_INVALID;
+    if (kind < 0 || kind > 6 || iters <= 0 || workgroups <= 0 || out == nullptr) return ROV_ERR_INVALID;
     if (!rov::aligned(out, 8)) return ROV_ERR_INVALID;
     const dim3 grid((unsigned)workgroups), block(256);
     hipStream_t st = (hipStream_t)stream;
@@ -80,7 +118,8 @@ extern "C" int rov_valu_probe(int kind, int iters, int workgroups, uint64_t* out
         case 2: hipLaunchKernelGGL(rov::probe_kernel<2>, grid, block, 0, st, out, iters, s); break;
         case 3: hipLaunchKernelGGL(rov::probe_kernel<3>, grid, block, 0, st, out, iters, s); break;
         case 4: hipLaunchKernelGGL(rov::probe_kernel<4>, grid, block, 0, st, out, iters, s); break;
-        default: hipLaunchKernelGGL(rov::probe_kernel<5>, grid, block, 0, st, out, iters, s); break;
+        case 5: hipLaunchKernelGGL(rov::probe_kernel<5>, grid, block, 0, st, out, iters, s); break;
+        default: hipLaunchKernelGGL(rov::probe_mfma_kernel, grid, block, 0, st, out, iters, s); break;
     }
     ROV_LAUNCH_CHECK();
     return ROV_OK;

@@ -114,3 +114,85 @@ def test_gemm_error_paths():
     assert L.rov_gemm(ctypes.c_void_p(A.data_ptr() + 2), p(A), p(C), 32, 32, 32, rov.BF16, 1, 1.0, 1.0, s) == rov.ERR_INVALID
     torch.cuda.synchronize()
     assert bool((C == 7.0).all())
+
+
+# ----------------------------------------------------------------------------- fp8 (OCP e4m3)
+FP8_TOL = 6e-2          # the workload definition's bar for fp8 GEMM outputs
+FP8_EXPECTED = 6e-3     # fp8 x fp8 products are exact in fp32; only the bf16 result rounding remains
+
+
+def _quantise(x):
+    """Per-tensor scale = amax/448; codes by the library conversion (plumbing); both sides get the codes."""
+    amax = float(np.max(np.abs(x)))
+    scale = float(np.float32(amax / 448.0))
+    codes = torch.from_numpy((x / np.float32(scale)).astype(np.float32)).to(torch.float8_e4m3fn)
+    return codes.view(torch.uint8), scale
+
+
+def test_gemm_fp8_decodes_every_code_as_ocp_e4m3():
+    from oracle import numerics as ON
+    table = ON.e4m3_decode_table()
+    K, N, M = 128, 256, 128
+    A = torch.zeros((M, K), dtype=torch.uint8)
+    A[torch.arange(M), torch.arange(M)] = 0x38                      # 1.0
+    W = torch.zeros((N, K), dtype=torch.uint8)
+    W[torch.arange(N), torch.arange(N) % K] = torch.arange(N, dtype=torch.int32).to(torch.uint8)
+    W[0x7F, 0x7F] = 0                                               # the two NaN codes are left out
+    W[0xFF, 0xFF % K] = 0
+    C = rov.gemm(A.cuda(), W.cuda(), transB=True)
+    torch.cuda.synchronize()
+    got = _f64(C)
+    for n in range(N):
+        if n in (0x7F, 0xFF):
+            continue
+        assert got[n % K, n] == table[n], (n, got[n % K, n], table[n])
+    assert np.count_nonzero(got) == 256 - 4                         # +-0 and the two skipped codes
+
+
+@pytest.mark.parametrize("M,N,K", [
+    (256, 256, 128),        # one tile, one k-step
+    (512, 768, 896),        # several tiles, odd number of k-steps
+    (300, 520, 384),        # ragged M and N
+    (77, 130, 100),         # generic kernel (N % 4 != 0, K % 128 != 0)
+])
+def test_gemm_fp8_matches_oracle(M, N, K):
+    from oracle import numerics as ON
+    print("gemm fp8", M, N, K, flush=True)
+    rng = np.random.default_rng(M + N + K)
+    a, w = wl.gemm_operands(rng, M, K, N)
+    Aq, sa = _quantise(a)
+    Wq, sb = _quantise(w)
+    C = rov.gemm(Aq.cuda(), Wq.cuda(), transB=True, scaleA=sa, scaleB=sb)
+    torch.cuda.synchronize()
+    ref = sa * sb * OD.gemm(ON.e4m3_decode(Aq.numpy()), ON.e4m3_decode(Wq.numpy()), transB=True)
+    err = _rel_err(_f64(C), ref)
+    assert err <= FP8_TOL and err <= FP8_EXPECTED, err
+    # the oracle's own encoder picks the same codes as the plumbing conversion (zero sign aside)
+    mine = ON.e4m3_encode(a / np.float32(sa))
+    nz = (mine & 0x7F) != 0
+    assert np.array_equal(mine[nz], Aq.numpy()[nz])
+
+
+def test_gemm_fp8_llama70b_qkv_sampled():
+    # fourth workload's QKV projection at full size: 8192 x 8192 x 10240, fp8 e4m3, per-tensor scales
+    from oracle import numerics as ON
+    _, M, K, N = wl.CONFIGS[3]["gemms"][0]
+    print("gemm fp8 cfg4 qkv", M, K, N, flush=True)
+    rng = wl.rng_for(3)
+    a, w = wl.gemm_operands(rng, M, K, N)
+    Aq, sa = _quantise(a)
+    Wq, sb = _quantise(w)
+    C = rov.gemm(Aq.cuda(), Wq.cuda(), transB=True, scaleA=sa, scaleB=sb)
+    torch.cuda.synchronize()
+    Ch = _f64(C)
+    srng = np.random.default_rng(9)
+    rows = np.sort(srng.choice(M, 32, replace=False))
+    rows[0], rows[-1] = 0, M - 1
+    Wd = ON.e4m3_decode(Wq.numpy())
+    ref = sa * sb * OD.gemm(ON.e4m3_decode(Aq.numpy()[rows]), Wd, transB=True)
+    scale = float(np.max(np.abs(ref)))
+    err = float(np.max(np.abs(Ch[rows] - ref)) / scale)
+    assert err <= FP8_TOL and err <= FP8_EXPECTED, err
+    # reported only: distance to the unquantised product
+    full = OD.gemm(a[rows].astype(np.float64), w.astype(np.float64), transB=True)
+    print("fp8 vs unquantised product: rel err %.4f" % (np.max(np.abs(Ch[rows] - full)) / np.max(np.abs(full))), flush=True)

@@ -135,19 +135,29 @@ typedef int i32x4 __attribute__((ext_vector_type(4)));
 
 // One operand tile (256 rows x 128 bytes of k) from global to LDS.  Wave w copies row
 // blocks w, w+4, ... (8 rows each); within a block lane L fills physical chunk
-// L%8 of row L/8, which holds logical chunk (L%8) ^ (row%8).
-__device__ __forceinline__ void load_tile(const char* __restrict__ src, size_t ld_bytes, int row0,
-                                          int max_row, size_t k0_bytes, char* lds_tile, int wave,
-                                          int lane) {
+// L%8 of row L/8, which holds logical chunk (L%8) ^ (row%8).  `panel` points at the first
+// row of the 256-row operand panel plus the k offset (wave-uniform); voff[i] is the lane's
+// constant byte offset inside the panel for row block i, so the address is a scalar base
+// plus a 32-bit vector offset and the loop does no vector address arithmetic.
+__device__ __forceinline__ void load_tile(const char* __restrict__ panel, const uint32_t (&voff)[8],
+                                          char* lds_tile, int wave) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const int blk = wave + 4 * i;                // 0..31
+        __builtin_amdgcn_global_load_lds((gptr_t)(panel + voff[i]), (lptr_t)(lds_tile + blk * 8 * kRowBytes),
+                                         16, 0, 0);
+    }
+}
+
+__device__ __forceinline__ void lane_offsets(uint32_t (&voff)[8], size_t ld_bytes, int rows_valid, int wave,
+                                             int lane) {
     const int rl = lane >> 3;                        // row within the 8-row block
     const int chunk = (lane & 7) ^ rl;               // logical 16-byte chunk this lane fetches
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
-        const int blk = wave + 4 * i;                // 0..31
-        int row = row0 + blk * 8 + rl;
-        row = row < max_row ? row : max_row;         // clamp: rows past the edge are never stored
-        const char* g = src + (size_t)row * ld_bytes + k0_bytes + chunk * 16;
-        __builtin_amdgcn_global_load_lds((gptr_t)g, (lptr_t)(lds_tile + blk * 8 * kRowBytes), 16, 0, 0);
+        int row = (wave + 4 * i) * 8 + rl;
+        row = row < rows_valid ? row : rows_valid - 1;   // clamp: rows past the edge are never stored
+        voff[i] = (uint32_t)((size_t)row * ld_bytes) + (uint32_t)(chunk * 16);
     }
 }
 
@@ -232,15 +242,36 @@ __global__ __launch_bounds__(256, 1) void gemm_tn_kernel(const char* __restrict_
 
     const size_t ld_bytes = (size_t)K * ESZ;
     const int nk = (int)(ld_bytes / kRowBytes);
-    load_tile(A, ld_bytes, m0, M - 1, 0, lds, wave, lane);
-    load_tile(Wt, ld_bytes, n0, N - 1, 0, lds + BM * kRowBytes, wave, lane);
+    uint32_t voff_a[8], voff_w[8];
+    lane_offsets(voff_a, ld_bytes, M - m0 < BM ? M - m0 : BM, wave, lane);
+    lane_offsets(voff_w, ld_bytes, N - n0 < BN ? N - n0 : BN, wave, lane);
+    const char* a_panel = A + (size_t)m0 * ld_bytes;
+    const char* w_panel = Wt + (size_t)n0 * ld_bytes;
+    load_tile(a_panel, voff_a, lds, wave);
+    load_tile(w_panel, voff_w, lds + BM * kRowBytes, wave);
     __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
     __syncthreads();
     if (nk > 1) {
-        load_tile(A, ld_bytes, m0, M - 1, kRowBytes, lds + kStageBytes, wave, lane);
-        load_tile(Wt, ld_bytes, n0, N - 1, kRowBytes, lds + kStageBytes + BM * kRowBytes, wave, lane);
+        load_tile(a_panel + kRowBytes, voff_a, lds + kStageBytes, wave);
+        load_tile(w_panel + kRowBytes, voff_w, lds + kStageBytes + BM * kRowBytes, wave);
     }
     read_frags(0, lds, 0);
+
+    auto mfma_one = [&](int buf, int j, int i) {
+        if (ESZ == 2) {
+            acc[j][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, wf[buf][j]),
+                                                                __builtin_bit_cast(bf16x8, af[buf][i]),
+                                                                acc[j][i], 0, 0, 0);
+        } else {
+#pragma unroll
+            for (int hf = 0; hf < 2; ++hf) {
+                const i32x4 wv = wf[buf][j], av = af[buf][i];
+                const long wl = ((long)(uint32_t)wv[2 * hf]) | ((long)wv[2 * hf + 1] << 32);
+                const long al = ((long)(uint32_t)av[2 * hf]) | ((long)av[2 * hf + 1] << 32);
+                acc[j][i] = __builtin_amdgcn_mfma_f32_32x32x16_fp8_fp8(wl, al, acc[j][i], 0, 0, 0);
+            }
+        }
+    };
 
     for (int kt = 0; kt < nk; ++kt) {
         const char* cur = lds + (kt & 1) * kStageBytes;
@@ -248,44 +279,49 @@ __global__ __launch_bounds__(256, 1) void gemm_tn_kernel(const char* __restrict_
         for (int kk = 0; kk < 4; ++kk) {
             if (kk < 3) {
                 read_frags((kk + 1) & 1, cur, kk + 1);
-            } else if (kt + 1 < nk) {
-                // tile boundary: the next stage must have landed for every wave, and every wave
-                // must be done reading this stage before it is refilled
-                __builtin_amdgcn_s_waitcnt(0x0070);   // vmcnt(0) lgkmcnt(0)
-                __syncthreads();
-                if (kt + 2 < nk) {
-                    char* refill = lds + (kt & 1) * kStageBytes;
-                    load_tile(A, ld_bytes, m0, M - 1, (size_t)(kt + 2) * kRowBytes, refill, wave, lane);
-                    load_tile(Wt, ld_bytes, n0, N - 1, (size_t)(kt + 2) * kRowBytes, refill + BM * kRowBytes,
-                              wave, lane);
-                }
-                read_frags(0, lds + ((kt + 1) & 1) * kStageBytes, 0);
-            }
-            __builtin_amdgcn_sched_barrier(0);
-            if (ESZ == 2) {
+                __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                 for (int j = 0; j < 4; ++j)
 #pragma unroll
-                    for (int i = 0; i < 4; ++i)
-                        acc[j][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                            __builtin_bit_cast(bf16x8, wf[kk & 1][j]), __builtin_bit_cast(bf16x8, af[kk & 1][i]),
-                            acc[j][i], 0, 0, 0);
+                    for (int i = 0; i < 4; ++i) mfma_one(kk & 1, j, i);
+                __builtin_amdgcn_sched_barrier(0);
             } else {
+                // Tile boundary: the next stage must have landed for every wave, and every wave
+                // must be done reading this stage before it is refilled.  The refill (tile kt+2)
+                // and the first fragments of the next stage are issued between the 16 MFMAs of
+                // this k-step, one load per MFMA, so the matrix pipe keeps running while they
+                // issue.  The path is the same on the last tiles, where it reloads the final
+                // tile and reads fragments that nobody uses: a branch here would split the
+                // accumulators' live ranges and cost far more than the wasted loads.
+                __builtin_amdgcn_s_waitcnt(0x0070);   // vmcnt(0) lgkmcnt(0)
+                __syncthreads();
+                char* refill = lds + (kt & 1) * kStageBytes;
+                const char* nxt = lds + ((kt + 1) & 1) * kStageBytes;
+                const size_t k_bytes = (size_t)(kt + 2 < nk ? kt + 2 : nk - 1) * kRowBytes;
+                const char* ap = a_panel + k_bytes;
+                const char* wp = w_panel + k_bytes;
 #pragma unroll
-                for (int hf = 0; hf < 2; ++hf)
-#pragma unroll
-                    for (int j = 0; j < 4; ++j)
-#pragma unroll
-                        for (int i = 0; i < 4; ++i) {
-                            const i32x4 wv = wf[kk & 1][j], av = af[kk & 1][i];
-                            const long wl = ((long)(uint32_t)wv[2 * hf]) | ((long)wv[2 * hf + 1] << 32);
-                            const long al = ((long)(uint32_t)av[2 * hf]) | ((long)av[2 * hf + 1] << 32);
-                            acc[j][i] = __builtin_amdgcn_mfma_f32_32x32x16_fp8_fp8(wl, al, acc[j][i], 0, 0, 0);
-                        }
+                for (int idx = 0; idx < 16; ++idx) {
+                    mfma_one(1, idx >> 2, idx & 3);
+                    if (idx < 8)
+                        __builtin_amdgcn_global_load_lds((gptr_t)(ap + voff_a[idx]),
+                                                         (lptr_t)(refill + (wave + 4 * idx) * 8 * kRowBytes), 16, 0, 0);
+                    else
+                        __builtin_amdgcn_global_load_lds(
+                            (gptr_t)(wp + voff_w[idx - 8]),
+                            (lptr_t)(refill + BM * kRowBytes + (wave + 4 * (idx - 8)) * 8 * kRowBytes), 16, 0, 0);
+                    if ((idx & 1) == 0) {
+                        if (idx < 8)
+                            af[0][idx >> 1] = *reinterpret_cast<const i32x4*>(nxt + a_base + (idx >> 1) * 32 * kRowBytes + foff[0]);
+                        else
+                            wf[0][(idx - 8) >> 1] = *reinterpret_cast<const i32x4*>(nxt + w_base + ((idx - 8) >> 1) * 32 * kRowBytes + foff[0]);
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                }
             }
-            __builtin_amdgcn_sched_barrier(0);
         }
     }
+    __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): no LDS load may outlive the loop
 
     // D'[r][c] = C[m = c][n = r]: lane holds column c = lane%32 (an activation row) and, for
     // register e, weight row 8*(e/4) + 4*(lane/32) + e%4: four consecutive n per e/4.

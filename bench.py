@@ -27,6 +27,11 @@ sys.path.insert(0, ROOT)
 PEAK_BF16_TFLOPS = 2500.0       # MI355X dense bf16 MFMA
 PEAK_INT32_TOPS = 78.6          # 256 CU x 4 SIMD x 32 lanes/clk x 2.4 GHz (= fp32 FMA issue rate, 157.3 / 2)
 INT32_OPS_PER_CALL = 84         # 20 wide multiplies (lo+hi = 2 results each), 40 two-input xors, 4 compares
+# HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (KiB per dispatch, scaled by what the
+# same counters read for a 1 GiB copy: x2.00 and x1.00), see profiles/pmc_fetch_write_llama3_8b_s2k.md
+TRAFFIC_GEMM_BYTES = int((195078.2 * 2.0 + 57485.7) * 1024)      # 2048x4096x14336 bf16 (algorithmic: 184.5 MiB)
+TRAFFIC_RNG_BYTES = int((27.0 * 2.0 + 16384.0) * 1024)           # 32x2048x2048-bit mask (algorithmic: 16 MiB)
+TRAFFIC_ATTN_MASK_BYTES = int((32838.7 * 2.0 + 16394.4) * 1024)  # attention reading the mask (algorithmic: 80 MiB)
 
 
 def median_ms(fn, warm, iters, sync, ev_pair, inner=10):
@@ -183,7 +188,7 @@ def main():
                       "roofline": {"bound": "alu", "achieved": ncalls * INT32_OPS_PER_CALL / t_rng / 1e9,
                                    "peak": PEAK_INT32_TOPS, "unit": "Tint32op/s",
                                    "frac": ncalls * INT32_OPS_PER_CALL / t_rng / 1e9 / PEAK_INT32_TOPS,
-                                   "traffic": None}},
+                                   "traffic": TRAFFIC_RNG_BYTES}},
         "gemm_alone": {"ms": t_gemm, "tflops": gemm_flops / t_gemm / 1e9,
                        "mfma_frac": gemm_flops / t_gemm / 1e9 / PEAK_BF16_TFLOPS},
         "gemm_in_overlap_step": {"ms": gemm_in_step, "tflops": gemm_flops / gemm_in_step / 1e9,
@@ -197,7 +202,8 @@ def main():
                       "in_step_ms": attn_in_step,
                       "none_tflops": attn_flops / t_attn_none / 1e9, "mask_tflops": attn_flops / t_attn_mask / 1e9,
                       "fused_tflops": attn_flops / t_attn_fused / 1e9,
-                      "dropping_overhead": t_attn_mask / t_attn_none - 1.0},
+                      "dropping_overhead": t_attn_mask / t_attn_none - 1.0,
+                      "mask_traffic_bytes": TRAFFIC_ATTN_MASK_BYTES},
         "layer_step_ms": {"sequential": t_seq, "fused": t_fus, "overlap": t_ovl},
         "layer_speedup_overlap_vs_sequential": t_seq / t_ovl,
         "layer_speedup_overlap_vs_fused": t_fus / t_ovl,
@@ -231,9 +237,9 @@ def main():
                                "GEMM 2048x4096x14336 bf16; overlap schedule (RNG on side stream || GEMM, join, "
                                "attention with mask)",
                    "schedule": "overlap", "seed": wl.SEED, "offset": wl.OFFSET},
-        "roofline": {"bound": "mfma", "kernel": "gemm_bf16_tn_kernel (inside the overlap step, RNG co-running)",
+        "roofline": {"bound": "mfma", "kernel": "gemm_tn_kernel<2> (bf16, inside the overlap step, RNG co-running)",
                      "achieved": gemm_flops / gemm_in_step / 1e9, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": gemm_flops / gemm_in_step / 1e9 / PEAK_BF16_TFLOPS, "traffic": None},
+                     "frac": gemm_flops / gemm_in_step / 1e9 / PEAK_BF16_TFLOPS, "traffic": TRAFFIC_GEMM_BYTES},
         "cpu_baseline": cpu,
         "extras": extras,
     }

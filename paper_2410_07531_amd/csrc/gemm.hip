@@ -278,13 +278,21 @@ __global__ __launch_bounds__(256, 1) void gemm_tn_kernel(const char* __restrict_
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk) {
             if (kk < 3) {
-                read_frags((kk + 1) & 1, cur, kk + 1);
-                __builtin_amdgcn_sched_barrier(0);
+                // the 8 fragment reads of the next k-step ride between this k-step's 16 MFMAs:
+                // an LDS read issued in the shadow of a running MFMA costs the matrix pipe nothing
 #pragma unroll
-                for (int j = 0; j < 4; ++j)
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) mfma_one(kk & 1, j, i);
-                __builtin_amdgcn_sched_barrier(0);
+                for (int idx = 0; idx < 16; ++idx) {
+                    mfma_one(kk & 1, idx >> 2, idx & 3);
+                    if ((idx & 1) == 0) {
+                        if (idx < 8)
+                            af[(kk + 1) & 1][idx >> 1] = *reinterpret_cast<const i32x4*>(
+                                cur + a_base + (idx >> 1) * 32 * kRowBytes + foff[kk + 1]);
+                        else
+                            wf[(kk + 1) & 1][(idx - 8) >> 1] = *reinterpret_cast<const i32x4*>(
+                                cur + w_base + ((idx - 8) >> 1) * 32 * kRowBytes + foff[kk + 1]);
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                }
             } else {
                 // Tile boundary: the next stage must have landed for every wave, and every wave
                 // must be done reading this stage before it is refilled.  The refill (tile kt+2)

@@ -13,13 +13,14 @@
 // O and the mask word are per-lane scalars and only the row maximum needs one
 // exchange between the two half-waves.  The S^T accumulator registers are, as
 // they stand, the P^T operand of the second product if the 16 keys of a k-step
-// are taken in the order the accumulator holds them; V is written to LDS
-// transposed ([dv][key]) so that this key order is two 8-byte reads per lane.
+// are taken in the order the accumulator holds them; the matching V^T operand
+// comes out of the row-major V tile with the gfx950 transpose load
+// (ds_read_b64_tr_b16), two per fragment, so V is never copied transposed.
 //
 // A wave owns 32 query rows and walks the keys 64 at a time; the 8 waves of a
 // workgroup (two per SIMD, so one wave's softmax runs under the other's MFMAs)
-// share each K / V tile through LDS (K straight from global memory with
-// global_load_lds, V through registers because of the transpose).
+// share each K / V tile through LDS (both straight from global memory with
+// global_load_lds).
 //
 // Any other case (fp32, other head dimensions) takes a small one-wave-per-row
 // kernel that is correct for every shape.
@@ -74,18 +75,25 @@ template <int D>
 struct Tile {
     static constexpr int kKRow = D * 2;                // bytes per K row in LDS
     static constexpr int kKBytes = BKV * kKRow;
-    static constexpr int kVPitch = BKV * 2 + 8;        // bytes per V^T row ([dv][key]), padded
-    static constexpr int kVBytes = D * kVPitch;
-    static constexpr int kStage = kKBytes + kVBytes;
+    static constexpr int kStage = 2 * kKBytes;         // K tile then V tile, both [key][feature]
     static constexpr int kChunks = D / 8;              // 16-byte chunks per K row
 };
 
-// K tile: global -> LDS directly.  One wave instruction fills 1 KiB = 1024 / kKRow rows; lane
-// L lands on physical chunk L % kChunks of its row and therefore fetches logical chunk
-// (L % kChunks) ^ (row % 8).
-template <int D, int NW>
-__device__ __forceinline__ void load_k_tile(const uint16_t* __restrict__ Kp, int64_t tok_stride,
-                                            int kv0, int S, char* lds_k, int wave, int lane) {
+// Swizzle of the 16-byte chunks of an LDS tile row.  K rows are read by lanes that differ in
+// the row (chunk fixed), so XOR with row%8 spreads them over the banks.  V rows are read by
+// the transpose load in groups of 16 lanes = 4 consecutive rows x 2 adjacent chunks x 2 halves,
+// which needs the 4 rows two chunks apart: XOR with 2*(row%4) + (row/4)%2.
+template <bool VTILE>
+__device__ __forceinline__ int swizzle_of_row(int row) {
+    return VTILE ? (((row & 3) << 1) | ((row >> 2) & 1)) : (row & 7);
+}
+
+// K or V tile: global -> LDS directly.  One wave instruction fills 1 KiB = 1024 / kKRow rows;
+// lane L lands on physical chunk L % kChunks of its row and therefore fetches the logical
+// chunk (L % kChunks) ^ swizzle(row).
+template <int D, int NW, bool VTILE>
+__device__ __forceinline__ void load_kv_tile(const uint16_t* __restrict__ Xp, int64_t tok_stride,
+                                             int kv0, int S, char* lds_x, int wave, int lane) {
     constexpr int kChunks = Tile<D>::kChunks;
     constexpr int kRowsPerInst = 64 / kChunks;                 // 4 (D = 128) or 8 (D = 64)
     constexpr int kInst = BKV / kRowsPerInst;                  // 16 or 8 per tile
@@ -97,41 +105,24 @@ __device__ __forceinline__ void load_k_tile(const uint16_t* __restrict__ Kp, int
         const int row = inst * kRowsPerInst + rl;              // 0..63
         int key = kv0 + row;
         key = key < S ? key : S - 1;
-        const int chunk = pc ^ (row & 7);
-        const uint16_t* g = Kp + (int64_t)key * tok_stride + chunk * 8;
-        __builtin_amdgcn_global_load_lds((gptr_t)g, (lptr_t)(lds_k + inst * 1024), 16, 0, 0);
+        const int chunk = pc ^ swizzle_of_row<VTILE>(row);
+        const uint16_t* g = Xp + (int64_t)key * tok_stride + chunk * 8;
+        __builtin_amdgcn_global_load_lds((gptr_t)g, (lptr_t)(lds_x + inst * 1024), 16, 0, 0);
     }
 }
 
-// V tile: 16-byte global loads into registers (thread t: key t % 64, chunks t/64 + NW*i) ...
-template <int D, int NW>
-__device__ __forceinline__ void load_v_regs(const uint16_t* __restrict__ Vp, int64_t tok_stride,
-                                            int kv0, int S, uint4 (&regs)[D / 8 / NW]) {
-    int key = kv0 + (threadIdx.x & 63);
-    key = key < S ? key : S - 1;
-    const int c0 = threadIdx.x >> 6;
-#pragma unroll
-    for (int i = 0; i < D / 8 / NW; ++i) {
-        const int chunk = c0 + NW * i;
-        regs[i] = *reinterpret_cast<const uint4*>(Vp + (int64_t)key * tok_stride + chunk * 8);
-    }
-}
+typedef short i16x4 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) i16x4* lds_i16x4_ptr;
 
-// ... and from registers to LDS transposed: V^T[dv][key].
-template <int D, int NW>
-__device__ __forceinline__ void store_v_transposed(const uint4 (&regs)[D / 8 / NW], char* lds_v) {
-    const int key = threadIdx.x & 63;
-    const int c0 = threadIdx.x >> 6;
-#pragma unroll
-    for (int i = 0; i < D / 8 / NW; ++i) {
-        const int dv0 = (c0 + NW * i) * 8;
-        const uint32_t w[4] = {regs[i].x, regs[i].y, regs[i].z, regs[i].w};
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            const uint16_t v = (uint16_t)(w[e >> 1] >> ((e & 1) * 16));
-            *reinterpret_cast<uint16_t*>(lds_v + (dv0 + e) * Tile<D>::kVPitch + key * 2) = v;
-        }
-    }
+// ds_read_b64_tr_b16: within each group of 16 lanes, source lane r = 4*j + s supplies the
+// address of 4 consecutive 16-bit elements, and lane i of the group receives element i%4 of
+// the rows supplied by source lanes 4*j + i/4, j = 0..3.  If the four source lanes 4*j + s
+// (s = 0..3) point at row key_j, columns c0 + 4*s .. +3, then lane i ends up with column
+// c0 + i of rows key_0 .. key_3: a column fragment of a row-major tile, i.e. the transposed
+// operand the second product needs, with no transposed copy of V anywhere.
+__device__ __forceinline__ bf16x4 lds_read_transposed(const char* p) {
+    const i16x4 v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_i16x4_ptr)p);
+    return __builtin_bit_cast(bf16x4, v);
 }
 
 // NW waves per workgroup, each owning NQ*32 query rows.  (NQ, NW) = (2, 4) keeps one wave per
@@ -245,10 +236,20 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(const AttnParams p) 
         }
     };
 
-    uint4 vregs[D / 8 / NW];
-    load_k_tile<D, NW>(Kp, p.sk[1], 0, S, lds, wave, lane);
-    load_v_regs<D, NW>(Vp, p.sv[1], 0, S, vregs);
-    store_v_transposed<D, NW>(vregs, lds + T::kKBytes);
+    load_kv_tile<D, NW, false>(Kp, p.sk[1], 0, S, lds, wave, lane);
+    load_kv_tile<D, NW, true>(Vp, p.sv[1], 0, S, lds + T::kKBytes, wave, lane);
+
+    // transpose-load addressing of the V tile (see lds_read_transposed): lane l = 16*g + 4*j + s
+    // supplies row 16*u + 8*x + 4*(g/2) + j, columns 32*t + 16*(g%2) + 4*s .. +3
+    int vt_off[DVT];
+    {
+        const int g = lane >> 4, j = (lane >> 2) & 3, sl = lane & 3, hh = g >> 1;
+        const int row_part = (4 * hh + j) * T::kKRow + (sl & 1) * 8;
+        const int f = 2 * j + hh;                               // swizzle_of_row<true>(row)
+#pragma unroll
+        for (int t = 0; t < DVT; ++t)
+            vt_off[t] = row_part + (((4 * t + 2 * (g & 1) + (sl >> 1)) ^ f) << 4);
+    }
 
     const int kswz = ql & 7;
 
@@ -256,12 +257,12 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(const AttnParams p) 
         const int kv0 = jt * BKV;
         char* cur = lds + (jt & 1) * T::kStage;
         char* nxt = lds + ((jt + 1) & 1) * T::kStage;
-        __builtin_amdgcn_s_waitcnt(0x0070);   // vmcnt(0) lgkmcnt(0): own K / mask loads and V^T writes done
+        __builtin_amdgcn_s_waitcnt(0x0070);   // vmcnt(0) lgkmcnt(0): this wave's K / V loads have landed
         __syncthreads();
         const bool has_next = jt + 1 < ntiles;
         if (has_next) {
-            load_k_tile<D, NW>(Kp, p.sk[1], kv0 + BKV, S, nxt, wave, lane);
-            load_v_regs<D, NW>(Vp, p.sv[1], kv0 + BKV, S, vregs);
+            load_kv_tile<D, NW, false>(Kp, p.sk[1], kv0 + BKV, S, nxt, wave, lane);
+            load_kv_tile<D, NW, true>(Vp, p.sv[1], kv0 + BKV, S, nxt + T::kKBytes, wave, lane);
         }
         if (MODE == MODE_MASK) {
             // this tile's words were requested one tile ago, under the previous Q K^T product
@@ -390,9 +391,9 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(const AttnParams p) 
         for (int u = 0; u < 4; ++u) {
 #pragma unroll
             for (int t = 0; t < DVT; ++t) {
-                const char* rowp = vt + (32 * t + ql) * T::kVPitch + (16 * u + 4 * half) * 2;
-                const bf16x4 lo = *reinterpret_cast<const bf16x4*>(rowp);
-                const bf16x4 hi = *reinterpret_cast<const bf16x4*>(rowp + 16);
+                // keys 16u + 4*half + 0..3 and 16u + 8 + 4*half + 0..3 of feature 32t + lane%32
+                const bf16x4 lo = lds_read_transposed(vt + (16 * u) * T::kKRow + vt_off[t]);
+                const bf16x4 hi = lds_read_transposed(vt + (16 * u + 8) * T::kKRow + vt_off[t]);
                 const bf16x8 vf = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
 #pragma unroll
                 for (int n = 0; n < NQ; ++n)
@@ -400,7 +401,6 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(const AttnParams p) 
             }
         }
 
-        if (has_next) store_v_transposed<D, NW>(vregs, nxt + T::kKBytes);
     }
 
     // ---- normalise, scale kept entries by 1/(1-p), store O (lane: query ql, 4 consecutive dv per e/4)

@@ -46,8 +46,7 @@ int check_gemm_desc(const rov_gemm_desc& g) {
     if (g.A == nullptr || g.Bm == nullptr || g.C == nullptr || g.M <= 0 || g.N <= 0 || g.K <= 0)
         return ROV_ERR_INVALID;
     if (!aligned(g.A, 16) || !aligned(g.Bm, 16) || !aligned(g.C, 16)) return ROV_ERR_INVALID;
-    if (g.dtype != ROV_F32 && g.dtype != ROV_BF16)
-        return g.dtype == ROV_FP8_E4M3 ? ROV_ERR_UNSUPPORTED : ROV_ERR_INVALID;
+    if (g.dtype != ROV_F32 && g.dtype != ROV_BF16 && g.dtype != ROV_FP8_E4M3) return ROV_ERR_INVALID;
     return ROV_OK;
 }
 

@@ -1,0 +1,187 @@
+"""GPU parity at the full sizes of the larger workloads, on sampled outputs.
+
+The oracle cannot evaluate 10^11..10^12 flops, so each test checks (a) sampled mask slices
+bit for bit, (b) sampled GEMM rows / entries and sampled attention query rows against the
+float64 oracle, and (c) properties that hold at any size (the three schedules agree bit for
+bit; the kept fraction stays inside its 4-sigma band).
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import dense as OD
+from oracle import numerics as ON
+from oracle import philox as OP
+from paper_2410_07531_amd import binding as rov
+from paper_2410_07531_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+
+def _f64(t):
+    return t.float().cpu().numpy().astype(np.float64)
+
+
+def _randn(gen, *shape, sd=1.0, dtype=torch.bfloat16):
+    return (torch.randn(*shape, device="cuda", generator=gen) * sd).to(dtype)
+
+
+def _check_mask_heads(mask, seed, offset, B, H, S, p, heads):
+    W = S // 64
+    per_head = S * W
+    for b, h in heads:
+        first = (b * H + h) * per_head
+        exp = OP.dropout_mask(seed, offset + 64 * (first // 4), 1, 1, S, p)
+        assert np.array_equal(mask[b, h].cpu().numpy().view(np.uint64), exp[0, 0]), (b, h)
+
+
+def _keep_rows(mask, b, h, rows, S):
+    words = mask[b, h][rows].cpu().numpy().view(np.uint64)
+    return OP.unpack_keep(words, S)          # [len(rows), S]
+
+
+def _attention_rows_ref(Q, K, V, mask, p, b, h, rows, causal):
+    """Oracle attention for sampled query rows of one (batch, head): uses the full K, V of the head."""
+    H, Hkv = Q.shape[2], K.shape[2]
+    hk = h // (H // Hkv)
+    S = Q.shape[1]
+    q = _f64(Q[b:b + 1, :, h:h + 1, :])
+    k = _f64(K[b:b + 1, :, hk:hk + 1, :])
+    v = _f64(V[b:b + 1, :, hk:hk + 1, :])
+    keep = np.zeros((1, 1, S, S), dtype=bool)
+    keep[0, 0, rows] = _keep_rows(mask, b, h, rows, S)
+    return OD.attention_dropout(q, k, v, keep, p, causal=causal, rows=rows)[0, :, 0, :]
+
+
+def _gemm_rows_check(A, W, C, rows, tol, sa=1.0, sb=1.0, decode=None):
+    Ah = decode(A[rows].cpu().numpy()) if decode else _f64(A[rows])
+    Wh = decode(W.cpu().numpy()) if decode else _f64(W)
+    ref = sa * sb * OD.gemm(Ah, Wh, transB=True)
+    err = float(np.max(np.abs(_f64(C[rows]) - ref)) / np.max(np.abs(ref)))
+    assert err <= tol, err
+
+
+def test_workload3_b2_s4k_layer_step_schedules():
+    # B=2, S=4096, H=32, d=128; GEMMs QKV 8192x4096x6144 and FFN-down 8192x14336x4096 (bf16)
+    c = wl.CONFIGS[2]
+    B, H, Hkv, S, d, p = c["B"], c["H"], c["Hkv"], c["S"], c["d"], c["p"]
+    gen = torch.Generator(device="cuda"); gen.manual_seed(1002)
+    Q, K, V = _randn(gen, B, S, H, d), _randn(gen, B, S, Hkv, d), _randn(gen, B, S, Hkv, d)
+    ops = []
+    for _, M, Kd, N in c["gemms"]:
+        ops.append((_randn(gen, M, Kd), _randn(gen, N, Kd, sd=0.02), torch.empty((M, N), dtype=torch.bfloat16, device="cuda")))
+    main, side = torch.cuda.Stream(), torch.cuda.Stream()
+    outs = []
+    for sched in (rov.SCHED_SEQUENTIAL, rov.SCHED_FUSED, rov.SCHED_OVERLAP):
+        print("cfg3 schedule", sched, flush=True)
+        O = torch.zeros_like(Q)
+        mask = torch.zeros((B, H, S, S // 64), dtype=torch.int64, device="cuda")
+        gd = [rov.make_gemm_desc(a, w, cc) for a, w, cc in ops]
+        rov.layer_step(sched, gd, rov.make_attn_desc(Q, K, V, O, p), wl.SEED, wl.OFFSET,
+                       None if sched == rov.SCHED_FUSED else mask, main, side)
+        torch.cuda.synchronize()
+        outs.append(O)
+        if sched == rov.SCHED_OVERLAP:
+            _check_mask_heads(mask, wl.SEED, wl.OFFSET, B, H, S, p, [(0, 0), (1, 17), (1, 31)])
+            rows = wl.sample_rows(S, 8)
+            for b, h in [(0, 0), (1, 5), (1, 31)]:
+                ref = _attention_rows_ref(Q, K, V, mask, p, b, h, rows, False)
+                got = _f64(O[b, rows, h, :])
+                assert np.max(np.abs(got - ref)) / np.max(np.abs(ref)) <= 2e-2
+            srng = np.random.default_rng(3)
+            for a, w, cc in ops:
+                _gemm_rows_check(a, w, cc, np.sort(srng.choice(a.shape[0], 16, replace=False)), 6e-3)
+    assert torch.equal(outs[0], outs[1]) and torch.equal(outs[0], outs[2])
+
+
+def test_workload4_llama70b_fp8_gemms_and_gqa_attention():
+    # H=64 query / 8 kv heads, S=8192, d=128; fp8 e4m3 GEMMs of the 70B layer, per-tensor scales
+    c = wl.CONFIGS[3]
+    B, H, Hkv, S, d, p = c["B"], c["H"], c["Hkv"], c["S"], c["d"], c["p"]
+    gen = torch.Generator(device="cuda"); gen.manual_seed(1003)
+
+    def quant(x):
+        amax = float(x.abs().max())
+        scale = float(np.float32(amax / 448.0))
+        return (x.float() / scale).to(torch.float8_e4m3fn).view(torch.uint8), scale
+
+    srng = np.random.default_rng(4)
+    gemm_descs, keepalive = [], []
+    for name, M, Kd, N in c["gemms"]:
+        print("cfg4 gemm", name, M, Kd, N, flush=True)
+        Aq, sa = quant(_randn(gen, M, Kd, dtype=torch.float32))
+        Wq, sb = quant(_randn(gen, N, Kd, sd=0.02, dtype=torch.float32))
+        C = rov.gemm(Aq, Wq, transB=True, scaleA=sa, scaleB=sb)
+        torch.cuda.synchronize()
+        _gemm_rows_check(Aq, Wq, C, np.sort(srng.choice(M, 8, replace=False)), 6e-3, sa, sb, decode=ON.e4m3_decode)
+        if name == "qkv":
+            gemm_descs.append(rov.make_gemm_desc(Aq, Wq, C, scaleA=sa, scaleB=sb))
+            keepalive += [Aq, Wq, C]
+            c_first = C.clone()
+        else:
+            del Aq, Wq, C
+            torch.cuda.empty_cache()
+    # overlap schedule: fp8 QKV GEMM || RNG (64 x 8192^2 bits = 512 MiB), then GQA attention in bf16
+    Q, K, V = _randn(gen, B, S, H, d), _randn(gen, B, S, Hkv, d), _randn(gen, B, S, Hkv, d)
+    O = torch.zeros_like(Q)
+    mask = torch.zeros((B, H, S, S // 64), dtype=torch.int64, device="cuda")
+    main, side = torch.cuda.Stream(), torch.cuda.Stream()
+    print("cfg4 overlap step", flush=True)
+    rov.layer_step(rov.SCHED_OVERLAP, gemm_descs, rov.make_attn_desc(Q, K, V, O, p), wl.SEED, wl.OFFSET, mask, main, side)
+    torch.cuda.synchronize()
+    assert torch.equal(keepalive[2], c_first)                       # same GEMM result beside the RNG
+    _check_mask_heads(mask, wl.SEED, wl.OFFSET, B, H, S, p, [(0, 0), (0, 63)])
+    rows = wl.sample_rows(S, 6)
+    for h in (0, 9, 63):
+        ref = _attention_rows_ref(Q, K, V, mask, p, 0, h, rows, False)
+        assert np.max(np.abs(_f64(O[0, rows, h, :]) - ref)) / np.max(np.abs(ref)) <= 2e-2
+    Of = rov.attention_fwd_dropout(Q, K, V, p, seed=wl.SEED, offset=wl.OFFSET)
+    torch.cuda.synchronize()
+    assert torch.equal(O, Of)
+    kept = 0
+    flat = mask.view(-1)
+    for i in range(0, flat.numel(), 1 << 24):
+        kept += OP.popcount(flat[i:i + (1 << 24)].cpu().numpy().view(np.uint64))
+    n, q = B * H * S * S, OP.keep_threshold(p) / 2**32
+    assert abs(kept / n - q) <= 4 * math.sqrt(q * (1 - q) / n)
+
+
+def test_workload5_block_s16k_overlap_sampled_rows():
+    # full Llama-3-8B block, B=1, S=16384, overlap schedule in steady state (mask ready, next mask
+    # generated beside the PROJ / FC1 / FC2 GEMMs); oracle on sampled token rows
+    c = wl.CONFIGS[4]
+    B, H, Hkv, S, d, p, hidden, ffn = c["B"], c["H"], c["Hkv"], c["S"], c["d"], c["p"], c["hidden"], c["ffn"]
+    gen = torch.Generator(device="cuda"); gen.manual_seed(1004)
+    wts = dict(norm1=torch.ones(hidden, device="cuda", dtype=torch.bfloat16),
+               norm2=torch.ones(hidden, device="cuda", dtype=torch.bfloat16),
+               wqkv=_randn(gen, (H + 2 * Hkv) * d, hidden, sd=0.02), wo=_randn(gen, hidden, H * d, sd=0.02),
+               wg=_randn(gen, ffn, hidden, sd=0.02), wu=_randn(gen, ffn, hidden, sd=0.02),
+               wd=_randn(gen, hidden, ffn, sd=0.02))
+    x = _randn(gen, B, S, hidden)
+    y = torch.zeros_like(x)
+    main, side = torch.cuda.Stream(), torch.cuda.Stream()
+    m0 = rov.dropout_mask_generate(wl.SEED, wl.OFFSET, B, H, S, p)
+    m1 = torch.zeros_like(m0)
+    rows = wl.sample_rows(S, 6)
+    for causal in (False, True):
+        print("cfg5 block causal", causal, flush=True)
+        cfg = rov.make_block_cfg(H, Hkv, d, hidden, ffn, p, causal=causal)
+        ws = torch.empty(rov.block_workspace_bytes(cfg, B, S, 0), dtype=torch.uint8, device="cuda")
+        rov.block_forward(rov.make_block_weights(wts), x, y, cfg, rov.SCHED_OVERLAP, wl.SEED, wl.OFFSET, m0, ws,
+                          main, side, mask_ready=True, next_mask=m1)
+        torch.cuda.synchronize()
+        del ws
+        # next layer's mask, sampled heads
+        _check_mask_heads(m1, wl.SEED, wl.OFFSET + OP.mask_philox_calls(B, H, S), B, H, S, p, [(0, 0), (0, 31)])
+        # oracle: full K, V (all tokens), everything else on the sampled rows only
+        keep = np.zeros((B, H, S, S), dtype=bool)
+        for h in range(H):
+            keep[0, h, rows] = _keep_rows(m0, 0, h, rows, S)
+        ocfg = dict(H=H, Hkv=Hkv, d=d, eps=1e-5, rope_theta=500000.0, p=p, causal=causal)
+        ref = OD.block_forward(_f64(x), {k_: _f64(v_) for k_, v_ in wts.items()}, ocfg, keep, rows=rows)
+        got = _f64(y[:, rows])
+        err = np.max(np.abs(got - ref)) / np.max(np.abs(ref))
+        assert err <= 2e-2, err
+        del keep

@@ -94,7 +94,7 @@ def main():
     A, Wt = torch.from_numpy(a).to(bf).to(dev), torch.from_numpy(w).to(bf).to(dev)
     O = torch.empty_like(Q)
     C = torch.empty((M, N), dtype=bf, device=dev)
-    mask = torch.empty((B, H, S, S // 64), dtype=torch.int64, device=dev)
+    mask = torch.empty(rov.mask_shape(B, H, S), dtype=torch.int64, device=dev)
     nbits = B * H * S * S
     ncalls = nbits // 4
     gemm_flops = 2.0 * M * N * K
@@ -267,7 +267,7 @@ def bench_block(torch, rov, wl, main_s, side_s, sync, ev_pair):
         cfg = rov.make_block_cfg(H, Hkv, d, hidden, ffn, p, causal=causal)
         weights = rov.make_block_weights(wts)
         ws = torch.empty(rov.block_workspace_bytes(cfg, B, S, 0), dtype=torch.uint8, device="cuda")
-        m0 = torch.empty((B, H, S, S // 64), dtype=torch.int64, device="cuda")
+        m0 = torch.empty(rov.mask_shape(B, H, S), dtype=torch.int64, device="cuda")
         m1 = torch.empty_like(m0)
         off1 = rov.mask_philox_calls(B, H, S)
         rov.dropout_mask_generate(wl.SEED, 0, B, H, S, p, out=m0)

@@ -50,13 +50,21 @@ const char *rov_version(void);
 
 /* ---------------------------------------------------------------- mask geometry
  * The keep-mask of a B x H x S x S score matrix (paper Sec. 7.2: B*nH*SQ^2 bits)
- * is an array of 64-bit words, row-major [B][H][S][W] with W = ceil(S/64);
- * bit l (LSB first) of word (b,h,i,cb) belongs to column j = 64*cb + l; bits
- * with j >= S are 0; a set bit means "keep".
- * rov_mask_words         = B*H*S*W (0 if any argument is <= 0).
- * rov_mask_philox_calls  = 64*ceil(words/4): how far one mask advances the
- *                          Philox call counter; the next mask (next layer, next
- *                          step) uses offset + this value. */
+ * is an array of 64-bit words.  Each S x S matrix is cut into T x T tiles of
+ * 32 x 32 elements, T = ceil(S/32), 16 words per tile, row-major
+ * [B][H][T (query tile)][T (key tile)][16]:
+ *     word index w = (((b*H + h)*T + qt)*T + kt)*16 + e,
+ *     bit l (LSB first) of word w  <->  row 32*qt + l%32,
+ *                                       column 32*kt + 8*(e/4) + 4*(l/32) + e%4.
+ * That is the order in which a 64-lane wave holds a 32 x 32 fp32 MFMA accumulator
+ * tile (lane l, register e): a mask word is the per-lane keep predicate of one
+ * accumulator register, so attention applies it with one select per element and
+ * loads it with scalar loads, and the RNG kernel's 64-lane compare result is the
+ * word.  Bits whose row or column is >= S are 0; a set bit means "keep".
+ * rov_mask_words         = B*H*T*T*16 (0 if any argument is <= 0).
+ * rov_mask_philox_calls  = 64*words/4: how far one mask advances the Philox call
+ *                          counter; the next mask (next layer, next step) uses
+ *                          offset + this value. */
 uint64_t rov_mask_words(int B, int H, int S);
 uint64_t rov_mask_philox_calls(int B, int H, int S);
 
@@ -76,8 +84,8 @@ int rov_philox_raw(uint64_t seed, uint64_t first_counter, uint64_t ncalls, int r
  * numbers in HBM for later use by the Attention kernel").
  * Mask words are taken in groups of four (g = w / 4, r = w % 4).  Lane l of
  * group g makes Philox-4x32-10 call number offset + 64*g + l; output word r of
- * that call, x, decides bit l of mask word 4*g + r: keep iff x < T with
- * T = floor((1 - p) * 2^32) computed in double from the float p.
+ * that call, x, decides bit l of mask word 4*g + r: keep iff x < Tp with
+ * Tp = floor((1 - p) * 2^32) computed in double from the float p.
  * out: device, 8-byte aligned, rov_mask_words(B,H,S) uint64, fully overwritten.
  * Requires B,H,S > 0 and 0 <= p < 1 (p == 0 keeps everything). */
 int rov_dropout_mask_generate(uint64_t seed, uint64_t offset, int B, int H, int S, float p,

@@ -84,9 +84,10 @@ def mask_philox_calls(B, H, S):
 
 
 def dropout_mask(seed, offset, B, H, S, p, rounds=10):
-    """Keep-mask words, uint64[B, H, S, ceil(S/64)] (bit l of a word = column 64*cb+l)."""
-    W = (S + 63) // 64
-    out = np.zeros((B, H, S, W), dtype=np.uint64)
+    """Keep-mask words, uint64[B, H, T, T, 16] with T = ceil(S/32): 32 x 32 tiles of 16 words;
+    bit l of word e of tile (qt, kt) = element (32 qt + l%32, 32 kt + 8 (e/4) + 4 (l/32) + e%4)."""
+    T = (S + 31) // 32
+    out = np.zeros((B, H, T, T, 16), dtype=np.uint64)
     rc = lib().oracle_dropout_mask_rounds(int(seed) & (2**64 - 1), int(offset) & (2**64 - 1),
                                           B, H, S, ctypes.c_float(p), int(rounds), out.ctypes.data)
     if rc != 0:
@@ -104,10 +105,28 @@ def num_threads():
 
 
 def unpack_keep(words, S):
-    """bool[..., S] keep matrix from mask words [..., ceil(S/64)] (LSB-first bits)."""
+    """bool[..., S, S] keep matrix from mask words [..., T, T, 16] (T = ceil(S/32))."""
     w = np.ascontiguousarray(words, dtype="<u8")
-    bits = np.unpackbits(w.view(np.uint8), axis=-1, bitorder="little")
-    return bits[..., :S].astype(bool)
+    T = w.shape[-3]
+    lead = w.shape[:-3]
+    bits = np.unpackbits(w.view(np.uint8), axis=-1, bitorder="little")       # [..., qt, kt, 16*64]
+    bits = bits.reshape(lead + (T, T, 4, 4, 2, 32))                          # qt, kt, e/4, e%4, l/32, l%32
+    nd = len(lead)
+    # row = (qt, l%32); column = (kt, e/4, l/32, e%4)
+    order = tuple(range(nd)) + (nd + 0, nd + 5, nd + 1, nd + 2, nd + 4, nd + 3)
+    full = bits.transpose(order).reshape(lead + (32 * T, 32 * T))
+    return full[..., :S, :S].astype(bool)
+
+
+def unpack_keep_rows(tile_rows, S):
+    """bool[..., 32, S] for one row of tiles: words [..., T, 16] of a fixed qt."""
+    w = np.ascontiguousarray(tile_rows, dtype="<u8")
+    T = w.shape[-2]
+    lead = w.shape[:-2]
+    bits = np.unpackbits(w.view(np.uint8), axis=-1, bitorder="little").reshape(lead + (T, 4, 4, 2, 32))
+    nd = len(lead)
+    order = tuple(range(nd)) + (nd + 4, nd + 0, nd + 1, nd + 3, nd + 2)
+    return bits.transpose(order).reshape(lead + (32, 32 * T))[..., :S].astype(bool)
 
 
 # ---------------------------------------------------------------------------
@@ -133,20 +152,22 @@ def philox4x32_py(ctr, key, rounds=10):
 
 def dropout_mask_py(seed, offset, B, H, S, p, rounds=10):
     """Element-by-element evaluation of the mask definition (no grouping)."""
-    T = int((1.0 - float(np.float32(p))) * 4294967296.0)  # IEEE double, truncation = floor
-    W = (S + 63) // 64
-    out = np.zeros((B, H, S, W), dtype=np.uint64)
+    thr = int((1.0 - float(np.float32(p))) * 4294967296.0)  # IEEE double, truncation = floor
+    T = (S + 31) // 32
+    out = np.zeros((B, H, T, T, 16), dtype=np.uint64)
     flat = out.reshape(-1)
     key = [seed & _MASK32, (seed >> 32) & _MASK32]
     for w in range(flat.size):
         word = 0
+        e, kt, qt = w % 16, (w // 16) % T, (w // (16 * T)) % T
         for l in range(64):
-            j = 64 * (w % W) + l
-            if j >= S:
+            i = 32 * qt + l % 32
+            j = 32 * kt + 8 * (e // 4) + 4 * (l // 32) + e % 4
+            if i >= S or j >= S:
                 continue
             n = (offset + 64 * (w >> 2) + l) % 2**64
             x = philox4x32_py([n & _MASK32, n >> 32, 0, 0], key, rounds)[w & 3]
-            if x < T:
+            if x < thr:
                 word |= 1 << l
         flat[w] = word
     return out

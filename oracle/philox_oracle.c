@@ -14,8 +14,8 @@
  *    publication's Philox-4x32 and are pinned by its known-answer vectors.
  *  - The paper (Sec. 6.1, Sec. 7.2) says the stand-alone RNG kernel stores one
  *    bit per element of the B x nH x SQ x SQ score matrix.  The paper does not
- *    say how (seed, offset, element) map to (counter, key, output word); the
- *    map used here is a reading, written out in oracle_dropout_mask().
+ *    say how (seed, offset, element) map to (counter, key, output word, bit);
+ *    the map used here is a reading, written out in oracle_dropout_mask().
  *
  * Parity pins (tests marked "not gpu"): known-answer vectors for R = 10 and
  * R = 7, the C++26 engine's specified 10000th output, threshold closed forms,
@@ -89,10 +89,12 @@ int oracle_keep_threshold(float p, uint64_t *T)
     return 0;
 }
 
+/* Mask geometry: the S x S score matrix of one (batch, head) is cut into T x T tiles of
+ * 32 x 32 elements, T = ceil(S/32); a tile is 16 words of 64 bits. */
 uint64_t oracle_mask_words(int B, int H, int S)
 {
-    uint64_t W = ((uint64_t)S + 63u) / 64u;
-    return (uint64_t)B * (uint64_t)H * (uint64_t)S * W;
+    uint64_t T = ((uint64_t)S + 31u) / 32u;
+    return (uint64_t)B * (uint64_t)H * T * T * 16u;
 }
 
 /* Number of Philox calls one mask consumes: 64 lanes per group of 4 words. */
@@ -102,28 +104,32 @@ uint64_t oracle_mask_philox_calls(int B, int H, int S)
     return 64u * ((words + 3u) / 4u);
 }
 
-/* Keep-mask for a B x H x S x S score matrix (paper Sec. 6.1 / 7.2: one bit
- * per element, B*nH*SQ^2 bits).
+/* Keep-mask for a B x H x S x S score matrix (paper Sec. 6.1 / 7.2: one bit per element,
+ * B*nH*SQ^2 bits when S is a multiple of 32).
  *
- * Layout: each score row (b, h, i) occupies W = ceil(S/64) consecutive 64-bit
- * words; word index w = ((b*H + h)*S + i)*W + cb; bit l (LSB first) of word w
- * is column j = 64*cb + l.  Bits with j >= S are 0.  Bit = 1 means keep.
+ * Layout (the paper does not fix one; this is the reading taken): word index
+ *     w = (((b*H + h)*T + qt)*T + kt)*16 + e,   T = ceil(S/32), 0 <= e < 16;
+ * bit l (LSB first, 0 <= l < 64) of word w is the element
+ *     row  i = 32*qt + (l % 32),
+ *     col  j = 32*kt + 8*(e / 4) + 4*(l / 32) + (e % 4).
+ * This is the order in which a 64-lane wave of a CDNA matrix core holds a 32 x 32 fp32
+ * accumulator tile (lane l, register e), so a mask word is directly a per-lane predicate for
+ * one accumulator register.  Bits whose row or column is >= S are 0.  Bit = 1 means keep.
  *
- * Random words: words are taken in groups of four, g = w / 4, r = w % 4.
- * Lane l of group g makes Philox call number n = offset + 64*g + l (mod 2^64)
- * with `rounds` rounds; output word r of that call decides bit l of mask word
- * 4*g + r.  `offset` counts Philox calls.
+ * Random words: words are taken in groups of four, g = w / 4, r = w % 4.  Lane l of group g
+ * makes Philox call number n = offset + 64*g + l (mod 2^64) with `rounds` rounds; output word
+ * r of that call decides bit l of mask word 4*g + r.  `offset` counts Philox calls.
  *
  * Returns 0, or -1 for invalid arguments (out untouched). */
 int oracle_dropout_mask_rounds(uint64_t seed, uint64_t offset, int B, int H, int S,
                                float p, int rounds, uint64_t *out)
 {
-    uint64_t T;
+    uint64_t Tkeep;
     if (B <= 0 || H <= 0 || S <= 0 || rounds <= 0 || out == NULL) return -1;
-    if (oracle_keep_threshold(p, &T) != 0) return -1;
-    const uint64_t W = ((uint64_t)S + 63u) / 64u;
+    if (oracle_keep_threshold(p, &Tkeep) != 0) return -1;
+    const uint64_t T = ((uint64_t)S + 31u) / 32u;
     const uint64_t words = oracle_mask_words(B, H, S);
-    const uint64_t groups = (words + 3u) / 4u;
+    const uint64_t groups = words / 4u;   /* words is a multiple of 16 */
 
 #pragma omp parallel for schedule(static)
     for (int64_t gi = 0; gi < (int64_t)groups; ++gi) {
@@ -134,16 +140,16 @@ int oracle_dropout_mask_rounds(uint64_t seed, uint64_t offset, int B, int H, int
             philox_call(seed, offset + 64u * g + l, rounds, x);
             for (unsigned r = 0; r < 4; ++r) {
                 const uint64_t w = 4u * g + r;
-                if (w >= words) continue;
-                const uint64_t j = 64u * (w % W) + l; /* column of this bit */
-                if (j < (uint64_t)S && (uint64_t)x[r] < T)
+                const uint64_t e = w % 16u;
+                const uint64_t kt = (w / 16u) % T;
+                const uint64_t qt = (w / (16u * T)) % T;
+                const uint64_t i = 32u * qt + (l % 32u);                         /* row */
+                const uint64_t j = 32u * kt + 8u * (e / 4u) + 4u * (l / 32u) + (e % 4u);   /* column */
+                if (i < (uint64_t)S && j < (uint64_t)S && (uint64_t)x[r] < Tkeep)
                     acc[r] |= (uint64_t)1 << l;
             }
         }
-        for (unsigned r = 0; r < 4; ++r) {
-            const uint64_t w = 4u * g + r;
-            if (w < words) out[w] = acc[r];
-        }
+        for (unsigned r = 0; r < 4; ++r) out[4u * g + r] = acc[r];
     }
     return 0;
 }

@@ -149,12 +149,17 @@ def philox_raw(seed, first_counter, ncalls, rounds=10, out=None, stream=None):
     return out
 
 
+def mask_shape(B, H, S):
+    """Shape of the keep-mask word array: [B, H, T, T, 16] with T = ceil(S/32)."""
+    T = (S + 31) // 32
+    return (B, H, T, T, 16)
+
+
 def dropout_mask_generate(seed, offset, B, H, S, p, out=None, rounds=None, stream=None):
-    """Keep-mask words as an int64 tensor [B, H, S, ceil(S/64)] (bit patterns of uint64)."""
+    """Keep-mask words as an int64 tensor of shape mask_shape(B, H, S) (bit patterns of uint64)."""
     import torch
-    W = (S + 63) // 64
     if out is None:
-        out = torch.empty((B, H, S, W), dtype=torch.int64, device="cuda")
+        out = torch.empty(mask_shape(B, H, S), dtype=torch.int64, device="cuda")
     L = load()
     if rounds is None:
         rc = L.rov_dropout_mask_generate(seed & (2**64 - 1), offset & (2**64 - 1), B, H, S, p,

@@ -3,9 +3,10 @@
 // Three ways to get the keep bits, all giving the same bits:
 //   MODE_NONE  p == 0, no dropout;
 //   MODE_MASK  the paper's "attention with element dropping": keep-mask words written
-//              earlier by the stand-alone RNG kernel are loaded one KV tile ahead, so the
-//              loads sit under the Q K^T matrix multiply (Sec. 6.1);
-//   MODE_FUSED the paper's fusion baseline: the kernel runs Philox itself.
+//              earlier by the stand-alone RNG kernel; a word is the 64 lanes' keep bits for
+//              one accumulator register, fetched with scalar loads and applied with one
+//              select per element;
+//   MODE_FUSED the paper's fusion baseline: every lane runs Philox for its own elements.
 //
 // bf16 kernel, head dimension 64 or 128, on the matrix cores.  Everything is
 // computed transposed, S^T = K Q^T and O^T = V^T P^T with MFMA 32x32x16, because
@@ -43,7 +44,7 @@ struct AttnParams {
     const uint64_t* mask;
     int64_t sq[3], sk[3], sv[3], so[3];   // element strides (batch, token, head)
     int B, H, Hkv, S, d;
-    int W;                                // mask words per row
+    int W;                                // mask tiles per side, ceil(S/32)
     int nq;                               // query blocks per (batch, head)
     int causal;
     float scale_log2;                     // log2(e) / sqrt(d)
@@ -111,6 +112,7 @@ __device__ __forceinline__ void load_kv_tile(const uint16_t* __restrict__ Xp, in
     }
 }
 
+typedef const __attribute__((address_space(4))) uint64_t* const_u64_ptr;
 typedef short i16x4 __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) i16x4* lds_i16x4_ptr;
 
@@ -195,46 +197,23 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(const AttnParams p) 
     const int kv_end = p.causal ? min(S, q_last + 1) : S;
     const int ntiles = (kv_end + BKV - 1) / BKV;
 
-    // Keep words.  MODE_MASK: one 8-byte word per query row and KV tile, loaded one tile
-    // ahead.  MODE_FUSED: when W % 4 == 0 the words of 4 consecutive KV tiles of a row are one
-    // Philox group; the wave generates them with the group/ballot routine of the stand-alone
-    // RNG kernel into LDS, [2 buffers][NQ*32 rows][4 words].  Otherwise one word per row and
-    // tile is generated.
-    constexpr int kMaskBuf = NQ * 32 * 32;                       // bytes per buffer per wave
-    char* mlds = lds + 2 * T::kStage + wave * (2 * kMaskBuf);
-    const bool aligned4 = (p.W & 3) == 0;
-    const uint64_t row0_words = (((uint64_t)b * p.H + h) * S) * (uint64_t)p.W;   // first word of row 0
-    const uint64_t* mrow[NQ];
-    uint2 mword[NQ], mnext[NQ];
+    // Keep words.  The mask is stored as 32 x 32 tiles of 16 words in accumulator order (see
+    // rov.h): word e of tile (qt, kt) holds, in bit l, the keep bit of the element that lane l
+    // has in accumulator register e of S^T tile (keys 32*kt.., queries 32*qt..).  The wave's
+    // query tile is fixed, so its words for a KV tile are 2 x 16 consecutive, wave-uniform words:
+    // MODE_MASK fetches them with scalar loads and applies each with one select; MODE_FUSED
+    // needs no words at all, every lane draws the Philox outputs of its own elements.
+    const uint32_t Tt = (uint32_t)p.W;                                    // tiles per side
+    const uint64_t bh_tiles = ((uint64_t)b * p.H + h) * Tt;
+    const uint64_t* mtile[NQ];      // words of tile (qt, 0) for each of the wave's query tiles
+    uint64_t wtile[NQ];             // index of that word in the whole mask (fused: Philox numbering)
 #pragma unroll
     for (int n = 0; n < NQ; ++n) {
-        const int q = qrow[n] < S ? qrow[n] : S - 1;
-        mrow[n] = p.mask + row0_words + (uint64_t)q * p.W;
-        mword[n] = make_uint2(0xFFFFFFFFu, 0xFFFFFFFFu);
-        if (MODE == MODE_MASK) mnext[n] = *reinterpret_cast<const uint2*>(mrow[n]);
+        uint32_t qt = (uint32_t)(q0 / 32 + n);
+        qt = qt < Tt ? qt : Tt - 1;                                       // rows past S are never stored
+        wtile[n] = ((bh_tiles + qt) * Tt) * 16u;
+        mtile[n] = p.mask + wtile[n];
     }
-    // In-kernel generation of the same group: 16 rows at a time, word r of row gi parked in
-    // lane 4*gi + r, then one 8-byte LDS store per lane (same layout as the DMA).
-    auto mask_generate = [&](int group, int buf) {
-#pragma unroll 1
-        for (int c = 0; c < NQ * 2; ++c) {
-            uint32_t vlo = 0u, vhi = 0u;
-#pragma unroll 4
-            for (int gi = 0; gi < 16; ++gi) {
-                int row = q0 + 16 * c + gi;
-                row = row < S ? row : S - 1;
-                const uint64_t w = row0_words + (uint64_t)row * p.W + 4u * (uint64_t)group;
-                uint64_t bal[4];
-                philox_group_ballots<10, true>(p.offset + 64u * (w >> 2), lane, p.k0, p.k1, p.t_minus_1, bal);
-#pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    vlo = write_lane((uint32_t)bal[r], 4u * gi + r, vlo);
-                    vhi = write_lane((uint32_t)(bal[r] >> 32), 4u * gi + r, vhi);
-                }
-            }
-            *reinterpret_cast<uint2*>(mlds + buf * kMaskBuf + (64 * c + lane) * 8) = make_uint2(vlo, vhi);
-        }
-    };
 
     load_kv_tile<D, NW, false>(Kp, p.sk[1], 0, S, lds, wave, lane);
     load_kv_tile<D, NW, true>(Vp, p.sv[1], 0, S, lds + T::kKBytes, wave, lane);
@@ -252,6 +231,8 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(const AttnParams p) 
     }
 
     const int kswz = ql & 7;
+    static_assert(NQ == 1, "the keep-word warm-up load covers one query tile per wave");
+    uint32_t warm = 0u, sink = 0u;   // L2 warm-up of the next tile's keep words (MODE_MASK)
 
     for (int jt = 0; jt < ntiles; ++jt) {
         const int kv0 = jt * BKV;
@@ -264,48 +245,6 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(const AttnParams p) 
             load_kv_tile<D, NW, false>(Kp, p.sk[1], kv0 + BKV, S, nxt, wave, lane);
             load_kv_tile<D, NW, true>(Vp, p.sv[1], kv0 + BKV, S, nxt + T::kKBytes, wave, lane);
         }
-        if (MODE == MODE_MASK) {
-            // this tile's words were requested one tile ago, under the previous Q K^T product
-#pragma unroll
-            for (int n = 0; n < NQ; ++n) {
-                mword[n] = mnext[n];
-                if (has_next) mnext[n] = *reinterpret_cast<const uint2*>(mrow[n] + (jt + 1));
-            }
-        }
-        if (MODE == MODE_FUSED) {
-            const int group = jt >> 2, gbuf = group & 1;
-            if (aligned4) {
-                if ((jt & 3) == 0) mask_generate(group, gbuf);
-#pragma unroll
-                for (int n = 0; n < NQ; ++n)
-                    mword[n] = *reinterpret_cast<const uint2*>(mlds + gbuf * kMaskBuf +
-                                                               (32 * n + ql) * 32 + (jt & 3) * 8);
-            } else {
-                // one word per row and tile: the group holding word row*W + jt, its word w % 4
-#pragma unroll 1
-                for (int c = 0; c < NQ * 2; ++c) {
-                    uint32_t vlo = 0u, vhi = 0u;
-#pragma unroll 2
-                    for (int gi = 0; gi < 16; ++gi) {
-                        int row = q0 + 16 * c + gi;
-                        row = row < S ? row : S - 1;
-                        const uint64_t w = row0_words + (uint64_t)row * p.W + (uint64_t)jt;
-                        uint64_t bal[4];
-                        philox_group_ballots<10, true>(p.offset + 64u * (w >> 2), lane, p.k0, p.k1,
-                                                       p.t_minus_1, bal);
-                        const uint32_t sel = (uint32_t)(w & 3u);
-                        const uint64_t bw = sel == 0 ? bal[0] : sel == 1 ? bal[1] : sel == 2 ? bal[2] : bal[3];
-                        vlo = write_lane((uint32_t)bw, (uint32_t)gi, vlo);
-                        vhi = write_lane((uint32_t)(bw >> 32), (uint32_t)gi, vhi);
-                    }
-                    if (lane < 16) *reinterpret_cast<uint2*>(mlds + (16 * c + lane) * 8) = make_uint2(vlo, vhi);
-                }
-#pragma unroll
-                for (int n = 0; n < NQ; ++n)
-                    mword[n] = *reinterpret_cast<const uint2*>(mlds + (32 * n + ql) * 8);
-            }
-        }
-
         // ---- S^T = K Q^T for 64 keys x NQ*32 queries
         f32x16 s[2][NQ];
 #pragma unroll
@@ -325,6 +264,33 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(const AttnParams p) 
                 for (int n = 0; n < NQ; ++n)
                     s[t][n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[n][ks], s[t][n], 0, 0, 0);
             }
+        }
+
+        // ---- keep words of this KV tile: 2 key tiles x 16 words per query tile, wave-uniform.
+        // They are requested here, right after the Q K^T MFMAs have been issued, through the
+        // constant address space (memory nobody writes while this kernel runs), i.e. with
+        // scalar loads into the SGPR pairs that the selects below use as lane predicates.  The
+        // lines were pulled into L2 one tile earlier by `warm` (a vector load whose value is
+        // only folded into a sink), so the scalar loads return while the row maxima and
+        // exponentials are being computed.
+        uint64_t mw[NQ][2][16];
+        if (MODE == MODE_MASK) {
+#pragma unroll
+            for (int n = 0; n < NQ; ++n)
+#pragma unroll
+                for (int t = 0; t < 2; ++t) {
+                    uint32_t kt = (uint32_t)(2 * jt + t);
+                    kt = kt < Tt ? kt : Tt - 1;
+                    const const_u64_ptr wp = (const_u64_ptr)(uintptr_t)(mtile[n] + (uint64_t)kt * 16u);
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) mw[n][t][e] = wp[e];
+                }
+            sink ^= warm;                       // the previous warm-up load has long landed
+            // 64 lanes x 4 bytes = the 32 words of the next two key tiles (16 words if the tile
+            // row has a single tile); clamped so that it never leaves this query tile's row
+            uint32_t ktn = (uint32_t)(2 * jt + 2);
+            ktn = ktn + 1 < Tt ? ktn : (Tt >= 2 ? Tt - 2 : 0);
+            warm = reinterpret_cast<const uint32_t*>(mtile[0] + (uint64_t)ktn * 16u)[lane & (Tt >= 2 ? 63 : 31)];
         }
 
         // ---- online softmax, dropout, P^T fragments
@@ -355,18 +321,38 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(const AttnParams p) 
             float sum = 0.0f;
 #pragma unroll
             for (int t = 0; t < 2; ++t) {
-                uint32_t bits = 0xFFFFFFFFu;
-                if (MODE != MODE_NONE) bits = (t == 0 ? mword[n].x : mword[n].y) >> (4 * half);
+                uint32_t kt = (uint32_t)(2 * jt + t);
+                kt = kt < Tt ? kt : Tt - 1;        // a key tile past S: its scores are -inf already
 #pragma unroll
                 for (int e = 0; e < 16; ++e) {
-                    float pe = fast_exp2(s[t][n][e] - m_safe);
+                    const float pe = fast_exp2(s[t][n][e] - m_safe);
                     sum += pe;   // the normaliser counts dropped entries too
-                    if (MODE != MODE_NONE) {
-                        // sign-extended 1-bit field -> all-ones / zero mask, then one AND
-                        const int keep = __builtin_amdgcn_sbfe((int)bits, 8 * (e >> 2) + (e & 3), 1);
-                        pe = __uint_as_float(__float_as_uint(pe) & (uint32_t)keep);
-                    }
                     s[t][n][e] = pe;
+                }
+                if (MODE == MODE_MASK) {
+#pragma unroll
+                    for (int e = 0; e < 16; ++e)
+                        s[t][n][e] = __builtin_amdgcn_inverse_ballot_w64(mw[n][t][e]) ? s[t][n][e] : 0.0f;
+                }
+                if (MODE == MODE_FUSED) {
+                    // word e = 4*c + r of this tile is output r of the lane's Philox call
+                    // offset + 64*(first_word/4 + c) + lane
+                    const uint64_t g0 = (wtile[n] + (uint64_t)kt * 16u) >> 2;
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) {
+                        const uint64_t base = p.offset + 64u * (g0 + (uint64_t)c);
+                        const uint32_t blo = (uint32_t)base, bhi = (uint32_t)(base >> 32);
+                        const uint32_t c0 = blo + (uint32_t)lane;
+                        uint32_t x[4];
+                        if (blo <= 0xFFFFFFFFu - 63u) {
+                            philox4x32_low_counter<10>(c0, bhi, p.k0, p.k1, x);
+                        } else {
+                            philox4x32<10>(c0, bhi + (c0 < blo ? 1u : 0u), 0u, 0u, p.k0, p.k1, x);
+                        }
+#pragma unroll
+                        for (int r = 0; r < 4; ++r)
+                            s[t][n][4 * c + r] = x[r] <= p.t_minus_1 ? s[t][n][4 * c + r] : 0.0f;
+                    }
                 }
             }
             l_run[n] = l_run[n] * alpha + sum;
@@ -402,6 +388,10 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(const AttnParams p) 
         }
 
     }
+
+    // the warm-up values only have to look used (no mask pattern makes this condition true
+    // for a lane id >= 64)
+    if (MODE == MODE_MASK && (sink ^ warm) == 0x9E3779B9u && lane == 1000) m_run[0] = 0.0f;
 
     // ---- normalise, scale kept entries by 1/(1-p), store O (lane: query ql, 4 consecutive dv per e/4)
 #pragma unroll
@@ -471,7 +461,9 @@ __global__ __launch_bounds__(256) void attn_generic_kernel(const AttnParams p) {
     float acc[4] = {0.f, 0.f, 0.f, 0.f};   // output features lane, lane+64, lane+128, lane+192
     float m_run = -INFINITY, l_run = 0.0f;
     const int kv_end = p.causal ? row + 1 : S;
-    const uint64_t wrow = (((uint64_t)b * p.H + h) * S + row) * p.W;
+    // tile row of this query row in the mask: words of tile (row/32, kt) start at wrow + 16*kt;
+    // element (row, key) is bit 32*((key%32)/4 % 2) + row%32 of word 4*((key%32)/8) + key%4
+    const uint64_t wrow = ((((uint64_t)b * p.H + h) * p.W + (uint64_t)(row >> 5)) * p.W) * 16u;
     for (int c0 = 0; c0 < kv_end; c0 += 256) {
         float sc[4];
         float mx = -INFINITY;
@@ -501,11 +493,13 @@ __global__ __launch_bounds__(256) void attn_generic_kernel(const AttnParams p) {
                 pe = fast_exp2(sc[i] - m_new);
                 sum += pe;
                 bool keep = true;
+                const int kl = key & 31;
+                const uint64_t w = wrow + (uint64_t)(key >> 5) * 16u + (uint64_t)(4 * (kl >> 3) + (kl & 3));
+                const uint32_t bit = 32u * ((uint32_t)(kl >> 2) & 1u) + ((uint32_t)row & 31u);
                 if (MODE == MODE_MASK) {
-                    keep = (p.mask[wrow + (key >> 6)] >> (key & 63)) & 1ull;
+                    keep = (p.mask[w] >> bit) & 1ull;
                 } else if (MODE == MODE_FUSED) {
-                    const uint64_t w = wrow + (uint64_t)(key >> 6);
-                    const uint64_t ncall = p.offset + 64u * (w >> 2) + (uint64_t)(key & 63);
+                    const uint64_t ncall = p.offset + 64u * (w >> 2) + (uint64_t)bit;
                     uint32_t x[4];
                     philox4x32<10>((uint32_t)ncall, (uint32_t)(ncall >> 32), 0u, 0u, p.k0, p.k1, x);
                     const uint32_t sel = (uint32_t)(w & 3u);
@@ -547,7 +541,7 @@ int launch_bf16(const AttnParams& prm, int mode, hipStream_t stream) {
     const long long nblocks = (long long)prm2.nq * prm.H * prm.B;
     if (nblocks > 0x7FFFFFFFLL) return ROV_ERR_UNSUPPORTED;
     const dim3 grid((unsigned)nblocks), block(NW * 64);
-    const int lds_bytes = 2 * Tile<D>::kStage + NW * 2 * (NQ * 32 * 32);   // K/V stages + per-wave keep words
+    const int lds_bytes = 2 * Tile<D>::kStage;   // two K/V stages
     void (*kern)(const AttnParams) = mode == MODE_NONE   ? attn_bf16_kernel<D, NQ, NW, MODE_NONE>
                                      : mode == MODE_MASK ? attn_bf16_kernel<D, NQ, NW, MODE_MASK>
                                                          : attn_bf16_kernel<D, NQ, NW, MODE_FUSED>;
@@ -593,7 +587,7 @@ int launch_attention(const void* Q, const void* K, const void* V, void* O, int B
         prm.sv[i] = strides[6 + i]; prm.so[i] = strides[9 + i];
     }
     prm.B = B; prm.H = H; prm.Hkv = Hkv; prm.S = S; prm.d = d;
-    prm.W = (S + 63) / 64;
+    prm.W = (S + 31) / 32;
     prm.causal = causal != 0;
     prm.scale_log2 = 1.4426950408889634f / sqrtf((float)d);
     prm.inv_keep = p > 0.0f ? 1.0f / (1.0f - p) : 1.0f;

@@ -4,9 +4,11 @@
 //
 // Shape of the work on gfx950: the kernel reads nothing and is bound by VALU
 // issue (20 wide multiplies per call, Table 1 "ALU pipe"/"Issue stage").  One
-// wave owns a chunk of 64 consecutive mask words = 16 groups of 4 words.  For
-// each group every lane makes one Philox call; the four compares of its output
-// words are, as 64-lane ballots, exactly the four mask words of the group.
+// wave owns a chunk of 64 consecutive mask words = 16 groups of 4 words = 4
+// tiles of 32 x 32 score elements.  For each group every lane makes one Philox
+// call; the four compares of its output words are, as 64-lane ballots, exactly
+// the four mask words of the group (a mask word is the 64 lanes' bits for one
+// accumulator register of a 32 x 32 MFMA tile, see rov.h).
 // Each ballot is dropped into the lane that will store it (v_writelane), and
 // after 16 groups the wave issues one fully coalesced 512-byte store.
 #include <hip/hip_runtime.h>
@@ -27,25 +29,38 @@ constexpr int kGroupsPerChunk = 16;   // 16 groups x 4 words = 64 words = one 8-
 std::atomic<int> g_rng_max_workgroups{0};
 std::atomic<int> g_rng_overlap_wgs_per_cu{2};
 
-// One chunk: 16 groups -> 64 mask words, word 4*gi + r parked in lane 4*gi + r of (vhi:vlo).
+// One chunk: 16 groups -> 64 mask words = 4 whole tiles of 32 x 32 elements; word 4*gi + r is
+// parked in lane 4*gi + r of (vhi:vlo).  RAGGED (S % 32 != 0): bits whose row or column lies
+// beyond S are cleared; (qt, kt) are the tile coordinates of the chunk's first tile.
 template <int R, bool RAGGED, bool CARRY>
 __device__ __forceinline__ void mask_chunk(uint64_t base, uint32_t lane, uint32_t k0, uint32_t k1,
-                                           uint32_t t_minus_1, uint32_t W, uint32_t cb,
-                                           uint64_t tail_mask, uint32_t& vlo, uint32_t& vhi) {
+                                           uint32_t t_minus_1, uint32_t T, uint32_t S, uint32_t qt,
+                                           uint32_t kt, uint32_t& vlo, uint32_t& vhi) {
 #pragma unroll 2
     for (int gi = 0; gi < kGroupsPerChunk; ++gi) {
         uint64_t b[4];
         philox_group_ballots<R, CARRY>(base + 64u * (uint64_t)gi, lane, k0, k1, t_minus_1, b);
+        uint32_t row_mask = 0xFFFFFFFFu;
+        if (RAGGED) {
+            const uint32_t rows_valid = S - 32u * qt;          // >= 1
+            if (rows_valid < 32u) row_mask = (1u << rows_valid) - 1u;
+        }
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-            uint64_t bits = b[r];
+            uint32_t lo = (uint32_t)b[r], hi = (uint32_t)(b[r] >> 32);
             if (RAGGED) {
-                if (cb == W - 1u) bits &= tail_mask;   // columns >= S stay 0
-                cb = (cb + 1u == W) ? 0u : cb + 1u;
+                // word e = 4*(gi%4) + r: lanes 0-31 hold column 32*kt + 8*(gi%4) + r, lanes 32-63 that + 4
+                const uint32_t col = 32u * kt + 8u * ((uint32_t)gi & 3u) + (uint32_t)r;
+                lo = col < S ? (lo & row_mask) : 0u;
+                hi = col + 4u < S ? (hi & row_mask) : 0u;
             }
             const uint32_t dst = 4u * (uint32_t)gi + (uint32_t)r;
-            vlo = write_lane((uint32_t)bits, dst, vlo);
-            vhi = write_lane((uint32_t)(bits >> 32), dst, vhi);
+            vlo = write_lane(lo, dst, vlo);
+            vhi = write_lane(hi, dst, vhi);
+        }
+        if (RAGGED && (gi & 3) == 3) {   // next tile
+            kt = kt + 1u == T ? 0u : kt + 1u;
+            if (kt == 0u) qt = qt + 1u == T ? 0u : qt + 1u;
         }
     }
 }
@@ -53,21 +68,25 @@ __device__ __forceinline__ void mask_chunk(uint64_t base, uint32_t lane, uint32_
 template <int R, bool RAGGED>
 __global__ __launch_bounds__(kWavesPerBlock * 64) void mask_kernel(
     uint64_t* __restrict__ out, uint64_t words, uint64_t nchunks, uint64_t offset, uint32_t k0,
-    uint32_t k1, uint32_t t_minus_1, uint32_t W, uint64_t tail_mask) {
+    uint32_t k1, uint32_t t_minus_1, uint32_t T, uint32_t S) {
     const uint32_t lane = threadIdx.x & 63u;
     const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const uint64_t stride = (uint64_t)gridDim.x * kWavesPerBlock;
     for (uint64_t chunk = (uint64_t)blockIdx.x * kWavesPerBlock + wave; chunk < nchunks;
          chunk += stride) {
         uint32_t vlo = 0u, vhi = 0u;
-        uint32_t cb = 0u;   // column block of the chunk's first word (ragged rows only)
-        if (RAGGED) cb = (uint32_t)((chunk * 64u) % W);
+        uint32_t qt = 0u, kt = 0u;   // tile coordinates of the chunk's first tile (ragged only)
+        if (RAGGED) {
+            const uint64_t tile = chunk * 4u;
+            kt = (uint32_t)(tile % T);
+            qt = (uint32_t)((tile / T) % T);
+        }
         // first call number of the chunk; its 1024 calls are base .. base + 1023
         const uint64_t base = offset + 64u * kGroupsPerChunk * chunk;
         if ((uint32_t)base <= 0xFFFFFFFFu - (64u * kGroupsPerChunk - 1u)) {
-            mask_chunk<R, RAGGED, false>(base, lane, k0, k1, t_minus_1, W, cb, tail_mask, vlo, vhi);
+            mask_chunk<R, RAGGED, false>(base, lane, k0, k1, t_minus_1, T, S, qt, kt, vlo, vhi);
         } else {
-            mask_chunk<R, RAGGED, true>(base, lane, k0, k1, t_minus_1, W, cb, tail_mask, vlo, vhi);
+            mask_chunk<R, RAGGED, true>(base, lane, k0, k1, t_minus_1, T, S, qt, kt, vlo, vhi);
         }
         const uint64_t widx = chunk * 64u + lane;
         if (widx < words) out[widx] = ((uint64_t)vhi << 32) | vlo;
@@ -89,7 +108,7 @@ __global__ __launch_bounds__(256) void raw_kernel(uint32_t* __restrict__ out, ui
 template <int R>
 int launch_mask_r(uint64_t* out, uint64_t words, uint64_t offset, uint32_t k0, uint32_t k1,
                   uint32_t t_minus_1, int S, bool coresident, hipStream_t stream) {
-    const uint32_t W = (uint32_t)(((uint64_t)S + 63u) / 64u);
+    const uint32_t T = (uint32_t)(((uint64_t)S + 31u) / 32u);
     const uint64_t nchunks = (words + 63u) / 64u;
     uint64_t blocks = (nchunks + kWavesPerBlock - 1) / kWavesPerBlock;
     int cap = g_rng_max_workgroups.load();
@@ -100,15 +119,13 @@ int launch_mask_r(uint64_t* out, uint64_t words, uint64_t offset, uint32_t k0, u
         cap = coresident ? device_cu_count() * g_rng_overlap_wgs_per_cu.load() : device_cu_count() * 64;
     }
     if (blocks > (uint64_t)cap) blocks = (uint64_t)cap;
-    const int rem = S & 63;
     const dim3 grid((unsigned)blocks), block(kWavesPerBlock * 64);
-    if (rem == 0) {
+    if ((S & 31) == 0) {
         hipLaunchKernelGGL((mask_kernel<R, false>), grid, block, 0, stream, out, words, nchunks,
-                           offset, k0, k1, t_minus_1, W, ~0ull);
+                           offset, k0, k1, t_minus_1, T, (uint32_t)S);
     } else {
-        const uint64_t tail_mask = (1ull << rem) - 1ull;
         hipLaunchKernelGGL((mask_kernel<R, true>), grid, block, 0, stream, out, words, nchunks,
-                           offset, k0, k1, t_minus_1, W, tail_mask);
+                           offset, k0, k1, t_minus_1, T, (uint32_t)S);
     }
     ROV_LAUNCH_CHECK();
     return ROV_OK;
@@ -130,11 +147,11 @@ int launch_mask(uint64_t seed, uint64_t offset, int B, int H, int S, float p, in
     if (!aligned(out, 8)) return ROV_ERR_INVALID;
     uint32_t tm1;
     if (!keep_threshold_minus_1(p, &tm1)) return ROV_ERR_INVALID;
-    const uint64_t W = ((uint64_t)S + 63u) / 64u;
-    // words = B*H*S*W; refuse anything that cannot be a real buffer (> 2^40 words)
-    const long double wd = (long double)B * H * S * W;
+    const uint64_t T = ((uint64_t)S + 31u) / 32u;
+    // words = B*H*T*T*16; refuse anything that cannot be a real buffer (> 2^40 words)
+    const long double wd = (long double)B * H * T * T * 16.0L;
     if (wd > 1099511627776.0L) return ROV_ERR_UNSUPPORTED;
-    const uint64_t words = (uint64_t)B * (uint64_t)H * (uint64_t)S * W;
+    const uint64_t words = (uint64_t)B * (uint64_t)H * T * T * 16u;
     const uint32_t k0 = (uint32_t)seed, k1 = (uint32_t)(seed >> 32);
     switch (rounds) {
         case 10: return launch_mask_r<10>(out, words, offset, k0, k1, tm1, S, coresident, stream);
@@ -151,8 +168,8 @@ extern "C" {
 
 uint64_t rov_mask_words(int B, int H, int S) {
     if (B <= 0 || H <= 0 || S <= 0) return 0;
-    const uint64_t W = ((uint64_t)S + 63u) / 64u;
-    return (uint64_t)B * (uint64_t)H * (uint64_t)S * W;
+    const uint64_t T = ((uint64_t)S + 31u) / 32u;
+    return (uint64_t)B * (uint64_t)H * T * T * 16u;
 }
 
 uint64_t rov_mask_philox_calls(int B, int H, int S) {

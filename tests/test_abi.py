@@ -27,12 +27,13 @@ def test_header_symbols_are_exported_and_bound():
 def test_host_only_entry_points():
     L = binding.load()
     assert L.rov_version().startswith(b"rov")
-    assert binding.mask_words(1, 2, 128) == 512
-    assert binding.mask_words(1, 1, 70) == 140
+    assert binding.mask_words(1, 2, 128) == 2 * 4 * 4 * 16
+    assert binding.mask_words(1, 1, 70) == 3 * 3 * 16
     assert binding.mask_words(0, 1, 70) == 0
     assert binding.mask_philox_calls(1, 2, 128) == 64 * 128
-    assert binding.mask_philox_calls(1, 1, 70) == 64 * 35
-    assert binding.mask_philox_calls(1, 1, 1) == 64
+    assert binding.mask_philox_calls(1, 1, 70) == 64 * 36
+    assert binding.mask_philox_calls(1, 1, 1) == 64 * 4
+    assert binding.mask_shape(2, 3, 70) == (2, 3, 3, 3, 16)
     assert L.rov_last_hip_error() == 0
 
 

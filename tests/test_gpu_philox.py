@@ -95,8 +95,8 @@ def test_mask_largest_workload_sampled_and_counted():
     B, H, S, p = c["B"], c["H"], c["S"], c["p"]
     print("mask cfg5", flush=True)
     m = rov.dropout_mask_generate(wl.SEED, wl.OFFSET, B, H, S, p)
-    W = S // 64
-    words_per_head = S * W
+    T = S // 32
+    words_per_head = T * T * 16
     for h in (0, 13, 31):
         # head h alone is the mask tail starting at word h*words_per_head (offset splitting)
         exp = OP.dropout_mask(wl.SEED, wl.OFFSET + 64 * (h * words_per_head // 4), 1, 1, S, p)
@@ -117,7 +117,7 @@ def test_mask_largest_workload_sampled_and_counted():
 
 def test_mask_error_paths_leave_output_untouched():
     import torch
-    out = torch.full((1, 1, 64, 1), 0x5A5A5A5A, dtype=torch.int64, device="cuda")
+    out = torch.full(rov.mask_shape(1, 1, 64), 0x5A5A5A5A, dtype=torch.int64, device="cuda")
     L = rov.load()
     ptr = ctypes.c_void_p(out.data_ptr())
     s = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)

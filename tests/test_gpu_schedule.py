@@ -41,7 +41,7 @@ def test_layer_step_three_schedules(dtype, B, S, H, Hkv, d, gemm):
         print("layer_step", dtype, sched, flush=True)
         O = torch.zeros_like(Q)
         C = torch.zeros((M, N), dtype=torch.float32 if dtype == torch.float32 else torch.bfloat16, device="cuda")
-        mask = torch.full((B, H, S, (S + 63) // 64), 0x2AAAAAAAAAAAAAAA, dtype=torch.int64, device="cuda")  # poison
+        mask = torch.full(rov.mask_shape(B, H, S), 0x2AAAAAAAAAAAAAAA, dtype=torch.int64, device="cuda")  # poison
         torch.cuda.synchronize()
         gd = [rov.make_gemm_desc(A, W, C)]
         ad = rov.make_attn_desc(Q, K, V, O, p)
@@ -69,7 +69,7 @@ def test_layer_step_invalid_arguments():
     s = torch.cuda.Stream()
     with pytest.raises(rov.RovError):
         rov.layer_step(rov.SCHED_OVERLAP, [], ad, 1, 0, None, s, torch.cuda.Stream())      # mask missing
-    mask = torch.zeros((1, 2, 64, 1), dtype=torch.int64, device="cuda")
+    mask = torch.zeros(rov.mask_shape(1, 2, 64), dtype=torch.int64, device="cuda")
     with pytest.raises(rov.RovError):
         rov.layer_step(rov.SCHED_OVERLAP, [], ad, 1, 0, mask, s, s)                        # same stream
     with pytest.raises(rov.RovError):
@@ -98,13 +98,12 @@ def test_block_forward_three_schedules_match_oracle(causal):
     weights = rov.make_block_weights(wd)
     ws = torch.empty(rov.block_workspace_bytes(cfg, B, S, 0), dtype=torch.uint8, device="cuda")
     main, side = torch.cuda.Stream(), torch.cuda.Stream()
-    W = (S + 63) // 64
     ys = {}
     for name, sched, ready in (("seq", rov.SCHED_SEQUENTIAL, False), ("fused", rov.SCHED_FUSED, False),
                                ("ovl_first", rov.SCHED_OVERLAP, False), ("ovl_steady", rov.SCHED_OVERLAP, True)):
         print("block", name, causal, flush=True)
         y = torch.zeros_like(x)
-        mask = torch.zeros((B, H, S, W), dtype=torch.int64, device="cuda")
+        mask = torch.zeros(rov.mask_shape(B, H, S), dtype=torch.int64, device="cuda")
         nxt = torch.zeros_like(mask) if name == "ovl_steady" else None
         if ready:
             rov.dropout_mask_generate(seed, offset, B, H, S, p, out=mask)
@@ -137,7 +136,7 @@ def test_block_workspace_and_argument_errors():
     assert need >= 2 * T * (2 * hidden + (H + 2 * Hkv) * d + H * d + 2 * ffn)
     ws = torch.empty(need - 256, dtype=torch.uint8, device="cuda")
     y = torch.full_like(x, 5.0)
-    mask = torch.zeros((B, H, S, 1), dtype=torch.int64, device="cuda")
+    mask = torch.zeros(rov.mask_shape(B, H, S), dtype=torch.int64, device="cuda")
     s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
     with pytest.raises(rov.RovError) as e:
         rov.block_forward(weights, x, y, cfg, rov.SCHED_SEQUENTIAL, 1, 0, mask, ws, s1, s2)

@@ -29,8 +29,8 @@ def _randn(gen, *shape, sd=1.0, dtype=torch.bfloat16):
 
 
 def _check_mask_heads(mask, seed, offset, B, H, S, p, heads):
-    W = S // 64
-    per_head = S * W
+    T = S // 32
+    per_head = T * T * 16
     for b, h in heads:
         first = (b * H + h) * per_head
         exp = OP.dropout_mask(seed, offset + 64 * (first // 4), 1, 1, S, p)
@@ -38,8 +38,12 @@ def _check_mask_heads(mask, seed, offset, B, H, S, p, heads):
 
 
 def _keep_rows(mask, b, h, rows, S):
-    words = mask[b, h][rows].cpu().numpy().view(np.uint64)
-    return OP.unpack_keep(words, S)          # [len(rows), S]
+    """bool [len(rows), S]: keep bits of the sampled query rows, unpacked from their tile rows."""
+    out = np.zeros((len(rows), S), dtype=bool)
+    for n, r in enumerate(rows):
+        tile_row = mask[b, h, r // 32].cpu().numpy().view(np.uint64)     # [T, 16]
+        out[n] = OP.unpack_keep_rows(tile_row, S)[r % 32]
+    return out
 
 
 def _attention_rows_ref(Q, K, V, mask, p, b, h, rows, causal):
@@ -77,7 +81,7 @@ def test_workload3_b2_s4k_layer_step_schedules():
     for sched in (rov.SCHED_SEQUENTIAL, rov.SCHED_FUSED, rov.SCHED_OVERLAP):
         print("cfg3 schedule", sched, flush=True)
         O = torch.zeros_like(Q)
-        mask = torch.zeros((B, H, S, S // 64), dtype=torch.int64, device="cuda")
+        mask = torch.zeros(rov.mask_shape(B, H, S), dtype=torch.int64, device="cuda")
         gd = [rov.make_gemm_desc(a, w, cc) for a, w, cc in ops]
         rov.layer_step(sched, gd, rov.make_attn_desc(Q, K, V, O, p), wl.SEED, wl.OFFSET,
                        None if sched == rov.SCHED_FUSED else mask, main, side)
@@ -126,7 +130,7 @@ def test_workload4_llama70b_fp8_gemms_and_gqa_attention():
     # overlap schedule: fp8 QKV GEMM || RNG (64 x 8192^2 bits = 512 MiB), then GQA attention in bf16
     Q, K, V = _randn(gen, B, S, H, d), _randn(gen, B, S, Hkv, d), _randn(gen, B, S, Hkv, d)
     O = torch.zeros_like(Q)
-    mask = torch.zeros((B, H, S, S // 64), dtype=torch.int64, device="cuda")
+    mask = torch.zeros(rov.mask_shape(B, H, S), dtype=torch.int64, device="cuda")
     main, side = torch.cuda.Stream(), torch.cuda.Stream()
     print("cfg4 overlap step", flush=True)
     rov.layer_step(rov.SCHED_OVERLAP, gemm_descs, rov.make_attn_desc(Q, K, V, O, p), wl.SEED, wl.OFFSET, mask, main, side)

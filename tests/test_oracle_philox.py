@@ -119,7 +119,7 @@ def test_mask_worked_example_tiny_config():
 
 @pytest.mark.parametrize("B,H,S,p,seed,offset", [
     (1, 2, 128, 0.1, 1234, 0),
-    (1, 1, 70, 0.3, 99, 5),             # ragged: S not a multiple of 64; words not a multiple of 4
+    (1, 1, 70, 0.3, 99, 5),             # ragged: S not a multiple of 32 (padding rows and columns)
     (2, 3, 33, 0.5, 2**40 + 7, 2**32 - 64),   # carry into the second counter word
     (1, 1, 1, 0.1, 1, 0),
 ])
@@ -131,9 +131,8 @@ def test_mask_c_matches_python_integers(B, H, S, p, seed, offset):
 
 def test_mask_equals_thresholded_raw_stream():
     # mask bit (w, l) == raw[offset + 64*(w>>2) + l][w & 3] < T, built with numpy from the raw stream
-    B, H, S, p, seed, offset = 1, 3, 192, 0.1, 777, 12345
-    W = 3
-    words = B * H * S * W
+    B, H, S, p, seed, offset = 1, 3, 192, 0.1, 777, 12345      # S % 32 == 0: no padding bits
+    words = B * H * (S // 32) ** 2 * 16
     raw = P.philox_raw(seed, offset, 64 * ((words + 3) // 4), 10).reshape(-1, 64, 4)   # [g, l, r]
     bits = (raw.astype(np.uint64) < P.keep_threshold(p)).transpose(0, 2, 1).reshape(-1, 64)[:words]  # [w, l]
     weights = (np.uint64(1) << np.arange(64, dtype=np.uint64))
@@ -143,12 +142,41 @@ def test_mask_equals_thresholded_raw_stream():
 
 
 def test_mask_padding_bits_are_zero_and_p0_keeps_all():
-    S = 70
+    S = 70                                   # 3 x 3 tiles of 32: rows / columns 70..95 are padding
     m = P.dropout_mask(5, 0, 1, 2, S, 0.0)
-    keep = P.unpack_keep(m, 128)
-    assert keep[..., :S].all() and not keep[..., S:].any()
+    keep = P.unpack_keep(m, 96)
+    assert keep[..., :S, :S].all() and not keep[..., S:, :].any() and not keep[..., :, S:].any()
+    assert P.popcount(m) == 2 * S * S
     m = P.dropout_mask(5, 0, 1, 2, S, 0.4)
-    assert not P.unpack_keep(m, 128)[..., S:].any()
+    k2 = P.unpack_keep(m, 96)
+    assert not k2[..., S:, :].any() and not k2[..., :, S:].any()
+
+
+def test_mask_layout_element_to_word_bit_map():
+    # element (i, j) of head h sits in tile (i/32, j/32), word e = 4*((j%32)/8) + (j%32)%4,
+    # bit l = 32*(((j%32)/4)%2) + i%32 -- spelled out here independently of unpack_keep
+    B, H, S, p = 1, 2, 100, 0.3
+    m = P.dropout_mask(21, 9, B, H, S, p)
+    keep = P.unpack_keep(m, S)
+    rng = np.random.default_rng(0)
+    for _ in range(500):
+        h, i, j = int(rng.integers(H)), int(rng.integers(S)), int(rng.integers(S))
+        jl = j % 32
+        e = 4 * (jl // 8) + jl % 4
+        l = 32 * ((jl // 4) % 2) + i % 32
+        assert ((int(m[0, h, i // 32, j // 32, e]) >> l) & 1) == int(keep[0, h, i, j])
+    # the raw-stream view of the same bit: word index w, group w//4, lane l, output word w%4
+    T = 4
+    raw = P.philox_raw(21, 9, 64 * (m.size // 4), 10)
+    thr = P.keep_threshold(p)
+    for _ in range(200):
+        h, i, j = int(rng.integers(H)), int(rng.integers(S)), int(rng.integers(S))
+        jl = j % 32
+        e, l = 4 * (jl // 8) + jl % 4, 32 * ((jl // 4) % 2) + i % 32
+        w = ((h * T + i // 32) * T + j // 32) * 16 + e
+        assert bool(keep[0, h, i, j]) == (int(raw[64 * (w // 4) + l, w % 4]) < thr)
+    # one row of tiles unpacks to the same 32 rows
+    assert np.array_equal(P.unpack_keep_rows(m[0, 1, 2], S), keep[0, 1, 64:96])
 
 
 def test_mask_reproducible_and_seed_offset_sensitive():
@@ -183,10 +211,10 @@ def test_offset_splitting():
     # a mask generated from word 4k on, with the offset advanced by 64k calls, is the tail of the full mask
     B, H, S, p = 1, 4, 128, 0.1
     full = P.dropout_mask(42, 1000, B, H, S, p).reshape(-1)
-    # tail that starts at head 2: words = 2*128*2 = 512 => k = 128 groups
+    # tail that starts at head 2: words = 2 heads * 16 tiles * 16 = 512 => k = 128 groups
     tail = P.dropout_mask(42, 1000 + 64 * 128, 1, 2, S, p).reshape(-1)
     assert np.array_equal(full[512:], tail)
-    assert P.mask_philox_calls(B, H, S) == 64 * (B * H * S * 2 // 4)
+    assert P.mask_philox_calls(B, H, S) == 64 * (B * H * 16 * 16 // 4)
     # consecutive masks with the offset advanced by mask_philox_calls never share a call:
     nxt = P.dropout_mask(42, 1000 + P.mask_philox_calls(B, H, S), B, H, S, p).reshape(-1)
     assert not np.array_equal(full, nxt)
@@ -202,16 +230,17 @@ def test_monotone_in_p():
 def test_lane_word_and_row_independence_smoke():
     B, H, S, p = 1, 8, 512, 0.5
     m = P.dropout_mask(3, 0, B, H, S, p)
-    keep = P.unpack_keep(m, S).reshape(-1, S // 64, 64)       # [row, cb, lane]
     q = 0.5
-    n_per_lane = keep.shape[0] * keep.shape[1]
-    lane_freq = keep.sum(axis=(0, 1)) / n_per_lane
-    assert np.all(np.abs(lane_freq - q) <= 4.5 * math.sqrt(q * (1 - q) / n_per_lane))
     flat = m.reshape(-1)
+    bits = np.unpackbits(flat.view(np.uint8).reshape(-1, 8), axis=1, bitorder="little")   # [word, lane]
+    n_per_lane = bits.shape[0]
+    lane_freq = bits.sum(axis=0) / n_per_lane
+    assert np.all(np.abs(lane_freq - q) <= 4.5 * math.sqrt(q * (1 - q) / n_per_lane))
     for r in range(4):                                          # frequency per word slot r = w & 3
         sub = flat[r::4]
         assert _four_sigma_ok(P.popcount(sub), sub.size * 64, q)
     rows = P.unpack_keep(m, S).reshape(-1, S)
+    assert abs(rows.mean() - q) <= 4 * math.sqrt(q * (1 - q) / rows.size)
     x = np.logical_xor(rows[:-1], rows[1:]).mean()
     assert abs(x - 2 * q * (1 - q)) < 4 * math.sqrt(0.25 / rows[:-1].size)
 

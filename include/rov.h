@@ -91,6 +91,14 @@ int rov_philox_raw(uint64_t seed, uint64_t first_counter, uint64_t ncalls, int r
 int rov_dropout_mask_generate(uint64_t seed, uint64_t offset, int B, int H, int S, float p,
                               uint64_t *out, void *stream);
 
+/* Same bits, but only what causal attention reads: every tile with key tile <= query
+ * tile is written; of the other tiles, those that share a 64-word chunk (4 consecutive
+ * tiles) with a needed tile are written too, the rest of `out` is left untouched.  Halves
+ * the RNG work when the mask is only used with causal != 0 (rov_layer_step and
+ * rov_block_forward call it that way for causal attention). */
+int rov_dropout_mask_generate_causal(uint64_t seed, uint64_t offset, int B, int H, int S, float p,
+                                     uint64_t *out, void *stream);
+
 /* Same with a selectable round count (paper Sec. 5.2 studies 3, 5 and 7 rounds).
  * rounds in {3, 5, 7, 10}. */
 int rov_dropout_mask_generate_rounds(uint64_t seed, uint64_t offset, int B, int H, int S, float p,

@@ -61,6 +61,7 @@ SIGNATURES = {
     "rov_philox_raw": (_i, [_u64, _u64, _u64, _i, _p, _p]),
     "rov_dropout_mask_generate": (_i, [_u64, _u64, _i, _i, _i, _f, _p, _p]),
     "rov_dropout_mask_generate_rounds": (_i, [_u64, _u64, _i, _i, _i, _f, _i, _p, _p]),
+    "rov_dropout_mask_generate_causal": (_i, [_u64, _u64, _i, _i, _i, _f, _p, _p]),
     "rov_set_rng_max_workgroups": (_i, [_i]),
     "rov_set_rng_overlap_workgroups_per_cu": (_i, [_i]),
     "rov_trace_enable": (_i, [_i]),
@@ -153,6 +154,14 @@ def mask_shape(B, H, S):
     """Shape of the keep-mask word array: [B, H, T, T, 16] with T = ceil(S/32)."""
     T = (S + 31) // 32
     return (B, H, T, T, 16)
+
+
+def dropout_mask_generate_causal(seed, offset, B, H, S, p, out, stream=None):
+    """Writes only the tiles causal attention reads (plus their chunk neighbours) into `out`."""
+    _check(load().rov_dropout_mask_generate_causal(seed & (2**64 - 1), offset & (2**64 - 1), B, H, S, p,
+                                                   ctypes.c_void_p(out.data_ptr()), _stream_ptr(stream)),
+           "rov_dropout_mask_generate_causal")
+    return out
 
 
 def dropout_mask_generate(seed, offset, B, H, S, p, out=None, rounds=None, stream=None):

@@ -65,21 +65,27 @@ __device__ __forceinline__ void mask_chunk(uint64_t base, uint32_t lane, uint32_
     }
 }
 
+// lower_only: skip every chunk (4 consecutive tiles) none of whose tiles has key tile <= query
+// tile, i.e. which causal attention never reads; what is written has the same bits either way.
 template <int R, bool RAGGED>
 __global__ __launch_bounds__(kWavesPerBlock * 64) void mask_kernel(
     uint64_t* __restrict__ out, uint64_t words, uint64_t nchunks, uint64_t offset, uint32_t k0,
-    uint32_t k1, uint32_t t_minus_1, uint32_t T, uint32_t S) {
+    uint32_t k1, uint32_t t_minus_1, uint32_t T, uint32_t S, int lower_only) {
     const uint32_t lane = threadIdx.x & 63u;
     const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const uint64_t stride = (uint64_t)gridDim.x * kWavesPerBlock;
     for (uint64_t chunk = (uint64_t)blockIdx.x * kWavesPerBlock + wave; chunk < nchunks;
          chunk += stride) {
         uint32_t vlo = 0u, vhi = 0u;
-        uint32_t qt = 0u, kt = 0u;   // tile coordinates of the chunk's first tile (ragged only)
-        if (RAGGED) {
+        uint32_t qt = 0u, kt = 0u;   // tile coordinates of the chunk's first tile
+        if (RAGGED || lower_only) {
             const uint64_t tile = chunk * 4u;
             kt = (uint32_t)(tile % T);
             qt = (uint32_t)((tile / T) % T);
+            // the chunk's tiles are (qt, kt) .. (qt, kt+3), wrapping into row qt+1 at kt = T;
+            // a wrapped tile (qt+1, 0) is always needed, so only a chunk that stays inside its
+            // row with kt > qt can be skipped
+            if (lower_only && kt > qt && kt + 3u < T) continue;
         }
         // first call number of the chunk; its 1024 calls are base .. base + 1023
         const uint64_t base = offset + 64u * kGroupsPerChunk * chunk;
@@ -107,7 +113,7 @@ __global__ __launch_bounds__(256) void raw_kernel(uint32_t* __restrict__ out, ui
 
 template <int R>
 int launch_mask_r(uint64_t* out, uint64_t words, uint64_t offset, uint32_t k0, uint32_t k1,
-                  uint32_t t_minus_1, int S, bool coresident, hipStream_t stream) {
+                  uint32_t t_minus_1, int S, bool coresident, bool lower_only, hipStream_t stream) {
     const uint32_t T = (uint32_t)(((uint64_t)S + 31u) / 32u);
     const uint64_t nchunks = (words + 63u) / 64u;
     uint64_t blocks = (nchunks + kWavesPerBlock - 1) / kWavesPerBlock;
@@ -122,10 +128,10 @@ int launch_mask_r(uint64_t* out, uint64_t words, uint64_t offset, uint32_t k0, u
     const dim3 grid((unsigned)blocks), block(kWavesPerBlock * 64);
     if ((S & 31) == 0) {
         hipLaunchKernelGGL((mask_kernel<R, false>), grid, block, 0, stream, out, words, nchunks,
-                           offset, k0, k1, t_minus_1, T, (uint32_t)S);
+                           offset, k0, k1, t_minus_1, T, (uint32_t)S, (int)lower_only);
     } else {
         hipLaunchKernelGGL((mask_kernel<R, true>), grid, block, 0, stream, out, words, nchunks,
-                           offset, k0, k1, t_minus_1, T, (uint32_t)S);
+                           offset, k0, k1, t_minus_1, T, (uint32_t)S, (int)lower_only);
     }
     ROV_LAUNCH_CHECK();
     return ROV_OK;
@@ -142,7 +148,7 @@ bool keep_threshold_minus_1(float p, uint32_t* t_minus_1) {
 }
 
 int launch_mask(uint64_t seed, uint64_t offset, int B, int H, int S, float p, int rounds,
-                uint64_t* out, hipStream_t stream, bool coresident) {
+                uint64_t* out, hipStream_t stream, bool coresident, bool lower_only) {
     if (B <= 0 || H <= 0 || S <= 0 || out == nullptr) return ROV_ERR_INVALID;
     if (!aligned(out, 8)) return ROV_ERR_INVALID;
     uint32_t tm1;
@@ -154,10 +160,10 @@ int launch_mask(uint64_t seed, uint64_t offset, int B, int H, int S, float p, in
     const uint64_t words = (uint64_t)B * (uint64_t)H * T * T * 16u;
     const uint32_t k0 = (uint32_t)seed, k1 = (uint32_t)(seed >> 32);
     switch (rounds) {
-        case 10: return launch_mask_r<10>(out, words, offset, k0, k1, tm1, S, coresident, stream);
-        case 7: return launch_mask_r<7>(out, words, offset, k0, k1, tm1, S, coresident, stream);
-        case 5: return launch_mask_r<5>(out, words, offset, k0, k1, tm1, S, coresident, stream);
-        case 3: return launch_mask_r<3>(out, words, offset, k0, k1, tm1, S, coresident, stream);
+        case 10: return launch_mask_r<10>(out, words, offset, k0, k1, tm1, S, coresident, lower_only, stream);
+        case 7: return launch_mask_r<7>(out, words, offset, k0, k1, tm1, S, coresident, lower_only, stream);
+        case 5: return launch_mask_r<5>(out, words, offset, k0, k1, tm1, S, coresident, lower_only, stream);
+        case 3: return launch_mask_r<3>(out, words, offset, k0, k1, tm1, S, coresident, lower_only, stream);
         default: return ROV_ERR_INVALID;
     }
 }
@@ -203,6 +209,11 @@ int rov_philox_raw(uint64_t seed, uint64_t first_counter, uint64_t ncalls, int r
 int rov_dropout_mask_generate(uint64_t seed, uint64_t offset, int B, int H, int S, float p,
                               uint64_t* out, void* stream) {
     return rov::launch_mask(seed, offset, B, H, S, p, 10, out, (hipStream_t)stream);
+}
+
+int rov_dropout_mask_generate_causal(uint64_t seed, uint64_t offset, int B, int H, int S, float p,
+                                     uint64_t* out, void* stream) {
+    return rov::launch_mask(seed, offset, B, H, S, p, 10, out, (hipStream_t)stream, false, true);
 }
 
 int rov_dropout_mask_generate_rounds(uint64_t seed, uint64_t offset, int B, int H, int S, float p,

@@ -35,8 +35,9 @@ void trace_end(int slot, hipStream_t st);
 
 // Launchers used across translation units (all asynchronous on `stream`).
 // coresident: launch a small persistent grid meant to run beside a GEMM (overlap schedule).
+// lower_only: write only what causal attention reads (tiles with key tile <= query tile).
 int launch_mask(uint64_t seed, uint64_t offset, int B, int H, int S, float p, int rounds,
-                uint64_t* out, hipStream_t stream, bool coresident = false);
+                uint64_t* out, hipStream_t stream, bool coresident = false, bool lower_only = false);
 int launch_gemm(const void* A, const void* Bm, void* C, int M, int N, int K, int dtype, int transB,
                 float scaleA, float scaleB, hipStream_t stream);
 // C = alpha * A W^T + R (R: bf16 [M,N] or nullptr); bf16 MFMA path only when R is given.

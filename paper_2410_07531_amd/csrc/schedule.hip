@@ -78,9 +78,10 @@ int t_gemm(const void* A, const void* Bm, void* C, const void* R, int M, int N, 
 }
 
 int t_mask(uint64_t seed, uint64_t offset, int B, int H, int S, float p, uint64_t* out, hipStream_t st,
-           bool coresident = false) {
-    return traced(ROV_TRACE_RNG, st,
-                  [&] { return launch_mask(seed, offset, B, H, S, p, 10, out, st, coresident); });
+           bool coresident, bool lower_only) {
+    return traced(ROV_TRACE_RNG, st, [&] {
+        return launch_mask(seed, offset, B, H, S, p, 10, out, st, coresident, lower_only);
+    });
 }
 
 size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
@@ -159,7 +160,7 @@ extern "C" int rov_layer_step(int schedule, const rov_gemm_desc* gemms, int n_ge
             rc = t_gemm(g.A, g.Bm, g.C, nullptr, g.M, g.N, g.K, g.dtype, g.transB, g.scaleA, g.scaleB, ms);
             if (rc != ROV_OK) return rc;
         }
-        rc = t_mask(seed, offset, attn->B, attn->H, attn->S, attn->p, mask, ss, true);
+        rc = t_mask(seed, offset, attn->B, attn->H, attn->S, attn->p, mask, ss, true, attn->causal != 0);
         if (rc != ROV_OK) return rc;
         ROV_HIP_TRY(hipEventRecord(ev->join, ss));
         for (int i = 1; i < n_gemms; ++i) {
@@ -172,7 +173,7 @@ extern "C" int rov_layer_step(int schedule, const rov_gemm_desc* gemms, int n_ge
         rc = run_gemms(ms);
         if (rc != ROV_OK) return rc;
         if (need_mask) {
-            rc = t_mask(seed, offset, attn->B, attn->H, attn->S, attn->p, mask, ms);
+            rc = t_mask(seed, offset, attn->B, attn->H, attn->S, attn->p, mask, ms, false, attn->causal != 0);
             if (rc != ROV_OK) return rc;
         }
     }
@@ -253,10 +254,10 @@ extern "C" int rov_block_forward(const rov_block_weights* w, const void* x, void
     ROV_STEP(t_gemm(h, w->wqkv, qkv, nullptr, (int)T, qkv_n, hidden, ROV_BF16, 1, 1.0f, 1.0f, ms));
     if (use_mask && !mask_ready) {
         if (overlap) {
-            ROV_STEP(t_mask(seed, offset, B, H, S, cfg->p, mask, ss, true));
+            ROV_STEP(t_mask(seed, offset, B, H, S, cfg->p, mask, ss, true, cfg->causal != 0));
             ROV_HIP_TRY(hipEventRecord(ev->join, ss));
         } else {
-            ROV_STEP(t_mask(seed, offset, B, H, S, cfg->p, mask, ms));
+            ROV_STEP(t_mask(seed, offset, B, H, S, cfg->p, mask, ms, false, cfg->causal != 0));
         }
     }
     ROV_STEP(traced(ROV_TRACE_GLUE, ms, [&] {   // q heads then k heads
@@ -284,7 +285,8 @@ extern "C" int rov_block_forward(const rov_block_weights* w, const void* x, void
     }
     ROV_STEP(t_gemm(att, w->wo, x2, x, (int)T, hidden, H * d, ROV_BF16, 1, 1.0f, 1.0f, ms));
     if (overlap && next_mask != nullptr) {
-        ROV_STEP(t_mask(seed, offset + rov_mask_philox_calls(B, H, S), B, H, S, cfg->p, next_mask, ss, true));
+        ROV_STEP(t_mask(seed, offset + rov_mask_philox_calls(B, H, S), B, H, S, cfg->p, next_mask, ss, true,
+                        cfg->causal != 0));
         ROV_HIP_TRY(hipEventRecord(ev->join, ss));
     }
     ROV_STEP(traced(ROV_TRACE_GLUE, ms, [&] { return launch_rmsnorm(x2, w->norm2, h, T, hidden, cfg->eps, ms); }));

@@ -115,6 +115,27 @@ def test_mask_largest_workload_sampled_and_counted():
     torch.cuda.empty_cache()
 
 
+@pytest.mark.parametrize("B,H,S", [(1, 2, 256), (2, 3, 200), (1, 1, 32), (1, 2, 1024)])
+def test_mask_causal_variant_writes_what_causal_attention_reads(B, H, S):
+    import torch
+    p, seed, offset = 0.1, 7, 12345
+    poison = 0x2AAAAAAAAAAAAAAA
+    out = torch.full(rov.mask_shape(B, H, S), poison, dtype=torch.int64, device="cuda")
+    rov.dropout_mask_generate_causal(seed, offset, B, H, S, p, out)
+    got = _np_u64(out)
+    exp = OP.dropout_mask(seed, offset, B, H, S, p)
+    T = (S + 31) // 32
+    qt, kt = np.meshgrid(np.arange(T), np.arange(T), indexing="ij")
+    lower = kt <= qt
+    assert np.array_equal(got[:, :, lower], exp[:, :, lower])            # every needed tile, same bits
+    upper = got[:, :, ~lower]
+    untouched = (upper == np.uint64(poison)).all(axis=-1)
+    same = (upper == exp[:, :, ~lower]).all(axis=-1)
+    assert np.all(untouched | same)                                       # the rest: untouched or the same bits
+    if T >= 16:
+        assert untouched.mean() > 0.6                                     # and most of it is really skipped
+
+
 def test_mask_error_paths_leave_output_untouched():
     import torch
     out = torch.full(rov.mask_shape(1, 1, 64), 0x5A5A5A5A, dtype=torch.int64, device="cuda")

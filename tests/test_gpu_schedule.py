@@ -114,7 +114,13 @@ def test_block_forward_three_schedules_match_oracle(causal):
         ys[name] = y
         if nxt is not None:
             exp = OP.dropout_mask(seed, offset + OP.mask_philox_calls(B, H, S), B, H, S, p)
-            assert np.array_equal(nxt.cpu().numpy().view(np.uint64), exp)
+            got = nxt.cpu().numpy().view(np.uint64)
+            if causal:      # only the tiles causal attention reads are guaranteed
+                T = S // 32
+                lower = np.tril(np.ones((T, T), dtype=bool))
+                assert np.array_equal(got[:, :, lower], exp[:, :, lower])
+            else:
+                assert np.array_equal(got, exp)
     for name in ("fused", "ovl_first", "ovl_steady"):
         assert torch.equal(ys["seq"], ys[name]), name
     keep = OP.unpack_keep(OP.dropout_mask(seed, offset, B, H, S, p), S)

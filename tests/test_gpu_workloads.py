@@ -28,13 +28,18 @@ def _randn(gen, *shape, sd=1.0, dtype=torch.bfloat16):
     return (torch.randn(*shape, device="cuda", generator=gen) * sd).to(dtype)
 
 
-def _check_mask_heads(mask, seed, offset, B, H, S, p, heads):
+def _check_mask_heads(mask, seed, offset, B, H, S, p, heads, lower_only=False):
     T = S // 32
     per_head = T * T * 16
+    lower = np.tril(np.ones((T, T), dtype=bool))
     for b, h in heads:
         first = (b * H + h) * per_head
         exp = OP.dropout_mask(seed, offset + 64 * (first // 4), 1, 1, S, p)
-        assert np.array_equal(mask[b, h].cpu().numpy().view(np.uint64), exp[0, 0]), (b, h)
+        got = mask[b, h].cpu().numpy().view(np.uint64)
+        if lower_only:
+            assert np.array_equal(got[lower], exp[0, 0][lower]), (b, h)
+        else:
+            assert np.array_equal(got, exp[0, 0]), (b, h)
 
 
 def _keep_rows(mask, b, h, rows, S):
@@ -177,8 +182,9 @@ def test_workload5_block_s16k_overlap_sampled_rows():
                           main, side, mask_ready=True, next_mask=m1)
         torch.cuda.synchronize()
         del ws
-        # next layer's mask, sampled heads
-        _check_mask_heads(m1, wl.SEED, wl.OFFSET + OP.mask_philox_calls(B, H, S), B, H, S, p, [(0, 0), (0, 31)])
+        # next layer's mask, sampled heads (causal: the tiles causal attention reads)
+        _check_mask_heads(m1, wl.SEED, wl.OFFSET + OP.mask_philox_calls(B, H, S), B, H, S, p, [(0, 0), (0, 31)],
+                          lower_only=causal)
         # oracle: full K, V (all tokens), everything else on the sampled rows only
         keep = np.zeros((B, H, S, S), dtype=bool)
         for h in range(H):

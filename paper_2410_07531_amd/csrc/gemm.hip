@@ -2,24 +2,34 @@
 // (paper Sec. 3.2, Table 1 GEMM column: MMA-bound, L2 read bandwidth second).
 //
 // bf16 fast path (A [M,K] and weights [N,K], both K-contiguous):
-//   - workgroup tile 256 x 256, K step 64, 4 waves in a 2 x 2 grid, each wave
-//     owning a 128 x 128 block as 4 x 4 MFMA 32x32x16 tiles (256 fp32
-//     accumulators per lane);
-//   - tiles go from global memory straight into LDS (global_load_lds, 16 bytes
-//     per lane), two 64 KiB stages; a wave's 64 lanes always fill 1 KiB of
-//     consecutive LDS, so the bank swizzle (16-byte chunk index XOR row%8) is
-//     applied on the global-address side;
+//   - workgroup tile 256 x 256, 4 waves in a 2 x 2 grid, each wave owning a
+//     128 x 128 block as 8 x 8 MFMA 16x16x32 tiles (256 fp32 accumulators per
+//     lane, kept in AGPRs).  The 16x16x32 shape is used because under the
+//     board's power limit it sustains about a quarter more flop/s on random
+//     data than 32x32x16 (measured with a register-only loop: 2.05 against
+//     1.66 PFLOP/s);
+//   - operands go from global memory straight into LDS (buffer_load ... lds,
+//     16 bytes per lane) through a ring of four 32 KiB slots, one MFMA k-step
+//     (64 bytes of k per row) per slot, loaded four steps ahead and issued one
+//     load per four MFMAs, so that the texture-address unit shared by the four
+//     waves never sees a burst; a wave's 64 lanes always fill 1 KiB of
+//     consecutive LDS, so the bank swizzle is applied on the global-address side;
+//   - the fragments of step s+1 are read from LDS during the first half of
+//     step s, so no MFMA waits for an LDS read issued just before it;
 //   - the MFMA is issued with the weight fragment as first operand, so each
 //     lane ends up with 4 consecutive output columns and stores 8 bytes at once;
 //   - workgroup ids are remapped so that the workgroups that land on one XCD
-//     (one L2) cover a compact block of output tiles.
-// The register budget is capped below the full file so that RNG waves can be
-// co-resident on every SIMD (the paper's carve-out, Sec. 6.2).
+//     (one L2) cover a compact block of output tiles, and the k loop of a
+//     workgroup starts at a k offset that depends on its tile row, so that the
+//     workgroups of an XCD do not all fetch the same 64-byte column of every
+//     row (the same cache channel) at the same time.
+// The register budget (140 VGPRs + 256 AGPRs of 512) leaves room for RNG
+// waves on every SIMD (the paper's carve-out, Sec. 6.2).
 //
-// fp8 (OCP e4m3) uses the same kernel: a tile row is 128 bytes either way (64
-// bf16 or 128 fp8 values), and each 16-byte fragment feeds two MFMA 32x32x16
-// fp8 instructions (which 8 of the 16 k-values a half-wave supplies is the same
-// for both operands, so the sum is unchanged).
+// fp8 (OCP e4m3) uses the same kernel: a ring row is 64 bytes either way (32
+// bf16 or 64 fp8 values), and each 16-byte fragment feeds two MFMA 16x16x32
+// fp8 instructions (which 8 of the 16 k-values a lane group supplies is the
+// same for both operands, so the sum is unchanged).
 //
 // Everything else (fp32, [K,N] weights, K not a multiple of the tile depth)
 // takes a small LDS-tiled VALU kernel that is correct for any shape.
@@ -126,48 +136,26 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(const T* __restrict__
 
 // ------------------------------------------------------------------ MFMA kernel (bf16 / fp8)
 constexpr int BM = 256, BN = 256;
-constexpr int kRowBytes = 128;                      // one tile row: 64 bf16 or 128 fp8 values
-constexpr int kStageBytes = (BM + BN) * kRowBytes;  // 64 KiB: A tile then W tile
+constexpr int kRowBytes = 64;                       // one ring-slot row: 32 bf16 or 64 fp8 values
+constexpr int kSlotBytes = (BM + BN) * kRowBytes;   // 32 KiB: A rows then W rows
+constexpr int kSlots = 4;
+constexpr int kLdsBytes = kSlots * kSlotBytes;      // 128 KiB
 
-typedef const __attribute__((address_space(1))) void* gptr_t;
 typedef __attribute__((address_space(3))) void* lptr_t;
 typedef int i32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 
-// One operand tile (256 rows x 128 bytes of k) from global to LDS.  Wave w copies row
-// blocks w, w+4, ... (8 rows each); within a block lane L fills physical chunk
-// L%8 of row L/8, which holds logical chunk (L%8) ^ (row%8).  `panel` points at the first
-// row of the 256-row operand panel plus the k offset (wave-uniform); voff[i] is the lane's
-// constant byte offset inside the panel for row block i, so the address is a scalar base
-// plus a 32-bit vector offset and the loop does no vector address arithmetic.
-__device__ __forceinline__ void load_tile(const char* __restrict__ panel, const uint32_t (&voff)[8],
-                                          char* lds_tile, int wave) {
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        const int blk = wave + 4 * i;                // 0..31
-        __builtin_amdgcn_global_load_lds((gptr_t)(panel + voff[i]), (lptr_t)(lds_tile + blk * 8 * kRowBytes),
-                                         16, 0, 0);
-    }
-}
-
-__device__ __forceinline__ void lane_offsets(uint32_t (&voff)[8], size_t ld_bytes, int rows_valid, int wave,
-                                             int lane) {
-    const int rl = lane >> 3;                        // row within the 8-row block
-    const int chunk = (lane & 7) ^ rl;               // logical 16-byte chunk this lane fetches
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        int row = (wave + 4 * i) * 8 + rl;
-        row = row < rows_valid ? row : rows_valid - 1;   // clamp: rows past the edge are never stored
-        voff[i] = (uint32_t)((size_t)row * ld_bytes) + (uint32_t)(chunk * 16);
-    }
-}
+// 16-byte chunk swizzle of a 64-byte LDS row (4 chunks).  Rows of equal parity among any 8
+// consecutive rows, and rows 4 apart among any 16, get different values, so a fragment read
+// (lanes = consecutive rows, same logical chunk) touches every bank group once.
+__device__ __forceinline__ int row_swizzle(int row) { return ((row >> 1) & 3) ^ ((row >> 3) & 1); }
 
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 
 // Reads one accumulator value where it is needed.  The "a" constraint keeps the value in its
-// accumulation register until this point; without it the register allocator copies all 256
-// accumulators to ordinary VGPRs at the loop exit and the kernel needs the whole register file,
-// leaving no room for co-resident RNG waves.
+// accumulation register until this point, so the epilogue never needs a second copy of the
+// 256 accumulators in ordinary VGPRs.
 __device__ __forceinline__ float acc_read(float v) {
     float r;
     asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(r) : "a"(v));
@@ -176,7 +164,7 @@ __device__ __forceinline__ float acc_read(float v) {
 
 __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
     f32x2 v = {lo, hi};
-    bf16x2 h = __builtin_convertvector(v, bf16x2);   // v_cvt_pk_bf16_f32: nearest, ties to even
+    bf16x2 h = __builtin_convertvector(v, bf16x2);
     return *reinterpret_cast<uint32_t*>(&h);
 }
 
@@ -212,158 +200,162 @@ __global__ __launch_bounds__(256, 1) void gemm_tn_kernel(const char* __restrict_
     const int tn = in_band / band_rows;
     const int m0 = tm * BM, n0 = tn * BN;
 
-    f32x16 acc[4][4];   // [weight-row block j][activation-row block i]
+    f32x4 acc[8][8];   // [weight-row block j (16 rows)][activation-row block i (16 rows)]
 #pragma unroll
-    for (int j = 0; j < 4; ++j)
+    for (int j = 0; j < 8; ++j)
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
+        for (int i = 0; i < 8; ++i)
 #pragma unroll
-            for (int e = 0; e < 16; ++e) acc[j][i][e] = 0.0f;
+            for (int e = 0; e < 4; ++e) acc[j][i][e] = 0.0f;
 
-    // per-lane fragment addressing: row = base + lane%32, k-chunk = 2*kk + lane/32, swizzled by row%8
-    const int frow = lane & 31;
-    const int fhalf = lane >> 5;
-    const int swz = lane & 7;
-    int foff[4];
-#pragma unroll
-    for (int kk = 0; kk < 4; ++kk) foff[kk] = frow * kRowBytes + (((2 * kk + fhalf) ^ swz) << 4);
+    // fragment of MFMA 16x16x32: lane holds row lane%16, k-chunk (8 bf16 / 16 fp8) lane/16 of the step
+    const int frow = lane & 15;
+    const int fchunk = lane >> 4;
+    const int foff = frow * kRowBytes + ((fchunk ^ row_swizzle(frow)) << 4);   // block bases are multiples of 16
     const int a_base = (wm * 128) * kRowBytes;
     const int w_base = BM * kRowBytes + (wn * 128) * kRowBytes;
 
-    i32x4 af[2][4], wf[2][4];   // 16-byte fragments of the current and the next k-step
-    auto read_frags = [&](int buf, const char* stage, int kk) {
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-            af[buf][i] = *reinterpret_cast<const i32x4*>(stage + a_base + i * 32 * kRowBytes + foff[kk]);
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-            wf[buf][j] = *reinterpret_cast<const i32x4*>(stage + w_base + j * 32 * kRowBytes + foff[kk]);
-    };
-
+    // Loads: one wave instruction moves 16 rows x 64 bytes (1 KiB, linear in LDS).  Wave w issues
+    // row blocks w, w+4, w+8, w+12 of each operand: 8 instructions per ring step.  Lane L fills
+    // physical chunk L%4 of row L/4, i.e. fetches logical chunk (L%4) ^ swizzle(row).
     const size_t ld_bytes = (size_t)K * ESZ;
-    const int nk = (int)(ld_bytes / kRowBytes);
-    uint32_t voff_a[8], voff_w[8];
-    lane_offsets(voff_a, ld_bytes, M - m0 < BM ? M - m0 : BM, wave, lane);
-    lane_offsets(voff_w, ld_bytes, N - n0 < BN ? N - n0 : BN, wave, lane);
+    const int ns = (int)(ld_bytes / kRowBytes);       // ring steps (even)
+    const int rows_a = M - m0 < BM ? M - m0 : BM;
+    const int rows_w = N - n0 < BN ? N - n0 : BN;
+    uint32_t voff_a[4], voff_w[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int row = (wave + 4 * j) * 16 + (lane >> 2);
+        const int chunk = (lane & 3) ^ row_swizzle(row);
+        const int ra = row < rows_a ? row : rows_a - 1;   // rows past the edge are never stored
+        const int rw = row < rows_w ? row : rows_w - 1;
+        voff_a[j] = (uint32_t)((size_t)ra * ld_bytes) + (uint32_t)(chunk * 16);
+        voff_w[j] = (uint32_t)((size_t)rw * ld_bytes) + (uint32_t)(chunk * 16);
+    }
     const char* a_panel = A + (size_t)m0 * ld_bytes;
     const char* w_panel = Wt + (size_t)n0 * ld_bytes;
-    load_tile(a_panel, voff_a, lds, wave);
-    load_tile(w_panel, voff_w, lds + BM * kRowBytes, wave);
-    __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
-    __syncthreads();
-    if (nk > 1) {
-        load_tile(a_panel + kRowBytes, voff_a, lds + kStageBytes, wave);
-        load_tile(w_panel + kRowBytes, voff_w, lds + kStageBytes + BM * kRowBytes, wave);
-    }
-    read_frags(0, lds, 0);
+    // ring step at which this workgroup starts its cyclic walk over k (the sum does not depend on
+    // the order; the fp32 rounding does, deterministically)
+    const int kstart = (int)(((unsigned)tm * 2u) % (unsigned)ns);
+    // Buffer resources over the two operand panels (scalar base, per-lane 32-bit offset, scalar k
+    // offset; the range ends with the last valid row, so an offset beyond it would read zeros).
+    auto make_rsrc = [](const char* base, size_t bytes) {
+        const uint64_t b = (uint64_t)(uintptr_t)base;
+        i32x4 r;
+        r[0] = __builtin_amdgcn_readfirstlane((int)(uint32_t)b);
+        r[1] = __builtin_amdgcn_readfirstlane((int)(uint32_t)((b >> 32) & 0xFFFFu));
+        r[2] = __builtin_amdgcn_readfirstlane((int)(uint32_t)bytes);
+        r[3] = 0x00020000;
+        return r;
+    };
+    const i32x4 rsrc_a = make_rsrc(a_panel, (size_t)rows_a * ld_bytes);
+    const i32x4 rsrc_w = make_rsrc(w_panel, (size_t)rows_w * ld_bytes);
+    const uint32_t lds_base = (uint32_t)(uintptr_t)(lptr_t)lds;
 
+    // Load instruction q (0..3 = A row blocks, 4..7 = W row blocks) of ring step `step` into the
+    // ring slot at LDS byte address `slot`.  Inline assembly, so that the compiler's wait-count
+    // pass does not see an LDS write it cannot tell apart from the fragment reads (it would force
+    // vmcnt(0) before every LDS read); the waits are placed by hand below.
+    auto issue = [&](int q, int step, uint32_t slot) {
+        int st = step < ns ? step : ns - 1;       // past the end: harmless reload of the last step
+        st += kstart;
+        st = st >= ns ? st - ns : st;
+        const int koff = st * kRowBytes;
+        if (q < 4) {
+            const uint32_t dst = slot + (uint32_t)((wave + 4 * q) * 1024);
+            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+                         :: "s"(dst), "v"(voff_a[q]), "s"(rsrc_a), "s"(koff) : "memory", "m0");
+        } else {
+            const uint32_t dst = slot + (uint32_t)(BM * kRowBytes + (wave + 4 * (q - 4)) * 1024);
+            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+                         :: "s"(dst), "v"(voff_w[q - 4]), "s"(rsrc_w), "s"(koff) : "memory", "m0");
+        }
+    };
+
+    i32x4 af[2][8], wf[2][8];   // fragments of the current and the next ring step
+    auto read_frag = [&](int buf, const char* slot, int f /*0..7 = A block, 8..15 = W block*/) {
+        if (f < 8)
+            af[buf][f] = *reinterpret_cast<const i32x4*>(slot + a_base + f * 16 * kRowBytes + foff);
+        else
+            wf[buf][f - 8] = *reinterpret_cast<const i32x4*>(slot + w_base + (f - 8) * 16 * kRowBytes + foff);
+    };
+    // The MFMAs are written as inline assembly with explicit register classes (accumulators in
+    // AGPRs, fragments in VGPRs): left to itself the register allocator mixes the two files for 64
+    // four-register accumulators and fills the loop with accumulator moves and spills.
     auto mfma_one = [&](int buf, int j, int i) {
         if (ESZ == 2) {
-            acc[j][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, wf[buf][j]),
-                                                                __builtin_bit_cast(bf16x8, af[buf][i]),
-                                                                acc[j][i], 0, 0, 0);
+            asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc[j][i]) : "v"(wf[buf][j]), "v"(af[buf][i]));
         } else {
 #pragma unroll
             for (int hf = 0; hf < 2; ++hf) {
                 const i32x4 wv = wf[buf][j], av = af[buf][i];
                 const long wl = ((long)(uint32_t)wv[2 * hf]) | ((long)wv[2 * hf + 1] << 32);
                 const long al = ((long)(uint32_t)av[2 * hf]) | ((long)av[2 * hf + 1] << 32);
-                acc[j][i] = __builtin_amdgcn_mfma_f32_32x32x16_fp8_fp8(wl, al, acc[j][i], 0, 0, 0);
+                asm volatile("v_mfma_f32_16x16x32_fp8_fp8 %0, %1, %2, %0" : "+a"(acc[j][i]) : "v"(wl), "v"(al));
             }
         }
     };
 
-    for (int kt = 0; kt < nk; ++kt) {
-        const char* cur = lds + (kt & 1) * kStageBytes;
+    // Ring of 4 slots, one MFMA k-step (64 bytes of k per row) per slot; step t lives in slot t % 4.
+    // At the top of step s every wave has the fragments of step s in registers, so slot s % 4 is
+    // free and takes the loads of step s+4 (8 per wave, one every 4 MFMAs in the second half of the
+    // step); the fragments of step s+1 are read in the first half.  Loads complete in order, so
+    // "step s+1 has landed" is vmcnt <= 16 (steps s+2, s+3 are the only later ones in flight).
 #pragma unroll
-        for (int kk = 0; kk < 4; ++kk) {
-            if (kk < 3) {
-                // the 8 fragment reads of the next k-step ride between this k-step's 16 MFMAs:
-                // an LDS read issued in the shadow of a running MFMA costs the matrix pipe nothing
+    for (int t = 0; t < 4; ++t)
 #pragma unroll
-                for (int idx = 0; idx < 16; ++idx) {
-                    mfma_one(kk & 1, idx >> 2, idx & 3);
-                    if ((idx & 1) == 0) {
-                        if (idx < 8)
-                            af[(kk + 1) & 1][idx >> 1] = *reinterpret_cast<const i32x4*>(
-                                cur + a_base + (idx >> 1) * 32 * kRowBytes + foff[kk + 1]);
-                        else
-                            wf[(kk + 1) & 1][(idx - 8) >> 1] = *reinterpret_cast<const i32x4*>(
-                                cur + w_base + ((idx - 8) >> 1) * 32 * kRowBytes + foff[kk + 1]);
-                    }
-                    __builtin_amdgcn_sched_barrier(0);
-                }
-            } else {
-                // Tile boundary: the next stage must have landed for every wave, and every wave
-                // must be done reading this stage before it is refilled.  The refill (tile kt+2)
-                // and the first fragments of the next stage are issued between the 16 MFMAs of
-                // this k-step, one load per MFMA, so the matrix pipe keeps running while they
-                // issue.  The path is the same on the last tiles, where it reloads the final
-                // tile and reads fragments that nobody uses: a branch here would split the
-                // accumulators' live ranges and cost far more than the wasted loads.
-                __builtin_amdgcn_s_waitcnt(0x0070);   // vmcnt(0) lgkmcnt(0)
-                __syncthreads();
-                char* refill = lds + (kt & 1) * kStageBytes;
-                const char* nxt = lds + ((kt + 1) & 1) * kStageBytes;
-                const size_t k_bytes = (size_t)(kt + 2 < nk ? kt + 2 : nk - 1) * kRowBytes;
-                const char* ap = a_panel + k_bytes;
-                const char* wp = w_panel + k_bytes;
+        for (int q = 0; q < 8; ++q) issue(q, t, lds_base + t * kSlotBytes);
+    __builtin_amdgcn_s_waitcnt(0x4F78);   // vmcnt(24): step 0 has landed
+    __syncthreads();
 #pragma unroll
-                for (int idx = 0; idx < 16; ++idx) {
-                    mfma_one(1, idx >> 2, idx & 3);
-                    if (idx < 8)
-                        __builtin_amdgcn_global_load_lds((gptr_t)(ap + voff_a[idx]),
-                                                         (lptr_t)(refill + (wave + 4 * idx) * 8 * kRowBytes), 16, 0, 0);
-                    else
-                        __builtin_amdgcn_global_load_lds(
-                            (gptr_t)(wp + voff_w[idx - 8]),
-                            (lptr_t)(refill + BM * kRowBytes + (wave + 4 * (idx - 8)) * 8 * kRowBytes), 16, 0, 0);
-                    if ((idx & 1) == 0) {
-                        if (idx < 8)
-                            af[0][idx >> 1] = *reinterpret_cast<const i32x4*>(nxt + a_base + (idx >> 1) * 32 * kRowBytes + foff[0]);
-                        else
-                            wf[0][(idx - 8) >> 1] = *reinterpret_cast<const i32x4*>(nxt + w_base + ((idx - 8) >> 1) * 32 * kRowBytes + foff[0]);
-                    }
-                    __builtin_amdgcn_sched_barrier(0);
-                }
-            }
+    for (int f = 0; f < 16; ++f) read_frag(0, lds, f);
+
+    auto step_body = [&](int buf, int s) {
+        const char* nxt = lds + ((s + 1) & 3) * kSlotBytes;
+        const uint32_t slot = lds_base + (s & 3) * kSlotBytes;
+        __builtin_amdgcn_s_waitcnt(0x4070);   // vmcnt(16) lgkmcnt(0)
+        __syncthreads();
+#pragma unroll
+        for (int idx = 0; idx < 64; ++idx) {
+            mfma_one(buf, idx >> 3, idx & 7);
+            if (idx < 32 && (idx & 1) == 0) read_frag(buf ^ 1, nxt, idx >> 1);
+            if (idx >= 32 && (idx & 3) == 1) issue((idx - 32) >> 2, s + 4, slot);
+            __builtin_amdgcn_sched_barrier(0);
         }
+    };
+    for (int s = 0; s < ns; s += 2) {
+        step_body(0, s);
+        step_body(1, s + 1);
     }
     __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): no LDS load may outlive the loop
+    asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");   // the last MFMA results are in the accumulators before they are read
 
-    // D'[r][c] = C[m = c][n = r]: lane holds column c = lane%32 (an activation row) and, for
-    // register e, weight row 8*(e/4) + 4*(lane/32) + e%4: four consecutive n per e/4.
-    // N is a multiple of 4 here, so a group of four columns is inside or outside as a whole.
-    const int mrow = lane & 31;
-    const int nsub = (lane >> 5) * 4;
+    // D'[r][c] = C[m = c][n = r]: lane holds activation row lane%16 and weight rows 4*(lane/16) + e
+    const int mrow = lane & 15;
+    const int nsub = (lane >> 4) * 4;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int m = m0 + wm * 128 + i * 32 + mrow;
+    for (int i = 0; i < 8; ++i) {
+        const int m = m0 + wm * 128 + i * 16 + mrow;
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            // keep the accumulator read-out block by block: a hoisted read-out of all 256
-            // values would double the kernel's register footprint
-            __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const int n = n0 + wn * 128 + j * 32 + q * 8 + nsub;
-                float c0 = alpha * acc_read(acc[j][i][q * 4 + 0]);
-                float c1 = alpha * acc_read(acc[j][i][q * 4 + 1]);
-                float c2 = alpha * acc_read(acc[j][i][q * 4 + 2]);
-                float c3 = alpha * acc_read(acc[j][i][q * 4 + 3]);
-                if (m < M && n < N) {
-                    if (R != nullptr) {   // fused residual add (wave-uniform branch)
-                        const uint2 r = *reinterpret_cast<const uint2*>(R + (size_t)m * N + n);
-                        c0 += __uint_as_float(r.x << 16);
-                        c1 += __uint_as_float(r.x & 0xFFFF0000u);
-                        c2 += __uint_as_float(r.y << 16);
-                        c3 += __uint_as_float(r.y & 0xFFFF0000u);
-                    }
-                    uint2 v;
-                    v.x = pack_bf16x2(c0, c1);
-                    v.y = pack_bf16x2(c2, c3);
-                    *reinterpret_cast<uint2*>(C + (size_t)m * N + n) = v;
+        for (int j = 0; j < 8; ++j) {
+            const int n = n0 + wn * 128 + j * 16 + nsub;
+            float c0 = alpha * acc_read(acc[j][i][0]);
+            float c1 = alpha * acc_read(acc[j][i][1]);
+            float c2 = alpha * acc_read(acc[j][i][2]);
+            float c3 = alpha * acc_read(acc[j][i][3]);
+            if (m < M && n < N) {
+                if (R != nullptr) {
+                    const uint2 r = *reinterpret_cast<const uint2*>(R + (size_t)m * N + n);
+                    c0 += __uint_as_float(r.x << 16);
+                    c1 += __uint_as_float(r.x & 0xFFFF0000u);
+                    c2 += __uint_as_float(r.y << 16);
+                    c3 += __uint_as_float(r.y & 0xFFFF0000u);
                 }
+                uint2 v;
+                v.x = pack_bf16x2(c0, c1);
+                v.y = pack_bf16x2(c2, c3);
+                *reinterpret_cast<uint2*>(C + (size_t)m * N + n) = v;
             }
         }
     }
@@ -386,18 +378,21 @@ int launch_gemm_residual(const void* A, const void* Bm, void* C, const void* R, 
     const bool tb = transB != 0;
     const int esz = dtype == ROV_BF16 ? 2 : 1;
 
-    if (dtype != ROV_F32 && tb && ((size_t)K * esz) % kRowBytes == 0 && (N % 4) == 0) {
+    if (dtype != ROV_F32 && tb && ((size_t)K * esz) % (2 * kRowBytes) == 0 && (N % 4) == 0) {
         const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
         const long long T = (long long)tiles_m * tiles_n;
         if (T > 0x7FFFFFFFLL) return ROV_ERR_UNSUPPORTED;
+        // a 256-row operand panel is addressed with 32-bit byte offsets
+        if ((unsigned long long)BM * (unsigned long long)K * (unsigned long long)esz > 0xFFFFFFFFull)
+            return ROV_ERR_UNSUPPORTED;
         auto kern = esz == 2 ? gemm_tn_kernel<2> : gemm_tn_kernel<1>;
         static bool attr_set[2] = {false, false};
         if (!attr_set[esz - 1]) {
             ROV_HIP_TRY(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                            2 * kStageBytes));
+                                            kLdsBytes));
             attr_set[esz - 1] = true;
         }
-        hipLaunchKernelGGL(kern, dim3((unsigned)T), dim3(256), 2 * kStageBytes, stream, (const char*)A,
+        hipLaunchKernelGGL(kern, dim3((unsigned)T), dim3(256), kLdsBytes, stream, (const char*)A,
                            (const char*)Bm, (uint16_t*)C, (const uint16_t*)R, M, N, K, alpha, tiles_m,
                            tiles_n);
         ROV_LAUNCH_CHECK();

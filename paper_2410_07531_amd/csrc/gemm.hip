@@ -255,7 +255,8 @@ __global__ __launch_bounds__(256, 1) void gemm_tn_kernel(const char* __restrict_
     // Load instruction q (0..3 = A row blocks, 4..7 = W row blocks) of ring step `step` into the
     // ring slot at LDS byte address `slot`.  Inline assembly, so that the compiler's wait-count
     // pass does not see an LDS write it cannot tell apart from the fragment reads (it would force
-    // vmcnt(0) before every LDS read); the waits are placed by hand below.
+    // vmcnt(0) before every LDS read); the waits are placed by hand below.  M0 (the LDS base of
+    // the transfer) is a reserved register that compiled code only sets right before its own uses.
     auto issue = [&](int q, int step, uint32_t slot) {
         int st = step < ns ? step : ns - 1;       // past the end: harmless reload of the last step
         st += kstart;
@@ -264,11 +265,11 @@ __global__ __launch_bounds__(256, 1) void gemm_tn_kernel(const char* __restrict_
         if (q < 4) {
             const uint32_t dst = slot + (uint32_t)((wave + 4 * q) * 1024);
             asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
-                         :: "s"(dst), "v"(voff_a[q]), "s"(rsrc_a), "s"(koff) : "memory", "m0");
+                         :: "s"(dst), "v"(voff_a[q]), "s"(rsrc_a), "s"(koff) : "memory");
         } else {
             const uint32_t dst = slot + (uint32_t)(BM * kRowBytes + (wave + 4 * (q - 4)) * 1024);
             asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
-                         :: "s"(dst), "v"(voff_w[q - 4]), "s"(rsrc_w), "s"(koff) : "memory", "m0");
+                         :: "s"(dst), "v"(voff_w[q - 4]), "s"(rsrc_w), "s"(koff) : "memory");
         }
     };
 

@@ -145,10 +145,14 @@ typedef __attribute__((address_space(3))) void* lptr_t;
 typedef int i32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
-// 16-byte chunk swizzle of a 64-byte LDS row (4 chunks).  Rows of equal parity among any 8
-// consecutive rows, and rows 4 apart among any 16, get different values, so a fragment read
-// (lanes = consecutive rows, same logical chunk) touches every bank group once.
-__device__ __forceinline__ int row_swizzle(int row) { return ((row >> 1) & 3) ^ ((row >> 3) & 1); }
+// 16-byte chunk swizzle of a 64-byte LDS row (4 chunks).  A 64-lane ds_read_b128 is served 16
+// lanes at a time over 64 banks of 4 bytes, and the lanes that go together are not consecutive:
+// measured on gfx950 with a two-lane probe and the bank-conflict counter, they are
+// {0-3, 12-15, 20-27}, {4-11, 16-19, 28-31} and the same two sets + 32.  A fragment read has
+// lane = 16*chunk + row, so such a set holds rows 0-3 and 12-15 of one logical chunk and rows
+// 4-11 of the next; with the chunk index XORed by (-(row/4)) & 3 its 16 addresses fall into 16
+// different bank groups (counter: 0 conflict cycles, against 4 of 8 cycles per read before).
+__device__ __forceinline__ int row_swizzle(int row) { return (0 - (row >> 2)) & 3; }
 
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));

@@ -41,6 +41,13 @@ def lib():
         L.oracle_dropout_mask_rounds.argtypes = [u64, u64, ctypes.c_int, ctypes.c_int, ctypes.c_int,
                                                  ctypes.c_float, ctypes.c_int, ctypes.c_void_p]
         L.oracle_dropout_mask_rounds.restype = ctypes.c_int
+        L.oracle_dropout_mask_bits.argtypes = [u64, u64, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+                                               ctypes.c_float, ctypes.c_int, ctypes.c_int, ctypes.c_void_p]
+        L.oracle_dropout_mask_bits.restype = ctypes.c_int
+        L.oracle_keep_threshold_bits.argtypes = [ctypes.c_float, ctypes.c_int, u64p]
+        L.oracle_keep_threshold_bits.restype = ctypes.c_int
+        L.oracle_mask_philox_calls_bits.argtypes = [ctypes.c_int] * 4
+        L.oracle_mask_philox_calls_bits.restype = u64
         L.oracle_popcount_words.argtypes = [ctypes.c_void_p, u64]
         L.oracle_popcount_words.restype = u64
         L.oracle_num_threads.argtypes = []
@@ -90,6 +97,30 @@ def dropout_mask(seed, offset, B, H, S, p, rounds=10):
     out = np.zeros((B, H, T, T, 16), dtype=np.uint64)
     rc = lib().oracle_dropout_mask_rounds(int(seed) & (2**64 - 1), int(offset) & (2**64 - 1),
                                           B, H, S, ctypes.c_float(p), int(rounds), out.ctypes.data)
+    if rc != 0:
+        raise ValueError("invalid mask arguments")
+    return out
+
+
+def keep_threshold_bits(p, bits):
+    """Tb = floor((1 - p) * 2^bits) from the float32 value of p; bits in {8, 16, 32}."""
+    T = ctypes.c_uint64(0)
+    if lib().oracle_keep_threshold_bits(ctypes.c_float(p), int(bits), ctypes.byref(T)) != 0:
+        raise ValueError("p must satisfy 0 <= p < 1 and bits must be 8, 16 or 32")
+    return int(T.value)
+
+
+def mask_philox_calls_bits(B, H, S, bits):
+    return int(lib().oracle_mask_philox_calls_bits(B, H, S, int(bits)))
+
+
+def dropout_mask_bits(seed, offset, B, H, S, p, bits, rounds=10):
+    """Keep-mask drawn with `bits` random bits per element (8, 16 or 32): same layout as
+    dropout_mask; words in groups of 4*32/bits, field e/4 of output word e%4 decides word e."""
+    T = (S + 31) // 32
+    out = np.zeros((B, H, T, T, 16), dtype=np.uint64)
+    rc = lib().oracle_dropout_mask_bits(int(seed) & (2**64 - 1), int(offset) & (2**64 - 1), B, H, S,
+                                        ctypes.c_float(p), int(rounds), int(bits), out.ctypes.data)
     if rc != 0:
         raise ValueError("invalid mask arguments")
     return out
@@ -150,9 +181,10 @@ def philox4x32_py(ctr, key, rounds=10):
     return [c0, c1, c2, c3]
 
 
-def dropout_mask_py(seed, offset, B, H, S, p, rounds=10):
+def dropout_mask_py(seed, offset, B, H, S, p, rounds=10, bits=32):
     """Element-by-element evaluation of the mask definition (no grouping)."""
-    thr = int((1.0 - float(np.float32(p))) * 4294967296.0)  # IEEE double, truncation = floor
+    thr = int((1.0 - float(np.float32(p))) * float(2**bits))  # IEEE double, truncation = floor
+    E = 4 * (32 // bits)
     T = (S + 31) // 32
     out = np.zeros((B, H, T, T, 16), dtype=np.uint64)
     flat = out.reshape(-1)
@@ -165,8 +197,9 @@ def dropout_mask_py(seed, offset, B, H, S, p, rounds=10):
             j = 32 * kt + 8 * (e // 4) + 4 * (l // 32) + e % 4
             if i >= S or j >= S:
                 continue
-            n = (offset + 64 * (w >> 2) + l) % 2**64
-            x = philox4x32_py([n & _MASK32, n >> 32, 0, 0], key, rounds)[w & 3]
+            n = (offset + 64 * (w // E) + l) % 2**64
+            x = philox4x32_py([n & _MASK32, n >> 32, 0, 0], key, rounds)[(w % E) % 4]
+            x = (x >> (bits * ((w % E) // 4))) & (2**bits - 1)
             if x < thr:
                 word |= 1 << l
         flat[w] = word

@@ -20,7 +20,9 @@
  * Parity pins (tests marked "not gpu"): known-answer vectors for R = 10 and
  * R = 7, the C++26 engine's specified 10000th output, threshold closed forms,
  * kept-fraction within 4 sigma, offset splitting, monotonicity in p, and an
- * independent big-integer Python evaluation of the same definitions.
+ * independent big-integer Python evaluation of the same definitions; for the
+ * 8/16-bit variants additionally a hand-decoded example on the pinned raw
+ * words and a numpy reconstruction from the raw stream.
  * Statistical quality of Philox itself: parity unpinned (taken from the cited
  * publication).
  */
@@ -158,6 +160,73 @@ int oracle_dropout_mask(uint64_t seed, uint64_t offset, int B, int H, int S,
                         float p, uint64_t *out)
 {
     return oracle_dropout_mask_rounds(seed, offset, B, H, S, p, 10, out);
+}
+
+/* Narrow-threshold variants (the paper, Sec. 5.2, reduces the RNG cost by running fewer
+ * rounds; spending fewer random bits per element is the other knob of the same trade-off and is
+ * this build's addition, not the paper's): each 32-bit output word of a call is cut into
+ * 32/bits fields of `bits` bits, field s = (x >> (bits*s)) & (2^bits - 1), and one field decides
+ * one element: keep iff field < Tb with Tb = floor((1 - p) * 2^bits), in IEEE double from the
+ * float p.  The kept probability is therefore quantised to Tb / 2^bits (230/256 for p = 0.1
+ * and bits = 8).
+ *
+ * Words are taken in groups of E = 4 * 32/bits (16 for bits = 8, 8 for bits = 16, 4 for
+ * bits = 32): g = w / E, e = w % E.  Lane l of group g makes call number offset + 64*g + l;
+ * field s = e / 4 of output word r = e % 4 of that call decides bit l of mask word E*g + e.
+ * bits = 32 is oracle_dropout_mask_rounds.  Layout of words and bits as above. */
+int oracle_keep_threshold_bits(float p, int bits, uint64_t *T)
+{
+    if (!(p >= 0.0f) || !(p < 1.0f)) return -1;
+    if (bits != 8 && bits != 16 && bits != 32) return -1;
+    double t = (1.0 - (double)p) * (double)((uint64_t)1 << bits);
+    *T = (uint64_t)t;
+    return 0;
+}
+
+uint64_t oracle_mask_philox_calls_bits(int B, int H, int S, int bits)
+{
+    if (bits != 8 && bits != 16 && bits != 32) return 0;
+    const uint64_t E = 4u * (32u / (unsigned)bits);
+    uint64_t words = oracle_mask_words(B, H, S);
+    return 64u * ((words + E - 1u) / E);
+}
+
+int oracle_dropout_mask_bits(uint64_t seed, uint64_t offset, int B, int H, int S,
+                             float p, int rounds, int bits, uint64_t *out)
+{
+    uint64_t Tkeep;
+    if (B <= 0 || H <= 0 || S <= 0 || rounds <= 0 || out == NULL) return -1;
+    if (oracle_keep_threshold_bits(p, bits, &Tkeep) != 0) return -1;
+    const uint64_t T = ((uint64_t)S + 31u) / 32u;
+    const uint64_t words = oracle_mask_words(B, H, S);
+    const uint64_t E = 4u * (32u / (unsigned)bits);
+    const uint64_t fmask = bits == 32 ? 0xFFFFFFFFull : (((uint64_t)1 << bits) - 1u);
+    const uint64_t groups = words / E;    /* words is a multiple of 16 */
+
+#pragma omp parallel for schedule(static)
+    for (int64_t gi = 0; gi < (int64_t)groups; ++gi) {
+        const uint64_t g = (uint64_t)gi;
+        uint64_t acc[16];
+        memset(acc, 0, sizeof acc);
+        for (unsigned l = 0; l < 64; ++l) {
+            uint32_t x[4];
+            philox_call(seed, offset + 64u * g + l, rounds, x);
+            for (unsigned e = 0; e < E; ++e) {
+                const unsigned r = e % 4u, s = e / 4u;
+                const uint64_t field = ((uint64_t)x[r] >> ((unsigned)bits * s)) & fmask;
+                const uint64_t w = E * g + e;
+                const uint64_t ew = w % 16u;
+                const uint64_t kt = (w / 16u) % T;
+                const uint64_t qt = (w / (16u * T)) % T;
+                const uint64_t i = 32u * qt + (l % 32u);
+                const uint64_t j = 32u * kt + 8u * (ew / 4u) + 4u * (l / 32u) + (ew % 4u);
+                if (i < (uint64_t)S && j < (uint64_t)S && field < Tkeep)
+                    acc[e] |= (uint64_t)1 << l;
+            }
+        }
+        for (unsigned e = 0; e < E; ++e) out[E * g + e] = acc[e];
+    }
+    return 0;
 }
 
 /* Number of set bits in a word array (kept-fraction tests and timing sink). */

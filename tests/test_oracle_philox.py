@@ -257,3 +257,105 @@ def test_rounds_variants_differ_and_match_python():
         assert np.array_equal(a, P.dropout_mask_py(11, 3, 1, 1, 64, 0.2, rounds=R))
     assert not np.array_equal(P.dropout_mask(11, 3, 1, 1, 64, 0.2, rounds=7),
                               P.dropout_mask(11, 3, 1, 1, 64, 0.2, rounds=10))
+
+
+# ---------------------------------------------------------------------------
+# Narrow-threshold variants: 8 or 16 random bits per element
+# ---------------------------------------------------------------------------
+def test_bits_threshold_closed_forms():
+    from fractions import Fraction
+    assert P.keep_threshold_bits(0.1, 8) == 230           # 0.9 * 256 = 230.4
+    assert P.keep_threshold_bits(0.1, 16) == 58982        # 0.9 * 65536 = 58982.4
+    assert P.keep_threshold_bits(0.5, 8) == 128 and P.keep_threshold_bits(0.5, 16) == 32768
+    assert P.keep_threshold_bits(0.0, 8) == 256 and P.keep_threshold_bits(0.0, 16) == 65536
+    for bits in (8, 16, 32):
+        for p in [0.1, 0.2, 0.3, 0.05, 0.9, 0.999, 1e-3, 0.7071]:
+            pf = float(np.float32(p))
+            assert P.keep_threshold_bits(p, bits) == int((1 - Fraction(pf)) * 2**bits)
+        assert P.keep_threshold_bits(0.3, 32) == P.keep_threshold(0.3)
+    for bad in [(0.1, 4), (0.1, 12), (0.1, 64), (1.0, 8), (-0.1, 16)]:
+        with pytest.raises(ValueError):
+            P.keep_threshold_bits(*bad)
+
+
+def test_bits_32_is_the_plain_mask():
+    for args in [(1234, 0, 1, 2, 128, 0.1), (9, 2**32 - 64, 2, 1, 70, 0.4)]:
+        assert np.array_equal(P.dropout_mask_bits(*args, 32), P.dropout_mask(*args))
+        assert P.mask_philox_calls_bits(*args[2:5], 32) == P.mask_philox_calls(*args[2:5])
+
+
+def test_bits_worked_example_from_pinned_raw_words():
+    # calls 0 and 1 under seed 1234 (pinned above through the known-answer-checked block function):
+    #   call 0 -> 2090b348 da7cf0ab 4401906f cbca470e,  call 1 -> 9eeede35 1cbe137c fa277093 147edd50
+    # 8 bits: field s of word r is byte s; T8(0.1) = 230 = 0xe6.  Lane 1, r = 0: bytes 35 de ee 9e ->
+    # kept, kept, DROPPED (0xee >= 0xe6), kept: bit 1 of mask words 0, 4, 8, 12.
+    m8 = P.dropout_mask_bits(1234, 0, 1, 2, 128, 0.1, 8).reshape(-1)
+    assert [(int(m8[4 * s]) >> 1) & 1 for s in range(4)] == [1, 1, 0, 1]
+    # lane 0, r = 3: cbca470e -> bytes 0e 47 ca cb, all below 0xe6; r = 1: da7cf0ab -> ab f0 7c da: f0 dropped
+    assert [(int(m8[4 * s + 3]) >> 0) & 1 for s in range(4)] == [1, 1, 1, 1]
+    assert [(int(m8[4 * s + 1]) >> 0) & 1 for s in range(4)] == [1, 0, 1, 1]
+    # 16 bits: T16(0.1) = 58982 = 0xe666.  Lane 1, r = 2: fa277093 -> halves 7093 (kept), fa27 (dropped)
+    m16 = P.dropout_mask_bits(1234, 0, 1, 2, 128, 0.1, 16).reshape(-1)
+    assert [(int(m16[4 * s + 2]) >> 1) & 1 for s in range(2)] == [1, 0]
+    # lane 0, r = 1: da7cf0ab -> f0ab dropped (>= e666), da7c kept
+    assert [(int(m16[4 * s + 1]) >> 0) & 1 for s in range(2)] == [0, 1]
+
+
+@pytest.mark.parametrize("bits", [8, 16])
+@pytest.mark.parametrize("B,H,S,p,seed,offset", [
+    (1, 2, 128, 0.1, 1234, 0),
+    (1, 1, 70, 0.3, 99, 5),
+    (2, 3, 33, 0.5, 2**40 + 7, 2**32 - 64),
+    (1, 1, 1, 0.1, 1, 0),
+])
+def test_bits_c_matches_python_integers(bits, B, H, S, p, seed, offset):
+    a = P.dropout_mask_bits(seed, offset, B, H, S, p, bits)
+    b = P.dropout_mask_py(seed, offset, B, H, S, p, bits=bits)
+    assert np.array_equal(a, b)
+
+
+@pytest.mark.parametrize("bits", [8, 16])
+def test_bits_mask_equals_thresholded_fields_of_raw_stream(bits):
+    # built with numpy from the (separately pinned) raw stream: word E*g + 4*s + r, bit l
+    #   == field s of raw[offset + 64*g + l][r] < Tb
+    B, H, S, p, seed, offset = 1, 3, 192, 0.1, 777, 12345
+    nf = 32 // bits
+    E = 4 * nf
+    words = B * H * (S // 32) ** 2 * 16
+    raw = P.philox_raw(seed, offset, 64 * (words // E), 10).reshape(-1, 64, 4).astype(np.uint64)   # [g, l, r]
+    fields = np.stack([(raw >> np.uint64(bits * s)) & np.uint64(2**bits - 1) for s in range(nf)], axis=1)  # [g, s, l, r]
+    keep = fields < np.uint64(P.keep_threshold_bits(p, bits))
+    keep = keep.transpose(0, 1, 3, 2).reshape(-1, 64)                                                # [(g, s, r), l]
+    weights = (np.uint64(1) << np.arange(64, dtype=np.uint64))
+    expect = (keep.astype(np.uint64) * weights).sum(axis=1, dtype=np.uint64)
+    got = P.dropout_mask_bits(seed, offset, B, H, S, p, bits).reshape(-1)
+    assert np.array_equal(got, expect)
+    assert P.mask_philox_calls_bits(B, H, S, bits) == 64 * (words // E)
+
+
+@pytest.mark.parametrize("bits", [8, 16])
+def test_bits_kept_fraction_within_four_sigma_of_quantised_probability(bits):
+    # the kept probability is Tb / 2^bits, not 1 - p: 230/256 = 0.8984 for 8 bits at p = 0.1
+    B, H, S, p = 1, 8, 512, 0.1
+    m = P.dropout_mask_bits(1234, 0, B, H, S, p, bits)
+    q = P.keep_threshold_bits(p, bits) / 2**bits
+    assert _four_sigma_ok(P.popcount(m), B * H * S * S, q)
+    if bits == 8:   # and it is measurably not 1 - p at this size (the reason 32 bits is the default)
+        assert not _four_sigma_ok(P.popcount(m), B * H * S * S, 0.9)
+    for s_field in range(32 // bits):                      # every field position on its own
+        sub = m.reshape(-1, 4 * (32 // bits))[:, 4 * s_field:4 * s_field + 4]
+        assert _four_sigma_ok(P.popcount(sub), sub.size * 64, q)
+
+
+@pytest.mark.parametrize("bits", [8, 16])
+def test_bits_padding_monotone_and_offset_splitting(bits):
+    S = 70
+    m = P.dropout_mask_bits(5, 0, 1, 2, S, 0.0, bits)
+    assert P.popcount(m) == 2 * S * S                      # p = 0 keeps exactly the in-range elements
+    a = P.dropout_mask_bits(7, 0, 1, 2, 256, 0.1, bits).reshape(-1)
+    b = P.dropout_mask_bits(7, 0, 1, 2, 256, 0.3, bits).reshape(-1)
+    assert np.all((b & ~a) == 0) and P.popcount(b) < P.popcount(a)
+    full = P.dropout_mask_bits(42, 1000, 1, 4, 128, 0.1, bits).reshape(-1)
+    E = 4 * (32 // bits)
+    tail = P.dropout_mask_bits(42, 1000 + 64 * (512 // E), 1, 2, 128, 0.1, bits).reshape(-1)
+    assert np.array_equal(full[512:], tail)

@@ -104,6 +104,22 @@ int rov_dropout_mask_generate_causal(uint64_t seed, uint64_t offset, int B, int 
 int rov_dropout_mask_generate_rounds(uint64_t seed, uint64_t offset, int B, int H, int S, float p,
                                      int rounds, uint64_t *out, void *stream);
 
+/* Same layout and call numbering, but with `bits` (8, 16 or 32) random bits per element
+ * instead of 32 - the other way, next to fewer rounds (paper Sec. 5.2), of making the RNG
+ * kernel cheaper; an addition of this library, not the paper's.  Each 32-bit output word of
+ * a call is cut into 32/bits fields, field s = (x >> (bits*s)) & (2^bits - 1); mask words are
+ * taken in groups of E = 4*32/bits: lane l of group g = w / E makes call number
+ * offset + 64*g + l, and field (w % E) / 4 of output word (w % E) % 4 decides bit l of word w:
+ * keep iff field < Tb, Tb = floor((1 - p) * 2^bits) in double from the float p.  The kept
+ * probability is quantised to Tb / 2^bits (230/256 for p = 0.1 at 8 bits).  bits == 32 is
+ * rov_dropout_mask_generate.  One mask advances the call counter by
+ * rov_mask_philox_calls_bits = 64*words/E (0 for an unsupported `bits`).  10 rounds.
+ * rov_attention_fwd_dropout reads such a mask like any other; its fused variant (mask ==
+ * NULL) always draws 32 bits per element.  Other values of bits: ROV_ERR_INVALID. */
+uint64_t rov_mask_philox_calls_bits(int B, int H, int S, int bits);
+int rov_dropout_mask_generate_bits(uint64_t seed, uint64_t offset, int B, int H, int S, float p,
+                                   int bits, uint64_t *out, void *stream);
+
 /* Launch-shape control for the RNG kernel, used by the overlap experiments
  * (paper Sec. 6.2: the RNG kernel must fit beside a GEMM that owns most of each
  * compute unit).  max_workgroups <= 0 restores the default (enough workgroups

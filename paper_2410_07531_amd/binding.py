@@ -62,6 +62,8 @@ SIGNATURES = {
     "rov_dropout_mask_generate": (_i, [_u64, _u64, _i, _i, _i, _f, _p, _p]),
     "rov_dropout_mask_generate_rounds": (_i, [_u64, _u64, _i, _i, _i, _f, _i, _p, _p]),
     "rov_dropout_mask_generate_causal": (_i, [_u64, _u64, _i, _i, _i, _f, _p, _p]),
+    "rov_dropout_mask_generate_bits": (_i, [_u64, _u64, _i, _i, _i, _f, _i, _p, _p]),
+    "rov_mask_philox_calls_bits": (_u64, [_i, _i, _i, _i]),
     "rov_set_rng_max_workgroups": (_i, [_i]),
     "rov_set_rng_overlap_workgroups_per_cu": (_i, [_i]),
     "rov_trace_enable": (_i, [_i]),
@@ -132,6 +134,10 @@ def mask_philox_calls(B, H, S):
     return int(load().rov_mask_philox_calls(B, H, S))
 
 
+def mask_philox_calls_bits(B, H, S, bits):
+    return int(load().rov_mask_philox_calls_bits(B, H, S, int(bits)))
+
+
 def set_rng_max_workgroups(n):
     return int(load().rov_set_rng_max_workgroups(int(n)))
 
@@ -177,6 +183,17 @@ def dropout_mask_generate(seed, offset, B, H, S, p, out=None, rounds=None, strea
         rc = L.rov_dropout_mask_generate_rounds(seed & (2**64 - 1), offset & (2**64 - 1), B, H, S, p, int(rounds),
                                                 ctypes.c_void_p(out.data_ptr()), _stream_ptr(stream))
     _check(rc, "rov_dropout_mask_generate")
+    return out
+
+
+def dropout_mask_generate_bits(seed, offset, B, H, S, p, bits, out=None, stream=None):
+    """Keep-mask drawn with `bits` (8, 16 or 32) random bits per element; same shape and layout."""
+    import torch
+    if out is None:
+        out = torch.empty(mask_shape(B, H, S), dtype=torch.int64, device="cuda")
+    _check(load().rov_dropout_mask_generate_bits(seed & (2**64 - 1), offset & (2**64 - 1), B, H, S, p, int(bits),
+                                                 ctypes.c_void_p(out.data_ptr()), _stream_ptr(stream)),
+           "rov_dropout_mask_generate_bits")
     return out
 
 

@@ -99,6 +99,82 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void mask_kernel(
     }
 }
 
+// Narrow-threshold chunk: BITS (8 or 16) random bits per element.  One Philox call per lane now
+// serves E = 4 * 32/BITS mask words: field s of output word r decides word E*gi + 4*s + r of the
+// chunk.  A chunk is still 64 words = 4 tiles; tile t of the chunk has coordinates (qts[t], kts[t]).
+template <int BITS, bool RAGGED, bool CARRY>
+__device__ __forceinline__ void mask_chunk_bits(uint64_t base, uint32_t lane, uint32_t k0, uint32_t k1,
+                                                uint32_t tb, uint32_t S, const uint32_t (&qts)[4],
+                                                const uint32_t (&kts)[4], uint32_t& vlo, uint32_t& vhi) {
+    constexpr int NF = 32 / BITS;          // fields per output word
+    constexpr int E = 4 * NF;              // mask words per group
+#pragma unroll
+    for (int gi = 0; gi < 64 / E; ++gi) {
+        const uint64_t b = base + 64u * (uint64_t)gi;
+        const uint32_t blo = (uint32_t)b, bhi = (uint32_t)(b >> 32);
+        const uint32_t c0 = blo + lane;
+        uint32_t x[4];
+        if (!CARRY) {
+            philox4x32_low_counter<10>(c0, bhi, k0, k1, x);
+        } else {
+            philox4x32<10>(c0, bhi + (c0 < blo ? 1u : 0u), 0u, 0u, k0, k1, x);
+        }
+#pragma unroll
+        for (int s = 0; s < NF; ++s)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const uint32_t field = (x[r] >> (BITS * s)) & ((1u << BITS) - 1u);
+                const uint64_t bal = __ballot(field < tb);
+                uint32_t lo = (uint32_t)bal, hi = (uint32_t)(bal >> 32);
+                const int dst = E * gi + 4 * s + r;            // word of the chunk
+                if (RAGGED) {
+                    const int t = dst >> 4, ew = dst & 15;     // tile of the chunk, word of the tile
+                    const uint32_t rows_valid = S - 32u * qts[t];
+                    const uint32_t row_mask = rows_valid < 32u ? (1u << rows_valid) - 1u : 0xFFFFFFFFu;
+                    const uint32_t col = 32u * kts[t] + 8u * (uint32_t)(ew >> 2) + (uint32_t)(ew & 3);
+                    lo = col < S ? (lo & row_mask) : 0u;
+                    hi = col + 4u < S ? (hi & row_mask) : 0u;
+                }
+                vlo = write_lane(lo, (uint32_t)dst, vlo);
+                vhi = write_lane(hi, (uint32_t)dst, vhi);
+            }
+    }
+}
+
+template <int BITS, bool RAGGED>
+__global__ __launch_bounds__(kWavesPerBlock * 64) void mask_bits_kernel(
+    uint64_t* __restrict__ out, uint64_t words, uint64_t nchunks, uint64_t offset, uint32_t k0,
+    uint32_t k1, uint32_t tb, uint32_t T, uint32_t S) {
+    constexpr uint32_t kCallsPerChunk = 64u * (64u / (4u * (32u / BITS)));   // 256 (8 bits) or 512 (16 bits)
+    const uint32_t lane = threadIdx.x & 63u;
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const uint64_t stride = (uint64_t)gridDim.x * kWavesPerBlock;
+    for (uint64_t chunk = (uint64_t)blockIdx.x * kWavesPerBlock + wave; chunk < nchunks;
+         chunk += stride) {
+        uint32_t vlo = 0u, vhi = 0u;
+        uint32_t qts[4] = {0u, 0u, 0u, 0u}, kts[4] = {0u, 0u, 0u, 0u};
+        if (RAGGED) {
+            const uint64_t tile = chunk * 4u;
+            uint32_t kt = (uint32_t)(tile % T), qt = (uint32_t)((tile / T) % T);
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                qts[t] = qt;
+                kts[t] = kt;
+                kt = kt + 1u == T ? 0u : kt + 1u;
+                if (kt == 0u) qt = qt + 1u == T ? 0u : qt + 1u;
+            }
+        }
+        const uint64_t base = offset + (uint64_t)kCallsPerChunk * chunk;
+        if ((uint32_t)base <= 0xFFFFFFFFu - (kCallsPerChunk - 1u)) {
+            mask_chunk_bits<BITS, RAGGED, false>(base, lane, k0, k1, tb, S, qts, kts, vlo, vhi);
+        } else {
+            mask_chunk_bits<BITS, RAGGED, true>(base, lane, k0, k1, tb, S, qts, kts, vlo, vhi);
+        }
+        const uint64_t widx = chunk * 64u + lane;
+        if (widx < words) out[widx] = ((uint64_t)vhi << 32) | vlo;
+    }
+}
+
 __global__ __launch_bounds__(256) void raw_kernel(uint32_t* __restrict__ out, uint64_t ncalls,
                                                   uint64_t first, uint32_t k0, uint32_t k1,
                                                   int rounds) {
@@ -132,6 +208,27 @@ int launch_mask_r(uint64_t* out, uint64_t words, uint64_t offset, uint32_t k0, u
     } else {
         hipLaunchKernelGGL((mask_kernel<R, true>), grid, block, 0, stream, out, words, nchunks,
                            offset, k0, k1, t_minus_1, T, (uint32_t)S, (int)lower_only);
+    }
+    ROV_LAUNCH_CHECK();
+    return ROV_OK;
+}
+
+template <int BITS>
+int launch_mask_bits_b(uint64_t* out, uint64_t words, uint64_t offset, uint32_t k0, uint32_t k1,
+                       uint32_t tb, int S, hipStream_t stream) {
+    const uint32_t T = (uint32_t)(((uint64_t)S + 31u) / 32u);
+    const uint64_t nchunks = (words + 63u) / 64u;
+    uint64_t blocks = (nchunks + kWavesPerBlock - 1) / kWavesPerBlock;
+    int cap = g_rng_max_workgroups.load();
+    if (cap <= 0) cap = device_cu_count() * 64;
+    if (blocks > (uint64_t)cap) blocks = (uint64_t)cap;
+    const dim3 grid((unsigned)blocks), block(kWavesPerBlock * 64);
+    if ((S & 31) == 0) {
+        hipLaunchKernelGGL((mask_bits_kernel<BITS, false>), grid, block, 0, stream, out, words, nchunks,
+                           offset, k0, k1, tb, T, (uint32_t)S);
+    } else {
+        hipLaunchKernelGGL((mask_bits_kernel<BITS, true>), grid, block, 0, stream, out, words, nchunks,
+                           offset, k0, k1, tb, T, (uint32_t)S);
     }
     ROV_LAUNCH_CHECK();
     return ROV_OK;
@@ -219,6 +316,31 @@ int rov_dropout_mask_generate_causal(uint64_t seed, uint64_t offset, int B, int 
 int rov_dropout_mask_generate_rounds(uint64_t seed, uint64_t offset, int B, int H, int S, float p,
                                      int rounds, uint64_t* out, void* stream) {
     return rov::launch_mask(seed, offset, B, H, S, p, rounds, out, (hipStream_t)stream);
+}
+
+uint64_t rov_mask_philox_calls_bits(int B, int H, int S, int bits) {
+    if (bits != 8 && bits != 16 && bits != 32) return 0;
+    const uint64_t words = rov_mask_words(B, H, S);
+    const uint64_t E = 4u * (32u / (unsigned)bits);
+    return 64u * ((words + E - 1u) / E);
+}
+
+int rov_dropout_mask_generate_bits(uint64_t seed, uint64_t offset, int B, int H, int S, float p,
+                                   int bits, uint64_t* out, void* stream) {
+    using namespace rov;
+    if (bits == 32) return launch_mask(seed, offset, B, H, S, p, 10, out, (hipStream_t)stream);
+    if (bits != 8 && bits != 16) return ROV_ERR_INVALID;
+    if (B <= 0 || H <= 0 || S <= 0 || out == nullptr || !aligned(out, 8)) return ROV_ERR_INVALID;
+    if (!(p >= 0.0f) || !(p < 1.0f)) return ROV_ERR_INVALID;
+    const uint64_t T = ((uint64_t)S + 31u) / 32u;
+    const long double wd = (long double)B * H * T * T * 16.0L;
+    if (wd > 1099511627776.0L) return ROV_ERR_UNSUPPORTED;
+    const uint64_t words = (uint64_t)B * (uint64_t)H * T * T * 16u;
+    // keep iff field < Tb, Tb = floor((1 - p) * 2^bits) in double from the float p (0 <= Tb <= 2^bits)
+    const uint32_t tb = (uint32_t)(uint64_t)((1.0 - (double)p) * (double)(1u << bits));
+    const uint32_t k0 = (uint32_t)seed, k1 = (uint32_t)(seed >> 32);
+    return bits == 8 ? launch_mask_bits_b<8>(out, words, offset, k0, k1, tb, S, (hipStream_t)stream)
+                     : launch_mask_bits_b<16>(out, words, offset, k0, k1, tb, S, (hipStream_t)stream);
 }
 
 }  // extern "C"

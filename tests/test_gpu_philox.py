@@ -154,3 +154,26 @@ def test_mask_error_paths_leave_output_untouched():
     assert L.rov_philox_raw(1, 0, 0, 10, ctypes.c_void_p(0), s) == rov.OK
     torch.cuda.synchronize()
     assert bool((out == 0x5A5A5A5A).all())
+
+
+@pytest.mark.parametrize("bits", [8, 16, 32])
+@pytest.mark.parametrize("B,H,S,p,seed,offset", MASK_CASES + [
+    (1, 2, 96, 0.9999, 6, 0),                              # 8 bits: threshold 0, nothing kept
+    (1, 32, 2048, 0.1, wl.SEED, wl.OFFSET),                # the measured workload at full size
+])
+def test_mask_bits_bit_exact(bits, B, H, S, p, seed, offset):
+    print("mask bits", bits, B, H, S, p, seed, offset, flush=True)
+    got = _np_u64(rov.dropout_mask_generate_bits(seed, offset, B, H, S, p, bits))
+    exp = OP.dropout_mask_bits(seed, offset, B, H, S, p, bits)
+    assert np.array_equal(got, exp)
+    assert rov.mask_philox_calls_bits(B, H, S, bits) == OP.mask_philox_calls_bits(B, H, S, bits)
+
+
+def test_mask_bits_rejects_other_widths():
+    import torch
+    out = torch.zeros(rov.mask_shape(1, 1, 32), dtype=torch.int64, device="cuda")
+    for bits in (0, 4, 12, 24, 64):
+        with pytest.raises(RuntimeError):
+            rov.dropout_mask_generate_bits(1, 0, 1, 1, 32, 0.1, bits, out=out)
+        assert rov.mask_philox_calls_bits(1, 1, 32, bits) == 0
+    assert int(out.abs().sum()) == 0                        # nothing was written

@@ -120,6 +120,17 @@ uint64_t rov_mask_philox_calls_bits(int B, int H, int S, int bits);
 int rov_dropout_mask_generate_bits(uint64_t seed, uint64_t offset, int B, int H, int S, float p,
                                    int bits, uint64_t *out, void *stream);
 
+/* Rows of the mask only (paper Sec. 7.2: chunking along the sequence bounds the mask's
+ * memory).  Writes the tile rows that cover query rows [q_begin, min(q_begin + q_rows, S)) of
+ * every (batch, head), compactly as [B][H][nqt][T][16] with nqt = ceil((q_end - q_begin)/32):
+ * exactly the words the full mask of rov_dropout_mask_generate has there (call numbers come
+ * from the position in the full mask, so chunked and unchunked runs drop the same elements).
+ * q_begin must be a multiple of 32 and < S; q_rows > 0.  rov_mask_words_rows = B*H*nqt*T*16
+ * (0 for invalid arguments). */
+uint64_t rov_mask_words_rows(int B, int H, int S, int q_begin, int q_rows);
+int rov_dropout_mask_generate_rows(uint64_t seed, uint64_t offset, int B, int H, int S, float p,
+                                   int q_begin, int q_rows, uint64_t *out, void *stream);
+
 /* Launch-shape control for the RNG kernel, used by the overlap experiments
  * (paper Sec. 6.2: the RNG kernel must fit beside a GEMM that owns most of each
  * compute unit).  max_workgroups <= 0 restores the default (enough workgroups
@@ -174,6 +185,16 @@ int rov_attention_fwd_dropout(const void *Q, const void *K, const void *V, void 
                               int dtype, int causal, float p, const uint64_t *mask,
                               uint64_t seed, uint64_t offset, void *stream);
 
+/* Same for query rows [q_begin, min(q_begin + q_rows, S)) only: those rows of O are written,
+ * the others are left alone.  mask_rows (may be NULL: fused variant) holds just the tile rows
+ * of that range, as written by rov_dropout_mask_generate_rows with the same q_begin, q_rows.
+ * q_begin: multiple of 32, < S. */
+int rov_attention_fwd_dropout_rows(const void *Q, const void *K, const void *V, void *O,
+                                   int B, int H, int Hkv, int S, int d, const int64_t strides[12],
+                                   int dtype, int causal, float p, const uint64_t *mask_rows,
+                                   uint64_t seed, uint64_t offset, int q_begin, int q_rows,
+                                   void *stream);
+
 /* ---------------------------------------------------------------- schedules
  * One "layer step" of the paper's silicon experiment (Sec. 6.1): n_gemms
  * independent GEMMs, the RNG kernel, then attention with dropout, arranged by
@@ -209,6 +230,17 @@ typedef struct rov_attn_desc {
 int rov_layer_step(int schedule, const rov_gemm_desc *gemms, int n_gemms, const rov_attn_desc *attn,
                    uint64_t seed, uint64_t offset, uint64_t *mask, void *main_stream,
                    void *side_stream);
+
+/* The overlap schedule with the mask pipelined in chunks of q_chunk_rows query rows (paper
+ * Sec. 7.2, sequence chunking): mask_ring holds two slots of
+ * rov_mask_words_rows(B,H,S,0,q_chunk_rows) words instead of the whole mask.  Chunks 0 and 1 are
+ * generated on side_stream beside the GEMMs; attention runs chunk by chunk on main_stream, and
+ * chunk c+2 is generated into the slot of chunk c while attention works on chunk c+1.  Output
+ * and dropped elements are those of rov_layer_step with the full mask.  Requires attn->p > 0,
+ * q_chunk_rows a positive multiple of 32, side_stream != main_stream. */
+int rov_layer_step_chunked(const rov_gemm_desc *gemms, int n_gemms, const rov_attn_desc *attn,
+                           uint64_t seed, uint64_t offset, int q_chunk_rows, uint64_t *mask_ring,
+                           void *main_stream, void *side_stream);
 
 /* ---------------------------------------------------------------- kernel tracing
  * Per-kernel timing of what rov_layer_step and rov_block_forward launch (the

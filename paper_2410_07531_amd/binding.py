@@ -64,6 +64,13 @@ SIGNATURES = {
     "rov_dropout_mask_generate_causal": (_i, [_u64, _u64, _i, _i, _i, _f, _p, _p]),
     "rov_dropout_mask_generate_bits": (_i, [_u64, _u64, _i, _i, _i, _f, _i, _p, _p]),
     "rov_mask_philox_calls_bits": (_u64, [_i, _i, _i, _i]),
+    "rov_mask_words_rows": (_u64, [_i, _i, _i, _i, _i]),
+    "rov_dropout_mask_generate_rows": (_i, [_u64, _u64, _i, _i, _i, _f, _i, _i, _p, _p]),
+    "rov_attention_fwd_dropout_rows": (_i, [_p, _p, _p, _p, _i, _i, _i, _i, _i,
+                                            ctypes.POINTER(ctypes.c_int64), _i, _i, _f, _p, _u64, _u64,
+                                            _i, _i, _p]),
+    "rov_layer_step_chunked": (_i, [ctypes.POINTER(GemmDesc), _i, ctypes.POINTER(AttnDesc), _u64, _u64, _i,
+                                    _p, _p, _p]),
     "rov_set_rng_max_workgroups": (_i, [_i]),
     "rov_set_rng_overlap_workgroups_per_cu": (_i, [_i]),
     "rov_trace_enable": (_i, [_i]),
@@ -233,6 +240,46 @@ def attention_fwd_dropout(Q, K, V, p, mask=None, seed=0, offset=0, causal=False,
         ctypes.c_void_p(O.data_ptr()), B, H, Hkv, S, d, strides, _dtype_code(Q), int(bool(causal)), float(p),
         mptr, seed & (2**64 - 1), offset & (2**64 - 1), _stream_ptr(stream)), "rov_attention_fwd_dropout")
     return O
+
+
+def mask_words_rows(B, H, S, q_begin, q_rows):
+    return int(load().rov_mask_words_rows(B, H, S, int(q_begin), int(q_rows)))
+
+
+def dropout_mask_generate_rows(seed, offset, B, H, S, p, q_begin, q_rows, out=None, stream=None):
+    """Tile rows of query rows [q_begin, q_begin + q_rows): int64 tensor [B, H, nqt, T, 16]."""
+    import torch
+    if out is None:
+        T = (S + 31) // 32
+        nqt = (min(q_begin + q_rows, S) - q_begin + 31) // 32
+        out = torch.empty((B, H, nqt, T, 16), dtype=torch.int64, device="cuda")
+    _check(load().rov_dropout_mask_generate_rows(seed & (2**64 - 1), offset & (2**64 - 1), B, H, S, p,
+                                                 int(q_begin), int(q_rows), ctypes.c_void_p(out.data_ptr()),
+                                                 _stream_ptr(stream)), "rov_dropout_mask_generate_rows")
+    return out
+
+
+def attention_fwd_dropout_rows(Q, K, V, p, q_begin, q_rows, O, mask_rows=None, seed=0, offset=0, causal=False,
+                               stream=None):
+    """Computes query rows [q_begin, q_begin + q_rows) of O in place; mask_rows holds those tile rows."""
+    B, S, H, d = Q.shape
+    Hkv = K.shape[2]
+    strides = _strides12(Q, K, V, O)
+    mptr = ctypes.c_void_p(mask_rows.data_ptr()) if mask_rows is not None else ctypes.c_void_p(0)
+    _check(load().rov_attention_fwd_dropout_rows(
+        ctypes.c_void_p(Q.data_ptr()), ctypes.c_void_p(K.data_ptr()), ctypes.c_void_p(V.data_ptr()),
+        ctypes.c_void_p(O.data_ptr()), B, H, Hkv, S, d, strides, _dtype_code(Q), int(bool(causal)), float(p),
+        mptr, seed & (2**64 - 1), offset & (2**64 - 1), int(q_begin), int(q_rows), _stream_ptr(stream)),
+        "rov_attention_fwd_dropout_rows")
+    return O
+
+
+def layer_step_chunked(gemm_descs, attn_desc, seed, offset, q_chunk_rows, mask_ring, main_stream, side_stream):
+    arr = (GemmDesc * len(gemm_descs))(*gemm_descs)
+    _check(load().rov_layer_step_chunked(arr, len(gemm_descs), ctypes.byref(attn_desc), seed & (2**64 - 1),
+                                         offset & (2**64 - 1), int(q_chunk_rows),
+                                         ctypes.c_void_p(mask_ring.data_ptr()), _stream_ptr(main_stream),
+                                         _stream_ptr(side_stream)), "rov_layer_step_chunked")
 
 
 def make_gemm_desc(A, Bm, C, transB=True, scaleA=1.0, scaleB=1.0):

@@ -46,6 +46,8 @@ struct AttnParams {
     int B, H, Hkv, S, d;
     int W;                                // mask tiles per side, ceil(S/32)
     int nq;                               // query blocks per (batch, head)
+    int q_begin, q_end;                   // query rows computed by this launch: [q_begin, q_end)
+    int mask_qt0, mask_nqt;               // tile rows the mask buffer holds: [mask_qt0, mask_qt0 + mask_nqt)
     int causal;
     float scale_log2;                     // log2(e) / sqrt(d)
     float inv_keep;                       // 1 / (1 - p)
@@ -168,7 +170,8 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(const AttnParams p) 
     }
     const int b = bh / p.H, h = bh % p.H;
     const int hk = h / (p.H / p.Hkv);
-    const int q0 = qblk * BQ + wave * (32 * NQ);
+    const int q0 = p.q_begin + qblk * BQ + wave * (32 * NQ);
+    const int q_end = p.q_end;
 
     const uint16_t* Qp = (const uint16_t*)p.Q + b * p.sq[0] + h * p.sq[2];
     const uint16_t* Kp = (const uint16_t*)p.K + b * p.sk[0] + hk * p.sk[2];
@@ -182,7 +185,7 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(const AttnParams p) 
     for (int n = 0; n < NQ; ++n) {
         int q = q0 + 32 * n + ql;
         qrow[n] = q;
-        q = q < S ? q : S - 1;
+        q = q < q_end ? q : q_end - 1;
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks)
             qf[n][ks] = *reinterpret_cast<const bf16x8*>(Qp + (int64_t)q * p.sq[1] + 16 * ks + 8 * half);
@@ -200,7 +203,7 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(const AttnParams p) 
     for (int n = 0; n < NQ; ++n) { m_run[n] = -INFINITY; l_run[n] = 0.0f; }
 
     // number of KV tiles this workgroup walks (causal: up to its last query row)
-    const int q_last = min(qblk * BQ + BQ, S) - 1;
+    const int q_last = min(p.q_begin + qblk * BQ + BQ, q_end) - 1;
     const int kv_end = p.causal ? min(S, q_last + 1) : S;
     const int ntiles = (kv_end + BKV - 1) / BKV;
 
@@ -217,9 +220,11 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(const AttnParams p) 
 #pragma unroll
     for (int n = 0; n < NQ; ++n) {
         uint32_t qt = (uint32_t)(q0 / 32 + n);
-        qt = qt < Tt ? qt : Tt - 1;                                       // rows past S are never stored
+        const uint32_t qt_last = (uint32_t)(p.mask_qt0 + p.mask_nqt - 1);
+        qt = qt < qt_last ? qt : qt_last;                                 // rows past q_end are never stored
         wtile[n] = ((bh_tiles + qt) * Tt) * 16u;
-        mtile[n] = p.mask + wtile[n];
+        // the buffer holds mask_nqt tile rows per (batch, head), starting at tile row mask_qt0
+        mtile[n] = p.mask + ((((uint64_t)b * p.H + h) * (uint32_t)p.mask_nqt + (qt - (uint32_t)p.mask_qt0)) * Tt) * 16u;
     }
 
     load_kv_tile<D, NW, false>(Kp, p.sk[1], 0, S, lds, wave, lane);
@@ -405,7 +410,7 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(const AttnParams p) 
     for (int n = 0; n < NQ; ++n) {
         const float l = l_run[n] + __shfl_xor(l_run[n], 32);
         const float f = l > 0.0f ? p.inv_keep / l : 0.0f;
-        if (qrow[n] < S) {
+        if (qrow[n] < q_end) {
             uint16_t* orow = Op + (int64_t)qrow[n] * p.so[1];
 #pragma unroll
             for (int t = 0; t < DVT; ++t)
@@ -454,11 +459,11 @@ __global__ __launch_bounds__(256) void attn_generic_kernel(const AttnParams p) {
     __shared__ float qs[4][256];
     __shared__ float ps[4][256];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int row = blockIdx.x * 4 + wave;
+    const int row = p.q_begin + blockIdx.x * 4 + wave;
     const int b = blockIdx.z, h = blockIdx.y;
     const int hk = h / (p.H / p.Hkv);
     const int S = p.S, d = p.d;
-    if (row >= S) return;   // whole wave leaves; no block-wide barrier below
+    if (row >= p.q_end) return;   // whole wave leaves; no block-wide barrier below
     const TT* Qp = (const TT*)p.Q + b * p.sq[0] + h * p.sq[2] + (int64_t)row * p.sq[1];
     const TT* Kp = (const TT*)p.K + b * p.sk[0] + hk * p.sk[2];
     const TT* Vp = (const TT*)p.V + b * p.sv[0] + hk * p.sv[2];
@@ -471,6 +476,8 @@ __global__ __launch_bounds__(256) void attn_generic_kernel(const AttnParams p) {
     // tile row of this query row in the mask: words of tile (row/32, kt) start at wrow + 16*kt;
     // element (row, key) is bit 32*((key%32)/4 % 2) + row%32 of word 4*((key%32)/8) + key%4
     const uint64_t wrow = ((((uint64_t)b * p.H + h) * p.W + (uint64_t)(row >> 5)) * p.W) * 16u;
+    // same tile row inside the mask buffer, which holds tile rows [mask_qt0, mask_qt0 + mask_nqt)
+    const uint64_t mrow = ((((uint64_t)b * p.H + h) * p.mask_nqt + (uint64_t)((row >> 5) - p.mask_qt0)) * p.W) * 16u;
     for (int c0 = 0; c0 < kv_end; c0 += 256) {
         float sc[4];
         float mx = -INFINITY;
@@ -501,10 +508,11 @@ __global__ __launch_bounds__(256) void attn_generic_kernel(const AttnParams p) {
                 sum += pe;
                 bool keep = true;
                 const int kl = key & 31;
-                const uint64_t w = wrow + (uint64_t)(key >> 5) * 16u + (uint64_t)(4 * (kl >> 3) + (kl & 3));
+                const uint64_t wo = (uint64_t)(key >> 5) * 16u + (uint64_t)(4 * (kl >> 3) + (kl & 3));
+                const uint64_t w = wrow + wo;
                 const uint32_t bit = 32u * ((uint32_t)(kl >> 2) & 1u) + ((uint32_t)row & 31u);
                 if (MODE == MODE_MASK) {
-                    keep = (p.mask[w] >> bit) & 1ull;
+                    keep = (p.mask[mrow + wo] >> bit) & 1ull;
                 } else if (MODE == MODE_FUSED) {
                     const uint64_t ncall = p.offset + 64u * (w >> 2) + (uint64_t)bit;
                     uint32_t x[4];
@@ -544,7 +552,7 @@ template <int D, int NQ, int NW>
 int launch_bf16(const AttnParams& prm, int mode, hipStream_t stream) {
     const int bq = NW * 32 * NQ;
     AttnParams prm2 = prm;
-    prm2.nq = (prm.S + bq - 1) / bq;
+    prm2.nq = (prm.q_end - prm.q_begin + bq - 1) / bq;
     const long long nblocks = (long long)prm2.nq * prm.H * prm.B;
     if (nblocks > 0x7FFFFFFFLL) return ROV_ERR_UNSUPPORTED;
     const dim3 grid((unsigned)nblocks), block(NW * 64);
@@ -561,7 +569,7 @@ int launch_bf16(const AttnParams& prm, int mode, hipStream_t stream) {
 
 template <typename TT>
 int launch_generic(const AttnParams& prm, int mode, hipStream_t stream) {
-    const dim3 grid((unsigned)((prm.S + 3) / 4), (unsigned)prm.H, (unsigned)prm.B), block(256);
+    const dim3 grid((unsigned)((prm.q_end - prm.q_begin + 3) / 4), (unsigned)prm.H, (unsigned)prm.B), block(256);
     if (mode == MODE_NONE)
         hipLaunchKernelGGL((attn_generic_kernel<TT, MODE_NONE>), grid, block, 0, stream, prm);
     else if (mode == MODE_MASK)
@@ -577,6 +585,15 @@ int launch_generic(const AttnParams& prm, int mode, hipStream_t stream) {
 int launch_attention(const void* Q, const void* K, const void* V, void* O, int B, int H, int Hkv,
                      int S, int d, const int64_t strides[12], int dtype, int causal, float p,
                      const uint64_t* mask, uint64_t seed, uint64_t offset, hipStream_t stream) {
+    return launch_attention_rows(Q, K, V, O, B, H, Hkv, S, d, strides, dtype, causal, p, mask, false, seed,
+                                 offset, 0, S, stream);
+}
+
+int launch_attention_rows(const void* Q, const void* K, const void* V, void* O, int B, int H, int Hkv,
+                          int S, int d, const int64_t strides[12], int dtype, int causal, float p,
+                          const uint64_t* mask, bool mask_is_rows, uint64_t seed, uint64_t offset,
+                          int q_begin, int q_rows, hipStream_t stream) {
+    if (S <= 0 || q_begin < 0 || q_rows <= 0 || q_begin >= S || (q_begin & 31) != 0) return ROV_ERR_INVALID;
     if (Q == nullptr || K == nullptr || V == nullptr || O == nullptr || strides == nullptr)
         return ROV_ERR_INVALID;
     if (B <= 0 || H <= 0 || Hkv <= 0 || S <= 0 || d <= 0 || (H % Hkv) != 0) return ROV_ERR_INVALID;
@@ -595,6 +612,11 @@ int launch_attention(const void* Q, const void* K, const void* V, void* O, int B
     }
     prm.B = B; prm.H = H; prm.Hkv = Hkv; prm.S = S; prm.d = d;
     prm.W = (S + 31) / 32;
+    prm.q_begin = q_begin;
+    prm.q_end = (int64_t)q_begin + q_rows < S ? q_begin + q_rows : S;
+    // a mask of rows holds exactly the tile rows of [q_begin, q_end); a full mask holds all of them
+    prm.mask_qt0 = mask_is_rows ? q_begin / 32 : 0;
+    prm.mask_nqt = mask_is_rows ? (prm.q_end - q_begin + 31) / 32 : prm.W;
     prm.causal = causal != 0;
     prm.scale_log2 = 1.4426950408889634f / sqrtf((float)d);
     prm.inv_keep = p > 0.0f ? 1.0f / (1.0f - p) : 1.0f;
@@ -619,6 +641,15 @@ int launch_attention(const void* Q, const void* K, const void* V, void* O, int B
 }
 
 }  // namespace rov
+
+extern "C" int rov_attention_fwd_dropout_rows(const void* Q, const void* K, const void* V, void* O, int B,
+                                              int H, int Hkv, int S, int d, const int64_t strides[12],
+                                              int dtype, int causal, float p, const uint64_t* mask_rows,
+                                              uint64_t seed, uint64_t offset, int q_begin, int q_rows,
+                                              void* stream) {
+    return rov::launch_attention_rows(Q, K, V, O, B, H, Hkv, S, d, strides, dtype, causal, p, mask_rows, true,
+                                      seed, offset, q_begin, q_rows, (hipStream_t)stream);
+}
 
 extern "C" int rov_attention_fwd_dropout(const void* Q, const void* K, const void* V, void* O, int B,
                                          int H, int Hkv, int S, int d, const int64_t strides[12],

@@ -99,6 +99,36 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void mask_kernel(
     }
 }
 
+// Rows of tiles [qt0, qt0 + nqt) of every (batch, head), written compactly as
+// [B*H][nqt][T][16]: the bits are those of the full mask (call numbers come from the global word
+// index), only the destination differs.  One "segment" per (batch, head): seg_words = nqt*T*16
+// words in `out`, starting at global word seg*seg_stride + seg_first.
+template <int R, bool RAGGED>
+__global__ __launch_bounds__(kWavesPerBlock * 64) void mask_rows_kernel(
+    uint64_t* __restrict__ out, uint64_t seg_words, uint64_t chunks_per_seg, uint64_t nseg,
+    uint64_t seg_stride, uint64_t seg_first, uint64_t offset, uint32_t k0, uint32_t k1,
+    uint32_t t_minus_1, uint32_t T, uint32_t S) {
+    const uint32_t lane = threadIdx.x & 63u;
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const uint64_t stride = (uint64_t)gridDim.x * kWavesPerBlock;
+    const uint64_t nchunks = nseg * chunks_per_seg;
+    for (uint64_t c = (uint64_t)blockIdx.x * kWavesPerBlock + wave; c < nchunks; c += stride) {
+        const uint64_t seg = c / chunks_per_seg, lc = c - seg * chunks_per_seg;
+        const uint64_t gw = seg * seg_stride + seg_first + lc * 64u;   // first global word (multiple of 16)
+        const uint64_t tile = gw >> 4;
+        const uint32_t kt = (uint32_t)(tile % T), qt = (uint32_t)((tile / T) % T);
+        uint32_t vlo = 0u, vhi = 0u;
+        const uint64_t base = offset + 16u * gw;   // 64 calls per 4 words
+        if ((uint32_t)base <= 0xFFFFFFFFu - (64u * kGroupsPerChunk - 1u)) {
+            mask_chunk<R, RAGGED, false>(base, lane, k0, k1, t_minus_1, T, S, qt, kt, vlo, vhi);
+        } else {
+            mask_chunk<R, RAGGED, true>(base, lane, k0, k1, t_minus_1, T, S, qt, kt, vlo, vhi);
+        }
+        const uint64_t lw = lc * 64u + lane;
+        if (lw < seg_words) out[seg * seg_words + lw] = ((uint64_t)vhi << 32) | vlo;
+    }
+}
+
 // Narrow-threshold chunk: BITS (8 or 16) random bits per element.  One Philox call per lane now
 // serves E = 4 * 32/BITS mask words: field s of output word r decides word E*gi + 4*s + r of the
 // chunk.  A chunk is still 64 words = 4 tiles; tile t of the chunk has coordinates (qts[t], kts[t]).
@@ -265,6 +295,39 @@ int launch_mask(uint64_t seed, uint64_t offset, int B, int H, int S, float p, in
     }
 }
 
+int launch_mask_rows(uint64_t seed, uint64_t offset, int B, int H, int S, float p, int q_begin,
+                     int q_rows, uint64_t* out, hipStream_t stream, bool coresident) {
+    if (B <= 0 || H <= 0 || S <= 0 || out == nullptr || !aligned(out, 8)) return ROV_ERR_INVALID;
+    if (q_begin < 0 || q_rows <= 0 || q_begin >= S || (q_begin & 31) != 0) return ROV_ERR_INVALID;
+    uint32_t tm1;
+    if (!keep_threshold_minus_1(p, &tm1)) return ROV_ERR_INVALID;
+    const uint64_t T = ((uint64_t)S + 31u) / 32u;
+    const long double wd = (long double)B * H * T * T * 16.0L;
+    if (wd > 1099511627776.0L) return ROV_ERR_UNSUPPORTED;
+    const int64_t q_end = (int64_t)q_begin + q_rows < S ? (int64_t)q_begin + q_rows : S;
+    const uint64_t nqt = (uint64_t)((q_end - q_begin + 31) / 32);
+    const uint64_t seg_words = nqt * T * 16u;
+    const uint64_t cps = (seg_words + 63u) / 64u;
+    const uint64_t nseg = (uint64_t)B * (uint64_t)H;
+    uint64_t blocks = (nseg * cps + kWavesPerBlock - 1) / kWavesPerBlock;
+    int cap = g_rng_max_workgroups.load();
+    if (cap <= 0)
+        cap = coresident ? device_cu_count() * g_rng_overlap_wgs_per_cu.load() : device_cu_count() * 64;
+    if (blocks > (uint64_t)cap) blocks = (uint64_t)cap;
+    const dim3 grid((unsigned)blocks), block(kWavesPerBlock * 64);
+    const uint32_t k0 = (uint32_t)seed, k1 = (uint32_t)(seed >> 32);
+    const uint64_t seg_first = (uint64_t)(q_begin / 32) * T * 16u;
+    if ((S & 31) == 0) {
+        hipLaunchKernelGGL((mask_rows_kernel<10, false>), grid, block, 0, stream, out, seg_words, cps, nseg,
+                           T * T * 16u, seg_first, offset, k0, k1, tm1, (uint32_t)T, (uint32_t)S);
+    } else {
+        hipLaunchKernelGGL((mask_rows_kernel<10, true>), grid, block, 0, stream, out, seg_words, cps, nseg,
+                           T * T * 16u, seg_first, offset, k0, k1, tm1, (uint32_t)T, (uint32_t)S);
+    }
+    ROV_LAUNCH_CHECK();
+    return ROV_OK;
+}
+
 }  // namespace rov
 
 extern "C" {
@@ -273,6 +336,19 @@ uint64_t rov_mask_words(int B, int H, int S) {
     if (B <= 0 || H <= 0 || S <= 0) return 0;
     const uint64_t T = ((uint64_t)S + 31u) / 32u;
     return (uint64_t)B * (uint64_t)H * T * T * 16u;
+}
+
+uint64_t rov_mask_words_rows(int B, int H, int S, int q_begin, int q_rows) {
+    if (B <= 0 || H <= 0 || S <= 0 || q_begin < 0 || q_rows <= 0 || q_begin >= S || (q_begin & 31) != 0)
+        return 0;
+    const uint64_t T = ((uint64_t)S + 31u) / 32u;
+    const int64_t q_end = (int64_t)q_begin + q_rows < S ? (int64_t)q_begin + q_rows : S;
+    return (uint64_t)B * (uint64_t)H * (uint64_t)((q_end - q_begin + 31) / 32) * T * 16u;
+}
+
+int rov_dropout_mask_generate_rows(uint64_t seed, uint64_t offset, int B, int H, int S, float p,
+                                   int q_begin, int q_rows, uint64_t* out, void* stream) {
+    return rov::launch_mask_rows(seed, offset, B, H, S, p, q_begin, q_rows, out, (hipStream_t)stream, false);
 }
 
 uint64_t rov_mask_philox_calls(int B, int H, int S) {

@@ -38,6 +38,10 @@ void trace_end(int slot, hipStream_t st);
 // lower_only: write only what causal attention reads (tiles with key tile <= query tile).
 int launch_mask(uint64_t seed, uint64_t offset, int B, int H, int S, float p, int rounds,
                 uint64_t* out, hipStream_t stream, bool coresident = false, bool lower_only = false);
+// Tile rows [q_begin/32, ceil(min(q_begin+q_rows, S)/32)) of every (batch, head), compact
+// [B*H][nqt][T][16], same bits as the full mask.
+int launch_mask_rows(uint64_t seed, uint64_t offset, int B, int H, int S, float p, int q_begin,
+                     int q_rows, uint64_t* out, hipStream_t stream, bool coresident);
 int launch_gemm(const void* A, const void* Bm, void* C, int M, int N, int K, int dtype, int transB,
                 float scaleA, float scaleB, hipStream_t stream);
 // C = alpha * A W^T + R (R: bf16 [M,N] or nullptr); bf16 MFMA path only when R is given.
@@ -46,6 +50,13 @@ int launch_gemm_residual(const void* A, const void* Bm, void* C, const void* R, 
 int launch_attention(const void* Q, const void* K, const void* V, void* O, int B, int H, int Hkv,
                      int S, int d, const int64_t strides[12], int dtype, int causal, float p,
                      const uint64_t* mask, uint64_t seed, uint64_t offset, hipStream_t stream);
+
+// Query rows [q_begin, min(q_begin + q_rows, S)) only.  mask_is_rows: `mask` holds just the tile
+// rows of that range (as written by launch_mask_rows) instead of the full mask.
+int launch_attention_rows(const void* Q, const void* K, const void* V, void* O, int B, int H, int Hkv,
+                          int S, int d, const int64_t strides[12], int dtype, int causal, float p,
+                          const uint64_t* mask, bool mask_is_rows, uint64_t seed, uint64_t offset,
+                          int q_begin, int q_rows, hipStream_t stream);
 
 int launch_rmsnorm(const void* x, const void* weight, void* y, int64_t rows, int n, float eps,
                    hipStream_t stream);

@@ -22,6 +22,7 @@ namespace {
 
 struct Events {
     hipEvent_t fork = nullptr, join = nullptr;
+    hipEvent_t rng_done[2] = {nullptr, nullptr}, attn_done[2] = {nullptr, nullptr};   // chunked schedule
     bool ok = false;
 };
 
@@ -32,6 +33,10 @@ int get_events(Events** out) {
     if (!ev.ok) {
         ROV_HIP_TRY(hipEventCreateWithFlags(&ev.fork, hipEventDisableTiming));
         ROV_HIP_TRY(hipEventCreateWithFlags(&ev.join, hipEventDisableTiming));
+        for (int i = 0; i < 2; ++i) {
+            ROV_HIP_TRY(hipEventCreateWithFlags(&ev.rng_done[i], hipEventDisableTiming));
+            ROV_HIP_TRY(hipEventCreateWithFlags(&ev.attn_done[i], hipEventDisableTiming));
+        }
         ev.ok = true;
     }
     *out = &ev;
@@ -182,6 +187,78 @@ extern "C" int rov_layer_step(int schedule, const rov_gemm_desc* gemms, int n_ge
                                 attn->S, attn->d, attn->strides, attn->dtype, attn->causal, attn->p,
                                 need_mask ? mask : nullptr, seed, offset, ms);
     });
+}
+
+extern "C" int rov_layer_step_chunked(const rov_gemm_desc* gemms, int n_gemms, const rov_attn_desc* attn,
+                                      uint64_t seed, uint64_t offset, int q_chunk_rows,
+                                      uint64_t* mask_ring, void* main_stream, void* side_stream) {
+    using namespace rov;
+    if (attn == nullptr || n_gemms < 0 || (n_gemms > 0 && gemms == nullptr)) return ROV_ERR_INVALID;
+    for (int i = 0; i < n_gemms; ++i) {
+        const int rc = check_gemm_desc(gemms[i]);
+        if (rc != ROV_OK) return rc;
+    }
+    {
+        const int rc = check_attn_desc(*attn);
+        if (rc != ROV_OK) return rc;
+    }
+    if (!(attn->p > 0.0f)) return ROV_ERR_INVALID;                      // nothing to pipeline without dropout
+    if (q_chunk_rows <= 0 || (q_chunk_rows & 31) != 0) return ROV_ERR_INVALID;
+    if (mask_ring == nullptr || !aligned(mask_ring, 8) || main_stream == side_stream) return ROV_ERR_INVALID;
+    hipStream_t ms = (hipStream_t)main_stream, ss = (hipStream_t)side_stream;
+    const int S = attn->S, B = attn->B, H = attn->H;
+    const int nchunks = (S + q_chunk_rows - 1) / q_chunk_rows;
+    const uint64_t slot_words = rov_mask_words_rows(B, H, S, 0, q_chunk_rows);
+    uint64_t* slot[2] = {mask_ring, mask_ring + slot_words};
+
+    Events* ev = nullptr;
+    int rc = get_events(&ev);
+    if (rc != ROV_OK) return rc;
+    auto rng_chunk = [&](int c) {
+        rc = traced(ROV_TRACE_RNG, ss, [&] {
+            return launch_mask_rows(seed, offset, B, H, S, attn->p, c * q_chunk_rows, q_chunk_rows, slot[c & 1],
+                                    ss, true);
+        });
+        if (rc != ROV_OK) return rc;
+        ROV_HIP_TRY(hipEventRecord(ev->rng_done[c & 1], ss));
+        return (int)ROV_OK;
+    };
+    // the ring may still be read by work queued earlier on the main stream
+    ROV_HIP_TRY(hipEventRecord(ev->fork, ms));
+    ROV_HIP_TRY(hipStreamWaitEvent(ss, ev->fork, 0));
+    int next_gemm = 0;
+    if (n_gemms > 0) {   // first GEMM first, so that its workgroups claim the compute units
+        const rov_gemm_desc& g = gemms[0];
+        rc = t_gemm(g.A, g.Bm, g.C, nullptr, g.M, g.N, g.K, g.dtype, g.transB, g.scaleA, g.scaleB, ms);
+        if (rc != ROV_OK) return rc;
+        next_gemm = 1;
+    }
+    // the first two chunks of the mask are generated beside the GEMMs
+    for (int c = 0; c < 2 && c < nchunks; ++c) {
+        rc = rng_chunk(c);
+        if (rc != ROV_OK) return rc;
+    }
+    for (int i = next_gemm; i < n_gemms; ++i) {
+        const rov_gemm_desc& g = gemms[i];
+        rc = t_gemm(g.A, g.Bm, g.C, nullptr, g.M, g.N, g.K, g.dtype, g.transB, g.scaleA, g.scaleB, ms);
+        if (rc != ROV_OK) return rc;
+    }
+    for (int c = 0; c < nchunks; ++c) {
+        ROV_HIP_TRY(hipStreamWaitEvent(ms, ev->rng_done[c & 1], 0));
+        rc = traced(ROV_TRACE_ATTENTION, ms, [&] {
+            return launch_attention_rows(attn->Q, attn->K, attn->V, attn->O, B, H, attn->Hkv, S, attn->d,
+                                         attn->strides, attn->dtype, attn->causal, attn->p, slot[c & 1], true,
+                                         seed, offset, c * q_chunk_rows, q_chunk_rows, ms);
+        });
+        if (rc != ROV_OK) return rc;
+        if (c + 2 < nchunks) {   // chunk c+2 reuses this slot once attention has read it
+            ROV_HIP_TRY(hipEventRecord(ev->attn_done[c & 1], ms));
+            ROV_HIP_TRY(hipStreamWaitEvent(ss, ev->attn_done[c & 1], 0));
+            rc = rng_chunk(c + 2);
+            if (rc != ROV_OK) return rc;
+        }
+    }
+    return ROV_OK;
 }
 
 extern "C" size_t rov_block_workspace_bytes(const rov_block_cfg* cfg, int B, int S, int schedule) {

@@ -126,10 +126,13 @@ def main():
         return
 
     # ------------------------------------------------------------------ timed region (overlap schedule)
+    # Only the dominant kernel (the GEMM) carries timing events inside the timed region: two event
+    # records per step on the stream it runs on.  The other kernels of the step are timed the same
+    # way in a short pass of their own afterwards, so that their events do not slow the timed steps.
     for _ in range(args.warmup):
         step(rov.SCHED_OVERLAP)
     sync()
-    rov.trace_enable(True)
+    rov.trace_enable(True, [rov.TRACE_GEMM])
     rov.trace_read()
     sync()
     t0 = time.perf_counter()
@@ -140,11 +143,17 @@ def main():
     rov.trace_enable(False)
     trace = rov.trace_read()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
+    gemm_in_step = float(np.mean([ms for kind, ms in trace if kind == rov.TRACE_GEMM]))
+    rov.trace_enable(True)
+    for _ in range(50):
+        step(rov.SCHED_OVERLAP)
+    sync()
+    rov.trace_enable(False)
     by_kind = {}
-    for kind, ms in trace:
+    for kind, ms in rov.trace_read():
         by_kind.setdefault(kind, []).append(ms)
-    gemm_in_step = float(np.mean(by_kind[rov.TRACE_GEMM]))
     rng_in_step = float(np.mean(by_kind[rov.TRACE_RNG]))
+    rng_helper_in_step = float(np.mean(by_kind[rov.TRACE_RNG_HELPER])) if rov.TRACE_RNG_HELPER in by_kind else None
     attn_in_step = float(np.mean(by_kind[rov.TRACE_ATTENTION]))
 
     # ------------------------------------------------------------------ per-kernel and per-schedule numbers
@@ -180,7 +189,17 @@ def main():
         t_seq = median_ms(lambda: step(rov.SCHED_SEQUENTIAL), 5, 10, sync, ev_pair)
         t_fus = median_ms(lambda: step(rov.SCHED_FUSED), 5, 10, sync, ev_pair)
         t_ovl = median_ms(lambda: step(rov.SCHED_OVERLAP), 5, 10, sync, ev_pair)
-    hidden = 1.0 - (t_pair - t_gemm) / t_rng
+
+        def step_without_rng():   # the same GEMM and attention with the mask already in HBM
+            rov.gemm(A, Wt, C=C, stream=main_s)
+            rov.attention_fwd_dropout(Q, Kt, V, p, mask=mask, O=O, stream=main_s)
+
+        t_norng = median_ms(step_without_rng, 5, 10, sync, ev_pair)
+    # hidden fraction = 1 - (T[GEMM || RNG] - T[GEMM]) / T[RNG] on the fork / GEMM || RNG / join region;
+    # the whole-step variant charges the RNG with everything the overlap step takes longer than the
+    # same GEMM and attention run back to back without any RNG (clock and power effects included)
+    hidden_region = 1.0 - (t_pair - t_gemm) / t_rng
+    hidden = 1.0 - max(t_ovl - t_norng, 0.0) / t_rng
     gemm_slowdown = gemm_in_step / t_gemm - 1.0
 
     extras = {
@@ -194,10 +213,13 @@ def main():
         "gemm_in_overlap_step": {"ms": gemm_in_step, "tflops": gemm_flops / gemm_in_step / 1e9,
                                  "mfma_frac": gemm_flops / gemm_in_step / 1e9 / PEAK_BF16_TFLOPS,
                                  "slowdown_vs_alone": gemm_slowdown},
-        "rng_in_overlap_step": {"ms": rng_in_step, "slowdown_vs_alone": rng_in_step / t_rng - 1.0},
+        "rng_in_overlap_step": {"ms": rng_in_step, "slowdown_vs_alone": rng_in_step / t_rng - 1.0,
+                                "helper_launch_ms": rng_helper_in_step},
         "gemm_beside_rng_region_ms": t_pair,
         "rng_overlap_workgroups_per_cu": k_ovl,
-        "rng_hidden_fraction": hidden,
+        "rng_hidden_fraction": hidden_region,
+        "rng_hidden_fraction_whole_step": hidden,
+        "layer_step_without_rng_ms": t_norng,
         "attention": {"none_ms": t_attn_none, "mask_ms": t_attn_mask, "fused_ms": t_attn_fused,
                       "in_step_ms": attn_in_step,
                       "none_tflops": attn_flops / t_attn_none / 1e9, "mask_tflops": attn_flops / t_attn_mask / 1e9,

@@ -203,6 +203,10 @@ int rov_attention_fwd_dropout_rows(const void *Q, const void *K, const void *V, 
  *   ROV_SCHED_FUSED:      GEMMs -> attention(fused Philox) on main_stream.
  *   ROV_SCHED_OVERLAP:    RNG on side_stream concurrently with the GEMMs on
  *                         main_stream; attention(mask) on main_stream after both.
+ *                         If the RNG is not done when the GEMMs end, the rest of it runs
+ *                         at full speed (paper Sec. 3.3): a second RNG launch on
+ *                         main_stream shares the mask's chunks with the first through a
+ *                         work queue and exits at once when none are left.
  * mask: device buffer of rov_mask_words(B,H,S) words (unused for FUSED, may be
  * NULL there).  side_stream must differ from main_stream for OVERLAP. */
 typedef struct rov_gemm_desc {
@@ -250,12 +254,17 @@ int rov_layer_step_chunked(const rov_gemm_desc *gemms, int n_gemms, const rov_at
  * events (HOST-side wait on them only), writes up to max_records (kind,
  * milliseconds) pairs in launch order into the HOST arrays, stores the count in
  * *n_records and clears the log.  Kinds: ROV_TRACE_GEMM, _RNG, _ATTENTION,
- * _GLUE (RMSNorm / RoPE / SwiGLU).  At most 16384 records are kept between reads.
- * rov_trace_enable returns the previous setting. */
+ * _GLUE (RMSNorm / RoPE / SwiGLU), _RNG_HELPER (the second RNG launch of the overlap schedules,
+ * which finishes on main_stream, at full device width, what the small grid on side_stream has
+ * not produced by the time the GEMMs end).  At most 16384 records are kept between reads.
+ * rov_trace_enable(on): 0 switches tracing off, a negative value traces every kind, a positive
+ * value is a set of kinds (bit k set = trace kind k), so that a timed loop can carry the two
+ * events of its dominant kernel only.  Returns the previous setting. */
 #define ROV_TRACE_GEMM 0
 #define ROV_TRACE_RNG 1
 #define ROV_TRACE_ATTENTION 2
 #define ROV_TRACE_GLUE 3
+#define ROV_TRACE_RNG_HELPER 4
 int rov_trace_enable(int on);
 int rov_trace_read(int *kinds, float *ms, int max_records, int *n_records);
 

@@ -330,11 +330,20 @@ def block_forward(weights, x, y, cfg, schedule, seed, offset, mask, workspace, m
     return y
 
 
-TRACE_GEMM, TRACE_RNG, TRACE_ATTENTION, TRACE_GLUE = 0, 1, 2, 3
+TRACE_GEMM, TRACE_RNG, TRACE_ATTENTION, TRACE_GLUE, TRACE_RNG_HELPER = 0, 1, 2, 3, 4
 
 
-def trace_enable(on):
-    return int(load().rov_trace_enable(int(bool(on))))
+def trace_enable(on, kinds=None):
+    """on=False: off.  on=True: every kind, or only the kinds listed (e.g. [TRACE_GEMM])."""
+    if not on:
+        sel = 0
+    elif kinds is None:
+        sel = -1
+    else:
+        sel = 0
+        for k in kinds:
+            sel |= 1 << int(k)
+    return int(load().rov_trace_enable(sel))
 
 
 def trace_read(max_records=16384):

@@ -48,7 +48,8 @@ constexpr size_t kTraceMax = 16384;
 }  // namespace
 
 int trace_begin(int kind, hipStream_t st) {
-    if (!g_trace_on.load()) return -1;
+    const int sel = g_trace_on.load();
+    if (sel == 0 || (sel > 0 && !((sel >> kind) & 1))) return -1;
     std::lock_guard<std::mutex> lock(g_trace_mu);
     if (g_trace_used >= kTraceMax) return -1;
     if (g_trace_used == g_trace_pool.size()) {
@@ -73,7 +74,7 @@ void trace_end(int slot, hipStream_t st) {
 
 extern "C" {
 
-int rov_trace_enable(int on) { return rov::g_trace_on.exchange(on ? 1 : 0); }
+int rov_trace_enable(int on) { return rov::g_trace_on.exchange(on); }
 
 int rov_trace_read(int* kinds, float* ms, int max_records, int* n_records) {
     if (n_records == nullptr || max_records < 0 || (max_records > 0 && (kinds == nullptr || ms == nullptr)))

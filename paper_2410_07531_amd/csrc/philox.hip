@@ -26,6 +26,75 @@ namespace {
 constexpr int kWavesPerBlock = 4;
 constexpr int kGroupsPerChunk = 16;   // 16 groups x 4 words = 64 words = one 8-byte store per lane
 
+// Work queues for masks that two launches produce together (see launch_mask).  A queue slot
+// is 32 sub-queues, each with its own 128-byte line and its own contiguous share of the mask's
+// 64-word chunks: atomics on one address retire one after the other (about 10 ns each on this
+// chip, measured), so a single counter popped once per chunk would take longer than the Philox
+// work itself.  A wave pops `batch` chunks at a time from its home sub-queue and moves on to the
+// next sub-queue when that one is empty; empty sub-queues are recognised with a plain load.
+// A slot is reset by queue_reset_kernel before its launches; slots are handed out round-robin
+// so that back-to-back schedule calls never share one.
+constexpr int kQueueSlots = 64;
+constexpr int kSubQueues = 32;
+struct alignas(128) QueueCounter {
+    unsigned long long next;
+    unsigned long long pad[15];
+};
+__device__ QueueCounter g_queues[kQueueSlots][kSubQueues];
+std::atomic<unsigned> g_queue_cursor{0};
+
+__global__ void queue_reset_kernel(int slot) { g_queues[slot][threadIdx.x].next = 0ull; }
+
+// Where a wave's chunks come from: the grid striding over [0, nchunks) (slot < 0), or a queue.
+struct ChunkSource {
+    int slot;
+    uint64_t nchunks, stride;      // static mode: next = cur + stride
+    uint64_t per;                  // queue mode: chunks per sub-queue (a multiple of batch)
+    uint32_t batch, q, tried, lane;
+    uint64_t cur, end;             // queue mode: chunks [cur, end) are this wave's
+
+    __device__ __forceinline__ bool refill() {
+        while (tried < (uint32_t)kSubQueues) {
+            unsigned long long* ctr = &g_queues[slot][q].next;
+            const uint64_t lo = (uint64_t)q * per;
+            uint64_t hi = lo + per;
+            hi = hi < nchunks ? hi : nchunks;
+            if (lo < hi && __hip_atomic_load(ctr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < hi - lo) {
+                unsigned long long v = 0ull;
+                if (lane == 0u) v = atomicAdd(ctr, (unsigned long long)batch);
+                const uint32_t vl = __builtin_amdgcn_readfirstlane((uint32_t)v);
+                const uint32_t vh = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+                const uint64_t got = ((uint64_t)vh << 32) | vl;
+                if (got < hi - lo) {
+                    cur = lo + got;
+                    end = cur + batch < hi ? cur + batch : hi;
+                    return true;
+                }
+            }
+            q = q + 1u == (uint32_t)kSubQueues ? 0u : q + 1u;
+            ++tried;
+        }
+        return false;
+    }
+    __device__ __forceinline__ bool first(uint64_t wave_index) {
+        if (slot < 0) {
+            cur = wave_index;
+            return cur < nchunks;
+        }
+        q = (uint32_t)(wave_index % (uint64_t)kSubQueues);
+        tried = 0u;
+        return refill();
+    }
+    __device__ __forceinline__ bool next() {
+        if (slot < 0) {
+            cur += stride;
+            return cur < nchunks;
+        }
+        if (++cur < end) return true;
+        return refill();
+    }
+};
+
 std::atomic<int> g_rng_max_workgroups{0};
 std::atomic<int> g_rng_overlap_wgs_per_cu{2};
 
@@ -70,12 +139,17 @@ __device__ __forceinline__ void mask_chunk(uint64_t base, uint32_t lane, uint32_
 template <int R, bool RAGGED>
 __global__ __launch_bounds__(kWavesPerBlock * 64) void mask_kernel(
     uint64_t* __restrict__ out, uint64_t words, uint64_t nchunks, uint64_t offset, uint32_t k0,
-    uint32_t k1, uint32_t t_minus_1, uint32_t T, uint32_t S, int lower_only) {
+    uint32_t k1, uint32_t t_minus_1, uint32_t T, uint32_t S, int lower_only, int qslot, uint64_t qper,
+    uint32_t qbatch) {
     const uint32_t lane = threadIdx.x & 63u;
     const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const uint64_t stride = (uint64_t)gridDim.x * kWavesPerBlock;
-    for (uint64_t chunk = (uint64_t)blockIdx.x * kWavesPerBlock + wave; chunk < nchunks;
-         chunk += stride) {
+    // qslot < 0: the grid strides over the chunks; qslot >= 0: waves pull chunks from a queue that
+    // another launch of this kernel may be draining too
+    ChunkSource src;
+    src.slot = qslot; src.nchunks = nchunks; src.stride = (uint64_t)gridDim.x * kWavesPerBlock;
+    src.per = qper; src.batch = qbatch; src.lane = lane;
+    for (bool more = src.first((uint64_t)blockIdx.x * kWavesPerBlock + wave); more; more = src.next()) {
+        const uint64_t chunk = src.cur;
         uint32_t vlo = 0u, vhi = 0u;
         uint32_t qt = 0u, kt = 0u;   // tile coordinates of the chunk's first tile
         if (RAGGED || lower_only) {
@@ -107,12 +181,14 @@ template <int R, bool RAGGED>
 __global__ __launch_bounds__(kWavesPerBlock * 64) void mask_rows_kernel(
     uint64_t* __restrict__ out, uint64_t seg_words, uint64_t chunks_per_seg, uint64_t nseg,
     uint64_t seg_stride, uint64_t seg_first, uint64_t offset, uint32_t k0, uint32_t k1,
-    uint32_t t_minus_1, uint32_t T, uint32_t S) {
+    uint32_t t_minus_1, uint32_t T, uint32_t S, int qslot, uint64_t qper, uint32_t qbatch) {
     const uint32_t lane = threadIdx.x & 63u;
     const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const uint64_t stride = (uint64_t)gridDim.x * kWavesPerBlock;
-    const uint64_t nchunks = nseg * chunks_per_seg;
-    for (uint64_t c = (uint64_t)blockIdx.x * kWavesPerBlock + wave; c < nchunks; c += stride) {
+    ChunkSource src;
+    src.slot = qslot; src.nchunks = nseg * chunks_per_seg; src.stride = (uint64_t)gridDim.x * kWavesPerBlock;
+    src.per = qper; src.batch = qbatch; src.lane = lane;
+    for (bool more = src.first((uint64_t)blockIdx.x * kWavesPerBlock + wave); more; more = src.next()) {
+        const uint64_t c = src.cur;
         const uint64_t seg = c / chunks_per_seg, lc = c - seg * chunks_per_seg;
         const uint64_t gw = seg * seg_stride + seg_first + lc * 64u;   // first global word (multiple of 16)
         const uint64_t tile = gw >> 4;
@@ -217,27 +293,48 @@ __global__ __launch_bounds__(256) void raw_kernel(uint32_t* __restrict__ out, ui
     }
 }
 
+// Workgroups to launch.  Alone: enough to fill every SIMD's wave slots several times over.
+// Beside a GEMM: a persistent grid of a few workgroups per compute unit, so that the GEMM's
+// workgroup (most of the registers, most of the LDS) always still fits.  Helper: a persistent
+// grid that fills the device once (8 waves per SIMD) and drains what the queue still holds.
+// Queue geometry for a mask of nchunks chunks: batch size and chunks per sub-queue.  Batches of
+// up to 8 chunks keep the atomic rate far below what one address sustains; small masks get
+// smaller batches so that every compute unit still sees several of them.
+void queue_geometry(uint64_t nchunks, uint64_t* per, uint32_t* batch) {
+    uint64_t b = nchunks / ((uint64_t)kSubQueues * 128u);
+    b = b < 1u ? 1u : (b > 8u ? 8u : b);
+    uint64_t p = (nchunks + kSubQueues - 1) / kSubQueues;
+    p = (p + b - 1) / b * b;
+    *per = p;
+    *batch = (uint32_t)b;
+}
+
+int mask_grid_cap(int grid_mode) {
+    const int cap = g_rng_max_workgroups.load();
+    if (cap > 0) return cap;
+    if (grid_mode == MASK_GRID_BESIDE) return device_cu_count() * g_rng_overlap_wgs_per_cu.load();
+    if (grid_mode == MASK_GRID_HELPER) return device_cu_count() * 8;
+    return device_cu_count() * 64;
+}
+
 template <int R>
 int launch_mask_r(uint64_t* out, uint64_t words, uint64_t offset, uint32_t k0, uint32_t k1,
-                  uint32_t t_minus_1, int S, bool coresident, bool lower_only, hipStream_t stream) {
+                  uint32_t t_minus_1, int S, int grid_mode, int qslot, bool lower_only, hipStream_t stream) {
     const uint32_t T = (uint32_t)(((uint64_t)S + 31u) / 32u);
     const uint64_t nchunks = (words + 63u) / 64u;
     uint64_t blocks = (nchunks + kWavesPerBlock - 1) / kWavesPerBlock;
-    int cap = g_rng_max_workgroups.load();
-    if (cap <= 0) {
-        // alone: enough workgroups to fill every SIMD's wave slots several times over;
-        // beside a GEMM: a persistent grid of a few workgroups per compute unit, so that the
-        // GEMM's workgroup (most of the registers, most of the LDS) always still fits
-        cap = coresident ? device_cu_count() * g_rng_overlap_wgs_per_cu.load() : device_cu_count() * 64;
-    }
+    const int cap = mask_grid_cap(grid_mode);
     if (blocks > (uint64_t)cap) blocks = (uint64_t)cap;
     const dim3 grid((unsigned)blocks), block(kWavesPerBlock * 64);
+    uint64_t qper = 0;
+    uint32_t qbatch = 1;
+    queue_geometry(nchunks, &qper, &qbatch);
     if ((S & 31) == 0) {
         hipLaunchKernelGGL((mask_kernel<R, false>), grid, block, 0, stream, out, words, nchunks,
-                           offset, k0, k1, t_minus_1, T, (uint32_t)S, (int)lower_only);
+                           offset, k0, k1, t_minus_1, T, (uint32_t)S, (int)lower_only, qslot, qper, qbatch);
     } else {
         hipLaunchKernelGGL((mask_kernel<R, true>), grid, block, 0, stream, out, words, nchunks,
-                           offset, k0, k1, t_minus_1, T, (uint32_t)S, (int)lower_only);
+                           offset, k0, k1, t_minus_1, T, (uint32_t)S, (int)lower_only, qslot, qper, qbatch);
     }
     ROV_LAUNCH_CHECK();
     return ROV_OK;
@@ -274,8 +371,17 @@ bool keep_threshold_minus_1(float p, uint32_t* t_minus_1) {
     return true;
 }
 
+int mask_queue_acquire(hipStream_t stream, int* slot) {
+    const int s = (int)(g_queue_cursor.fetch_add(1u) % (unsigned)kQueueSlots);
+    hipLaunchKernelGGL(queue_reset_kernel, dim3(1), dim3(kSubQueues), 0, stream, s);
+    ROV_LAUNCH_CHECK();
+    *slot = s;
+    return ROV_OK;
+}
+
 int launch_mask(uint64_t seed, uint64_t offset, int B, int H, int S, float p, int rounds,
-                uint64_t* out, hipStream_t stream, bool coresident, bool lower_only) {
+                uint64_t* out, hipStream_t stream, int grid_mode, int qslot, bool lower_only) {
+    if (qslot >= kQueueSlots) return ROV_ERR_INVALID;
     if (B <= 0 || H <= 0 || S <= 0 || out == nullptr) return ROV_ERR_INVALID;
     if (!aligned(out, 8)) return ROV_ERR_INVALID;
     uint32_t tm1;
@@ -287,16 +393,17 @@ int launch_mask(uint64_t seed, uint64_t offset, int B, int H, int S, float p, in
     const uint64_t words = (uint64_t)B * (uint64_t)H * T * T * 16u;
     const uint32_t k0 = (uint32_t)seed, k1 = (uint32_t)(seed >> 32);
     switch (rounds) {
-        case 10: return launch_mask_r<10>(out, words, offset, k0, k1, tm1, S, coresident, lower_only, stream);
-        case 7: return launch_mask_r<7>(out, words, offset, k0, k1, tm1, S, coresident, lower_only, stream);
-        case 5: return launch_mask_r<5>(out, words, offset, k0, k1, tm1, S, coresident, lower_only, stream);
-        case 3: return launch_mask_r<3>(out, words, offset, k0, k1, tm1, S, coresident, lower_only, stream);
+        case 10: return launch_mask_r<10>(out, words, offset, k0, k1, tm1, S, grid_mode, qslot, lower_only, stream);
+        case 7: return launch_mask_r<7>(out, words, offset, k0, k1, tm1, S, grid_mode, qslot, lower_only, stream);
+        case 5: return launch_mask_r<5>(out, words, offset, k0, k1, tm1, S, grid_mode, qslot, lower_only, stream);
+        case 3: return launch_mask_r<3>(out, words, offset, k0, k1, tm1, S, grid_mode, qslot, lower_only, stream);
         default: return ROV_ERR_INVALID;
     }
 }
 
 int launch_mask_rows(uint64_t seed, uint64_t offset, int B, int H, int S, float p, int q_begin,
-                     int q_rows, uint64_t* out, hipStream_t stream, bool coresident) {
+                     int q_rows, uint64_t* out, hipStream_t stream, int grid_mode, int qslot) {
+    if (qslot >= kQueueSlots) return ROV_ERR_INVALID;
     if (B <= 0 || H <= 0 || S <= 0 || out == nullptr || !aligned(out, 8)) return ROV_ERR_INVALID;
     if (q_begin < 0 || q_rows <= 0 || q_begin >= S || (q_begin & 31) != 0) return ROV_ERR_INVALID;
     uint32_t tm1;
@@ -310,19 +417,20 @@ int launch_mask_rows(uint64_t seed, uint64_t offset, int B, int H, int S, float 
     const uint64_t cps = (seg_words + 63u) / 64u;
     const uint64_t nseg = (uint64_t)B * (uint64_t)H;
     uint64_t blocks = (nseg * cps + kWavesPerBlock - 1) / kWavesPerBlock;
-    int cap = g_rng_max_workgroups.load();
-    if (cap <= 0)
-        cap = coresident ? device_cu_count() * g_rng_overlap_wgs_per_cu.load() : device_cu_count() * 64;
+    const int cap = mask_grid_cap(grid_mode);
     if (blocks > (uint64_t)cap) blocks = (uint64_t)cap;
     const dim3 grid((unsigned)blocks), block(kWavesPerBlock * 64);
     const uint32_t k0 = (uint32_t)seed, k1 = (uint32_t)(seed >> 32);
+    uint64_t qper = 0;
+    uint32_t qbatch = 1;
+    queue_geometry(nseg * cps, &qper, &qbatch);
     const uint64_t seg_first = (uint64_t)(q_begin / 32) * T * 16u;
     if ((S & 31) == 0) {
         hipLaunchKernelGGL((mask_rows_kernel<10, false>), grid, block, 0, stream, out, seg_words, cps, nseg,
-                           T * T * 16u, seg_first, offset, k0, k1, tm1, (uint32_t)T, (uint32_t)S);
+                           T * T * 16u, seg_first, offset, k0, k1, tm1, (uint32_t)T, (uint32_t)S, qslot, qper, qbatch);
     } else {
         hipLaunchKernelGGL((mask_rows_kernel<10, true>), grid, block, 0, stream, out, seg_words, cps, nseg,
-                           T * T * 16u, seg_first, offset, k0, k1, tm1, (uint32_t)T, (uint32_t)S);
+                           T * T * 16u, seg_first, offset, k0, k1, tm1, (uint32_t)T, (uint32_t)S, qslot, qper, qbatch);
     }
     ROV_LAUNCH_CHECK();
     return ROV_OK;
@@ -348,7 +456,8 @@ uint64_t rov_mask_words_rows(int B, int H, int S, int q_begin, int q_rows) {
 
 int rov_dropout_mask_generate_rows(uint64_t seed, uint64_t offset, int B, int H, int S, float p,
                                    int q_begin, int q_rows, uint64_t* out, void* stream) {
-    return rov::launch_mask_rows(seed, offset, B, H, S, p, q_begin, q_rows, out, (hipStream_t)stream, false);
+    return rov::launch_mask_rows(seed, offset, B, H, S, p, q_begin, q_rows, out, (hipStream_t)stream,
+                                 rov::MASK_GRID_FULL, -1);
 }
 
 uint64_t rov_mask_philox_calls(int B, int H, int S) {
@@ -386,7 +495,7 @@ int rov_dropout_mask_generate(uint64_t seed, uint64_t offset, int B, int H, int 
 
 int rov_dropout_mask_generate_causal(uint64_t seed, uint64_t offset, int B, int H, int S, float p,
                                      uint64_t* out, void* stream) {
-    return rov::launch_mask(seed, offset, B, H, S, p, 10, out, (hipStream_t)stream, false, true);
+    return rov::launch_mask(seed, offset, B, H, S, p, 10, out, (hipStream_t)stream, rov::MASK_GRID_FULL, -1, true);
 }
 
 int rov_dropout_mask_generate_rounds(uint64_t seed, uint64_t offset, int B, int H, int S, float p,

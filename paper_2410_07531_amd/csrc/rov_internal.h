@@ -34,14 +34,23 @@ int trace_begin(int kind, hipStream_t st);
 void trace_end(int slot, hipStream_t st);
 
 // Launchers used across translation units (all asynchronous on `stream`).
-// coresident: launch a small persistent grid meant to run beside a GEMM (overlap schedule).
+// Grid of the RNG kernel: alone on the device; a small persistent grid meant to run beside a
+// GEMM (overlap schedules); or a device-filling persistent grid that helps such a small grid
+// finish, launched where the GEMMs end (the paper's "remaining RNG operations continue at full
+// speed once GEMM completes", Sec. 3.3).  The last two share the mask through a work queue:
+// qslot >= 0 (from mask_queue_acquire, which resets the slot on the given stream; it must be
+// ordered before both launches) makes the waves pull 64-word chunks from that queue, so each
+// chunk is produced by whichever launch gets to it first.  qslot < 0: static striding.
+enum { MASK_GRID_FULL = 0, MASK_GRID_BESIDE = 1, MASK_GRID_HELPER = 2 };
+int mask_queue_acquire(hipStream_t stream, int* slot);
 // lower_only: write only what causal attention reads (tiles with key tile <= query tile).
 int launch_mask(uint64_t seed, uint64_t offset, int B, int H, int S, float p, int rounds,
-                uint64_t* out, hipStream_t stream, bool coresident = false, bool lower_only = false);
+                uint64_t* out, hipStream_t stream, int grid_mode = MASK_GRID_FULL, int qslot = -1,
+                bool lower_only = false);
 // Tile rows [q_begin/32, ceil(min(q_begin+q_rows, S)/32)) of every (batch, head), compact
 // [B*H][nqt][T][16], same bits as the full mask.
 int launch_mask_rows(uint64_t seed, uint64_t offset, int B, int H, int S, float p, int q_begin,
-                     int q_rows, uint64_t* out, hipStream_t stream, bool coresident);
+                     int q_rows, uint64_t* out, hipStream_t stream, int grid_mode, int qslot);
 int launch_gemm(const void* A, const void* Bm, void* C, int M, int N, int K, int dtype, int transB,
                 float scaleA, float scaleB, hipStream_t stream);
 // C = alpha * A W^T + R (R: bf16 [M,N] or nullptr); bf16 MFMA path only when R is given.

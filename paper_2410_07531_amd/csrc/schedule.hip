@@ -83,11 +83,24 @@ int t_gemm(const void* A, const void* Bm, void* C, const void* R, int M, int N, 
 }
 
 int t_mask(uint64_t seed, uint64_t offset, int B, int H, int S, float p, uint64_t* out, hipStream_t st,
-           bool coresident, bool lower_only) {
-    return traced(ROV_TRACE_RNG, st, [&] {
-        return launch_mask(seed, offset, B, H, S, p, 10, out, st, coresident, lower_only);
+           int grid_mode, int qslot, bool lower_only) {
+    return traced(grid_mode == MASK_GRID_HELPER ? ROV_TRACE_RNG_HELPER : ROV_TRACE_RNG, st, [&] {
+        return launch_mask(seed, offset, B, H, S, p, 10, out, st, grid_mode, qslot, lower_only);
     });
 }
+
+// Will the small RNG grid finish while the GEMMs beside it run?  Then the plain launch is enough;
+// otherwise the mask goes through a work queue and a helper launch finishes it after the GEMMs.
+// The rates are this chip's measured ones, rounded against the RNG: about 1.0 PFLOP/s for the
+// bf16 / fp8 GEMM (30 TFLOP/s for the fp32 kernel) and 0.2 T Philox calls/s for the two-workgroups-
+// per-compute-unit grid beside a GEMM.  A wrong guess costs time, never correctness.
+bool rng_fits_beside(double gemm_flop, bool fp32, double rng_calls) {
+    const double t_gemm = gemm_flop / (fp32 ? 30e12 : 1.0e15);
+    const double t_rng = rng_calls / 0.2e12;
+    return t_rng < 0.8 * t_gemm;
+}
+
+double gemm_flop(int M, int N, int K) { return 2.0 * (double)M * (double)N * (double)K; }
 
 size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
@@ -140,9 +153,21 @@ extern "C" int rov_layer_step(int schedule, const rov_gemm_desc* gemms, int n_ge
     hipStream_t ms = (hipStream_t)main_stream, ss = (hipStream_t)side_stream;
 
     Events* ev = nullptr;
+    int qslot = -1;
     if (schedule == ROV_SCHED_OVERLAP && need_mask) {
-        const int rc = get_events(&ev);
+        int rc = get_events(&ev);
         if (rc != ROV_OK) return rc;
+        double flop = 0.0;
+        bool fp32 = false;
+        for (int i = 0; i < n_gemms; ++i) {
+            flop += gemm_flop(gemms[i].M, gemms[i].N, gemms[i].K);
+            fp32 = fp32 || gemms[i].dtype == ROV_F32;
+        }
+        const double calls = (double)rov_mask_philox_calls(attn->B, attn->H, attn->S) * (attn->causal ? 0.5 : 1.0);
+        if (!rng_fits_beside(flop, fp32, calls)) {
+            rc = mask_queue_acquire(ms, &qslot);   // reset here: ordered before both RNG launches
+            if (rc != ROV_OK) return rc;
+        }
         // the mask buffer may still be read by work already queued on the main stream
         ROV_HIP_TRY(hipEventRecord(ev->fork, ms));
         ROV_HIP_TRY(hipStreamWaitEvent(ss, ev->fork, 0));
@@ -165,7 +190,8 @@ extern "C" int rov_layer_step(int schedule, const rov_gemm_desc* gemms, int n_ge
             rc = t_gemm(g.A, g.Bm, g.C, nullptr, g.M, g.N, g.K, g.dtype, g.transB, g.scaleA, g.scaleB, ms);
             if (rc != ROV_OK) return rc;
         }
-        rc = t_mask(seed, offset, attn->B, attn->H, attn->S, attn->p, mask, ss, true, attn->causal != 0);
+        rc = t_mask(seed, offset, attn->B, attn->H, attn->S, attn->p, mask, ss, MASK_GRID_BESIDE, qslot,
+                    attn->causal != 0);
         if (rc != ROV_OK) return rc;
         ROV_HIP_TRY(hipEventRecord(ev->join, ss));
         for (int i = 1; i < n_gemms; ++i) {
@@ -173,12 +199,20 @@ extern "C" int rov_layer_step(int schedule, const rov_gemm_desc* gemms, int n_ge
             rc = t_gemm(g.A, g.Bm, g.C, nullptr, g.M, g.N, g.K, g.dtype, g.transB, g.scaleA, g.scaleB, ms);
             if (rc != ROV_OK) return rc;
         }
+        // whatever the small grid has not produced when the GEMMs end is finished at full speed
+        // (paper Sec. 3.3); waves of this launch leave at once if the queue is already empty
+        if (qslot >= 0) {
+            rc = t_mask(seed, offset, attn->B, attn->H, attn->S, attn->p, mask, ms, MASK_GRID_HELPER, qslot,
+                        attn->causal != 0);
+            if (rc != ROV_OK) return rc;
+        }
         ROV_HIP_TRY(hipStreamWaitEvent(ms, ev->join, 0));
     } else {
         rc = run_gemms(ms);
         if (rc != ROV_OK) return rc;
         if (need_mask) {
-            rc = t_mask(seed, offset, attn->B, attn->H, attn->S, attn->p, mask, ms, false, attn->causal != 0);
+            rc = t_mask(seed, offset, attn->B, attn->H, attn->S, attn->p, mask, ms, MASK_GRID_FULL, -1,
+                        attn->causal != 0);
             if (rc != ROV_OK) return rc;
         }
     }
@@ -214,15 +248,37 @@ extern "C" int rov_layer_step_chunked(const rov_gemm_desc* gemms, int n_gemms, c
     Events* ev = nullptr;
     int rc = get_events(&ev);
     if (rc != ROV_OK) return rc;
-    auto rng_chunk = [&](int c) {
+    int qslot[2] = {-1, -1};   // work queue of the chunk that currently owns each ring slot
+    auto rng_chunk = [&](int c) {   // small grid on the side stream
         rc = traced(ROV_TRACE_RNG, ss, [&] {
             return launch_mask_rows(seed, offset, B, H, S, attn->p, c * q_chunk_rows, q_chunk_rows, slot[c & 1],
-                                    ss, true);
+                                    ss, MASK_GRID_BESIDE, qslot[c & 1]);
         });
         if (rc != ROV_OK) return rc;
         ROV_HIP_TRY(hipEventRecord(ev->rng_done[c & 1], ss));
         return (int)ROV_OK;
     };
+    auto rng_help = [&](int c) {    // device-filling grid on the main stream: finishes the chunk
+        if (qslot[c & 1] < 0) return (int)ROV_OK;
+        return traced(ROV_TRACE_RNG_HELPER, ms, [&] {
+            return launch_mask_rows(seed, offset, B, H, S, attn->p, c * q_chunk_rows, q_chunk_rows, slot[c & 1],
+                                    ms, MASK_GRID_HELPER, qslot[c & 1]);
+        });
+    };
+    {   // chunks 0 and 1 run beside the GEMMs; later chunks run beside attention and always get help
+        double flop = 0.0;
+        bool fp32 = false;
+        for (int i = 0; i < n_gemms; ++i) {
+            flop += gemm_flop(gemms[i].M, gemms[i].N, gemms[i].K);
+            fp32 = fp32 || gemms[i].dtype == ROV_F32;
+        }
+        const double calls = 16.0 * (double)slot_words * (nchunks > 1 ? 2.0 : 1.0);
+        if (!rng_fits_beside(flop, fp32, calls))
+            for (int c = 0; c < 2 && c < nchunks; ++c) {
+                rc = mask_queue_acquire(ms, &qslot[c]);
+                if (rc != ROV_OK) return rc;
+            }
+    }
     // the ring may still be read by work queued earlier on the main stream
     ROV_HIP_TRY(hipEventRecord(ev->fork, ms));
     ROV_HIP_TRY(hipStreamWaitEvent(ss, ev->fork, 0));
@@ -244,6 +300,8 @@ extern "C" int rov_layer_step_chunked(const rov_gemm_desc* gemms, int n_gemms, c
         if (rc != ROV_OK) return rc;
     }
     for (int c = 0; c < nchunks; ++c) {
+        rc = rng_help(c);
+        if (rc != ROV_OK) return rc;
         ROV_HIP_TRY(hipStreamWaitEvent(ms, ev->rng_done[c & 1], 0));
         rc = traced(ROV_TRACE_ATTENTION, ms, [&] {
             return launch_attention_rows(attn->Q, attn->K, attn->V, attn->O, B, H, attn->Hkv, S, attn->d,
@@ -252,6 +310,8 @@ extern "C" int rov_layer_step_chunked(const rov_gemm_desc* gemms, int n_gemms, c
         });
         if (rc != ROV_OK) return rc;
         if (c + 2 < nchunks) {   // chunk c+2 reuses this slot once attention has read it
+            rc = mask_queue_acquire(ms, &qslot[c & 1]);
+            if (rc != ROV_OK) return rc;
             ROV_HIP_TRY(hipEventRecord(ev->attn_done[c & 1], ms));
             ROV_HIP_TRY(hipStreamWaitEvent(ss, ev->attn_done[c & 1], 0));
             rc = rng_chunk(c + 2);
@@ -323,7 +383,12 @@ extern "C" int rov_block_forward(const rov_block_weights* w, const void* x, void
     } while (0)
 
     // this block's own mask, if nobody produced it yet
+    int qslot = -1;
+    const double mask_calls = (double)rov_mask_philox_calls(B, H, S) * (cfg->causal ? 0.5 : 1.0);
     if (use_mask && !mask_ready && overlap) {
+        if (!rng_fits_beside(gemm_flop((int)((int64_t)B * S), (cfg->H + 2 * cfg->Hkv) * cfg->d, cfg->hidden), false,
+                             mask_calls))
+            ROV_STEP(mask_queue_acquire(ms, &qslot));
         ROV_HIP_TRY(hipEventRecord(ev->fork, ms));
         ROV_HIP_TRY(hipStreamWaitEvent(ss, ev->fork, 0));
     }
@@ -331,10 +396,12 @@ extern "C" int rov_block_forward(const rov_block_weights* w, const void* x, void
     ROV_STEP(t_gemm(h, w->wqkv, qkv, nullptr, (int)T, qkv_n, hidden, ROV_BF16, 1, 1.0f, 1.0f, ms));
     if (use_mask && !mask_ready) {
         if (overlap) {
-            ROV_STEP(t_mask(seed, offset, B, H, S, cfg->p, mask, ss, true, cfg->causal != 0));
+            ROV_STEP(t_mask(seed, offset, B, H, S, cfg->p, mask, ss, MASK_GRID_BESIDE, qslot, cfg->causal != 0));
             ROV_HIP_TRY(hipEventRecord(ev->join, ss));
+            if (qslot >= 0)
+                ROV_STEP(t_mask(seed, offset, B, H, S, cfg->p, mask, ms, MASK_GRID_HELPER, qslot, cfg->causal != 0));
         } else {
-            ROV_STEP(t_mask(seed, offset, B, H, S, cfg->p, mask, ms, false, cfg->causal != 0));
+            ROV_STEP(t_mask(seed, offset, B, H, S, cfg->p, mask, ms, MASK_GRID_FULL, -1, cfg->causal != 0));
         }
     }
     ROV_STEP(traced(ROV_TRACE_GLUE, ms, [&] {   // q heads then k heads
@@ -356,14 +423,18 @@ extern "C" int rov_block_forward(const rov_block_weights* w, const void* x, void
 
     // the next layer's mask runs beside this block's remaining GEMMs (it would compete with
     // attention for VALU issue, so it starts once attention is done)
+    int qslot_next = -1;
     if (overlap && next_mask != nullptr) {
+        const double rest = gemm_flop((int)T, hidden, H * d) + 2.0 * gemm_flop((int)T, ffn, hidden) +
+                            gemm_flop((int)T, hidden, ffn);
+        if (!rng_fits_beside(rest, false, mask_calls)) ROV_STEP(mask_queue_acquire(ms, &qslot_next));
         ROV_HIP_TRY(hipEventRecord(ev->fork, ms));
         ROV_HIP_TRY(hipStreamWaitEvent(ss, ev->fork, 0));
     }
     ROV_STEP(t_gemm(att, w->wo, x2, x, (int)T, hidden, H * d, ROV_BF16, 1, 1.0f, 1.0f, ms));
     if (overlap && next_mask != nullptr) {
-        ROV_STEP(t_mask(seed, offset + rov_mask_philox_calls(B, H, S), B, H, S, cfg->p, next_mask, ss, true,
-                        cfg->causal != 0));
+        ROV_STEP(t_mask(seed, offset + rov_mask_philox_calls(B, H, S), B, H, S, cfg->p, next_mask, ss,
+                        MASK_GRID_BESIDE, qslot_next, cfg->causal != 0));
         ROV_HIP_TRY(hipEventRecord(ev->join, ss));
     }
     ROV_STEP(traced(ROV_TRACE_GLUE, ms, [&] { return launch_rmsnorm(x2, w->norm2, h, T, hidden, cfg->eps, ms); }));
@@ -371,7 +442,13 @@ extern "C" int rov_block_forward(const rov_block_weights* w, const void* x, void
     ROV_STEP(t_gemm(h, w->wu, u, nullptr, (int)T, ffn, hidden, ROV_BF16, 1, 1.0f, 1.0f, ms));
     ROV_STEP(traced(ROV_TRACE_GLUE, ms, [&] { return launch_swiglu(g, u, g, T * ffn, ms); }));
     ROV_STEP(t_gemm(g, w->wd, y, x2, (int)T, hidden, ffn, ROV_BF16, 1, 1.0f, 1.0f, ms));
-    if (overlap && next_mask != nullptr) ROV_HIP_TRY(hipStreamWaitEvent(ms, ev->join, 0));
+    if (overlap && next_mask != nullptr) {
+        // what is left of the next mask when the last GEMM ends is finished at full speed
+        if (qslot_next >= 0)
+            ROV_STEP(t_mask(seed, offset + rov_mask_philox_calls(B, H, S), B, H, S, cfg->p, next_mask, ms,
+                            MASK_GRID_HELPER, qslot_next, cfg->causal != 0));
+        ROV_HIP_TRY(hipStreamWaitEvent(ms, ev->join, 0));
+    }
 #undef ROV_STEP
     return ROV_OK;
 }

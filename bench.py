@@ -231,11 +231,25 @@ def main():
         "layer_speedup_overlap_vs_fused": t_fus / t_ovl,
     }
 
+    # ------------------------------------------------------------------ limiter model beside the measurements
+    from paper_2410_07531_amd import limiter_model as LM
+    lm = LM.layer_step(LM.MI355X, B, H, S, d, [(M, N, K)])
+    extras["limiter_model_layer_step_ms"] = {
+        "gemm": lm["gemm"] * 1e3, "rng": lm["rng"] * 1e3, "attention_mask": lm["attention_mask"] * 1e3,
+        "attention_fused": lm["attention_fused"] * 1e3, "sequential": lm["baseline"] * 1e3,
+        "fused": lm["fusion"] * 1e3, "overlap": lm["overlap"] * 1e3, "hidden_fraction": lm["hidden_fraction"]}
+
     # ------------------------------------------------------------------ transformer block (configs[4])
     if not args.no_block:
         del Q, Kt, V, O, A, Wt, C
         torch.cuda.empty_cache()
         extras["block_llama3_8b_s16k"] = bench_block(torch, rov, wl, main_s, side_s, sync, ev_pair)
+        c5 = wl.CONFIGS[4]
+        for causal in (False, True):
+            bm = LM.block(LM.MI355X, c5["B"], c5["S"], c5["H"], c5["Hkv"], c5["d"], c5["hidden"], c5["ffn"], causal)
+            extras["block_llama3_8b_s16k"]["causal" if causal else "noncausal"]["limiter_model_ms"] = {
+                "sequential": bm["baseline"] * 1e3, "fused": bm["fusion"] * 1e3, "overlap": bm["overlap"] * 1e3,
+                "rng_exposed": bm["rng_exposed"] * 1e3}
 
     # ------------------------------------------------------------------ CPU oracle on a bounded sample
     cpu = None

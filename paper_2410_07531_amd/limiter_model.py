@@ -16,8 +16,8 @@ Two things differ from the paper's GH100 model and are stated where they enter:
     so its concurrent rate is a measured fraction of its stand-alone rate, and what is left when
     the GEMMs end runs at the stand-alone rate (the paper's rule, Sec. 3.3).
 """
-from dataclasses import dataclass, field
-from typing import Dict, List, Sequence, Tuple
+from dataclasses import dataclass
+from typing import Dict, Sequence, Tuple
 
 
 @dataclass(frozen=True)
@@ -47,7 +47,6 @@ class Chip:
     # Memory
     hbm_bytes_per_s: float = 8.0e12
     l2_to_cu_bytes_per_s: float = 13e12      # all CUs streaming GEMM operand slabs (measured inside the GEMM)
-    lds_bytes_per_clk_per_cu: float = 128.0
     # Interference, measured on the layer step: GEMM beside the small RNG grid, and the small grid's
     # rate relative to the stand-alone RNG kernel (paper Sec. 6.2 reports 4 % and 50 % on GH100).
     gemm_slowdown_beside_rng: float = 0.03

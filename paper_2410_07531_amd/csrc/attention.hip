@@ -311,21 +311,24 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(const AttnParams p) 
         const bool diag = p.causal && (kv0 + BKV - 1 > q0);   // some key of the tile may exceed a query
 #pragma unroll
         for (int n = 0; n < NQ; ++n) {
+            // the maximum is taken on the raw scores (the scale is positive) and the scale is folded
+            // into the exponent's multiply-add below: one VALU op less per element
             float mx = -INFINITY;
+            if (tail || diag) {   // wave-uniform: only the tiles on the diagonal and the last one
+#pragma unroll
+                for (int t = 0; t < 2; ++t)
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) {
+                        const int key = kv0 + 32 * t + 8 * (e >> 2) + 4 * half + (e & 3);
+                        const bool ok = key < S && (!p.causal || key <= qrow[n]);
+                        s[t][n][e] = ok ? s[t][n][e] : -INFINITY;
+                    }
+            }
 #pragma unroll
             for (int t = 0; t < 2; ++t)
 #pragma unroll
-                for (int e = 0; e < 16; ++e) {
-                    float v = s[t][n][e] * p.scale_log2;
-                    if (tail || diag) {
-                        const int key = kv0 + 32 * t + 8 * (e >> 2) + 4 * half + (e & 3);
-                        const bool ok = key < S && (!p.causal || key <= qrow[n]);
-                        v = ok ? v : -INFINITY;
-                    }
-                    s[t][n][e] = v;
-                    mx = fmaxf(mx, v);
-                }
-            mx = fmaxf(mx, __shfl_xor(mx, 32));
+                for (int e = 0; e < 16; ++e) mx = fmaxf(mx, s[t][n][e]);
+            mx = fmaxf(mx, __shfl_xor(mx, 32)) * p.scale_log2;
             const float m_new = fmaxf(m_run[n], mx);
             const float m_safe = m_new == -INFINITY ? 0.0f : m_new;
             const float alpha = fast_exp2(m_run[n] - m_safe);
@@ -337,7 +340,7 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(const AttnParams p) 
                 kt = kt < Tt ? kt : Tt - 1;        // a key tile past S: its scores are -inf already
 #pragma unroll
                 for (int e = 0; e < 16; ++e) {
-                    const float pe = fast_exp2(s[t][n][e] - m_safe);
+                    const float pe = fast_exp2(__builtin_fmaf(s[t][n][e], p.scale_log2, -m_safe));
                     sum += pe;   // the normaliser counts dropped entries too
                     s[t][n][e] = pe;
                 }
@@ -368,10 +371,14 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(const AttnParams p) 
                 }
             }
             l_run[n] = l_run[n] * alpha + sum;
+            // the running maximum settles after the first tiles; the rescale of the 64 output
+            // accumulators is skipped while no lane of the wave has a new maximum (alpha == 1)
+            if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0ull) {
 #pragma unroll
-            for (int t = 0; t < DVT; ++t)
+                for (int t = 0; t < DVT; ++t)
 #pragma unroll
-                for (int e = 0; e < 16; ++e) o[t][n][e] *= alpha;
+                    for (int e = 0; e < 16; ++e) o[t][n][e] *= alpha;
+            }
             // k-step u = 2*t + v of the second product takes registers 8*v .. 8*v+7 of tile t
 #pragma unroll
             for (int u = 0; u < 4; ++u) {

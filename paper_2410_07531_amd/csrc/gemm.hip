@@ -26,10 +26,10 @@
 // The register budget (140 VGPRs + 256 AGPRs of 512) leaves room for RNG
 // waves on every SIMD (the paper's carve-out, Sec. 6.2).
 //
-// fp8 (OCP e4m3) uses the same kernel: a ring row is 64 bytes either way (32
-// bf16 or 64 fp8 values), and each 16-byte fragment feeds two MFMA 16x16x32
-// fp8 instructions (which 8 of the 16 k-values a lane group supplies is the
-// same for both operands, so the sum is unchanged).
+// fp8 (OCP e4m3) has a kernel of its own with the same ring, loads and tile
+// order: a ring row is 64 bytes either way (32 bf16 or 64 fp8 values), and the
+// fp8 kernel multiplies with the double-rate MFMA 32x32x64 of the f8f6f4 family
+// (a lane's operand is half a ring row), so it does twice the flop per byte.
 //
 // Everything else (fp32, [K,N] weights, K not a multiple of the tile depth)
 // takes a small LDS-tiled VALU kernel that is correct for any shape.
@@ -144,6 +144,7 @@ constexpr int kLdsBytes = kSlots * kSlotBytes;      // 128 KiB
 typedef __attribute__((address_space(3))) void* lptr_t;
 typedef int i32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef int i32x8 __attribute__((ext_vector_type(8)));
 
 // 16-byte chunk swizzle of a 64-byte LDS row (4 chunks).  A 64-lane ds_read_b128 is served 16
 // lanes at a time over 64 banks of 4 bytes, and the lanes that go together are not consecutive:
@@ -172,8 +173,7 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
     return *reinterpret_cast<uint32_t*>(&h);
 }
 
-// ESZ: bytes per input element (2 = bf16, 1 = fp8 e4m3).  Output and residual are bf16.
-template <int ESZ>
+// bf16 inputs; output and residual are bf16.
 __global__ __launch_bounds__(256, 1) void gemm_tn_kernel(const char* __restrict__ A,
                                                          const char* __restrict__ Wt,
                                                          uint16_t* __restrict__ C,
@@ -204,6 +204,7 @@ __global__ __launch_bounds__(256, 1) void gemm_tn_kernel(const char* __restrict_
     const int tn = in_band / band_rows;
     const int m0 = tm * BM, n0 = tn * BN;
 
+    constexpr int ESZ = 2;
     f32x4 acc[8][8];   // [weight-row block j (16 rows)][activation-row block i (16 rows)]
 #pragma unroll
     for (int j = 0; j < 8; ++j)
@@ -212,7 +213,7 @@ __global__ __launch_bounds__(256, 1) void gemm_tn_kernel(const char* __restrict_
 #pragma unroll
             for (int e = 0; e < 4; ++e) acc[j][i][e] = 0.0f;
 
-    // fragment of MFMA 16x16x32: lane holds row lane%16, k-chunk (8 bf16 / 16 fp8) lane/16 of the step
+    // fragment of MFMA 16x16x32: lane holds row lane%16, k-chunk (8 bf16) lane/16 of the step
     const int frow = lane & 15;
     const int fchunk = lane >> 4;
     const int foff = frow * kRowBytes + ((fchunk ^ row_swizzle(frow)) << 4);   // block bases are multiples of 16
@@ -288,17 +289,7 @@ __global__ __launch_bounds__(256, 1) void gemm_tn_kernel(const char* __restrict_
     // AGPRs, fragments in VGPRs): left to itself the register allocator mixes the two files for 64
     // four-register accumulators and fills the loop with accumulator moves and spills.
     auto mfma_one = [&](int buf, int j, int i) {
-        if (ESZ == 2) {
-            asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc[j][i]) : "v"(wf[buf][j]), "v"(af[buf][i]));
-        } else {
-#pragma unroll
-            for (int hf = 0; hf < 2; ++hf) {
-                const i32x4 wv = wf[buf][j], av = af[buf][i];
-                const long wl = ((long)(uint32_t)wv[2 * hf]) | ((long)wv[2 * hf + 1] << 32);
-                const long al = ((long)(uint32_t)av[2 * hf]) | ((long)av[2 * hf + 1] << 32);
-                asm volatile("v_mfma_f32_16x16x32_fp8_fp8 %0, %1, %2, %0" : "+a"(acc[j][i]) : "v"(wl), "v"(al));
-            }
-        }
+        asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc[j][i]) : "v"(wf[buf][j]), "v"(af[buf][i]));
     };
 
     // Ring of 4 slots, one MFMA k-step (64 bytes of k per row) per slot; step t lives in slot t % 4.
@@ -366,6 +357,205 @@ __global__ __launch_bounds__(256, 1) void gemm_tn_kernel(const char* __restrict_
     }
 }
 
+// fp8 (OCP e4m3) with the double-rate MFMA 32x32x64 (f8f6f4 family, both operands fp8): the same
+// ring, loads, waits and tile order as gemm_tn_kernel; a ring row (64 bytes) is one k-step of 64
+// values, a lane's operand is half a row (32 bytes = two 16-byte chunks), and the wave's 128 x 128
+// block is 4 x 4 tiles of 32 x 32.  Twice the flop of the bf16 kernel per byte moved.
+__global__ __launch_bounds__(256, 1) void gemm_fp8_kernel(const char* __restrict__ A,
+                                                         const char* __restrict__ Wt,
+                                                         uint16_t* __restrict__ C,
+                                                         const uint16_t* __restrict__ R, int M, int N,
+                                                         int K, float alpha, int tiles_m, int tiles_n) {
+    extern __shared__ __attribute__((aligned(1024))) char lds[];
+    // Co-resident RNG waves only need the VALU issue slots this kernel leaves idle; raise this
+    // wave's issue priority so that they never delay its MFMA / LDS instruction stream.
+    __builtin_amdgcn_s_setprio(3);
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int wm = wave >> 1, wn = wave & 1;
+
+    // XCD-aware tile id: workgroup ids are dealt round-robin to the 8 XCDs; give each XCD a
+    // contiguous range of logical tiles, ordered in bands of 8 tile-rows with the row fastest.
+    const int T = tiles_m * tiles_n;
+    int id;
+    {
+        const int pid = blockIdx.x, per = T >> 3, rem = T & 7;
+        const int xcd = pid & 7, loc = pid >> 3;
+        id = xcd < rem ? xcd * (per + 1) + loc : rem * (per + 1) + (xcd - rem) * per + loc;
+    }
+    constexpr int GM = 8;
+    const int band = id / (GM * tiles_n);
+    const int band_rows = (tiles_m - band * GM) < GM ? (tiles_m - band * GM) : GM;
+    const int in_band = id - band * GM * tiles_n;
+    const int tm = band * GM + in_band % band_rows;
+    const int tn = in_band / band_rows;
+    const int m0 = tm * BM, n0 = tn * BN;
+
+    constexpr int ESZ = 1;
+    f32x16 acc[4][4];   // [weight-row block j (32 rows)][activation-row block i (32 rows)]
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[j][i][e] = 0.0f;
+
+    // fragment of MFMA 32x32x64: lane holds row lane%32 and the 32 k-values 32*(lane/32) .. +31 of
+    // the step, i.e. logical chunks 2*(lane/32) and 2*(lane/32) + 1 of the row
+    const int frow = lane & 31;
+    const int fhalf = lane >> 5;
+    const int foff0 = frow * kRowBytes + (((2 * fhalf) ^ row_swizzle(frow)) << 4);       // block bases are
+    const int foff1 = frow * kRowBytes + (((2 * fhalf + 1) ^ row_swizzle(frow)) << 4);   // multiples of 32
+    const int a_base = (wm * 128) * kRowBytes;
+    const int w_base = BM * kRowBytes + (wn * 128) * kRowBytes;
+
+    // Loads: one wave instruction moves 16 rows x 64 bytes (1 KiB, linear in LDS).  Wave w issues
+    // row blocks w, w+4, w+8, w+12 of each operand: 8 instructions per ring step.  Lane L fills
+    // physical chunk L%4 of row L/4, i.e. fetches logical chunk (L%4) ^ swizzle(row).
+    const size_t ld_bytes = (size_t)K * ESZ;
+    const int ns = (int)(ld_bytes / kRowBytes);       // ring steps (even)
+    const int rows_a = M - m0 < BM ? M - m0 : BM;
+    const int rows_w = N - n0 < BN ? N - n0 : BN;
+    uint32_t voff_a[4], voff_w[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int row = (wave + 4 * j) * 16 + (lane >> 2);
+        const int chunk = (lane & 3) ^ row_swizzle(row);
+        const int ra = row < rows_a ? row : rows_a - 1;   // rows past the edge are never stored
+        const int rw = row < rows_w ? row : rows_w - 1;
+        voff_a[j] = (uint32_t)((size_t)ra * ld_bytes) + (uint32_t)(chunk * 16);
+        voff_w[j] = (uint32_t)((size_t)rw * ld_bytes) + (uint32_t)(chunk * 16);
+    }
+    const char* a_panel = A + (size_t)m0 * ld_bytes;
+    const char* w_panel = Wt + (size_t)n0 * ld_bytes;
+    // ring step at which this workgroup starts its cyclic walk over k (the sum does not depend on
+    // the order; the fp32 rounding does, deterministically)
+    const int kstart = (int)(((unsigned)tm * 2u) % (unsigned)ns);
+    // Buffer resources over the two operand panels (scalar base, per-lane 32-bit offset, scalar k
+    // offset; the range ends with the last valid row, so an offset beyond it would read zeros).
+    auto make_rsrc = [](const char* base, size_t bytes) {
+        const uint64_t b = (uint64_t)(uintptr_t)base;
+        i32x4 r;
+        r[0] = __builtin_amdgcn_readfirstlane((int)(uint32_t)b);
+        r[1] = __builtin_amdgcn_readfirstlane((int)(uint32_t)((b >> 32) & 0xFFFFu));
+        r[2] = __builtin_amdgcn_readfirstlane((int)(uint32_t)bytes);
+        r[3] = 0x00020000;
+        return r;
+    };
+    const i32x4 rsrc_a = make_rsrc(a_panel, (size_t)rows_a * ld_bytes);
+    const i32x4 rsrc_w = make_rsrc(w_panel, (size_t)rows_w * ld_bytes);
+    const uint32_t lds_base = (uint32_t)(uintptr_t)(lptr_t)lds;
+
+    // Load instruction q (0..3 = A row blocks, 4..7 = W row blocks) of ring step `step` into the
+    // ring slot at LDS byte address `slot`.  Inline assembly, so that the compiler's wait-count
+    // pass does not see an LDS write it cannot tell apart from the fragment reads (it would force
+    // vmcnt(0) before every LDS read); the waits are placed by hand below.  M0 (the LDS base of
+    // the transfer) is a reserved register that compiled code only sets right before its own uses.
+    auto issue = [&](int q, int step, uint32_t slot) {
+        int st = step < ns ? step : ns - 1;       // past the end: harmless reload of the last step
+        st += kstart;
+        st = st >= ns ? st - ns : st;
+        const int koff = st * kRowBytes;
+        if (q < 4) {
+            const uint32_t dst = slot + (uint32_t)((wave + 4 * q) * 1024);
+            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+                         :: "s"(dst), "v"(voff_a[q]), "s"(rsrc_a), "s"(koff) : "memory");
+        } else {
+            const uint32_t dst = slot + (uint32_t)(BM * kRowBytes + (wave + 4 * (q - 4)) * 1024);
+            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+                         :: "s"(dst), "v"(voff_w[q - 4]), "s"(rsrc_w), "s"(koff) : "memory");
+        }
+    };
+
+    i32x8 af[2][4], wf[2][4];   // fragments of the current and the next ring step
+    // read r (0..15): half r%2 of fragment r/2 (0..3 = A block, 4..7 = W block)
+    auto read_frag = [&](int buf, const char* slot, int r) {
+        const int f = r >> 1;
+        const char* src = slot + (f < 4 ? a_base + f * 32 * kRowBytes : w_base + (f - 4) * 32 * kRowBytes) +
+                          ((r & 1) ? foff1 : foff0);
+        const i32x4 v = *reinterpret_cast<const i32x4*>(src);
+        i32x8& dst = f < 4 ? af[buf][f] : wf[buf][f - 4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) dst[4 * (r & 1) + e] = v[e];
+    };
+    // inline assembly with explicit register classes, as in gemm_tn_kernel
+    auto mfma_one = [&](int buf, int j, int i) {
+        asm volatile("v_mfma_f32_32x32x64_f8f6f4 %0, %1, %2, %0" : "+a"(acc[j][i]) : "v"(wf[buf][j]), "v"(af[buf][i]));
+    };
+
+    // Ring of 4 slots, one MFMA k-step (64 bytes of k per row) per slot; step t lives in slot t % 4.
+    // At the top of step s every wave has the fragments of step s in registers, so slot s % 4 is
+    // free and takes the loads of step s+4 (8 per wave, one every 4 MFMAs in the second half of the
+    // step); the fragments of step s+1 are read in the first half.  Loads complete in order, so
+    // "step s+1 has landed" is vmcnt <= 16 (steps s+2, s+3 are the only later ones in flight).
+#pragma unroll
+    for (int t = 0; t < 4; ++t)
+#pragma unroll
+        for (int q = 0; q < 8; ++q) issue(q, t, lds_base + t * kSlotBytes);
+    __builtin_amdgcn_s_waitcnt(0x4F78);   // vmcnt(24): step 0 has landed
+    __syncthreads();
+#pragma unroll
+    for (int r = 0; r < 16; ++r) read_frag(0, lds, r);
+
+    auto step_body = [&](int buf, int s) {
+        const char* nxt = lds + ((s + 1) & 3) * kSlotBytes;
+        const uint32_t slot = lds_base + (s & 3) * kSlotBytes;
+        __builtin_amdgcn_s_waitcnt(0x4070);   // vmcnt(16) lgkmcnt(0)
+        __syncthreads();
+#pragma unroll
+        for (int idx = 0; idx < 16; ++idx) {   // 16 MFMAs of 64 cycles: the bf16 step's time
+            mfma_one(buf, idx >> 2, idx & 3);
+            if (idx < 8) {
+                read_frag(buf ^ 1, nxt, 2 * idx);
+                read_frag(buf ^ 1, nxt, 2 * idx + 1);
+            } else {
+                issue(idx - 8, s + 4, slot);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+    for (int s = 0; s < ns; s += 2) {
+        step_body(0, s);
+        step_body(1, s + 1);
+    }
+    __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): no LDS load may outlive the loop
+    asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");   // the last MFMA results are in the accumulators before they are read
+
+    // D'[r][c] = C[m = c][n = r]: lane holds activation row lane%32 and, for register e, weight row
+    // 8*(e/4) + 4*(lane/32) + e%4: four consecutive n per e/4
+    const int mrow = lane & 31;
+    const int nsub = (lane >> 5) * 4;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int m = m0 + wm * 128 + i * 32 + mrow;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int n = n0 + wn * 128 + j * 32 + q * 8 + nsub;
+                float c0 = alpha * acc_read(acc[j][i][q * 4 + 0]);
+                float c1 = alpha * acc_read(acc[j][i][q * 4 + 1]);
+                float c2 = alpha * acc_read(acc[j][i][q * 4 + 2]);
+                float c3 = alpha * acc_read(acc[j][i][q * 4 + 3]);
+                if (m < M && n < N) {
+                    if (R != nullptr) {
+                        const uint2 r = *reinterpret_cast<const uint2*>(R + (size_t)m * N + n);
+                        c0 += __uint_as_float(r.x << 16);
+                        c1 += __uint_as_float(r.x & 0xFFFF0000u);
+                        c2 += __uint_as_float(r.y << 16);
+                        c3 += __uint_as_float(r.y & 0xFFFF0000u);
+                    }
+                    uint2 v;
+                    v.x = pack_bf16x2(c0, c1);
+                    v.y = pack_bf16x2(c2, c3);
+                    *reinterpret_cast<uint2*>(C + (size_t)m * N + n) = v;
+                }
+            }
+        }
+    }
+}
+
 }  // namespace
 
 int launch_gemm(const void* A, const void* Bm, void* C, int M, int N, int K, int dtype, int transB,
@@ -390,7 +580,7 @@ int launch_gemm_residual(const void* A, const void* Bm, void* C, const void* R, 
         // a 256-row operand panel is addressed with 32-bit byte offsets
         if ((unsigned long long)BM * (unsigned long long)K * (unsigned long long)esz > 0xFFFFFFFFull)
             return ROV_ERR_UNSUPPORTED;
-        auto kern = esz == 2 ? gemm_tn_kernel<2> : gemm_tn_kernel<1>;
+        auto kern = esz == 2 ? gemm_tn_kernel : gemm_fp8_kernel;
         static bool attr_set[2] = {false, false};
         if (!attr_set[esz - 1]) {
             ROV_HIP_TRY(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,

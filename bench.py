@@ -251,6 +251,10 @@ def main():
                 "sequential": bm["baseline"] * 1e3, "fused": bm["fusion"] * 1e3, "overlap": bm["overlap"] * 1e3,
                 "rng_exposed": bm["rng_exposed"] * 1e3}
 
+    # ------------------------------------------------------------------ 70B-shaped layer with fp8 GEMMs (configs[3])
+    if not args.no_block:
+        extras["layer_llama3_70b_fp8_s8k"] = bench_fp8_layer(torch, rov, wl, main_s, side_s, sync, ev_pair)
+
     # ------------------------------------------------------------------ CPU oracle on a bounded sample
     cpu = None
     if not args.no_cpu:
@@ -331,6 +335,56 @@ def bench_block(torch, rov, wl, main_s, side_s, sync, ev_pair):
             "speedup_overlap_vs_sequential": t_seq / t_ovl, "speedup_overlap_vs_fused": t_fus / t_ovl}
         del ws, m0, m1
         torch.cuda.empty_cache()
+    return res
+
+
+def bench_fp8_layer(torch, rov, wl, main_s, side_s, sync, ev_pair):
+    """All GEMMs of one Llama-3-70B-shaped layer in fp8 (e4m3, per-tensor scales; gate and up both
+    run), the keep-mask of its GQA attention (64 query / 8 kv heads, S = 8192) and the attention, in
+    the three schedules.  Inputs are drawn on the device; the GEMMs are independent of each other
+    (the paper's silicon experiment, Sec. 6.1, with every GEMM of the layer beside the RNG)."""
+    ci = 3
+    c = wl.CONFIGS[ci]
+    B, H, Hkv, S, d, p = c["B"], c["H"], c["Hkv"], c["S"], c["d"], c["p"]
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(1000 + ci)
+    f8 = torch.float8_e4m3fn
+
+    def quant(x):
+        scale = float(x.abs().max()) / 448.0
+        return (x / scale).to(f8), scale
+
+    descs, keep, flop = [], [], 0.0
+    shapes = [g for g in c["gemms"]] + [("ffn_gate",) + tuple(c["gemms"][2][1:])]
+    for _, M, K, N in shapes:
+        A8, sa = quant(torch.randn(M, K, device="cuda", generator=gen))
+        W8, sw = quant(torch.randn(N, K, device="cuda", generator=gen) * 0.02)
+        C = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+        descs.append(rov.make_gemm_desc(A8, W8, C, scaleA=sa, scaleB=sw))
+        keep += [A8, W8, C]
+        flop += 2.0 * M * N * K
+    bf = torch.bfloat16
+    Q = torch.randn(B, S, H, d, device="cuda", generator=gen).to(bf)
+    Kt = torch.randn(B, S, Hkv, d, device="cuda", generator=gen).to(bf)
+    V = torch.randn(B, S, Hkv, d, device="cuda", generator=gen).to(bf)
+    O = torch.empty_like(Q)
+    mask = torch.empty(rov.mask_shape(B, H, S), dtype=torch.int64, device="cuda")
+    ad = rov.make_attn_desc(Q, Kt, V, O, p)
+    res = {}
+    with torch.cuda.stream(main_s):
+        def gemms_only():
+            for g in descs:
+                rov.gemm_desc(g, stream=main_s)
+        t_g = median_ms(gemms_only, 2, 5, sync, ev_pair, inner=2)
+        t_r = median_ms(lambda: rov.dropout_mask_generate(wl.SEED, 0, B, H, S, p, out=mask, stream=main_s),
+                        2, 5, sync, ev_pair, inner=2)
+        for name, sched in (("sequential", rov.SCHED_SEQUENTIAL), ("fused", rov.SCHED_FUSED), ("overlap", rov.SCHED_OVERLAP)):
+            res[name + "_ms"] = median_ms(
+                lambda: rov.layer_step(sched, descs, ad, wl.SEED, 0, None if sched == rov.SCHED_FUSED else mask,
+                                       main_s, side_s), 2, 5, sync, ev_pair, inner=2)
+    res.update({"gemms_ms": t_g, "gemms_tflops": flop / t_g / 1e9, "gemms_fp8_mfma_frac": flop / t_g / 1e9 / 5000.0,
+                "rng_ms": t_r, "speedup_overlap_vs_sequential": res["sequential_ms"] / res["overlap_ms"],
+                "speedup_overlap_vs_fused": res["fused_ms"] / res["overlap_ms"]})
     return res
 
 

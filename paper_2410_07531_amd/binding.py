@@ -289,6 +289,12 @@ def make_gemm_desc(A, Bm, C, transB=True, scaleA=1.0, scaleB=1.0):
                     float(scaleA), float(scaleB))
 
 
+def gemm_desc(desc, stream=None):
+    """Runs the GEMM a GemmDesc describes."""
+    _check(load().rov_gemm(desc.A, desc.Bm, desc.C, desc.M, desc.N, desc.K, desc.dtype, desc.transB,
+                           desc.scaleA, desc.scaleB, _stream_ptr(stream)), "rov_gemm")
+
+
 def make_attn_desc(Q, K, V, O, p, causal=False):
     B, S, H, d = Q.shape
     desc = AttnDesc(Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(), B, H, K.shape[2], S, d,

@@ -26,6 +26,8 @@
 // Any other case (fp32, other head dimensions) takes a small one-wave-per-row
 // kernel that is correct for every shape.
 #include <hip/hip_runtime.h>
+
+#include <type_traits>
 #include <stdint.h>
 
 #include "philox_device.h"
@@ -100,26 +102,51 @@ __device__ __forceinline__ int swizzle_of_row(int row) {
 
 // K or V tile: global -> LDS directly.  One wave instruction fills 1 KiB = 1024 / kKRow rows;
 // lane L lands on physical chunk L % kChunks of its row and therefore fetches the logical
-// chunk (L % kChunks) ^ swizzle(row).
+// chunk (L % kChunks) ^ swizzle(row).  The lane's byte offsets from the tile's first row do not
+// change from tile to tile: they are computed once (kv_lane_offsets), and a tile that lies
+// wholly inside the sequence is fetched as wave-uniform base + 32-bit lane offset, with no
+// per-lane address arithmetic in the loop.  Only the last, ragged tile clamps its rows.
 template <int D, int NW, bool VTILE>
-__device__ __forceinline__ void load_kv_tile(const uint16_t* __restrict__ Xp, int64_t tok_stride,
-                                             int kv0, int S, char* lds_x, int wave, int lane) {
-    constexpr int kChunks = Tile<D>::kChunks;
-    constexpr int kRowsPerInst = 64 / kChunks;                 // 4 (D = 128) or 8 (D = 64)
-    constexpr int kInst = BKV / kRowsPerInst;                  // 16 or 8 per tile
-    const int rl = lane / kChunks;
-    const int pc = lane % kChunks;
+struct KvTileLoad {
+    static constexpr int kChunks = Tile<D>::kChunks;
+    static constexpr int kRowsPerInst = 64 / kChunks;          // 4 (D = 128) or 8 (D = 64)
+    static constexpr int kInst = BKV / kRowsPerInst;           // 16 or 8 per tile
+    static constexpr int kPerWave = kInst / NW;
+    uint32_t off[kPerWave];
+
+    __device__ __forceinline__ void init(int64_t tok_stride, int wave, int lane) {
+        const int rl = lane / kChunks, pc = lane % kChunks;
 #pragma unroll
-    for (int i = 0; i < kInst / NW; ++i) {
-        const int inst = wave + NW * i;
-        const int row = inst * kRowsPerInst + rl;              // 0..63
-        int key = kv0 + row;
-        key = key < S ? key : S - 1;
-        const int chunk = pc ^ swizzle_of_row<D, VTILE>(row);
-        const uint16_t* g = Xp + (int64_t)key * tok_stride + chunk * 8;
-        __builtin_amdgcn_global_load_lds((gptr_t)g, (lptr_t)(lds_x + inst * 1024), 16, 0, 0);
+        for (int i = 0; i < kPerWave; ++i) {
+            const int row = (wave + NW * i) * kRowsPerInst + rl;          // 0..63
+            const int chunk = pc ^ swizzle_of_row<D, VTILE>(row);
+            off[i] = (uint32_t)row * (uint32_t)tok_stride * 2u + (uint32_t)chunk * 16u;
+        }
     }
-}
+
+    __device__ __forceinline__ void load(const uint16_t* __restrict__ Xp, int64_t tok_stride, int kv0, int S,
+                                         char* lds_x, int wave, int lane) const {
+        if (kv0 + BKV <= S) {
+            const char* base = reinterpret_cast<const char*>(Xp + (int64_t)kv0 * tok_stride);
+#pragma unroll
+            for (int i = 0; i < kPerWave; ++i)
+                __builtin_amdgcn_global_load_lds((gptr_t)(base + off[i]), (lptr_t)(lds_x + (wave + NW * i) * 1024),
+                                                 16, 0, 0);
+        } else {
+            const int rl = lane / kChunks, pc = lane % kChunks;
+#pragma unroll
+            for (int i = 0; i < kPerWave; ++i) {
+                const int inst = wave + NW * i;
+                const int row = inst * kRowsPerInst + rl;
+                int key = kv0 + row;
+                key = key < S ? key : S - 1;
+                const int chunk = pc ^ swizzle_of_row<D, VTILE>(row);
+                const uint16_t* g = Xp + (int64_t)key * tok_stride + chunk * 8;
+                __builtin_amdgcn_global_load_lds((gptr_t)g, (lptr_t)(lds_x + inst * 1024), 16, 0, 0);
+            }
+        }
+    }
+};
 
 typedef const __attribute__((address_space(4))) uint64_t* const_u64_ptr;
 typedef short i16x4 __attribute__((ext_vector_type(4)));
@@ -227,8 +254,12 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(const AttnParams p) 
         mtile[n] = p.mask + ((((uint64_t)b * p.H + h) * (uint32_t)p.mask_nqt + (qt - (uint32_t)p.mask_qt0)) * Tt) * 16u;
     }
 
-    load_kv_tile<D, NW, false>(Kp, p.sk[1], 0, S, lds, wave, lane);
-    load_kv_tile<D, NW, true>(Vp, p.sv[1], 0, S, lds + T::kKBytes, wave, lane);
+    KvTileLoad<D, NW, false> kload;
+    KvTileLoad<D, NW, true> vload;
+    kload.init(p.sk[1], wave, lane);
+    vload.init(p.sv[1], wave, lane);
+    kload.load(Kp, p.sk[1], 0, S, lds, wave, lane);
+    vload.load(Vp, p.sv[1], 0, S, lds + T::kKBytes, wave, lane);
 
     // transpose-load addressing of the V tile (see lds_read_transposed): lane l = 16*g + 4*j + s
     // supplies row 16*u + 8*x + 4*(g/2) + j, columns 32*t + 16*(g%2) + 4*s .. +3
@@ -246,16 +277,19 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(const AttnParams p) 
     static_assert(NQ == 1, "the keep-word warm-up load covers one query tile per wave");
     uint32_t warm = 0u, sink = 0u;   // L2 warm-up of the next tile's keep words (MODE_MASK)
 
-    for (int jt = 0; jt < ntiles; ++jt) {
+    // One KV tile.  The LDS stage is a compile-time constant (the loop below alternates the two
+    // instantiations), so every fragment read is a loop-invariant lane address plus an immediate.
+    auto tile_step = [&](const int jt, auto stage_tag) __attribute__((always_inline)) {
+        constexpr int STAGE = decltype(stage_tag)::value;
         const int kv0 = jt * BKV;
-        char* cur = lds + (jt & 1) * T::kStage;
-        char* nxt = lds + ((jt + 1) & 1) * T::kStage;
+        char* cur = lds + STAGE * T::kStage;
+        char* nxt = lds + (STAGE ^ 1) * T::kStage;
         __builtin_amdgcn_s_waitcnt(0x0070);   // vmcnt(0) lgkmcnt(0): this wave's K / V loads have landed
         __syncthreads();
         const bool has_next = jt + 1 < ntiles;
         if (has_next) {
-            load_kv_tile<D, NW, false>(Kp, p.sk[1], kv0 + BKV, S, nxt, wave, lane);
-            load_kv_tile<D, NW, true>(Vp, p.sv[1], kv0 + BKV, S, nxt + T::kKBytes, wave, lane);
+            kload.load(Kp, p.sk[1], kv0 + BKV, S, nxt, wave, lane);
+            vload.load(Vp, p.sv[1], kv0 + BKV, S, nxt + T::kKBytes, wave, lane);
         }
         // ---- S^T = K Q^T for 64 keys x NQ*32 queries
         f32x16 s[2][NQ];
@@ -265,17 +299,30 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(const AttnParams p) 
             for (int n = 0; n < NQ; ++n)
 #pragma unroll
                 for (int e = 0; e < 16; ++e) s[t][n][e] = 0.0f;
+        // K fragments are read kAhead k-steps before the MFMAs that use them: the scheduling
+        // groups below pin that order (3 k-steps of reads, then per k-step its MFMAs followed by
+        // the reads of the k-step kAhead further on), so the LDS latency is paid once per tile
+        // and not once per k-step.
+        constexpr int kAhead = 3;
+        bf16x8 kf[KS][2];
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
+        for (int ks = 0; ks < KS; ++ks)
 #pragma unroll
-            for (int t = 0; t < 2; ++t) {
-                const int row = 32 * t + ql;
-                const bf16x8 kf = *reinterpret_cast<const bf16x8*>(
-                    cur + row * T::kKRow + (((2 * ks + half) ^ kswz) << 4));
+            for (int t = 0; t < 2; ++t)
+                kf[ks][t] = *reinterpret_cast<const bf16x8*>(
+                    cur + (32 * t + ql) * T::kKRow + (((2 * ks + half) ^ kswz) << 4));
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+            for (int t = 0; t < 2; ++t)
 #pragma unroll
                 for (int n = 0; n < NQ; ++n)
-                    s[t][n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[n][ks], s[t][n], 0, 0, 0);
-            }
+                    s[t][n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks][t], qf[n][ks], s[t][n], 0, 0, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 2 * kAhead, 0);          // DS reads
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 2 * NQ, 0);          // MFMAs of k-step ks
+            if (ks + kAhead < KS) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
         }
 
         // ---- keep words of this KV tile: 2 key tiles x 16 words per query tile, wave-uniform.
@@ -405,7 +452,10 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(const AttnParams p) 
                     o[t][n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[n][u], o[t][n], 0, 0, 0);
             }
         }
-
+    };
+    for (int jt = 0; jt < ntiles; jt += 2) {
+        tile_step(jt, std::integral_constant<int, 0>{});
+        if (jt + 1 < ntiles) tile_step(jt + 1, std::integral_constant<int, 1>{});
     }
 
     // the warm-up values only have to look used (no mask pattern makes this condition true
@@ -636,6 +686,8 @@ int launch_attention_rows(const void* Q, const void* K, const void* V, void* O, 
         // 16-byte vector access needs 8-element alignment of every row start
         bool ok = aligned(Q, 16) && aligned(K, 16) && aligned(V, 16) && aligned(O, 8);
         for (int i = 0; i < 12; ++i) ok = ok && (strides[i] % 8) == 0;
+        // K / V rows of a tile are addressed as base + 32-bit lane offset (63 token strides at most)
+        ok = ok && strides[4] >= 0 && strides[4] < (1 << 24) && strides[7] >= 0 && strides[7] < (1 << 24);
         if (ok) {
             // 8 waves x 32 query rows: two waves per SIMD (measured 1.5x faster than 4 waves x 64
             // rows at S = 16384: 905 vs 602 TFLOP/s without dropout)

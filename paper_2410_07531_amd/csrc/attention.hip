@@ -102,10 +102,17 @@ __device__ __forceinline__ int swizzle_of_row(int row) {
 
 // K or V tile: global -> LDS directly.  One wave instruction fills 1 KiB = 1024 / kKRow rows;
 // lane L lands on physical chunk L % kChunks of its row and therefore fetches the logical
-// chunk (L % kChunks) ^ swizzle(row).  The lane's byte offsets from the tile's first row do not
-// change from tile to tile: they are computed once (kv_lane_offsets), and a tile that lies
-// wholly inside the sequence is fetched as wave-uniform base + 32-bit lane offset, with no
-// per-lane address arithmetic in the loop.  Only the last, ragged tile clamps its rows.
+// chunk (L % kChunks) ^ swizzle(row).  The loads are buffer loads: a buffer resource over the
+// rows [0, S) of this (batch, kv head) as scalar base, the lane's byte offset from the tile's
+// first row (the same for every tile, computed once) as vector offset, and the tile's first
+// row as scalar offset -- no per-lane address arithmetic in the loop.  Rows at or beyond S lie
+// outside the resource's range and read as zeros (their scores are masked anyway).
+// Inline assembly on purpose: the compiler's wait-count pass cannot tell the LDS write of such
+// a load from the fragment reads of the other stage and would force vmcnt(0) before the
+// second product of every tile, i.e. wait for the prefetch in the middle of the tile it was
+// meant to run under; the kernel places its one vmcnt(0) per tile itself.  M0 (the LDS base of
+// the transfer) is a reserved register that compiled code only sets right before its own uses.
+typedef int i32x4 __attribute__((ext_vector_type(4)));
 template <int D, int NW, bool VTILE>
 struct KvTileLoad {
     static constexpr int kChunks = Tile<D>::kChunks;
@@ -113,37 +120,33 @@ struct KvTileLoad {
     static constexpr int kInst = BKV / kRowsPerInst;           // 16 or 8 per tile
     static constexpr int kPerWave = kInst / NW;
     uint32_t off[kPerWave];
+    uint32_t row_bytes;
+    i32x4 rsrc;
 
-    __device__ __forceinline__ void init(int64_t tok_stride, int wave, int lane) {
+    __device__ __forceinline__ void init(const uint16_t* Xp, int64_t tok_stride, int S, int wave, int lane) {
         const int rl = lane / kChunks, pc = lane % kChunks;
+        row_bytes = (uint32_t)tok_stride * 2u;
 #pragma unroll
         for (int i = 0; i < kPerWave; ++i) {
             const int row = (wave + NW * i) * kRowsPerInst + rl;          // 0..63
             const int chunk = pc ^ swizzle_of_row<D, VTILE>(row);
-            off[i] = (uint32_t)row * (uint32_t)tok_stride * 2u + (uint32_t)chunk * 16u;
+            off[i] = (uint32_t)row * row_bytes + (uint32_t)chunk * 16u;
         }
+        const uint64_t base = (uint64_t)(uintptr_t)Xp;
+        rsrc[0] = __builtin_amdgcn_readfirstlane((int)(uint32_t)base);
+        rsrc[1] = __builtin_amdgcn_readfirstlane((int)(uint32_t)((base >> 32) & 0xFFFFu));
+        rsrc[2] = __builtin_amdgcn_readfirstlane((int)((uint32_t)(S - 1) * row_bytes + (uint32_t)(D * 2)));
+        rsrc[3] = 0x00020000;
     }
 
-    __device__ __forceinline__ void load(const uint16_t* __restrict__ Xp, int64_t tok_stride, int kv0, int S,
-                                         char* lds_x, int wave, int lane) const {
-        if (kv0 + BKV <= S) {
-            const char* base = reinterpret_cast<const char*>(Xp + (int64_t)kv0 * tok_stride);
+    // lds_tile: LDS byte address of the tile
+    __device__ __forceinline__ void load(int kv0, uint32_t lds_tile, int wave) const {
+        const uint32_t soff = (uint32_t)kv0 * row_bytes;
 #pragma unroll
-            for (int i = 0; i < kPerWave; ++i)
-                __builtin_amdgcn_global_load_lds((gptr_t)(base + off[i]), (lptr_t)(lds_x + (wave + NW * i) * 1024),
-                                                 16, 0, 0);
-        } else {
-            const int rl = lane / kChunks, pc = lane % kChunks;
-#pragma unroll
-            for (int i = 0; i < kPerWave; ++i) {
-                const int inst = wave + NW * i;
-                const int row = inst * kRowsPerInst + rl;
-                int key = kv0 + row;
-                key = key < S ? key : S - 1;
-                const int chunk = pc ^ swizzle_of_row<D, VTILE>(row);
-                const uint16_t* g = Xp + (int64_t)key * tok_stride + chunk * 8;
-                __builtin_amdgcn_global_load_lds((gptr_t)g, (lptr_t)(lds_x + inst * 1024), 16, 0, 0);
-            }
+        for (int i = 0; i < kPerWave; ++i) {
+            const uint32_t dst = lds_tile + (uint32_t)((wave + NW * i) * 1024);
+            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+                         :: "s"(dst), "v"(off[i]), "s"(rsrc), "s"(soff) : "memory");
         }
     }
 };
@@ -256,10 +259,11 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(const AttnParams p) 
 
     KvTileLoad<D, NW, false> kload;
     KvTileLoad<D, NW, true> vload;
-    kload.init(p.sk[1], wave, lane);
-    vload.init(p.sv[1], wave, lane);
-    kload.load(Kp, p.sk[1], 0, S, lds, wave, lane);
-    vload.load(Vp, p.sv[1], 0, S, lds + T::kKBytes, wave, lane);
+    kload.init(Kp, p.sk[1], S, wave, lane);
+    vload.init(Vp, p.sv[1], S, wave, lane);
+    const uint32_t lds_base = (uint32_t)(uintptr_t)(lptr_t)lds;
+    kload.load(0, lds_base, wave);
+    vload.load(0, lds_base + T::kKBytes, wave);
 
     // transpose-load addressing of the V tile (see lds_read_transposed): lane l = 16*g + 4*j + s
     // supplies row 16*u + 8*x + 4*(g/2) + j, columns 32*t + 16*(g%2) + 4*s .. +3
@@ -283,13 +287,12 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(const AttnParams p) 
         constexpr int STAGE = decltype(stage_tag)::value;
         const int kv0 = jt * BKV;
         char* cur = lds + STAGE * T::kStage;
-        char* nxt = lds + (STAGE ^ 1) * T::kStage;
         __builtin_amdgcn_s_waitcnt(0x0070);   // vmcnt(0) lgkmcnt(0): this wave's K / V loads have landed
         __syncthreads();
         const bool has_next = jt + 1 < ntiles;
         if (has_next) {
-            kload.load(Kp, p.sk[1], kv0 + BKV, S, nxt, wave, lane);
-            vload.load(Vp, p.sv[1], kv0 + BKV, S, nxt + T::kKBytes, wave, lane);
+            kload.load(kv0 + BKV, lds_base + (STAGE ^ 1) * T::kStage, wave);
+            vload.load(kv0 + BKV, lds_base + (STAGE ^ 1) * T::kStage + T::kKBytes, wave);
         }
         // ---- S^T = K Q^T for 64 keys x NQ*32 queries
         f32x16 s[2][NQ];
@@ -324,6 +327,10 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(const AttnParams p) 
             __builtin_amdgcn_sched_group_barrier(0x008, 2 * NQ, 0);          // MFMAs of k-step ks
             if (ks + kAhead < KS) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
         }
+        // nothing below moves up into the first product: a scalar load of keep words between its
+        // LDS reads would turn every wait for a fragment into a wait for that load as well (the
+        // two share one counter, and scalar loads return out of order)
+        __builtin_amdgcn_sched_barrier(0);
 
         // ---- keep words of this KV tile: 2 key tiles x 16 words per query tile, wave-uniform.
         // They are requested here, right after the Q K^T MFMAs have been issued, through the
@@ -686,8 +693,9 @@ int launch_attention_rows(const void* Q, const void* K, const void* V, void* O, 
         // 16-byte vector access needs 8-element alignment of every row start
         bool ok = aligned(Q, 16) && aligned(K, 16) && aligned(V, 16) && aligned(O, 8);
         for (int i = 0; i < 12; ++i) ok = ok && (strides[i] % 8) == 0;
-        // K / V rows of a tile are addressed as base + 32-bit lane offset (63 token strides at most)
-        ok = ok && strides[4] >= 0 && strides[4] < (1 << 24) && strides[7] >= 0 && strides[7] < (1 << 24);
+        // K / V of one (batch, kv head) are addressed through a buffer resource: 32-bit byte offsets
+        for (int t = 4; t <= 7; t += 3)
+            ok = ok && strides[t] >= 0 && (uint64_t)(S - 1) * (uint64_t)strides[t] * 2u + 2u * (uint64_t)d < (1ull << 32);
         if (ok) {
             // 8 waves x 32 query rows: two waves per SIMD (measured 1.5x faster than 4 waves x 64
             // rows at S = 16384: 905 vs 602 TFLOP/s without dropout)

@@ -86,6 +86,26 @@ def test_attention_strided_views_and_carry_offset():
     assert torch.equal(O1, O2)
 
 
+def test_attention_token_stride_beyond_32_bit_offsets():
+    # K and V rows 2 GiB apart: the bf16 kernel addresses a (batch, kv head) with 32-bit byte offsets,
+    # so this call must take the generic kernel (64-bit addressing) and still match the oracle
+    B, S, H, d = 1, 3, 1, 128
+    stride = (1 << 30) + 8                                    # elements between consecutive tokens
+    Q, K0, V0 = _inputs(11, B, S, H, H, d, torch.bfloat16)
+    bufs = [torch.zeros((S - 1) * stride + d, dtype=torch.bfloat16, device="cuda") for _ in range(2)]
+    K, V = [b.as_strided((B, S, H, d), (S * stride, stride, d, 1)) for b in bufs]
+    K.copy_(K0)
+    V.copy_(V0)
+    p, seed = 0.25, 5
+    keep = OP.unpack_keep(OP.dropout_mask(seed, 0, B, H, S, p), S)
+    mask = rov.dropout_mask_generate(seed, 0, B, H, S, p)
+    O = rov.attention_fwd_dropout(Q, K, V, p, mask=mask)
+    torch.cuda.synchronize()
+    _check(O, Q, K0, V0, keep, p, False, torch.bfloat16)
+    del K, V, bufs
+    torch.cuda.empty_cache()
+
+
 def test_attention_constant_v_and_full_drop_rows():
     # V == c: O = c * kept softmax mass / (1-p); with p close to 1 many rows lose everything -> 0
     B, S, H, d = 1, 128, 2, 128

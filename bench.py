@@ -277,7 +277,7 @@ def main():
                                "GEMM 2048x4096x14336 bf16; overlap schedule (RNG on side stream || GEMM, join, "
                                "attention with mask)",
                    "schedule": "overlap", "seed": wl.SEED, "offset": wl.OFFSET},
-        "roofline": {"bound": "mfma", "kernel": "gemm_tn_kernel<2> (bf16, inside the overlap step, RNG co-running)",
+        "roofline": {"bound": "mfma", "kernel": "gemm_tn_kernel (bf16, inside the overlap step, RNG co-running)",
                      "achieved": gemm_flops / gemm_in_step / 1e9, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": gemm_flops / gemm_in_step / 1e9 / PEAK_BF16_TFLOPS, "traffic": TRAFFIC_GEMM_BYTES},
         "cpu_baseline": cpu,

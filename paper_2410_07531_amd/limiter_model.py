@@ -44,12 +44,19 @@ class Chip:
     # Attention: how much longer the kernel takes than its matrix-core time plus its VALU time (the two
     # pipes are fed by the same two waves per SIMD and overlap little; barriers and the K/V tile waits)
     attention_overhead: float = 1.05
+    # Mask mode beyond its one select per element (fitted: scalar keep-word loads, their waits, and the
+    # SGPR pressure of 64 live word halves): measured 4.6 ms against 3.8 ms without dropout at S = 16384
+    attention_mask_overhead: float = 1.13
     # Memory
     hbm_bytes_per_s: float = 8.0e12
     l2_to_cu_bytes_per_s: float = 13e12      # all CUs streaming GEMM operand slabs (measured inside the GEMM)
     # Interference, measured on the layer step: GEMM beside the small RNG grid, and the small grid's
     # rate relative to the stand-alone RNG kernel (paper Sec. 6.2 reports 4 % and 50 % on GH100).
     gemm_slowdown_beside_rng: float = 0.03
+    # the same two numbers when the RNG runs for the whole duration of the GEMMs (block at S = 16384:
+    # GEMMs 5.12 -> 5.93 ms, RNG 3.1 -> 6.6 ms)
+    gemm_slowdown_rng_throughout: float = 0.16
+    rng_rate_rng_throughout: float = 0.47
     rng_rate_beside_gemm: float = 0.35
     # Fixed costs: kernel launch on a busy stream, and a cross-stream event hop (fork or join).
     launch_s: float = 4e-6
@@ -106,10 +113,11 @@ def t_attention(chip: Chip, B: int, H: int, S: int, d: int, mode: str = "mask", 
     mode: "none" (no dropout), "mask" (drops with stored bits), "fused" (Philox in the kernel)."""
     elems = float(B) * H * S * S * (0.5 + 0.5 / max(S // 256, 1) if causal else 1.0)
     mfma = 4.0 * elems * d / (chip.mfma_flops * 0.80)    # MFMA 32x32x16: 1.66 of 2.05 PFLOP/s sustained
-    # VALU instructions per score element (SQ_INSTS_VALU / elements of the d = 128 kernel: 10.4 without
-    # dropout): scale, running max, subtract, exp2, sum, pack to bf16, the exchange of the row maximum,
-    # address arithmetic, and the rescale of the output accumulator (d / 64 per score element)
-    per_elem = 7.4 * chip.cyc_fp32 + chip.cyc_exp2 + (d / 64.0) * chip.cyc_fp32
+    # VALU instructions per score element, from the d = 128 kernel's loop (141 per 64-key tile and
+    # lane-row of 32 elements): multiply-add into the exponent, exp2, sum, half a max3, half a pack
+    # to bf16, and 0.4 of bookkeeping; the rescale of the output accumulator runs only while the
+    # running maximum still moves (first tiles) and is left out
+    per_elem = 3.4 * chip.cyc_fp32 + chip.cyc_exp2
     if mode != "none":
         per_elem += chip.cyc_fp32                        # one select per element
     if mode == "fused":
@@ -118,8 +126,9 @@ def t_attention(chip: Chip, B: int, H: int, S: int, d: int, mode: str = "mask", 
     valu = elems / 64.0 * per_elem / (_simd_count(chip) * chip.valu_clock_hz)
     mask_bytes = elems / 8.0 if mode == "mask" else 0.0
     hbm = (mask_bytes + 4.0 * B * S * H * d * 2.0) / chip.hbm_bytes_per_s
+    over = chip.attention_overhead * (chip.attention_mask_overhead if mode == "mask" else 1.0)
     return {"mfma": mfma, "valu": valu, "hbm": hbm,
-            "time": max(chip.attention_overhead * (mfma + valu), hbm) + chip.launch_s}
+            "time": max(over * (mfma + valu), hbm) + chip.launch_s}
 
 
 # --------------------------------------------------------------------------- schedules (paper Sec. 3.3)
@@ -136,8 +145,12 @@ def compose(chip: Chip, gemm_times: Sequence[float], rng_time: float, attn_mask_
     if rng_co <= g_co:
         region = g_co
         exposed = 0.0
-    else:                                                 # work left when the GEMMs end, at full rate
-        left = 1.0 - g_co / rng_co
+    else:
+        # the RNG is there for the whole of the GEMMs: they give up more of the (power-limited) clock
+        # and the RNG gets more of the issue slots; what is left when they end runs at full rate
+        g_co = g * (1.0 + chip.gemm_slowdown_rng_throughout)
+        rng_co = rng_time / chip.rng_rate_rng_throughout
+        left = max(0.0, 1.0 - g_co / rng_co)
         exposed = left * rng_time + chip.launch_s
         region = g_co + exposed
     overlap = region + 2.0 * chip.stream_hop_s + attn_mask_time

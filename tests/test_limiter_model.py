@@ -28,12 +28,15 @@ def test_overlap_when_rng_outlasts_the_gemms():
     # Sec. 3.3: what is left of the RNG when the GEMMs end runs at full speed
     g, r = 100e-6, 200e-6
     out = L.compose(C, [g], r, 0.0, 0.0)
-    g_co = g * (1 + C.gemm_slowdown_beside_rng)
-    done = g_co * C.rng_rate_beside_gemm / r                         # fraction produced beside the GEMM
+    g_co = g * (1 + C.gemm_slowdown_rng_throughout)                   # the RNG is there all along
+    done = g_co * C.rng_rate_rng_throughout / r                      # fraction produced beside the GEMM
     assert out["rng_exposed"] == pytest.approx((1 - done) * r + C.launch_s)
     assert out["overlap"] == pytest.approx(g_co + out["rng_exposed"] + 2 * C.stream_hop_s)
     # never worse than doing nothing beside the GEMM, up to the fixed costs
-    assert out["overlap"] <= out["baseline"] + g * C.gemm_slowdown_beside_rng + C.launch_s + 2 * C.stream_hop_s
+    assert out["overlap"] <= out["baseline"] + g * C.gemm_slowdown_rng_throughout + C.launch_s + 2 * C.stream_hop_s
+    # an RNG that only just outlasts the GEMMs is not charged more than all of itself
+    edge = L.compose(C, [g], g * 1.04 * C.rng_rate_beside_gemm, 0.0, 0.0)
+    assert 0.0 <= edge["rng_exposed"] <= edge["baseline"]
     # no GEMM at all: the whole RNG is exposed
     assert L.compose(C, [], r, 0.0, 0.0)["rng_exposed"] == pytest.approx(r + C.launch_s)
 

@@ -19,9 +19,10 @@
 // (ds_read_b64_tr_b16), two per fragment, so V is never copied transposed.
 //
 // A wave owns 32 query rows and walks the keys 64 at a time; the 8 waves of a
-// workgroup (two per SIMD, so one wave's softmax runs under the other's MFMAs)
-// share each K / V tile through LDS (both straight from global memory with
-// global_load_lds).
+// workgroup (two per SIMD: while one waits for LDS or the matrix pipe the other
+// issues) share each K / V tile through LDS, filled straight from global memory
+// with buffer loads that write LDS (two stages, the next tile in flight while
+// the current one is used).
 //
 // Any other case (fp32, other head dimensions) takes a small one-wave-per-row
 // kernel that is correct for every shape.
@@ -63,7 +64,6 @@ typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
-typedef const __attribute__((address_space(1))) void* gptr_t;
 typedef __attribute__((address_space(3))) void* lptr_t;
 
 __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {

@@ -382,6 +382,24 @@ def bench_fp8_layer(torch, rov, wl, main_s, side_s, sync, ev_pair):
             res[name + "_ms"] = median_ms(
                 lambda: rov.layer_step(sched, descs, ad, wl.SEED, 0, None if sched == rov.SCHED_FUSED else mask,
                                        main_s, side_s), 2, 5, sync, ev_pair, inner=2)
+        # fewer Philox rounds (paper Sec. 5.2; its silicon numbers are for 7 rounds)
+        sweep = {}
+        for rounds in (7, 5, 3):
+            r = {"rng_ms": median_ms(lambda: rov.dropout_mask_generate(wl.SEED, 0, B, H, S, p, out=mask, rounds=rounds,
+                                                                               stream=main_s),
+                                     2, 5, sync, ev_pair, inner=2)}
+            for name, sched in (("sequential", rov.SCHED_SEQUENTIAL), ("fused", rov.SCHED_FUSED),
+                                ("overlap", rov.SCHED_OVERLAP)):
+                r[name + "_ms"] = median_ms(
+                    lambda: rov.layer_step(sched, descs, ad, wl.SEED, 0, None if sched == rov.SCHED_FUSED else mask,
+                                           main_s, side_s, rounds=rounds), 2, 5, sync, ev_pair, inner=2)
+            r["speedup_overlap_vs_sequential"] = r["sequential_ms"] / r["overlap_ms"]
+            r["speedup_overlap_vs_fused"] = r["fused_ms"] / r["overlap_ms"]
+            # R16 on the whole step: the RNG time that no longer shows in the step
+            r["rng_hidden_fraction_whole_step"] = (r["sequential_ms"] - r["overlap_ms"]) / r["rng_ms"]
+            sweep["philox_%d" % rounds] = r
+        res["rounds"] = sweep
+    res["rng_hidden_fraction_whole_step"] = (res["sequential_ms"] - res["overlap_ms"]) / t_r
     res.update({"gemms_ms": t_g, "gemms_tflops": flop / t_g / 1e9, "gemms_fp8_mfma_frac": flop / t_g / 1e9 / 5000.0,
                 "rng_ms": t_r, "speedup_overlap_vs_sequential": res["sequential_ms"] / res["overlap_ms"],
                 "speedup_overlap_vs_fused": res["fused_ms"] / res["overlap_ms"]})

@@ -185,6 +185,15 @@ int rov_attention_fwd_dropout(const void *Q, const void *K, const void *V, void 
                               int dtype, int causal, float p, const uint64_t *mask,
                               uint64_t seed, uint64_t offset, void *stream);
 
+/* Same with a selectable Philox round count for the fused variant (paper Sec. 5.2): with
+ * mask == NULL and p > 0 the kernel draws the bits of
+ * rov_dropout_mask_generate_rounds(seed, offset, ..., rounds).  rounds in {3, 5, 7, 10}; with a
+ * mask, or p == 0, the value is only checked. */
+int rov_attention_fwd_dropout_rounds(const void *Q, const void *K, const void *V, void *O,
+                                     int B, int H, int Hkv, int S, int d, const int64_t strides[12],
+                                     int dtype, int causal, float p, const uint64_t *mask,
+                                     uint64_t seed, uint64_t offset, int rounds, void *stream);
+
 /* Same for query rows [q_begin, min(q_begin + q_rows, S)) only: those rows of O are written,
  * the others are left alone.  mask_rows (may be NULL: fused variant) holds just the tile rows
  * of that range, as written by rov_dropout_mask_generate_rows with the same q_begin, q_rows.
@@ -234,6 +243,16 @@ typedef struct rov_attn_desc {
 int rov_layer_step(int schedule, const rov_gemm_desc *gemms, int n_gemms, const rov_attn_desc *attn,
                    uint64_t seed, uint64_t offset, uint64_t *mask, void *main_stream,
                    void *side_stream);
+
+/* rov_layer_step with a selectable Philox round count (paper Sec. 5.2: fewer rounds shrink both
+ * the stand-alone RNG kernel and the fused attention kernel, and with them what the overlap
+ * schedule has to hide).  rounds in {3, 5, 7, 10} applies to the mask kernel (SEQUENTIAL, OVERLAP)
+ * and to the in-kernel generation (FUSED) alike, so the three schedules still drop the same
+ * elements: those of rov_dropout_mask_generate_rounds(seed, offset, ..., rounds).  rounds == 10 is
+ * rov_layer_step.  Other values: ROV_ERR_INVALID. */
+int rov_layer_step_rounds(int schedule, const rov_gemm_desc *gemms, int n_gemms,
+                          const rov_attn_desc *attn, uint64_t seed, uint64_t offset, int rounds,
+                          uint64_t *mask, void *main_stream, void *side_stream);
 
 /* The overlap schedule with the mask pipelined in chunks of q_chunk_rows query rows (paper
  * Sec. 7.2, sequence chunking): mask_ring holds two slots of

@@ -82,6 +82,11 @@ SIGNATURES = {
                                        ctypes.POINTER(ctypes.c_int64), _i, _i, _f, _p, _u64, _u64, _p]),
     "rov_layer_step": (_i, [_i, ctypes.POINTER(GemmDesc), _i, ctypes.POINTER(AttnDesc), _u64, _u64,
                             _p, _p, _p]),
+    "rov_layer_step_rounds": (_i, [_i, ctypes.POINTER(GemmDesc), _i, ctypes.POINTER(AttnDesc), _u64, _u64,
+                                   _i, _p, _p, _p]),
+    "rov_attention_fwd_dropout_rounds": (_i, [_p, _p, _p, _p, _i, _i, _i, _i, _i,
+                                              ctypes.POINTER(ctypes.c_int64), _i, _i, _f, _p, _u64, _u64, _i,
+                                              _p]),
     "rov_block_workspace_bytes": (ctypes.c_size_t, [ctypes.POINTER(BlockCfg), _i, _i, _i]),
     "rov_block_forward": (_i, [ctypes.POINTER(BlockWeights), _p, _p, _i, _i, ctypes.POINTER(BlockCfg),
                                _i, _u64, _u64, _i, _p, _p, _p, ctypes.c_size_t, _p, _p]),
@@ -226,8 +231,10 @@ def _strides12(Q, K, V, O):
     return arr
 
 
-def attention_fwd_dropout(Q, K, V, p, mask=None, seed=0, offset=0, causal=False, O=None, stream=None):
-    """Q [B,S,H,d], K/V [B,S,Hkv,d] -> O [B,S,H,d]; mask=None with p>0 selects the fused variant."""
+def attention_fwd_dropout(Q, K, V, p, mask=None, seed=0, offset=0, causal=False, O=None, stream=None,
+                          rounds=None):
+    """Q [B,S,H,d], K/V [B,S,Hkv,d] -> O [B,S,H,d]; mask=None with p>0 selects the fused variant
+    (rounds: its Philox round count, 3/5/7/10; None = the 10-round entry point)."""
     import torch
     B, S, H, d = Q.shape
     Hkv = K.shape[2]
@@ -235,6 +242,13 @@ def attention_fwd_dropout(Q, K, V, p, mask=None, seed=0, offset=0, causal=False,
         O = torch.empty_like(Q)
     strides = _strides12(Q, K, V, O)
     mptr = ctypes.c_void_p(mask.data_ptr()) if mask is not None else ctypes.c_void_p(0)
+    if rounds is not None:
+        _check(load().rov_attention_fwd_dropout_rounds(
+            ctypes.c_void_p(Q.data_ptr()), ctypes.c_void_p(K.data_ptr()), ctypes.c_void_p(V.data_ptr()),
+            ctypes.c_void_p(O.data_ptr()), B, H, Hkv, S, d, strides, _dtype_code(Q), int(bool(causal)),
+            float(p), mptr, seed & (2**64 - 1), offset & (2**64 - 1), int(rounds), _stream_ptr(stream)),
+            "rov_attention_fwd_dropout_rounds")
+        return O
     _check(load().rov_attention_fwd_dropout(
         ctypes.c_void_p(Q.data_ptr()), ctypes.c_void_p(K.data_ptr()), ctypes.c_void_p(V.data_ptr()),
         ctypes.c_void_p(O.data_ptr()), B, H, Hkv, S, d, strides, _dtype_code(Q), int(bool(causal)), float(p),
@@ -302,9 +316,15 @@ def make_attn_desc(Q, K, V, O, p, causal=False):
     return desc
 
 
-def layer_step(schedule, gemm_descs, attn_desc, seed, offset, mask, main_stream, side_stream):
+def layer_step(schedule, gemm_descs, attn_desc, seed, offset, mask, main_stream, side_stream, rounds=None):
     arr = (GemmDesc * len(gemm_descs))(*gemm_descs)
     mptr = ctypes.c_void_p(mask.data_ptr()) if mask is not None else ctypes.c_void_p(0)
+    if rounds is not None:
+        _check(load().rov_layer_step_rounds(int(schedule), arr, len(gemm_descs), ctypes.byref(attn_desc),
+                                            seed & (2**64 - 1), offset & (2**64 - 1), int(rounds), mptr,
+                                            _stream_ptr(main_stream), _stream_ptr(side_stream)),
+               "rov_layer_step_rounds")
+        return
     _check(load().rov_layer_step(int(schedule), arr, len(gemm_descs), ctypes.byref(attn_desc),
                                  seed & (2**64 - 1), offset & (2**64 - 1), mptr,
                                  _stream_ptr(main_stream), _stream_ptr(side_stream)), "rov_layer_step")

@@ -57,6 +57,7 @@ struct AttnParams {
     uint64_t offset;                      // Philox call offset (fused)
     uint32_t k0, k1;                      // Philox key (fused)
     uint32_t t_minus_1;                   // keep iff x <= t_minus_1 (fused)
+    int rounds;                           // Philox rounds (fused)
 };
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
@@ -169,7 +170,7 @@ __device__ __forceinline__ bf16x4 lds_read_transposed(const char* p) {
 // NW waves per workgroup, each owning NQ*32 query rows.  (NQ, NW) = (2, 4) keeps one wave per
 // SIMD with K/V fragments reused for two query tiles; (1, 8) puts two waves on every SIMD so
 // that one wave's softmax VALU work runs under the other's MFMAs.
-template <int D, int NQ, int NW, int MODE>
+template <int D, int NQ, int NW, int MODE, int R = 10>
 __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(const AttnParams p) {
     constexpr int BQ = NW * 32 * NQ;   // query rows per workgroup
     using T = Tile<D>;
@@ -414,9 +415,9 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(const AttnParams p) 
                         const uint32_t c0 = blo + (uint32_t)lane;
                         uint32_t x[4];
                         if (blo <= 0xFFFFFFFFu - 63u) {
-                            philox4x32_low_counter<10>(c0, bhi, p.k0, p.k1, x);
+                            philox4x32_low_counter<R>(c0, bhi, p.k0, p.k1, x);
                         } else {
-                            philox4x32<10>(c0, bhi + (c0 < blo ? 1u : 0u), 0u, 0u, p.k0, p.k1, x);
+                            philox4x32<R>(c0, bhi + (c0 < blo ? 1u : 0u), 0u, 0u, p.k0, p.k1, x);
                         }
 #pragma unroll
                         for (int r = 0; r < 4; ++r)
@@ -580,7 +581,7 @@ __global__ __launch_bounds__(256) void attn_generic_kernel(const AttnParams p) {
                 } else if (MODE == MODE_FUSED) {
                     const uint64_t ncall = p.offset + 64u * (w >> 2) + (uint64_t)bit;
                     uint32_t x[4];
-                    philox4x32<10>((uint32_t)ncall, (uint32_t)(ncall >> 32), 0u, 0u, p.k0, p.k1, x);
+                    philox4x32_dyn(p.rounds, (uint32_t)ncall, (uint32_t)(ncall >> 32), 0u, 0u, p.k0, p.k1, x);
                     const uint32_t sel = (uint32_t)(w & 3u);
                     const uint32_t xv = sel == 0 ? x[0] : sel == 1 ? x[1] : sel == 2 ? x[2] : x[3];
                     keep = xv <= p.t_minus_1;
@@ -621,9 +622,17 @@ int launch_bf16(const AttnParams& prm, int mode, hipStream_t stream) {
     if (nblocks > 0x7FFFFFFFLL) return ROV_ERR_UNSUPPORTED;
     const dim3 grid((unsigned)nblocks), block(NW * 64);
     const int lds_bytes = 2 * Tile<D>::kStage;   // two K/V stages
-    void (*kern)(const AttnParams) = mode == MODE_NONE   ? attn_bf16_kernel<D, NQ, NW, MODE_NONE>
-                                     : mode == MODE_MASK ? attn_bf16_kernel<D, NQ, NW, MODE_MASK>
-                                                         : attn_bf16_kernel<D, NQ, NW, MODE_FUSED>;
+    void (*kern)(const AttnParams) = mode == MODE_NONE ? attn_bf16_kernel<D, NQ, NW, MODE_NONE>
+                                                       : attn_bf16_kernel<D, NQ, NW, MODE_MASK>;
+    if (mode == MODE_FUSED) {   // the round count is a compile-time constant of the fused kernel
+        switch (prm.rounds) {
+            case 10: kern = attn_bf16_kernel<D, NQ, NW, MODE_FUSED, 10>; break;
+            case 7: kern = attn_bf16_kernel<D, NQ, NW, MODE_FUSED, 7>; break;
+            case 5: kern = attn_bf16_kernel<D, NQ, NW, MODE_FUSED, 5>; break;
+            case 3: kern = attn_bf16_kernel<D, NQ, NW, MODE_FUSED, 3>; break;
+            default: return ROV_ERR_INVALID;
+        }
+    }
     ROV_HIP_TRY(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
                                     lds_bytes));
     hipLaunchKernelGGL(kern, grid, block, lds_bytes, stream, prm2);
@@ -648,15 +657,16 @@ int launch_generic(const AttnParams& prm, int mode, hipStream_t stream) {
 
 int launch_attention(const void* Q, const void* K, const void* V, void* O, int B, int H, int Hkv,
                      int S, int d, const int64_t strides[12], int dtype, int causal, float p,
-                     const uint64_t* mask, uint64_t seed, uint64_t offset, hipStream_t stream) {
+                     const uint64_t* mask, uint64_t seed, uint64_t offset, hipStream_t stream, int rounds) {
     return launch_attention_rows(Q, K, V, O, B, H, Hkv, S, d, strides, dtype, causal, p, mask, false, seed,
-                                 offset, 0, S, stream);
+                                 offset, 0, S, stream, rounds);
 }
 
 int launch_attention_rows(const void* Q, const void* K, const void* V, void* O, int B, int H, int Hkv,
                           int S, int d, const int64_t strides[12], int dtype, int causal, float p,
                           const uint64_t* mask, bool mask_is_rows, uint64_t seed, uint64_t offset,
-                          int q_begin, int q_rows, hipStream_t stream) {
+                          int q_begin, int q_rows, hipStream_t stream, int rounds) {
+    if (rounds != 10 && rounds != 7 && rounds != 5 && rounds != 3) return ROV_ERR_INVALID;
     if (S <= 0 || q_begin < 0 || q_rows <= 0 || q_begin >= S || (q_begin & 31) != 0) return ROV_ERR_INVALID;
     if (Q == nullptr || K == nullptr || V == nullptr || O == nullptr || strides == nullptr)
         return ROV_ERR_INVALID;
@@ -687,6 +697,7 @@ int launch_attention_rows(const void* Q, const void* K, const void* V, void* O, 
     prm.offset = offset;
     prm.k0 = (uint32_t)seed; prm.k1 = (uint32_t)(seed >> 32);
     prm.t_minus_1 = tm1;
+    prm.rounds = rounds;
     const int mode = p == 0.0f ? MODE_NONE : (mask != nullptr ? MODE_MASK : MODE_FUSED);
 
     if (dtype == ROV_BF16 && (d == 64 || d == 128)) {
@@ -724,4 +735,12 @@ extern "C" int rov_attention_fwd_dropout(const void* Q, const void* K, const voi
                                          uint64_t seed, uint64_t offset, void* stream) {
     return rov::launch_attention(Q, K, V, O, B, H, Hkv, S, d, strides, dtype, causal, p, mask, seed,
                                  offset, (hipStream_t)stream);
+}
+
+extern "C" int rov_attention_fwd_dropout_rounds(const void* Q, const void* K, const void* V, void* O, int B,
+                                                int H, int Hkv, int S, int d, const int64_t strides[12],
+                                                int dtype, int causal, float p, const uint64_t* mask,
+                                                uint64_t seed, uint64_t offset, int rounds, void* stream) {
+    return rov::launch_attention(Q, K, V, O, B, H, Hkv, S, d, strides, dtype, causal, p, mask, seed,
+                                 offset, (hipStream_t)stream, rounds);
 }

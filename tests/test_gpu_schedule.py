@@ -62,6 +62,58 @@ def test_layer_step_three_schedules(dtype, B, S, H, Hkv, d, gemm):
     assert np.max(np.abs(_f64(cs[0]) - refc)) / np.max(np.abs(refc)) <= (6e-3 if dtype == torch.bfloat16 else 1e-5)
 
 
+@pytest.mark.parametrize("rounds", [3, 5, 7, 10])
+@pytest.mark.parametrize("dtype,d", [(torch.bfloat16, 128), (torch.float32, 64)])
+def test_layer_step_rounds_three_schedules(rounds, dtype, d):
+    # fewer Philox rounds (paper Sec. 5.2): the mask kernel and the fused attention must still drop
+    # the same elements, those of the oracle's mask with that round count
+    B, S, H, Hkv = 1, 320, 2, 1
+    rng = np.random.default_rng(21)
+    q, k, v = wl.qkv(rng, B, S, H, Hkv, d)
+    Q, K, V = _dev(q, dtype), _dev(k, dtype), _dev(v, dtype)
+    a, w = wl.gemm_operands(rng, 256, 256, 256)
+    A, W = _dev(a, dtype), _dev(w, dtype)
+    p, seed, offset = 0.3, 77, wl.CARRY_OFFSET - 640        # the mask's calls cross 2^32
+    words = OP.dropout_mask(seed, offset, B, H, S, p, rounds=rounds)
+    if rounds != 10:
+        assert not np.array_equal(words, OP.dropout_mask(seed, offset, B, H, S, p))
+    main, side = torch.cuda.Stream(), torch.cuda.Stream()
+    outs = []
+    for sched in (rov.SCHED_SEQUENTIAL, rov.SCHED_FUSED, rov.SCHED_OVERLAP):
+        print("layer_step_rounds", rounds, dtype, sched, flush=True)
+        O = torch.zeros_like(Q)
+        C = torch.zeros((256, 256), dtype=dtype, device="cuda")
+        mask = torch.zeros(rov.mask_shape(B, H, S), dtype=torch.int64, device="cuda")
+        torch.cuda.synchronize()
+        rov.layer_step(sched, [rov.make_gemm_desc(A, W, C)], rov.make_attn_desc(Q, K, V, O, p), seed, offset,
+                       None if sched == rov.SCHED_FUSED else mask, main, side, rounds=rounds)
+        torch.cuda.synchronize()
+        outs.append(O)
+        if sched != rov.SCHED_FUSED:
+            assert np.array_equal(mask.cpu().numpy().view(np.uint64), words)
+    assert torch.equal(outs[0], outs[1]) and torch.equal(outs[0], outs[2])
+    ref = OD.attention_dropout(_f64(Q), _f64(K), _f64(V), OP.unpack_keep(words, S), p)
+    tol = 2e-2 if dtype == torch.bfloat16 else 1e-4
+    assert np.max(np.abs(_f64(outs[0]) - ref)) / np.max(np.abs(ref)) <= tol
+    # the stand-alone attention entry point with a round count: same bits as the mask of that count
+    O2 = rov.attention_fwd_dropout(Q, K, V, p, seed=seed, offset=offset, rounds=rounds)
+    torch.cuda.synchronize()
+    assert torch.equal(O2, outs[0])
+
+
+def test_layer_step_rounds_rejects_other_counts():
+    Q = torch.zeros((1, 64, 1, 64), dtype=torch.bfloat16, device="cuda")
+    O = torch.zeros_like(Q)
+    main, side = torch.cuda.Stream(), torch.cuda.Stream()
+    mask = torch.zeros(rov.mask_shape(1, 1, 64), dtype=torch.int64, device="cuda")
+    for bad in (0, 4, 6, 11, -7):
+        with pytest.raises(rov.RovError):
+            rov.layer_step(rov.SCHED_OVERLAP, [], rov.make_attn_desc(Q, Q, Q, O, 0.1), 1, 0, mask, main, side,
+                           rounds=bad)
+        with pytest.raises(rov.RovError):
+            rov.attention_fwd_dropout(Q, Q, Q, 0.1, seed=1, offset=0, rounds=bad)
+
+
 def test_layer_step_invalid_arguments():
     Q = torch.zeros((1, 64, 2, 64), dtype=torch.bfloat16, device="cuda")
     O = torch.zeros_like(Q)

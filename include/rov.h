@@ -254,6 +254,15 @@ int rov_layer_step_rounds(int schedule, const rov_gemm_desc *gemms, int n_gemms,
                           const rov_attn_desc *attn, uint64_t seed, uint64_t offset, int rounds,
                           uint64_t *mask, void *main_stream, void *side_stream);
 
+/* rov_layer_step with `bits` (8, 16 or 32) random bits per element for the mask kernel, the
+ * other way of shrinking the RNG (paper Sec. 5.2): SEQUENTIAL and OVERLAP drop the elements of
+ * rov_dropout_mask_generate_bits(seed, offset, ..., bits).  The fused kernel has no narrow form:
+ * ROV_SCHED_FUSED with bits != 32 returns ROV_ERR_UNSUPPORTED.  bits == 32 is rov_layer_step.
+ * Other values: ROV_ERR_INVALID. */
+int rov_layer_step_bits(int schedule, const rov_gemm_desc *gemms, int n_gemms,
+                        const rov_attn_desc *attn, uint64_t seed, uint64_t offset, int bits,
+                        uint64_t *mask, void *main_stream, void *side_stream);
+
 /* The overlap schedule with the mask pipelined in chunks of q_chunk_rows query rows (paper
  * Sec. 7.2, sequence chunking): mask_ring holds two slots of
  * rov_mask_words_rows(B,H,S,0,q_chunk_rows) words instead of the whole mask.  Chunks 0 and 1 are

@@ -84,6 +84,8 @@ SIGNATURES = {
                             _p, _p, _p]),
     "rov_layer_step_rounds": (_i, [_i, ctypes.POINTER(GemmDesc), _i, ctypes.POINTER(AttnDesc), _u64, _u64,
                                    _i, _p, _p, _p]),
+    "rov_layer_step_bits": (_i, [_i, ctypes.POINTER(GemmDesc), _i, ctypes.POINTER(AttnDesc), _u64, _u64,
+                                 _i, _p, _p, _p]),
     "rov_attention_fwd_dropout_rounds": (_i, [_p, _p, _p, _p, _i, _i, _i, _i, _i,
                                               ctypes.POINTER(ctypes.c_int64), _i, _i, _f, _p, _u64, _u64, _i,
                                               _p]),
@@ -316,9 +318,16 @@ def make_attn_desc(Q, K, V, O, p, causal=False):
     return desc
 
 
-def layer_step(schedule, gemm_descs, attn_desc, seed, offset, mask, main_stream, side_stream, rounds=None):
+def layer_step(schedule, gemm_descs, attn_desc, seed, offset, mask, main_stream, side_stream, rounds=None,
+               bits=None):
     arr = (GemmDesc * len(gemm_descs))(*gemm_descs)
     mptr = ctypes.c_void_p(mask.data_ptr()) if mask is not None else ctypes.c_void_p(0)
+    if bits is not None:
+        _check(load().rov_layer_step_bits(int(schedule), arr, len(gemm_descs), ctypes.byref(attn_desc),
+                                          seed & (2**64 - 1), offset & (2**64 - 1), int(bits), mptr,
+                                          _stream_ptr(main_stream), _stream_ptr(side_stream)),
+               "rov_layer_step_bits")
+        return
     if rounds is not None:
         _check(load().rov_layer_step_rounds(int(schedule), arr, len(gemm_descs), ctypes.byref(attn_desc),
                                             seed & (2**64 - 1), offset & (2**64 - 1), int(rounds), mptr,

@@ -342,12 +342,11 @@ int launch_mask_r(uint64_t* out, uint64_t words, uint64_t offset, uint32_t k0, u
 
 template <int BITS>
 int launch_mask_bits_b(uint64_t* out, uint64_t words, uint64_t offset, uint32_t k0, uint32_t k1,
-                       uint32_t tb, int S, hipStream_t stream) {
+                       uint32_t tb, int S, int grid_mode, hipStream_t stream) {
     const uint32_t T = (uint32_t)(((uint64_t)S + 31u) / 32u);
     const uint64_t nchunks = (words + 63u) / 64u;
     uint64_t blocks = (nchunks + kWavesPerBlock - 1) / kWavesPerBlock;
-    int cap = g_rng_max_workgroups.load();
-    if (cap <= 0) cap = device_cu_count() * 64;
+    const int cap = mask_grid_cap(grid_mode);
     if (blocks > (uint64_t)cap) blocks = (uint64_t)cap;
     const dim3 grid((unsigned)blocks), block(kWavesPerBlock * 64);
     if ((S & 31) == 0) {
@@ -436,6 +435,25 @@ int launch_mask_rows(uint64_t seed, uint64_t offset, int B, int H, int S, float 
     return ROV_OK;
 }
 
+// `bits` (8 or 16; 32 = launch_mask) random bits per element; grid stride only (no work queue):
+// beside a GEMM the grid is the small persistent one and simply runs until it is done.
+int launch_mask_bits(uint64_t seed, uint64_t offset, int B, int H, int S, float p, int bits, uint64_t* out,
+                     hipStream_t stream, int grid_mode) {
+    if (bits == 32) return launch_mask(seed, offset, B, H, S, p, 10, out, stream, grid_mode, -1, false);
+    if (bits != 8 && bits != 16) return ROV_ERR_INVALID;
+    if (B <= 0 || H <= 0 || S <= 0 || out == nullptr || !aligned(out, 8)) return ROV_ERR_INVALID;
+    if (!(p >= 0.0f) || !(p < 1.0f)) return ROV_ERR_INVALID;
+    const uint64_t T = ((uint64_t)S + 31u) / 32u;
+    const long double wd = (long double)B * H * T * T * 16.0L;
+    if (wd > 1099511627776.0L) return ROV_ERR_UNSUPPORTED;
+    const uint64_t words = (uint64_t)B * (uint64_t)H * T * T * 16u;
+    // keep iff field < Tb, Tb = floor((1 - p) * 2^bits) in double from the float p (0 <= Tb <= 2^bits)
+    const uint32_t tb = (uint32_t)(uint64_t)((1.0 - (double)p) * (double)(1u << bits));
+    const uint32_t k0 = (uint32_t)seed, k1 = (uint32_t)(seed >> 32);
+    return bits == 8 ? launch_mask_bits_b<8>(out, words, offset, k0, k1, tb, S, grid_mode, stream)
+                     : launch_mask_bits_b<16>(out, words, offset, k0, k1, tb, S, grid_mode, stream);
+}
+
 }  // namespace rov
 
 extern "C" {
@@ -512,20 +530,7 @@ uint64_t rov_mask_philox_calls_bits(int B, int H, int S, int bits) {
 
 int rov_dropout_mask_generate_bits(uint64_t seed, uint64_t offset, int B, int H, int S, float p,
                                    int bits, uint64_t* out, void* stream) {
-    using namespace rov;
-    if (bits == 32) return launch_mask(seed, offset, B, H, S, p, 10, out, (hipStream_t)stream);
-    if (bits != 8 && bits != 16) return ROV_ERR_INVALID;
-    if (B <= 0 || H <= 0 || S <= 0 || out == nullptr || !aligned(out, 8)) return ROV_ERR_INVALID;
-    if (!(p >= 0.0f) || !(p < 1.0f)) return ROV_ERR_INVALID;
-    const uint64_t T = ((uint64_t)S + 31u) / 32u;
-    const long double wd = (long double)B * H * T * T * 16.0L;
-    if (wd > 1099511627776.0L) return ROV_ERR_UNSUPPORTED;
-    const uint64_t words = (uint64_t)B * (uint64_t)H * T * T * 16u;
-    // keep iff field < Tb, Tb = floor((1 - p) * 2^bits) in double from the float p (0 <= Tb <= 2^bits)
-    const uint32_t tb = (uint32_t)(uint64_t)((1.0 - (double)p) * (double)(1u << bits));
-    const uint32_t k0 = (uint32_t)seed, k1 = (uint32_t)(seed >> 32);
-    return bits == 8 ? launch_mask_bits_b<8>(out, words, offset, k0, k1, tb, S, (hipStream_t)stream)
-                     : launch_mask_bits_b<16>(out, words, offset, k0, k1, tb, S, (hipStream_t)stream);
+    return rov::launch_mask_bits(seed, offset, B, H, S, p, bits, out, (hipStream_t)stream, rov::MASK_GRID_FULL);
 }
 
 }  // extern "C"

@@ -47,6 +47,10 @@ int mask_queue_acquire(hipStream_t stream, int* slot);
 int launch_mask(uint64_t seed, uint64_t offset, int B, int H, int S, float p, int rounds,
                 uint64_t* out, hipStream_t stream, int grid_mode = MASK_GRID_FULL, int qslot = -1,
                 bool lower_only = false);
+
+// Same layout with `bits` (8, 16 or 32) random bits per element; grid stride, no work queue.
+int launch_mask_bits(uint64_t seed, uint64_t offset, int B, int H, int S, float p, int bits, uint64_t* out,
+                     hipStream_t stream, int grid_mode);
 // Tile rows [q_begin/32, ceil(min(q_begin+q_rows, S)/32)) of every (batch, head), compact
 // [B*H][nqt][T][16], same bits as the full mask.
 int launch_mask_rows(uint64_t seed, uint64_t offset, int B, int H, int S, float p, int q_begin,

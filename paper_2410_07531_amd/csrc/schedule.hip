@@ -83,8 +83,9 @@ int t_gemm(const void* A, const void* Bm, void* C, const void* R, int M, int N, 
 }
 
 int t_mask(uint64_t seed, uint64_t offset, int B, int H, int S, float p, uint64_t* out, hipStream_t st,
-           int grid_mode, int qslot, bool lower_only, int rounds = 10) {
+           int grid_mode, int qslot, bool lower_only, int rounds = 10, int bits = 32) {
     return traced(grid_mode == MASK_GRID_HELPER ? ROV_TRACE_RNG_HELPER : ROV_TRACE_RNG, st, [&] {
+        if (bits != 32) return launch_mask_bits(seed, offset, B, H, S, p, bits, out, st, grid_mode);
         return launch_mask(seed, offset, B, H, S, p, rounds, out, st, grid_mode, qslot, lower_only);
     });
 }
@@ -132,11 +133,15 @@ bool block_layout(const rov_block_cfg* c, int B, int S, BlockLayout* L) {
 }  // namespace
 }  // namespace rov
 
-extern "C" int rov_layer_step_rounds(int schedule, const rov_gemm_desc* gemms, int n_gemms,
-                                     const rov_attn_desc* attn, uint64_t seed, uint64_t offset, int rounds,
-                                     uint64_t* mask, void* main_stream, void* side_stream) {
-    using namespace rov;
+namespace rov {
+namespace {
+// The layer step for a round count (32 random bits per element) or a width (10 rounds).
+int layer_step_impl(int schedule, const rov_gemm_desc* gemms, int n_gemms, const rov_attn_desc* attn,
+                    uint64_t seed, uint64_t offset, int rounds, int bits, uint64_t* mask, void* main_stream,
+                    void* side_stream) {
     if (rounds != 10 && rounds != 7 && rounds != 5 && rounds != 3) return ROV_ERR_INVALID;
+    if (bits != 32 && bits != 16 && bits != 8) return ROV_ERR_INVALID;
+    if (bits != 32 && (rounds != 10 || schedule == ROV_SCHED_FUSED)) return ROV_ERR_UNSUPPORTED;
     if (!valid_schedule(schedule) || attn == nullptr || n_gemms < 0 || (n_gemms > 0 && gemms == nullptr))
         return ROV_ERR_INVALID;
     for (int i = 0; i < n_gemms; ++i) {
@@ -165,7 +170,8 @@ extern "C" int rov_layer_step_rounds(int schedule, const rov_gemm_desc* gemms, i
             fp32 = fp32 || gemms[i].dtype == ROV_F32;
         }
         const double calls = (double)rov_mask_philox_calls(attn->B, attn->H, attn->S) * (attn->causal ? 0.5 : 1.0);
-        if (!rng_fits_beside(flop, fp32, calls * (0.25 + 0.075 * rounds))) {   // cost per call ~ rounds
+        // (cost per call ~ rounds; the narrower kernels have no work-queue form and simply run on)
+        if (bits == 32 && !rng_fits_beside(flop, fp32, calls * (0.25 + 0.075 * rounds))) {
             rc = mask_queue_acquire(ms, &qslot);   // reset here: ordered before both RNG launches
             if (rc != ROV_OK) return rc;
         }
@@ -192,7 +198,7 @@ extern "C" int rov_layer_step_rounds(int schedule, const rov_gemm_desc* gemms, i
             if (rc != ROV_OK) return rc;
         }
         rc = t_mask(seed, offset, attn->B, attn->H, attn->S, attn->p, mask, ss, MASK_GRID_BESIDE, qslot,
-                    attn->causal != 0, rounds);
+                    attn->causal != 0, rounds, bits);
         if (rc != ROV_OK) return rc;
         ROV_HIP_TRY(hipEventRecord(ev->join, ss));
         for (int i = 1; i < n_gemms; ++i) {
@@ -204,7 +210,7 @@ extern "C" int rov_layer_step_rounds(int schedule, const rov_gemm_desc* gemms, i
         // (paper Sec. 3.3); waves of this launch leave at once if the queue is already empty
         if (qslot >= 0) {
             rc = t_mask(seed, offset, attn->B, attn->H, attn->S, attn->p, mask, ms, MASK_GRID_HELPER, qslot,
-                        attn->causal != 0, rounds);
+                        attn->causal != 0, rounds, bits);
             if (rc != ROV_OK) return rc;
         }
         ROV_HIP_TRY(hipStreamWaitEvent(ms, ev->join, 0));
@@ -213,7 +219,7 @@ extern "C" int rov_layer_step_rounds(int schedule, const rov_gemm_desc* gemms, i
         if (rc != ROV_OK) return rc;
         if (need_mask) {
             rc = t_mask(seed, offset, attn->B, attn->H, attn->S, attn->p, mask, ms, MASK_GRID_FULL, -1,
-                        attn->causal != 0, rounds);
+                        attn->causal != 0, rounds, bits);
             if (rc != ROV_OK) return rc;
         }
     }
@@ -224,11 +230,28 @@ extern "C" int rov_layer_step_rounds(int schedule, const rov_gemm_desc* gemms, i
     });
 }
 
+}  // namespace
+}  // namespace rov
+
 extern "C" int rov_layer_step(int schedule, const rov_gemm_desc* gemms, int n_gemms,
                               const rov_attn_desc* attn, uint64_t seed, uint64_t offset,
                               uint64_t* mask, void* main_stream, void* side_stream) {
-    return rov_layer_step_rounds(schedule, gemms, n_gemms, attn, seed, offset, 10, mask, main_stream,
-                                 side_stream);
+    return rov::layer_step_impl(schedule, gemms, n_gemms, attn, seed, offset, 10, 32, mask, main_stream,
+                                side_stream);
+}
+
+extern "C" int rov_layer_step_rounds(int schedule, const rov_gemm_desc* gemms, int n_gemms,
+                                     const rov_attn_desc* attn, uint64_t seed, uint64_t offset, int rounds,
+                                     uint64_t* mask, void* main_stream, void* side_stream) {
+    return rov::layer_step_impl(schedule, gemms, n_gemms, attn, seed, offset, rounds, 32, mask, main_stream,
+                                side_stream);
+}
+
+extern "C" int rov_layer_step_bits(int schedule, const rov_gemm_desc* gemms, int n_gemms,
+                                   const rov_attn_desc* attn, uint64_t seed, uint64_t offset, int bits,
+                                   uint64_t* mask, void* main_stream, void* side_stream) {
+    return rov::layer_step_impl(schedule, gemms, n_gemms, attn, seed, offset, 10, bits, mask, main_stream,
+                                side_stream);
 }
 
 extern "C" int rov_layer_step_chunked(const rov_gemm_desc* gemms, int n_gemms, const rov_attn_desc* attn,

@@ -101,6 +101,44 @@ def test_layer_step_rounds_three_schedules(rounds, dtype, d):
     assert torch.equal(O2, outs[0])
 
 
+@pytest.mark.parametrize("bits", [8, 16, 32])
+def test_layer_step_bits_sequential_and_overlap(bits):
+    # narrower random numbers (paper Sec. 5.2): both mask-based schedules write the oracle's mask of
+    # that width and drop exactly its elements; the fused schedule has no such form
+    B, S, H, Hkv, d, dtype = 1, 320, 2, 2, 128, torch.bfloat16
+    rng = np.random.default_rng(22)
+    q, k, v = wl.qkv(rng, B, S, H, Hkv, d)
+    Q, K, V = _dev(q, dtype), _dev(k, dtype), _dev(v, dtype)
+    a, w = wl.gemm_operands(rng, 256, 256, 256)
+    A, W = _dev(a, dtype), _dev(w, dtype)
+    p, seed, offset = 0.1, 78, 12345
+    words = OP.dropout_mask_bits(seed, offset, B, H, S, p, bits)
+    main, side = torch.cuda.Stream(), torch.cuda.Stream()
+    outs = []
+    for sched in (rov.SCHED_SEQUENTIAL, rov.SCHED_OVERLAP):
+        print("layer_step_bits", bits, sched, flush=True)
+        O = torch.zeros_like(Q)
+        C = torch.zeros((256, 256), dtype=dtype, device="cuda")
+        mask = torch.zeros(rov.mask_shape(B, H, S), dtype=torch.int64, device="cuda")
+        torch.cuda.synchronize()
+        rov.layer_step(sched, [rov.make_gemm_desc(A, W, C)], rov.make_attn_desc(Q, K, V, O, p), seed, offset, mask,
+                       main, side, bits=bits)
+        torch.cuda.synchronize()
+        assert np.array_equal(mask.cpu().numpy().view(np.uint64), words)
+        outs.append(O)
+    assert torch.equal(outs[0], outs[1])
+    ref = OD.attention_dropout(_f64(Q), _f64(K), _f64(V), OP.unpack_keep(words, S), p)
+    assert np.max(np.abs(_f64(outs[0]) - ref)) / np.max(np.abs(ref)) <= 2e-2
+    O = torch.zeros_like(Q)
+    if bits != 32:
+        with pytest.raises(rov.RovError):
+            rov.layer_step(rov.SCHED_FUSED, [], rov.make_attn_desc(Q, K, V, O, p), seed, offset, None, main, side,
+                           bits=bits)
+    with pytest.raises(rov.RovError):
+        rov.layer_step(rov.SCHED_OVERLAP, [], rov.make_attn_desc(Q, K, V, O, p), seed, offset, mask, main, side,
+                       bits=12)
+
+
 def test_layer_step_rounds_rejects_other_counts():
     Q = torch.zeros((1, 64, 1, 64), dtype=torch.bfloat16, device="cuda")
     O = torch.zeros_like(Q)

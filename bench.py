@@ -371,6 +371,7 @@ def bench_fp8_layer(torch, rov, wl, main_s, side_s, sync, ev_pair):
     mask = torch.empty(rov.mask_shape(B, H, S), dtype=torch.int64, device="cuda")
     ad = rov.make_attn_desc(Q, Kt, V, O, p)
     res = {}
+    sync()   # the inputs were produced on torch's current stream
     with torch.cuda.stream(main_s):
         def gemms_only():
             for g in descs:

@@ -136,7 +136,8 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(const T* __restrict__
 
 // ------------------------------------------------------------------ MFMA kernel (bf16 / fp8)
 constexpr int BM = 256, BN = 256;
-constexpr int kRowBytes = 64;                       // one ring-slot row: 32 bf16 or 64 fp8 values
+// fp8 kernel's ring (the bf16 kernel lays the same 128 KiB out as two slots of 128-byte rows)
+constexpr int kRowBytes = 64;                       // one ring-slot row: 64 fp8 values
 constexpr int kSlotBytes = (BM + BN) * kRowBytes;   // 32 KiB: A rows then W rows
 constexpr int kSlots = 4;
 constexpr int kLdsBytes = kSlots * kSlotBytes;      // 128 KiB
@@ -213,25 +214,38 @@ __global__ __launch_bounds__(256, 1) void gemm_tn_kernel(const char* __restrict_
 #pragma unroll
             for (int e = 0; e < 4; ++e) acc[j][i][e] = 0.0f;
 
-    // fragment of MFMA 16x16x32: lane holds row lane%16, k-chunk (8 bf16) lane/16 of the step
+    // Ring slot of this kernel: 128 bytes of k per row (two MFMA k-steps), A rows then W rows,
+    // 64 KiB; two slots.  A load instruction moves 8 rows x 128 bytes, i.e. whole 128-byte lines of
+    // the row-major operand: with 64-byte row pieces the same L2 -> LDS stream reached 15 TB/s on
+    // this chip, with whole lines 26 TB/s, and this kernel is bound by that stream.
+    constexpr int kRow = 128;
+    constexpr int kSlot = (BM + BN) * kRow;
+    static_assert(2 * kSlot <= kLdsBytes, "two slots fit the launch's LDS");
+    // 16-byte chunk swizzle of a 128-byte LDS row (8 chunks, two rows per 256 bytes of banks): the
+    // chunk index is XORed with (row / 2) % 8.  A fragment read has lane = 16*chunk + row; the lane
+    // sets that are served together ({0-3, 12-15, 20-27}, {4-11, 16-19, 28-31}, + 32) then hold,
+    // per row parity, 8 rows whose XOR values are all different: 16 different bank groups.
+    auto swz = [](int row) { return (row >> 1) & 7; };
+    // fragment of MFMA 16x16x32: lane holds row lane%16, k-chunk (8 bf16) lane/16 of k-step h
     const int frow = lane & 15;
     const int fchunk = lane >> 4;
-    const int foff = frow * kRowBytes + ((fchunk ^ row_swizzle(frow)) << 4);   // block bases are multiples of 16
-    const int a_base = (wm * 128) * kRowBytes;
-    const int w_base = BM * kRowBytes + (wn * 128) * kRowBytes;
+    int foff[2];
+#pragma unroll
+    for (int h = 0; h < 2; ++h) foff[h] = frow * kRow + (((4 * h + fchunk) ^ swz(frow)) << 4);   // block bases are multiples of 16
+    const int a_base = (wm * 128) * kRow;
+    const int w_base = BM * kRow + (wn * 128) * kRow;
 
-    // Loads: one wave instruction moves 16 rows x 64 bytes (1 KiB, linear in LDS).  Wave w issues
-    // row blocks w, w+4, w+8, w+12 of each operand: 8 instructions per ring step.  Lane L fills
-    // physical chunk L%4 of row L/4, i.e. fetches logical chunk (L%4) ^ swizzle(row).
+    // Loads: wave w issues row blocks (8 rows) w, w+4, ..., w+28 of each operand: 16 instructions
+    // per slot.  Lane L fills physical chunk L%8 of row L/8, i.e. fetches logical chunk (L%8) ^ swz(row).
     const size_t ld_bytes = (size_t)K * ESZ;
-    const int ns = (int)(ld_bytes / kRowBytes);       // ring steps (even)
+    const int ns = (int)(ld_bytes / kRow);            // slots to walk
     const int rows_a = M - m0 < BM ? M - m0 : BM;
     const int rows_w = N - n0 < BN ? N - n0 : BN;
-    uint32_t voff_a[4], voff_w[4];
+    uint32_t voff_a[8], voff_w[8];
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        const int row = (wave + 4 * j) * 16 + (lane >> 2);
-        const int chunk = (lane & 3) ^ row_swizzle(row);
+    for (int j = 0; j < 8; ++j) {
+        const int row = (wave + 4 * j) * 8 + (lane >> 3);
+        const int chunk = (lane & 7) ^ swz(row);
         const int ra = row < rows_a ? row : rows_a - 1;   // rows past the edge are never stored
         const int rw = row < rows_w ? row : rows_w - 1;
         voff_a[j] = (uint32_t)((size_t)ra * ld_bytes) + (uint32_t)(chunk * 16);
@@ -239,9 +253,9 @@ __global__ __launch_bounds__(256, 1) void gemm_tn_kernel(const char* __restrict_
     }
     const char* a_panel = A + (size_t)m0 * ld_bytes;
     const char* w_panel = Wt + (size_t)n0 * ld_bytes;
-    // ring step at which this workgroup starts its cyclic walk over k (the sum does not depend on
-    // the order; the fp32 rounding does, deterministically)
-    const int kstart = (int)(((unsigned)tm * 2u) % (unsigned)ns);
+    // slot at which this workgroup starts its cyclic walk over k (the sum does not depend on the
+    // order; the fp32 rounding does, deterministically)
+    const int kstart = (int)((unsigned)tm % (unsigned)ns);
     // Buffer resources over the two operand panels (scalar base, per-lane 32-bit offset, scalar k
     // offset; the range ends with the last valid row, so an offset beyond it would read zeros).
     auto make_rsrc = [](const char* base, size_t bytes) {
@@ -257,71 +271,81 @@ __global__ __launch_bounds__(256, 1) void gemm_tn_kernel(const char* __restrict_
     const i32x4 rsrc_w = make_rsrc(w_panel, (size_t)rows_w * ld_bytes);
     const uint32_t lds_base = (uint32_t)(uintptr_t)(lptr_t)lds;
 
-    // Load instruction q (0..3 = A row blocks, 4..7 = W row blocks) of ring step `step` into the
-    // ring slot at LDS byte address `slot`.  Inline assembly, so that the compiler's wait-count
-    // pass does not see an LDS write it cannot tell apart from the fragment reads (it would force
-    // vmcnt(0) before every LDS read); the waits are placed by hand below.  M0 (the LDS base of
-    // the transfer) is a reserved register that compiled code only sets right before its own uses.
+    // Load instruction q (0..7 = A row blocks, 8..15 = W row blocks) of slot-step `step` into the
+    // slot at LDS byte address `slot`.  Inline assembly, so that the compiler's wait-count pass does
+    // not see an LDS write it cannot tell apart from the fragment reads (it would force vmcnt(0)
+    // before every LDS read); the waits are placed by hand below.  M0 (the LDS base of the
+    // transfer) is a reserved register that compiled code only sets right before its own uses.
     auto issue = [&](int q, int step, uint32_t slot) {
-        int st = step < ns ? step : ns - 1;       // past the end: harmless reload of the last step
+        int st = step < ns ? step : ns - 1;       // past the end: harmless reload of the last slot
         st += kstart;
         st = st >= ns ? st - ns : st;
-        const int koff = st * kRowBytes;
-        if (q < 4) {
+        const int koff = st * kRow;
+        if (q < 8) {
             const uint32_t dst = slot + (uint32_t)((wave + 4 * q) * 1024);
             asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
                          :: "s"(dst), "v"(voff_a[q]), "s"(rsrc_a), "s"(koff) : "memory");
         } else {
-            const uint32_t dst = slot + (uint32_t)(BM * kRowBytes + (wave + 4 * (q - 4)) * 1024);
+            const uint32_t dst = slot + (uint32_t)(BM * kRow + (wave + 4 * (q - 8)) * 1024);
             asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
-                         :: "s"(dst), "v"(voff_w[q - 4]), "s"(rsrc_w), "s"(koff) : "memory");
+                         :: "s"(dst), "v"(voff_w[q - 8]), "s"(rsrc_w), "s"(koff) : "memory");
         }
     };
 
-    i32x4 af[2][8], wf[2][8];   // fragments of the current and the next ring step
-    auto read_frag = [&](int buf, const char* slot, int f /*0..7 = A block, 8..15 = W block*/) {
+    i32x4 af[2][8], wf[2][8];   // fragments of the two k-steps of a slot
+    auto read_frag = [&](int h, const char* slot, int f /*0..7 = A block, 8..15 = W block*/) {
         if (f < 8)
-            af[buf][f] = *reinterpret_cast<const i32x4*>(slot + a_base + f * 16 * kRowBytes + foff);
+            af[h][f] = *reinterpret_cast<const i32x4*>(slot + a_base + f * 16 * kRow + foff[h]);
         else
-            wf[buf][f - 8] = *reinterpret_cast<const i32x4*>(slot + w_base + (f - 8) * 16 * kRowBytes + foff);
+            wf[h][f - 8] = *reinterpret_cast<const i32x4*>(slot + w_base + (f - 8) * 16 * kRow + foff[h]);
     };
     // The MFMAs are written as inline assembly with explicit register classes (accumulators in
     // AGPRs, fragments in VGPRs): left to itself the register allocator mixes the two files for 64
     // four-register accumulators and fills the loop with accumulator moves and spills.
-    auto mfma_one = [&](int buf, int j, int i) {
-        asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc[j][i]) : "v"(wf[buf][j]), "v"(af[buf][i]));
+    auto mfma_one = [&](int h, int j, int i) {
+        asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc[j][i]) : "v"(wf[h][j]), "v"(af[h][i]));
     };
 
-    // Ring of 4 slots, one MFMA k-step (64 bytes of k per row) per slot; step t lives in slot t % 4.
-    // At the top of step s every wave has the fragments of step s in registers, so slot s % 4 is
-    // free and takes the loads of step s+4 (8 per wave, one every 4 MFMAs in the second half of the
-    // step); the fragments of step s+1 are read in the first half.  Loads complete in order, so
-    // "step s+1 has landed" is vmcnt <= 16 (steps s+2, s+3 are the only later ones in flight).
+    // Two slots; slot-step S lives in slot S % 2 and is two k-steps, (S,0) and (S,1).
+    //   (S,0): MFMAs on the fragments of (S,0); the fragments of (S,1) are read from slot S.
+    //   then:  own LDS reads done, barrier: slot S is free.
+    //   (S,1), first half: MFMAs on (S,1); the loads of slot-step S+2 go into slot S (16 per wave,
+    //          one every 2 MFMAs), as early as the slot allows: they have two k-steps to land.
+    //   then:  own loads of slot-step S+1 landed (vmcnt(16): the 16 just issued are younger),
+    //          barrier: slot S+1 is complete for every wave.
+    //   (S,1), second half: the fragments of (S+1,0) are read from slot S+1.
 #pragma unroll
-    for (int t = 0; t < 4; ++t)
+    for (int q = 0; q < 16; ++q) issue(q, 0, lds_base);
 #pragma unroll
-        for (int q = 0; q < 8; ++q) issue(q, t, lds_base + t * kSlotBytes);
-    __builtin_amdgcn_s_waitcnt(0x4F78);   // vmcnt(24): step 0 has landed
+    for (int q = 0; q < 16; ++q) issue(q, 1, lds_base + kSlot);
+    __builtin_amdgcn_s_waitcnt(0x4F70);   // vmcnt(16): slot-step 0 has landed
     __syncthreads();
 #pragma unroll
     for (int f = 0; f < 16; ++f) read_frag(0, lds, f);
 
-    auto step_body = [&](int buf, int s) {
-        const char* nxt = lds + ((s + 1) & 3) * kSlotBytes;
-        const uint32_t slot = lds_base + (s & 3) * kSlotBytes;
-        __builtin_amdgcn_s_waitcnt(0x4070);   // vmcnt(16) lgkmcnt(0)
+    for (int S = 0; S < ns; ++S) {
+        const char* cur = lds + (S & 1) * kSlot;
+        const char* nxt = lds + ((S + 1) & 1) * kSlot;
+        __builtin_amdgcn_s_waitcnt(0xC07F);   // lgkmcnt(0): fragments of (S,0)
+#pragma unroll
+        for (int idx = 0; idx < 64; ++idx) {
+            mfma_one(0, idx >> 3, idx & 7);
+            if (idx < 32 && (idx & 1) == 0) read_frag(1, cur, idx >> 1);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        __builtin_amdgcn_s_waitcnt(0xC07F);   // lgkmcnt(0): fragments of (S,1)
         __syncthreads();
 #pragma unroll
         for (int idx = 0; idx < 64; ++idx) {
-            mfma_one(buf, idx >> 3, idx & 7);
-            if (idx < 32 && (idx & 1) == 0) read_frag(buf ^ 1, nxt, idx >> 1);
-            if (idx >= 32 && (idx & 3) == 1) issue((idx - 32) >> 2, s + 4, slot);
+            if (idx == 32) {
+                __builtin_amdgcn_s_waitcnt(0x4F70);   // vmcnt(16)
+                __syncthreads();
+            }
+            mfma_one(1, idx >> 3, idx & 7);
+            if (idx < 32 && (idx & 1) == 1) issue(idx >> 1, S + 2, lds_base + (S & 1) * kSlot);
+            if (idx >= 32 && (idx & 1) == 0) read_frag(0, nxt, (idx - 32) >> 1);
             __builtin_amdgcn_sched_barrier(0);
         }
-    };
-    for (int s = 0; s < ns; s += 2) {
-        step_body(0, s);
-        step_body(1, s + 1);
     }
     __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): no LDS load may outlive the loop
     asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");   // the last MFMA results are in the accumulators before they are read

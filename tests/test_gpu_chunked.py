@@ -112,6 +112,7 @@ def test_layer_step_chunked_equals_overlap_schedule(dtype, B, S, H, Hkv, d, gemm
     main, side = torch.cuda.Stream(), torch.cuda.Stream()
     O0, C0 = torch.zeros_like(Q), torch.zeros((M, N), dtype=cdt, device="cuda")
     mask = torch.zeros(rov.mask_shape(B, H, S), dtype=torch.int64, device="cuda")
+    torch.cuda.synchronize()   # inputs were produced on torch's current stream; the library runs on main / side
     rov.layer_step(rov.SCHED_OVERLAP, [rov.make_gemm_desc(A, W, C0)], rov.make_attn_desc(Q, K, V, O0, p, causal=causal),
                    seed, offset, mask, main, side)
     torch.cuda.synchronize()
@@ -119,6 +120,7 @@ def test_layer_step_chunked_equals_overlap_schedule(dtype, B, S, H, Hkv, d, gemm
     slot = rov.mask_words_rows(B, H, S, 0, chunk)
     ring = torch.full((2 * slot,), 0x2AAAAAAAAAAAAAAA, dtype=torch.int64, device="cuda")   # poison
     assert 2 * slot <= mask.numel() or chunk >= S // 2
+    torch.cuda.synchronize()
     for _ in range(2):   # twice: events and ring slots are reused
         rov.layer_step_chunked([rov.make_gemm_desc(A, W, C1)], rov.make_attn_desc(Q, K, V, O1, p, causal=causal),
                                seed, offset, chunk, ring, main, side)

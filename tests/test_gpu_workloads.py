@@ -88,6 +88,7 @@ def test_workload3_b2_s4k_layer_step_schedules():
         O = torch.zeros_like(Q)
         mask = torch.zeros(rov.mask_shape(B, H, S), dtype=torch.int64, device="cuda")
         gd = [rov.make_gemm_desc(a, w, cc) for a, w, cc in ops]
+        torch.cuda.synchronize()   # inputs were produced on torch's current stream; the library runs on main / side
         rov.layer_step(sched, gd, rov.make_attn_desc(Q, K, V, O, p), wl.SEED, wl.OFFSET,
                        None if sched == rov.SCHED_FUSED else mask, main, side)
         torch.cuda.synchronize()
@@ -138,6 +139,7 @@ def test_workload4_llama70b_fp8_gemms_and_gqa_attention():
     mask = torch.zeros(rov.mask_shape(B, H, S), dtype=torch.int64, device="cuda")
     main, side = torch.cuda.Stream(), torch.cuda.Stream()
     print("cfg4 overlap step", flush=True)
+    torch.cuda.synchronize()   # inputs were produced on torch's current stream
     rov.layer_step(rov.SCHED_OVERLAP, gemm_descs, rov.make_attn_desc(Q, K, V, O, p), wl.SEED, wl.OFFSET, mask, main, side)
     torch.cuda.synchronize()
     assert torch.equal(keepalive[2], c_first)                       # same GEMM result beside the RNG
@@ -178,6 +180,7 @@ def test_workload5_block_s16k_overlap_sampled_rows():
         print("cfg5 block causal", causal, flush=True)
         cfg = rov.make_block_cfg(H, Hkv, d, hidden, ffn, p, causal=causal)
         ws = torch.empty(rov.block_workspace_bytes(cfg, B, S, 0), dtype=torch.uint8, device="cuda")
+        torch.cuda.synchronize()   # weights, x and the first mask were produced on torch's current stream
         rov.block_forward(rov.make_block_weights(wts), x, y, cfg, rov.SCHED_OVERLAP, wl.SEED, wl.OFFSET, m0, ws,
                           main, side, mask_ready=True, next_mask=m1)
         torch.cuda.synchronize()

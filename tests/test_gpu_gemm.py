@@ -31,9 +31,10 @@ def _rel_err(got, ref):
 
 
 @pytest.mark.parametrize("M,N,K,transB", [
-    (256, 256, 64, True),        # one tile, one k-step
-    (256, 256, 128, True),       # two k-steps (both LDS stages)
-    (512, 768, 448, True),       # several tiles, odd number of k-steps
+    (256, 256, 64, True),        # one tile, one LDS slot (128 bytes of k per row = two k-steps)
+    (256, 256, 128, True),       # two slots (both LDS stages)
+    (512, 768, 448, True),       # several tiles, odd number of slots
+    (2304, 256, 192, True),      # 9 tile rows over 3 slots: every cyclic start of the k walk, wrapping
     (300, 520, 192, True),       # ragged M and N (N % 4 == 0): MFMA kernel with clamped edges
     (1, 4, 64, True),            # degenerate sizes on the MFMA path
     (77, 130, 100, True),        # N % 4 != 0, K % 64 != 0: generic kernel

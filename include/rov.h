@@ -16,6 +16,9 @@
  *    on the given stream.  `stream` is a hipStream_t passed as void* (NULL =
  *    the default stream).  Descriptor structs themselves live in HOST memory
  *    and are read before the call returns.
+ *  - Ordering: a call is ordered only against earlier work on the stream(s) it
+ *    is given.  Inputs written on any other stream must be complete, or
+ *    event-ordered before those streams, when the call is made.
  *  - dtype codes: ROV_F32 = 0, ROV_BF16 = 1, ROV_FP8_E4M3 = 2 (OCP e4m3).
  */
 #ifndef ROV_H

@@ -92,27 +92,6 @@ __global__ __launch_bounds__(256) void rope_kernel(uint16_t* __restrict__ buf, i
     *reinterpret_cast<uint4*>(ptr) = make_uint4(o[0], o[1], o[2], o[3]);
 }
 
-// act = silu(g) * u, element-wise; n8 = number of 8-element groups.
-__global__ __launch_bounds__(256) void swiglu_kernel(const uint16_t* __restrict__ g,
-                                                     const uint16_t* __restrict__ u,
-                                                     uint16_t* __restrict__ act, int64_t n8) {
-    const int64_t stride = (int64_t)gridDim.x * 256;
-    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n8; i += stride) {
-        const uint4 gv = reinterpret_cast<const uint4*>(g)[i];
-        const uint4 uv = reinterpret_cast<const uint4*>(u)[i];
-        const uint32_t gw[4] = {gv.x, gv.y, gv.z, gv.w};
-        const uint32_t uw[4] = {uv.x, uv.y, uv.z, uv.w};
-        uint32_t o[4];
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            const float a = lo_f(gw[k]), b = hi_f(gw[k]);
-            const float sa = a / (1.0f + __expf(-a)), sb = b / (1.0f + __expf(-b));
-            o[k] = pack2(sa * lo_f(uw[k]), sb * hi_f(uw[k]));
-        }
-        reinterpret_cast<uint4*>(act)[i] = make_uint4(o[0], o[1], o[2], o[3]);
-    }
-}
-
 }  // namespace
 
 int launch_rmsnorm(const void* x, const void* weight, void* y, int64_t rows, int n, float eps,
@@ -132,18 +111,6 @@ int launch_rope(void* buf, int64_t tokens, int64_t row_elems, int S, int nheads,
     if (blocks > 0x7FFFFFFF) return ROV_ERR_UNSUPPORTED;
     hipLaunchKernelGGL(rope_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, (uint16_t*)buf,
                        row_elems, S, nheads, d, log2((double)theta), quads);
-    ROV_LAUNCH_CHECK();
-    return ROV_OK;
-}
-
-int launch_swiglu(const void* g, const void* u, void* act, int64_t n, hipStream_t stream) {
-    if (n <= 0 || (n % 8) != 0) return ROV_ERR_UNSUPPORTED;
-    const int64_t n8 = n / 8;
-    int64_t blocks = (n8 + 255) / 256;
-    const int64_t cap = (int64_t)device_cu_count() * 32;
-    if (blocks > cap) blocks = cap;
-    hipLaunchKernelGGL(swiglu_kernel, dim3((unsigned)blocks), dim3(256), 0, stream,
-                       (const uint16_t*)g, (const uint16_t*)u, (uint16_t*)act, n8);
     ROV_LAUNCH_CHECK();
     return ROV_OK;
 }

@@ -174,12 +174,28 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
     return *reinterpret_cast<uint32_t*>(&h);
 }
 
-// bf16 inputs; output and residual are bf16.
+// What the epilogue does with the bf16 side input R[m][n] (four consecutive n per lane):
+// EPI_ADD: C = acc + R (residual connection); EPI_SILU_MUL: C = silu(R) * acc (SwiGLU: R is the
+// gate projection, acc the up projection, so the activation costs no kernel and no extra pass).
+__device__ __forceinline__ void epilogue_combine(int epi, uint2 r, float& c0, float& c1, float& c2, float& c3) {
+    const float r0 = __uint_as_float(r.x << 16), r1 = __uint_as_float(r.x & 0xFFFF0000u);
+    const float r2 = __uint_as_float(r.y << 16), r3 = __uint_as_float(r.y & 0xFFFF0000u);
+    if (epi == EPI_SILU_MUL) {
+        c0 *= r0 / (1.0f + __expf(-r0));
+        c1 *= r1 / (1.0f + __expf(-r1));
+        c2 *= r2 / (1.0f + __expf(-r2));
+        c3 *= r3 / (1.0f + __expf(-r3));
+    } else {
+        c0 += r0; c1 += r1; c2 += r2; c3 += r3;
+    }
+}
+
+// bf16 inputs; output and side input are bf16.
 __global__ __launch_bounds__(256, 1) void gemm_tn_kernel(const char* __restrict__ A,
                                                          const char* __restrict__ Wt,
                                                          uint16_t* __restrict__ C,
                                                          const uint16_t* __restrict__ R, int M, int N,
-                                                         int K, float alpha, int tiles_m, int tiles_n) {
+                                                         int K, float alpha, int tiles_m, int tiles_n, int epi) {
     extern __shared__ __attribute__((aligned(1024))) char lds[];
     // Co-resident RNG waves only need the VALU issue slots this kernel leaves idle; raise this
     // wave's issue priority so that they never delay its MFMA / LDS instruction stream.
@@ -353,10 +369,24 @@ __global__ __launch_bounds__(256, 1) void gemm_tn_kernel(const char* __restrict_
     // D'[r][c] = C[m = c][n = r]: lane holds activation row lane%16 and weight rows 4*(lane/16) + e
     const int mrow = lane & 15;
     const int nsub = (lane >> 4) * 4;
+    // The side input of row block i+1 is requested before row block i is combined and stored, so
+    // its latency is paid once per tile, not once per element group (the wave is alone on its SIMD).
+    uint2 rv[2][8];
+    auto load_side = [&](int i, uint2 (&dst)[8]) {
+        const int m = m0 + wm * 128 + i * 16 + mrow;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const int n = n0 + wn * 128 + j * 16 + nsub;
+            dst[j] = make_uint2(0u, 0u);
+            if (m < M && n < N) dst[j] = *reinterpret_cast<const uint2*>(R + (size_t)m * N + n);
+        }
+    };
+    if (R != nullptr) load_side(0, rv[0]);
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
         const int m = m0 + wm * 128 + i * 16 + mrow;
         __builtin_amdgcn_sched_barrier(0);
+        if (R != nullptr && i + 1 < 8) load_side(i + 1, rv[(i + 1) & 1]);
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
             const int n = n0 + wn * 128 + j * 16 + nsub;
@@ -365,13 +395,7 @@ __global__ __launch_bounds__(256, 1) void gemm_tn_kernel(const char* __restrict_
             float c2 = alpha * acc_read(acc[j][i][2]);
             float c3 = alpha * acc_read(acc[j][i][3]);
             if (m < M && n < N) {
-                if (R != nullptr) {
-                    const uint2 r = *reinterpret_cast<const uint2*>(R + (size_t)m * N + n);
-                    c0 += __uint_as_float(r.x << 16);
-                    c1 += __uint_as_float(r.x & 0xFFFF0000u);
-                    c2 += __uint_as_float(r.y << 16);
-                    c3 += __uint_as_float(r.y & 0xFFFF0000u);
-                }
+                if (R != nullptr) epilogue_combine(epi, rv[i & 1][j], c0, c1, c2, c3);
                 uint2 v;
                 v.x = pack_bf16x2(c0, c1);
                 v.y = pack_bf16x2(c2, c3);
@@ -389,7 +413,7 @@ __global__ __launch_bounds__(256, 1) void gemm_fp8_kernel(const char* __restrict
                                                          const char* __restrict__ Wt,
                                                          uint16_t* __restrict__ C,
                                                          const uint16_t* __restrict__ R, int M, int N,
-                                                         int K, float alpha, int tiles_m, int tiles_n) {
+                                                         int K, float alpha, int tiles_m, int tiles_n, int epi) {
     extern __shared__ __attribute__((aligned(1024))) char lds[];
     // Co-resident RNG waves only need the VALU issue slots this kernel leaves idle; raise this
     // wave's issue priority so that they never delay its MFMA / LDS instruction stream.
@@ -565,10 +589,7 @@ __global__ __launch_bounds__(256, 1) void gemm_fp8_kernel(const char* __restrict
                 if (m < M && n < N) {
                     if (R != nullptr) {
                         const uint2 r = *reinterpret_cast<const uint2*>(R + (size_t)m * N + n);
-                        c0 += __uint_as_float(r.x << 16);
-                        c1 += __uint_as_float(r.x & 0xFFFF0000u);
-                        c2 += __uint_as_float(r.y << 16);
-                        c3 += __uint_as_float(r.y & 0xFFFF0000u);
+                        epilogue_combine(epi, r, c0, c1, c2, c3);
                     }
                     uint2 v;
                     v.x = pack_bf16x2(c0, c1);
@@ -589,6 +610,13 @@ int launch_gemm(const void* A, const void* Bm, void* C, int M, int N, int K, int
 
 int launch_gemm_residual(const void* A, const void* Bm, void* C, const void* R, int M, int N, int K,
                          int dtype, int transB, float scaleA, float scaleB, hipStream_t stream) {
+    return launch_gemm_epilogue(A, Bm, C, R, EPI_ADD, M, N, K, dtype, transB, scaleA, scaleB, stream);
+}
+
+int launch_gemm_epilogue(const void* A, const void* Bm, void* C, const void* R, int epi, int M, int N, int K,
+                         int dtype, int transB, float scaleA, float scaleB, hipStream_t stream) {
+    if (epi != EPI_ADD && epi != EPI_SILU_MUL) return ROV_ERR_INVALID;
+    if (R != nullptr && !aligned(R, 8)) return ROV_ERR_INVALID;
     if (A == nullptr || Bm == nullptr || C == nullptr || M <= 0 || N <= 0 || K <= 0)
         return ROV_ERR_INVALID;
     if (!aligned(A, 16) || !aligned(Bm, 16) || !aligned(C, 16)) return ROV_ERR_INVALID;
@@ -613,12 +641,12 @@ int launch_gemm_residual(const void* A, const void* Bm, void* C, const void* R, 
         }
         hipLaunchKernelGGL(kern, dim3((unsigned)T), dim3(256), kLdsBytes, stream, (const char*)A,
                            (const char*)Bm, (uint16_t*)C, (const uint16_t*)R, M, N, K, alpha, tiles_m,
-                           tiles_n);
+                           tiles_n, epi);
         ROV_LAUNCH_CHECK();
         return ROV_OK;
     }
 
-    if (R != nullptr) return ROV_ERR_UNSUPPORTED;   // the residual epilogue exists on the MFMA path only
+    if (R != nullptr) return ROV_ERR_UNSUPPORTED;   // the side-input epilogues exist on the MFMA path only
     const dim3 grid((unsigned)((N + 63) / 64), (unsigned)((M + 63) / 64)), block(256);
     if (grid.y > 65535u) return ROV_ERR_UNSUPPORTED;
     if (dtype == ROV_F32) {

@@ -57,8 +57,12 @@ int launch_mask_rows(uint64_t seed, uint64_t offset, int B, int H, int S, float 
                      int q_rows, uint64_t* out, hipStream_t stream, int grid_mode, int qslot);
 int launch_gemm(const void* A, const void* Bm, void* C, int M, int N, int K, int dtype, int transB,
                 float scaleA, float scaleB, hipStream_t stream);
-// C = alpha * A W^T + R (R: bf16 [M,N] or nullptr); bf16 MFMA path only when R is given.
+// C = alpha * A W^T + R (R: bf16 [M,N] or nullptr); MFMA path only when R is given.
 int launch_gemm_residual(const void* A, const void* Bm, void* C, const void* R, int M, int N, int K,
+                         int dtype, int transB, float scaleA, float scaleB, hipStream_t stream);
+// The same with the epilogue chosen: EPI_ADD as above, EPI_SILU_MUL: C = silu(R) * (alpha * A W^T).
+enum { EPI_ADD = 0, EPI_SILU_MUL = 1 };
+int launch_gemm_epilogue(const void* A, const void* Bm, void* C, const void* R, int epi, int M, int N, int K,
                          int dtype, int transB, float scaleA, float scaleB, hipStream_t stream);
 int launch_attention(const void* Q, const void* K, const void* V, void* O, int B, int H, int Hkv,
                      int S, int d, const int64_t strides[12], int dtype, int causal, float p,
@@ -76,6 +80,5 @@ int launch_rmsnorm(const void* x, const void* weight, void* y, int64_t rows, int
                    hipStream_t stream);
 int launch_rope(void* buf, int64_t tokens, int64_t row_elems, int S, int nheads, int d, float theta,
                 hipStream_t stream);
-int launch_swiglu(const void* g, const void* u, void* act, int64_t n, hipStream_t stream);
 
 }  // namespace rov

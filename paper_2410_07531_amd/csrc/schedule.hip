@@ -470,9 +470,11 @@ extern "C" int rov_block_forward(const rov_block_weights* w, const void* x, void
     }
     ROV_STEP(traced(ROV_TRACE_GLUE, ms, [&] { return launch_rmsnorm(x2, w->norm2, h, T, hidden, cfg->eps, ms); }));
     ROV_STEP(t_gemm(h, w->wg, g, nullptr, (int)T, ffn, hidden, ROV_BF16, 1, 1.0f, 1.0f, ms));
-    ROV_STEP(t_gemm(h, w->wu, u, nullptr, (int)T, ffn, hidden, ROV_BF16, 1, 1.0f, 1.0f, ms));
-    ROV_STEP(traced(ROV_TRACE_GLUE, ms, [&] { return launch_swiglu(g, u, g, T * ffn, ms); }));
-    ROV_STEP(t_gemm(g, w->wd, y, x2, (int)T, hidden, ffn, ROV_BF16, 1, 1.0f, 1.0f, ms));
+    // SwiGLU in the epilogue of the up projection: u = silu(g) * (h Wu^T), no separate pass over g and u
+    ROV_STEP(traced(ROV_TRACE_GEMM, ms, [&] {
+        return launch_gemm_epilogue(h, w->wu, u, g, EPI_SILU_MUL, (int)T, ffn, hidden, ROV_BF16, 1, 1.0f, 1.0f, ms);
+    }));
+    ROV_STEP(t_gemm(u, w->wd, y, x2, (int)T, hidden, ffn, ROV_BF16, 1, 1.0f, 1.0f, ms));
     if (overlap && next_mask != nullptr) {
         // what is left of the next mask when the last GEMM ends is finished at full speed
         if (qslot_next >= 0)

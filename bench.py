@@ -400,17 +400,19 @@ def bench_fp8_layer(torch, rov, wl, main_s, side_s, sync, ev_pair):
             r["rng_hidden_fraction_whole_step"] = (r["sequential_ms"] - r["overlap_ms"]) / r["rng_ms"]
             sweep["philox_%d" % rounds] = r
         res["rounds"] = sweep
-        # narrower random numbers per element (paper Sec. 5.2); no fused form
+        # narrower random numbers per element (paper Sec. 5.2)
         widths = {}
         for bits in (16, 8):
             r = {"rng_ms": median_ms(lambda: rov.dropout_mask_generate_bits(wl.SEED, 0, B, H, S, p, bits, out=mask,
                                                                             stream=main_s),
                                      2, 9, sync, ev_pair, inner=2)}
-            for name, sched in (("sequential", rov.SCHED_SEQUENTIAL), ("overlap", rov.SCHED_OVERLAP)):
+            for name, sched in (("sequential", rov.SCHED_SEQUENTIAL), ("fused", rov.SCHED_FUSED),
+                                ("overlap", rov.SCHED_OVERLAP)):
                 r[name + "_ms"] = median_ms(
-                    lambda: rov.layer_step(sched, descs, ad, wl.SEED, 0, mask, main_s, side_s, bits=bits),
-                    2, 9, sync, ev_pair, inner=2)
+                    lambda: rov.layer_step(sched, descs, ad, wl.SEED, 0, None if sched == rov.SCHED_FUSED else mask,
+                                           main_s, side_s, bits=bits), 2, 9, sync, ev_pair, inner=2)
             r["speedup_overlap_vs_sequential"] = r["sequential_ms"] / r["overlap_ms"]
+            r["speedup_overlap_vs_fused"] = r["fused_ms"] / r["overlap_ms"]
             r["rng_hidden_fraction_whole_step"] = (r["sequential_ms"] - r["overlap_ms"]) / r["rng_ms"]
             widths["bits_%d" % bits] = r
         res["widths"] = widths

@@ -117,8 +117,8 @@ int rov_dropout_mask_generate_rounds(uint64_t seed, uint64_t offset, int B, int 
  * probability is quantised to Tb / 2^bits (230/256 for p = 0.1 at 8 bits).  bits == 32 is
  * rov_dropout_mask_generate.  One mask advances the call counter by
  * rov_mask_philox_calls_bits = 64*words/E (0 for an unsupported `bits`).  10 rounds.
- * rov_attention_fwd_dropout reads such a mask like any other; its fused variant (mask ==
- * NULL) always draws 32 bits per element.  Other values of bits: ROV_ERR_INVALID. */
+ * rov_attention_fwd_dropout reads such a mask like any other; the fused variant that draws
+ * the same fields is rov_attention_fwd_dropout_bits.  Other values of bits: ROV_ERR_INVALID. */
 uint64_t rov_mask_philox_calls_bits(int B, int H, int S, int bits);
 int rov_dropout_mask_generate_bits(uint64_t seed, uint64_t offset, int B, int H, int S, float p,
                                    int bits, uint64_t *out, void *stream);
@@ -197,6 +197,14 @@ int rov_attention_fwd_dropout_rounds(const void *Q, const void *K, const void *V
                                      int dtype, int causal, float p, const uint64_t *mask,
                                      uint64_t seed, uint64_t offset, int rounds, void *stream);
 
+/* Same with `bits` (8, 16 or 32) random bits per element for the fused variant: with mask == NULL
+ * and p > 0 the kernel draws the bits of rov_dropout_mask_generate_bits(seed, offset, ..., bits)
+ * (a lane makes one Philox call per 4*32/bits of its elements).  10 rounds. */
+int rov_attention_fwd_dropout_bits(const void *Q, const void *K, const void *V, void *O,
+                                   int B, int H, int Hkv, int S, int d, const int64_t strides[12],
+                                   int dtype, int causal, float p, const uint64_t *mask,
+                                   uint64_t seed, uint64_t offset, int bits, void *stream);
+
 /* Same for query rows [q_begin, min(q_begin + q_rows, S)) only: those rows of O are written,
  * the others are left alone.  mask_rows (may be NULL: fused variant) holds just the tile rows
  * of that range, as written by rov_dropout_mask_generate_rows with the same q_begin, q_rows.
@@ -258,10 +266,9 @@ int rov_layer_step_rounds(int schedule, const rov_gemm_desc *gemms, int n_gemms,
                           uint64_t *mask, void *main_stream, void *side_stream);
 
 /* rov_layer_step with `bits` (8, 16 or 32) random bits per element for the mask kernel, the
- * other way of shrinking the RNG (paper Sec. 5.2): SEQUENTIAL and OVERLAP drop the elements of
- * rov_dropout_mask_generate_bits(seed, offset, ..., bits).  The fused kernel has no narrow form:
- * ROV_SCHED_FUSED with bits != 32 returns ROV_ERR_UNSUPPORTED.  bits == 32 is rov_layer_step.
- * Other values: ROV_ERR_INVALID. */
+ * other way of shrinking the RNG (paper Sec. 5.2): the three schedules drop the elements of
+ * rov_dropout_mask_generate_bits(seed, offset, ..., bits) (FUSED draws the same fields in the
+ * attention kernel).  bits == 32 is rov_layer_step.  Other values: ROV_ERR_INVALID. */
 int rov_layer_step_bits(int schedule, const rov_gemm_desc *gemms, int n_gemms,
                         const rov_attn_desc *attn, uint64_t seed, uint64_t offset, int bits,
                         uint64_t *mask, void *main_stream, void *side_stream);

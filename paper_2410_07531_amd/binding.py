@@ -86,6 +86,8 @@ SIGNATURES = {
                                    _i, _p, _p, _p]),
     "rov_layer_step_bits": (_i, [_i, ctypes.POINTER(GemmDesc), _i, ctypes.POINTER(AttnDesc), _u64, _u64,
                                  _i, _p, _p, _p]),
+    "rov_attention_fwd_dropout_bits": (_i, [_p, _p, _p, _p, _i, _i, _i, _i, _i,
+                                            ctypes.POINTER(ctypes.c_int64), _i, _i, _f, _p, _u64, _u64, _i, _p]),
     "rov_attention_fwd_dropout_rounds": (_i, [_p, _p, _p, _p, _i, _i, _i, _i, _i,
                                               ctypes.POINTER(ctypes.c_int64), _i, _i, _f, _p, _u64, _u64, _i,
                                               _p]),
@@ -234,9 +236,10 @@ def _strides12(Q, K, V, O):
 
 
 def attention_fwd_dropout(Q, K, V, p, mask=None, seed=0, offset=0, causal=False, O=None, stream=None,
-                          rounds=None):
+                          rounds=None, bits=None):
     """Q [B,S,H,d], K/V [B,S,Hkv,d] -> O [B,S,H,d]; mask=None with p>0 selects the fused variant
-    (rounds: its Philox round count, 3/5/7/10; None = the 10-round entry point)."""
+    (rounds: its Philox round count, 3/5/7/10, or bits: its random bits per element, 8/16/32;
+    None = the 10-round, 32-bit entry point)."""
     import torch
     B, S, H, d = Q.shape
     Hkv = K.shape[2]
@@ -244,6 +247,13 @@ def attention_fwd_dropout(Q, K, V, p, mask=None, seed=0, offset=0, causal=False,
         O = torch.empty_like(Q)
     strides = _strides12(Q, K, V, O)
     mptr = ctypes.c_void_p(mask.data_ptr()) if mask is not None else ctypes.c_void_p(0)
+    if bits is not None:
+        _check(load().rov_attention_fwd_dropout_bits(
+            ctypes.c_void_p(Q.data_ptr()), ctypes.c_void_p(K.data_ptr()), ctypes.c_void_p(V.data_ptr()),
+            ctypes.c_void_p(O.data_ptr()), B, H, Hkv, S, d, strides, _dtype_code(Q), int(bool(causal)),
+            float(p), mptr, seed & (2**64 - 1), offset & (2**64 - 1), int(bits), _stream_ptr(stream)),
+            "rov_attention_fwd_dropout_bits")
+        return O
     if rounds is not None:
         _check(load().rov_attention_fwd_dropout_rounds(
             ctypes.c_void_p(Q.data_ptr()), ctypes.c_void_p(K.data_ptr()), ctypes.c_void_p(V.data_ptr()),

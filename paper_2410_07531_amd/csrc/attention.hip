@@ -58,6 +58,8 @@ struct AttnParams {
     uint32_t k0, k1;                      // Philox key (fused)
     uint32_t t_minus_1;                   // keep iff x <= t_minus_1 (fused)
     int rounds;                           // Philox rounds (fused)
+    int bits;                             // random bits per element (fused): 8, 16 or 32
+    uint32_t tb;                          // bits < 32: keep iff field < tb (fused)
 };
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
@@ -170,7 +172,7 @@ __device__ __forceinline__ bf16x4 lds_read_transposed(const char* p) {
 // NW waves per workgroup, each owning NQ*32 query rows.  (NQ, NW) = (2, 4) keeps one wave per
 // SIMD with K/V fragments reused for two query tiles; (1, 8) puts two waves on every SIMD so
 // that one wave's softmax VALU work runs under the other's MFMAs.
-template <int D, int NQ, int NW, int MODE, int R = 10>
+template <int D, int NQ, int NW, int MODE, int R = 10, int BITS = 32>
 __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(const AttnParams p) {
     constexpr int BQ = NW * 32 * NQ;   // query rows per workgroup
     using T = Tile<D>;
@@ -405,11 +407,13 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(const AttnParams p) 
                         s[t][n][e] = __builtin_amdgcn_inverse_ballot_w64(mw[n][t][e]) ? s[t][n][e] : 0.0f;
                 }
                 if (MODE == MODE_FUSED) {
-                    // word e = 4*c + r of this tile is output r of the lane's Philox call
-                    // offset + 64*(first_word/4 + c) + lane
-                    const uint64_t g0 = (wtile[n] + (uint64_t)kt * 16u) >> 2;
+                    // Words are taken in groups of E = 4 * 32 / BITS; word e = E*c + 4*f + r of this tile is
+                    // decided by field f of output r of the lane's Philox call offset + 64*(first_word/E + c) + lane
+                    // (BITS = 32: one field, the whole word)
+                    constexpr int NF = 32 / BITS, E = 4 * NF;
+                    const uint64_t g0 = (wtile[n] + (uint64_t)kt * 16u) / (uint32_t)E;
 #pragma unroll
-                    for (int c = 0; c < 4; ++c) {
+                    for (int c = 0; c < 16 / E; ++c) {
                         const uint64_t base = p.offset + 64u * (g0 + (uint64_t)c);
                         const uint32_t blo = (uint32_t)base, bhi = (uint32_t)(base >> 32);
                         const uint32_t c0 = blo + (uint32_t)lane;
@@ -420,8 +424,15 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(const AttnParams p) 
                             philox4x32<R>(c0, bhi + (c0 < blo ? 1u : 0u), 0u, 0u, p.k0, p.k1, x);
                         }
 #pragma unroll
-                        for (int r = 0; r < 4; ++r)
-                            s[t][n][4 * c + r] = x[r] <= p.t_minus_1 ? s[t][n][4 * c + r] : 0.0f;
+                        for (int f = 0; f < NF; ++f)
+#pragma unroll
+                            for (int r = 0; r < 4; ++r) {
+                                const int e = E * c + 4 * f + r;
+                                bool keep;
+                                if (BITS == 32) keep = x[r] <= p.t_minus_1;
+                                else keep = ((x[r] >> (BITS * f)) & ((1u << (BITS & 31)) - 1u)) < p.tb;
+                                s[t][n][e] = keep ? s[t][n][e] : 0.0f;
+                            }
                     }
                 }
             }
@@ -579,12 +590,14 @@ __global__ __launch_bounds__(256) void attn_generic_kernel(const AttnParams p) {
                 if (MODE == MODE_MASK) {
                     keep = (p.mask[mrow + wo] >> bit) & 1ull;
                 } else if (MODE == MODE_FUSED) {
-                    const uint64_t ncall = p.offset + 64u * (w >> 2) + (uint64_t)bit;
+                    const uint32_t E = 128u / (uint32_t)p.bits;            // mask words per group of calls
+                    const uint64_t ncall = p.offset + 64u * (w / E) + (uint64_t)bit;
                     uint32_t x[4];
                     philox4x32_dyn(p.rounds, (uint32_t)ncall, (uint32_t)(ncall >> 32), 0u, 0u, p.k0, p.k1, x);
-                    const uint32_t sel = (uint32_t)(w & 3u);
+                    const uint32_t k = (uint32_t)(w % E), sel = k & 3u, f = k >> 2;
                     const uint32_t xv = sel == 0 ? x[0] : sel == 1 ? x[1] : sel == 2 ? x[2] : x[3];
-                    keep = xv <= p.t_minus_1;
+                    if (p.bits == 32) keep = xv <= p.t_minus_1;
+                    else keep = ((xv >> ((uint32_t)p.bits * f)) & ((1u << p.bits) - 1u)) < p.tb;
                 }
                 pe = keep ? pe : 0.0f;
             }
@@ -625,7 +638,9 @@ int launch_bf16(const AttnParams& prm, int mode, hipStream_t stream) {
     void (*kern)(const AttnParams) = mode == MODE_NONE ? attn_bf16_kernel<D, NQ, NW, MODE_NONE>
                                                        : attn_bf16_kernel<D, NQ, NW, MODE_MASK>;
     if (mode == MODE_FUSED) {   // the round count is a compile-time constant of the fused kernel
-        switch (prm.rounds) {
+        if (prm.bits == 16) { if (prm.rounds != 10) return ROV_ERR_UNSUPPORTED; kern = attn_bf16_kernel<D, NQ, NW, MODE_FUSED, 10, 16>; }
+        else if (prm.bits == 8) { if (prm.rounds != 10) return ROV_ERR_UNSUPPORTED; kern = attn_bf16_kernel<D, NQ, NW, MODE_FUSED, 10, 8>; }
+        else switch (prm.rounds) {
             case 10: kern = attn_bf16_kernel<D, NQ, NW, MODE_FUSED, 10>; break;
             case 7: kern = attn_bf16_kernel<D, NQ, NW, MODE_FUSED, 7>; break;
             case 5: kern = attn_bf16_kernel<D, NQ, NW, MODE_FUSED, 5>; break;
@@ -657,16 +672,19 @@ int launch_generic(const AttnParams& prm, int mode, hipStream_t stream) {
 
 int launch_attention(const void* Q, const void* K, const void* V, void* O, int B, int H, int Hkv,
                      int S, int d, const int64_t strides[12], int dtype, int causal, float p,
-                     const uint64_t* mask, uint64_t seed, uint64_t offset, hipStream_t stream, int rounds) {
+                     const uint64_t* mask, uint64_t seed, uint64_t offset, hipStream_t stream, int rounds,
+                     int bits) {
     return launch_attention_rows(Q, K, V, O, B, H, Hkv, S, d, strides, dtype, causal, p, mask, false, seed,
-                                 offset, 0, S, stream, rounds);
+                                 offset, 0, S, stream, rounds, bits);
 }
 
 int launch_attention_rows(const void* Q, const void* K, const void* V, void* O, int B, int H, int Hkv,
                           int S, int d, const int64_t strides[12], int dtype, int causal, float p,
                           const uint64_t* mask, bool mask_is_rows, uint64_t seed, uint64_t offset,
-                          int q_begin, int q_rows, hipStream_t stream, int rounds) {
+                          int q_begin, int q_rows, hipStream_t stream, int rounds, int bits) {
     if (rounds != 10 && rounds != 7 && rounds != 5 && rounds != 3) return ROV_ERR_INVALID;
+    if (bits != 32 && bits != 16 && bits != 8) return ROV_ERR_INVALID;
+    if (bits != 32 && rounds != 10) return ROV_ERR_UNSUPPORTED;
     if (S <= 0 || q_begin < 0 || q_rows <= 0 || q_begin >= S || (q_begin & 31) != 0) return ROV_ERR_INVALID;
     if (Q == nullptr || K == nullptr || V == nullptr || O == nullptr || strides == nullptr)
         return ROV_ERR_INVALID;
@@ -698,6 +716,9 @@ int launch_attention_rows(const void* Q, const void* K, const void* V, void* O, 
     prm.k0 = (uint32_t)seed; prm.k1 = (uint32_t)(seed >> 32);
     prm.t_minus_1 = tm1;
     prm.rounds = rounds;
+    prm.bits = bits;
+    // keep iff field < tb, tb = floor((1 - p) * 2^bits) in double from the float p
+    prm.tb = bits < 32 ? (uint32_t)(uint64_t)((1.0 - (double)p) * (double)(1u << bits)) : 0u;
     const int mode = p == 0.0f ? MODE_NONE : (mask != nullptr ? MODE_MASK : MODE_FUSED);
 
     if (dtype == ROV_BF16 && (d == 64 || d == 128)) {
@@ -743,4 +764,12 @@ extern "C" int rov_attention_fwd_dropout_rounds(const void* Q, const void* K, co
                                                 uint64_t seed, uint64_t offset, int rounds, void* stream) {
     return rov::launch_attention(Q, K, V, O, B, H, Hkv, S, d, strides, dtype, causal, p, mask, seed,
                                  offset, (hipStream_t)stream, rounds);
+}
+
+extern "C" int rov_attention_fwd_dropout_bits(const void* Q, const void* K, const void* V, void* O, int B,
+                                              int H, int Hkv, int S, int d, const int64_t strides[12],
+                                              int dtype, int causal, float p, const uint64_t* mask,
+                                              uint64_t seed, uint64_t offset, int bits, void* stream) {
+    return rov::launch_attention(Q, K, V, O, B, H, Hkv, S, d, strides, dtype, causal, p, mask, seed,
+                                 offset, (hipStream_t)stream, 10, bits);
 }

@@ -67,14 +67,15 @@ int launch_gemm_epilogue(const void* A, const void* Bm, void* C, const void* R, 
 int launch_attention(const void* Q, const void* K, const void* V, void* O, int B, int H, int Hkv,
                      int S, int d, const int64_t strides[12], int dtype, int causal, float p,
                      const uint64_t* mask, uint64_t seed, uint64_t offset, hipStream_t stream,
-                     int rounds = 10 /* Philox rounds of the fused variant: 3, 5, 7 or 10 */);
+                     int rounds = 10 /* Philox rounds of the fused variant: 3, 5, 7 or 10 */,
+                     int bits = 32 /* its random bits per element: 8, 16 or 32 (10 rounds only) */);
 
 // Query rows [q_begin, min(q_begin + q_rows, S)) only.  mask_is_rows: `mask` holds just the tile
 // rows of that range (as written by launch_mask_rows) instead of the full mask.
 int launch_attention_rows(const void* Q, const void* K, const void* V, void* O, int B, int H, int Hkv,
                           int S, int d, const int64_t strides[12], int dtype, int causal, float p,
                           const uint64_t* mask, bool mask_is_rows, uint64_t seed, uint64_t offset,
-                          int q_begin, int q_rows, hipStream_t stream, int rounds = 10);
+                          int q_begin, int q_rows, hipStream_t stream, int rounds = 10, int bits = 32);
 
 int launch_rmsnorm(const void* x, const void* weight, void* y, int64_t rows, int n, float eps,
                    hipStream_t stream);

@@ -141,7 +141,7 @@ int layer_step_impl(int schedule, const rov_gemm_desc* gemms, int n_gemms, const
                     void* side_stream) {
     if (rounds != 10 && rounds != 7 && rounds != 5 && rounds != 3) return ROV_ERR_INVALID;
     if (bits != 32 && bits != 16 && bits != 8) return ROV_ERR_INVALID;
-    if (bits != 32 && (rounds != 10 || schedule == ROV_SCHED_FUSED)) return ROV_ERR_UNSUPPORTED;
+    if (bits != 32 && rounds != 10) return ROV_ERR_UNSUPPORTED;
     if (!valid_schedule(schedule) || attn == nullptr || n_gemms < 0 || (n_gemms > 0 && gemms == nullptr))
         return ROV_ERR_INVALID;
     for (int i = 0; i < n_gemms; ++i) {
@@ -226,7 +226,7 @@ int layer_step_impl(int schedule, const rov_gemm_desc* gemms, int n_gemms, const
     return traced(ROV_TRACE_ATTENTION, ms, [&] {
         return launch_attention(attn->Q, attn->K, attn->V, attn->O, attn->B, attn->H, attn->Hkv,
                                 attn->S, attn->d, attn->strides, attn->dtype, attn->causal, attn->p,
-                                need_mask ? mask : nullptr, seed, offset, ms, rounds);
+                                need_mask ? mask : nullptr, seed, offset, ms, rounds, bits);
     });
 }
 

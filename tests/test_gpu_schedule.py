@@ -102,41 +102,44 @@ def test_layer_step_rounds_three_schedules(rounds, dtype, d):
 
 
 @pytest.mark.parametrize("bits", [8, 16, 32])
-def test_layer_step_bits_sequential_and_overlap(bits):
-    # narrower random numbers (paper Sec. 5.2): both mask-based schedules write the oracle's mask of
-    # that width and drop exactly its elements; the fused schedule has no such form
-    B, S, H, Hkv, d, dtype = 1, 320, 2, 2, 128, torch.bfloat16
+@pytest.mark.parametrize("dtype,d,S", [(torch.bfloat16, 128, 320), (torch.bfloat16, 64, 200), (torch.float32, 64, 100)])
+def test_layer_step_bits_three_schedules(bits, dtype, d, S):
+    # narrower random numbers (paper Sec. 5.2): the mask kernel writes the oracle's mask of that width,
+    # and the three schedules (the fused kernel draws the same fields itself) drop exactly its elements
+    B, H, Hkv = 1, 2, 2
     rng = np.random.default_rng(22)
     q, k, v = wl.qkv(rng, B, S, H, Hkv, d)
     Q, K, V = _dev(q, dtype), _dev(k, dtype), _dev(v, dtype)
     a, w = wl.gemm_operands(rng, 256, 256, 256)
     A, W = _dev(a, dtype), _dev(w, dtype)
-    p, seed, offset = 0.1, 78, 12345
+    p, seed, offset = 0.1, 78, wl.CARRY_OFFSET - 320          # the calls cross 2^32
     words = OP.dropout_mask_bits(seed, offset, B, H, S, p, bits)
     main, side = torch.cuda.Stream(), torch.cuda.Stream()
     outs = []
-    for sched in (rov.SCHED_SEQUENTIAL, rov.SCHED_OVERLAP):
-        print("layer_step_bits", bits, sched, flush=True)
+    for sched in (rov.SCHED_SEQUENTIAL, rov.SCHED_FUSED, rov.SCHED_OVERLAP):
+        print("layer_step_bits", bits, dtype, sched, flush=True)
         O = torch.zeros_like(Q)
         C = torch.zeros((256, 256), dtype=dtype, device="cuda")
         mask = torch.zeros(rov.mask_shape(B, H, S), dtype=torch.int64, device="cuda")
         torch.cuda.synchronize()
-        rov.layer_step(sched, [rov.make_gemm_desc(A, W, C)], rov.make_attn_desc(Q, K, V, O, p), seed, offset, mask,
-                       main, side, bits=bits)
+        rov.layer_step(sched, [rov.make_gemm_desc(A, W, C)], rov.make_attn_desc(Q, K, V, O, p), seed, offset,
+                       None if sched == rov.SCHED_FUSED else mask, main, side, bits=bits)
         torch.cuda.synchronize()
-        assert np.array_equal(mask.cpu().numpy().view(np.uint64), words)
+        if sched != rov.SCHED_FUSED:
+            assert np.array_equal(mask.cpu().numpy().view(np.uint64), words)
         outs.append(O)
-    assert torch.equal(outs[0], outs[1])
+    assert torch.equal(outs[0], outs[1]) and torch.equal(outs[0], outs[2])
     ref = OD.attention_dropout(_f64(Q), _f64(K), _f64(V), OP.unpack_keep(words, S), p)
-    assert np.max(np.abs(_f64(outs[0]) - ref)) / np.max(np.abs(ref)) <= 2e-2
-    O = torch.zeros_like(Q)
-    if bits != 32:
-        with pytest.raises(rov.RovError):
-            rov.layer_step(rov.SCHED_FUSED, [], rov.make_attn_desc(Q, K, V, O, p), seed, offset, None, main, side,
-                           bits=bits)
+    tol = 2e-2 if dtype == torch.bfloat16 else 1e-4
+    assert np.max(np.abs(_f64(outs[0]) - ref)) / np.max(np.abs(ref)) <= tol
+    O2 = rov.attention_fwd_dropout(Q, K, V, p, seed=seed, offset=offset, bits=bits)
+    torch.cuda.synchronize()
+    assert torch.equal(O2, outs[0])
     with pytest.raises(rov.RovError):
         rov.layer_step(rov.SCHED_OVERLAP, [], rov.make_attn_desc(Q, K, V, O, p), seed, offset, mask, main, side,
                        bits=12)
+    with pytest.raises(rov.RovError):
+        rov.attention_fwd_dropout(Q, K, V, p, seed=seed, offset=offset, bits=4)
 
 
 def test_layer_step_rounds_rejects_other_counts():

@@ -325,16 +325,20 @@ __global__ __launch_bounds__(256, 1) void gemm_tn_kernel(const char* __restrict_
     // Two slots; slot-step S lives in slot S % 2 and is two k-steps, (S,0) and (S,1).
     //   (S,0): MFMAs on the fragments of (S,0); the fragments of (S,1) are read from slot S.
     //   then:  own LDS reads done, barrier: slot S is free.
-    //   (S,1), first half: MFMAs on (S,1); the loads of slot-step S+2 go into slot S (16 per wave,
-    //          one every 2 MFMAs), as early as the slot allows: they have two k-steps to land.
-    //   then:  own loads of slot-step S+1 landed (vmcnt(16): the 16 just issued are younger),
-    //          barrier: slot S+1 is complete for every wave.
-    //   (S,1), second half: the fragments of (S+1,0) are read from slot S+1.
+    //   (S,1): MFMAs on (S,1); the loads of slot-step S+2 go into slot S, 16 per wave, one every
+    //          4 MFMAs over the whole k-step.  The four waves share one texture-address unit that
+    //          takes 16 cycles per load, as long as an MFMA runs, and a wave issues nothing while its
+    //          load waits there: at one load per 2 MFMAs per wave the unit is oversubscribed and the
+    //          matrix pipe starves (measured with loads that touch no memory: 1.79 against 1.94
+    //          PFLOP/s on zero operands).  The last load still has one and a half k-steps to land.
+    //   half-way through (S,1): own loads of slot-step S+1 landed (vmcnt(8): the 8 issued so far in
+    //          this k-step are younger), barrier: slot S+1 is complete for every wave; the fragments
+    //          of (S+1,0) are read from it in the second half.
 #pragma unroll
     for (int q = 0; q < 16; ++q) issue(q, 0, lds_base);
 #pragma unroll
-    for (int q = 0; q < 16; ++q) issue(q, 1, lds_base + kSlot);
-    __builtin_amdgcn_s_waitcnt(0x4F70);   // vmcnt(16): slot-step 0 has landed
+    for (int q = 0; q < 11; ++q) issue(q, 1, lds_base + kSlot);   // its last 5 loads go out in (0,0) like everywhere below
+    __builtin_amdgcn_s_waitcnt(0x0F7B);   // vmcnt(11): slot-step 0 has landed
     __syncthreads();
 #pragma unroll
     for (int f = 0; f < 16; ++f) read_frag(0, lds, f);
@@ -347,6 +351,7 @@ __global__ __launch_bounds__(256, 1) void gemm_tn_kernel(const char* __restrict_
         for (int idx = 0; idx < 64; ++idx) {
             mfma_one(0, idx >> 3, idx & 7);
             if (idx < 32 && (idx & 1) == 0) read_frag(1, cur, idx >> 1);
+            if (idx < 32 && idx % 6 == 3) issue(11 + idx / 6, S + 1, lds_base + ((S + 1) & 1) * kSlot);   // loads 11..15 of slot-step S+1
             __builtin_amdgcn_sched_barrier(0);
         }
         __builtin_amdgcn_s_waitcnt(0xC07F);   // lgkmcnt(0): fragments of (S,1)
@@ -354,11 +359,11 @@ __global__ __launch_bounds__(256, 1) void gemm_tn_kernel(const char* __restrict_
 #pragma unroll
         for (int idx = 0; idx < 64; ++idx) {
             if (idx == 32) {
-                __builtin_amdgcn_s_waitcnt(0x4F70);   // vmcnt(16)
+                __builtin_amdgcn_s_waitcnt(0x0F76);   // vmcnt(6)
                 __syncthreads();
             }
             mfma_one(1, idx >> 3, idx & 7);
-            if (idx < 32 && (idx & 1) == 1) issue(idx >> 1, S + 2, lds_base + (S & 1) * kSlot);
+            if (idx % 6 == 1) issue(idx / 6, S + 2, lds_base + (S & 1) * kSlot);          // loads 0..10 of slot-step S+2
             if (idx >= 32 && (idx & 1) == 0) read_frag(0, nxt, (idx - 32) >> 1);
             __builtin_amdgcn_sched_barrier(0);
         }
@@ -533,7 +538,7 @@ __global__ __launch_bounds__(256, 1) void gemm_fp8_kernel(const char* __restrict
 
     // Ring of 4 slots, one MFMA k-step (64 bytes of k per row) per slot; step t lives in slot t % 4.
     // At the top of step s every wave has the fragments of step s in registers, so slot s % 4 is
-    // free and takes the loads of step s+4 (8 per wave, one every 4 MFMAs in the second half of the
+    // free and takes the loads of step s+4 (8 per wave, one every 2 MFMAs = 128 cycles over the whole
     // step); the fragments of step s+1 are read in the first half.  Loads complete in order, so
     // "step s+1 has landed" is vmcnt <= 16 (steps s+2, s+3 are the only later ones in flight).
 #pragma unroll
@@ -556,9 +561,8 @@ __global__ __launch_bounds__(256, 1) void gemm_fp8_kernel(const char* __restrict
             if (idx < 8) {
                 read_frag(buf ^ 1, nxt, 2 * idx);
                 read_frag(buf ^ 1, nxt, 2 * idx + 1);
-            } else {
-                issue(idx - 8, s + 4, slot);
             }
+            if (idx & 1) issue(idx >> 1, s + 4, slot);   // one load per 2 MFMAs over the whole step (see gemm_tn_kernel)
             __builtin_amdgcn_sched_barrier(0);
         }
     };

@@ -325,15 +325,17 @@ __global__ __launch_bounds__(256, 1) void gemm_tn_kernel(const char* __restrict_
     // Two slots; slot-step S lives in slot S % 2 and is two k-steps, (S,0) and (S,1).
     //   (S,0): MFMAs on the fragments of (S,0); the fragments of (S,1) are read from slot S.
     //   then:  own LDS reads done, barrier: slot S is free.
-    //   (S,1): MFMAs on (S,1); the loads of slot-step S+2 go into slot S, 16 per wave, one every
-    //          4 MFMAs over the whole k-step.  The four waves share one texture-address unit that
-    //          takes 16 cycles per load, as long as an MFMA runs, and a wave issues nothing while its
-    //          load waits there: at one load per 2 MFMAs per wave the unit is oversubscribed and the
-    //          matrix pipe starves (measured with loads that touch no memory: 1.79 against 1.94
-    //          PFLOP/s on zero operands).  The last load still has one and a half k-steps to land.
-    //   half-way through (S,1): own loads of slot-step S+1 landed (vmcnt(8): the 8 issued so far in
-    //          this k-step are younger), barrier: slot S+1 is complete for every wave; the fragments
-    //          of (S+1,0) are read from it in the second half.
+    //   (S,1): MFMAs on (S,1); half-way through: own loads of slot-step S+1 landed, barrier (slot
+    //          S+1 is complete for every wave), then the fragments of (S+1,0) are read from it.
+    // Loads of slot-step S+2 (into slot S), 16 per wave, go out one per 6 MFMAs: 11 in (S,1), the
+    // last 5 in (S+1,0).  The four waves share one texture-address unit that takes 16 cycles per
+    // load, as long as an MFMA runs, and a wave issues nothing while its load waits there: at one
+    // load per 2 MFMAs per wave the unit is oversubscribed and the matrix pipe starves (measured
+    // with loads that touch no memory, zero operands: 1.79 PFLOP/s at one per 2, 1.94 at one per 4).
+    // At the barrier inside (S,1) a wave has issued 6 younger loads: vmcnt(6).  Letting the waves
+    // take turns behind different MFMAs would remove the rest of the queueing, but a taken branch
+    // around the load costs more than the load, and a load under an empty EXEC mask still costs
+    // its 16 cycles (both measured: 20 % and 35 % slower).
 #pragma unroll
     for (int q = 0; q < 16; ++q) issue(q, 0, lds_base);
 #pragma unroll

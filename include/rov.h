@@ -170,6 +170,15 @@ int rov_valu_probe(int kind, int iters, int workgroups, uint64_t *out, void *str
 int rov_gemm(const void *A, const void *Bm, void *C, int M, int N, int K, int dtype, int transB,
              float scaleA, float scaleB, void *stream);
 
+/* Tile width of the bf16 matrix-core GEMM kernel (the Table 1 GEMM column's
+ * MMA-bound kernel), in output columns: 0 = chosen per call from the shape (the
+ * default: the width that wastes least of the last round of workgroups over the
+ * compute units), or one of 128, 160, 192, 224, 256 for every later call.  The
+ * result is the same sum in the same order for every width.  For experiments
+ * and tests; process-wide.  Returns the previous value, or ROV_ERR_INVALID
+ * (nothing changed) for any other argument. */
+int rov_set_gemm_tile_cols(int cols);
+
 /* ---------------------------------------------------------------- attention
  * O = dropout(softmax(Q K^T / sqrt(d))) V, dropout applied to the softmax
  * output (paper Sec. 2.2), kept probabilities scaled by 1/(1-p); the softmax

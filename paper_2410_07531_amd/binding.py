@@ -72,6 +72,7 @@ SIGNATURES = {
     "rov_layer_step_chunked": (_i, [ctypes.POINTER(GemmDesc), _i, ctypes.POINTER(AttnDesc), _u64, _u64, _i,
                                     _p, _p, _p]),
     "rov_set_rng_max_workgroups": (_i, [_i]),
+    "rov_set_gemm_tile_cols": (_i, [_i]),
     "rov_set_rng_overlap_workgroups_per_cu": (_i, [_i]),
     "rov_trace_enable": (_i, [_i]),
     "rov_trace_read": (_i, [ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_float), _i,
@@ -156,6 +157,13 @@ def mask_philox_calls_bits(B, H, S, bits):
 
 def set_rng_max_workgroups(n):
     return int(load().rov_set_rng_max_workgroups(int(n)))
+
+
+def set_gemm_tile_cols(cols):
+    r = int(load().rov_set_gemm_tile_cols(int(cols)))
+    if r < 0:
+        raise RovError(r, "rov_set_gemm_tile_cols")
+    return r
 
 
 def set_rng_overlap_workgroups_per_cu(n):

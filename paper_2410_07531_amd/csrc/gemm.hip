@@ -38,8 +38,12 @@
 
 #include "rov_internal.h"
 
+#include <atomic>
+
 namespace rov {
 namespace {
+
+std::atomic<int> g_tile_cols{0};   // rov_set_gemm_tile_cols: 0 = per shape
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
@@ -190,7 +194,12 @@ __device__ __forceinline__ void epilogue_combine(int epi, uint2 r, float& c0, fl
     }
 }
 
-// bf16 inputs; output and side input are bf16.
+// bf16 inputs; output and side input are bf16.  NJ = weight-row blocks (16 rows) per wave: the
+// workgroup tile is 256 x 32*NJ.  NJ = 8 moves the fewest bytes per flop; the narrower tiles exist
+// for shapes whose tile count would otherwise leave the last round over the compute units partly
+// empty (2048 x 14336: 448 tiles of 256 x 256 are 1.75 rounds over 256 units and take the time of
+// 2; 512 tiles of 256 x 224 are 2 rounds of 7/8 the work each).
+template <int NJ>
 __global__ __launch_bounds__(256, 1) void gemm_tn_kernel(const char* __restrict__ A,
                                                          const char* __restrict__ Wt,
                                                          uint16_t* __restrict__ C,
@@ -219,12 +228,13 @@ __global__ __launch_bounds__(256, 1) void gemm_tn_kernel(const char* __restrict_
     const int in_band = id - band * GM * tiles_n;
     const int tm = band * GM + in_band % band_rows;
     const int tn = in_band / band_rows;
-    const int m0 = tm * BM, n0 = tn * BN;
+    constexpr int BNT = 32 * NJ;                 // tile width (weight rows)
+    const int m0 = tm * BM, n0 = tn * BNT;
 
     constexpr int ESZ = 2;
-    f32x4 acc[8][8];   // [weight-row block j (16 rows)][activation-row block i (16 rows)]
+    f32x4 acc[NJ][8];   // [weight-row block j (16 rows)][activation-row block i (16 rows)]
 #pragma unroll
-    for (int j = 0; j < 8; ++j)
+    for (int j = 0; j < NJ; ++j)
 #pragma unroll
         for (int i = 0; i < 8; ++i)
 #pragma unroll
@@ -235,7 +245,7 @@ __global__ __launch_bounds__(256, 1) void gemm_tn_kernel(const char* __restrict_
     // the row-major operand: with 64-byte row pieces the same L2 -> LDS stream reached 15 TB/s on
     // this chip, with whole lines 26 TB/s, and this kernel is bound by that stream.
     constexpr int kRow = 128;
-    constexpr int kSlot = (BM + BN) * kRow;
+    constexpr int kSlot = (BM + BN) * kRow;      // slot stride (the widest tile's); W rows follow the A rows
     static_assert(2 * kSlot <= kLdsBytes, "two slots fit the launch's LDS");
     // 16-byte chunk swizzle of a 128-byte LDS row (8 chunks, two rows per 256 bytes of banks): the
     // chunk index is XORed with (row / 2) % 8.  A fragment read has lane = 16*chunk + row; the lane
@@ -249,15 +259,15 @@ __global__ __launch_bounds__(256, 1) void gemm_tn_kernel(const char* __restrict_
 #pragma unroll
     for (int h = 0; h < 2; ++h) foff[h] = frow * kRow + (((4 * h + fchunk) ^ swz(frow)) << 4);   // block bases are multiples of 16
     const int a_base = (wm * 128) * kRow;
-    const int w_base = BM * kRow + (wn * 128) * kRow;
+    const int w_base = BM * kRow + (wn * 16 * NJ) * kRow;
 
-    // Loads: wave w issues row blocks (8 rows) w, w+4, ..., w+28 of each operand: 16 instructions
+    // Loads: wave w issues row blocks (8 rows) w, w+4, ... of each operand: 8 + NJ instructions
     // per slot.  Lane L fills physical chunk L%8 of row L/8, i.e. fetches logical chunk (L%8) ^ swz(row).
     const size_t ld_bytes = (size_t)K * ESZ;
     const int ns = (int)(ld_bytes / kRow);            // slots to walk
     const int rows_a = M - m0 < BM ? M - m0 : BM;
-    const int rows_w = N - n0 < BN ? N - n0 : BN;
-    uint32_t voff_a[8], voff_w[8];
+    const int rows_w = N - n0 < BNT ? N - n0 : BNT;
+    uint32_t voff_a[8], voff_w[NJ];
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
         const int row = (wave + 4 * j) * 8 + (lane >> 3);
@@ -265,7 +275,7 @@ __global__ __launch_bounds__(256, 1) void gemm_tn_kernel(const char* __restrict_
         const int ra = row < rows_a ? row : rows_a - 1;   // rows past the edge are never stored
         const int rw = row < rows_w ? row : rows_w - 1;
         voff_a[j] = (uint32_t)((size_t)ra * ld_bytes) + (uint32_t)(chunk * 16);
-        voff_w[j] = (uint32_t)((size_t)rw * ld_bytes) + (uint32_t)(chunk * 16);
+        if (j < NJ) voff_w[j] = (uint32_t)((size_t)rw * ld_bytes) + (uint32_t)(chunk * 16);
     }
     const char* a_panel = A + (size_t)m0 * ld_bytes;
     const char* w_panel = Wt + (size_t)n0 * ld_bytes;
@@ -287,7 +297,7 @@ __global__ __launch_bounds__(256, 1) void gemm_tn_kernel(const char* __restrict_
     const i32x4 rsrc_w = make_rsrc(w_panel, (size_t)rows_w * ld_bytes);
     const uint32_t lds_base = (uint32_t)(uintptr_t)(lptr_t)lds;
 
-    // Load instruction q (0..7 = A row blocks, 8..15 = W row blocks) of slot-step `step` into the
+    // Load instruction q (0..7 = A row blocks, 8..7+NJ = W row blocks) of slot-step `step` into the
     // slot at LDS byte address `slot`.  Inline assembly, so that the compiler's wait-count pass does
     // not see an LDS write it cannot tell apart from the fragment reads (it would force vmcnt(0)
     // before every LDS read); the waits are placed by hand below.  M0 (the LDS base of the
@@ -308,8 +318,8 @@ __global__ __launch_bounds__(256, 1) void gemm_tn_kernel(const char* __restrict_
         }
     };
 
-    i32x4 af[2][8], wf[2][8];   // fragments of the two k-steps of a slot
-    auto read_frag = [&](int h, const char* slot, int f /*0..7 = A block, 8..15 = W block*/) {
+    i32x4 af[2][8], wf[2][NJ];   // fragments of the two k-steps of a slot
+    auto read_frag = [&](int h, const char* slot, int f /*0..7 = A block, 8..7+NJ = W block*/) {
         if (f < 8)
             af[h][f] = *reinterpret_cast<const i32x4*>(slot + a_base + f * 16 * kRow + foff[h]);
         else
@@ -322,51 +332,60 @@ __global__ __launch_bounds__(256, 1) void gemm_tn_kernel(const char* __restrict_
         asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc[j][i]) : "v"(wf[h][j]), "v"(af[h][i]));
     };
 
-    // Two slots; slot-step S lives in slot S % 2 and is two k-steps, (S,0) and (S,1).
-    //   (S,0): MFMAs on the fragments of (S,0); the fragments of (S,1) are read from slot S.
+    // Two slots; slot-step S lives in slot S % 2 and is two k-steps, (S,0) and (S,1), of NM = 8*NJ
+    // MFMAs each.
+    //   (S,0): MFMAs on the fragments of (S,0); the NF = 8+NJ fragments of (S,1) are read from slot S.
     //   then:  own LDS reads done, barrier: slot S is free.
-    //   (S,1): MFMAs on (S,1); half-way through: own loads of slot-step S+1 landed, barrier (slot
-    //          S+1 is complete for every wave), then the fragments of (S+1,0) are read from it.
-    // Loads of slot-step S+2 (into slot S), 16 per wave, go out one per 6 MFMAs: 11 in (S,1), the
-    // last 5 in (S+1,0).  The four waves share one texture-address unit that takes 16 cycles per
-    // load, as long as an MFMA runs, and a wave issues nothing while its load waits there: at one
-    // load per 2 MFMAs per wave the unit is oversubscribed and the matrix pipe starves (measured
-    // with loads that touch no memory, zero operands: 1.79 PFLOP/s at one per 2, 1.94 at one per 4).
-    // At the barrier inside (S,1) a wave has issued 6 younger loads: vmcnt(6).  Letting the waves
-    // take turns behind different MFMAs would remove the rest of the queueing, but a taken branch
-    // around the load costs more than the load, and a load under an empty EXEC mask still costs
-    // its 16 cycles (both measured: 20 % and 35 % slower).
+    //   (S,1): MFMAs on (S,1); at MFMA HB = NM - 2*NF: own loads of slot-step S+1 landed, barrier
+    //          (slot S+1 is complete for every wave), then the fragments of (S+1,0) are read from it,
+    //          one per 2 MFMAs, which takes the rest of the k-step.
+    // Loads of slot-step S+2 (into slot S), NL = 8+NJ per wave, go out one per G MFMAs: P1 of them
+    // in (S,1), the rest in (S+1,0).  The four waves share one texture-address unit that takes 16
+    // cycles per load, as long as an MFMA runs, and a wave issues nothing while its load waits
+    // there: at one load per 2 MFMAs per wave the unit is oversubscribed and the matrix pipe starves
+    // (measured with loads that touch no memory, zero operands: 1.79 PFLOP/s at one per 2, 1.94 at
+    // one per 4).  At the barrier inside (S,1) a wave has issued VMB younger loads: vmcnt(VMB).
+    // Letting the waves take turns behind different MFMAs would remove the rest of the queueing,
+    // but a taken branch around the load costs more than the load, and a load under an empty EXEC
+    // mask still costs its 16 cycles (both measured: 20 % and 35 % slower).
+    constexpr int NM = 8 * NJ, NF = 8 + NJ, NL = 8 + NJ;
+    constexpr int G = NJ >= 5 ? 6 : 5;
+    constexpr int HB = NM - 2 * NF;
+    constexpr int P1 = (NM - 2) / G + 1;               // load slots idx % G == 1 of a k-step
+    constexpr int P0 = NM >= 4 ? (NM - 4) / G + 1 : 0; // load slots idx % G == 3 of a k-step
+    constexpr int VMB = HB >= 2 ? (HB - 2) / G + 1 : 0;
+    static_assert(HB >= 0 && P1 <= NL && NL - P1 <= P0 && VMB < 16, "load schedule fits the k-steps");
 #pragma unroll
-    for (int q = 0; q < 16; ++q) issue(q, 0, lds_base);
+    for (int q = 0; q < NL; ++q) issue(q, 0, lds_base);
 #pragma unroll
-    for (int q = 0; q < 11; ++q) issue(q, 1, lds_base + kSlot);   // its last 5 loads go out in (0,0) like everywhere below
-    __builtin_amdgcn_s_waitcnt(0x0F7B);   // vmcnt(11): slot-step 0 has landed
+    for (int q = 0; q < P1; ++q) issue(q, 1, lds_base + kSlot);   // its other loads go out in (0,0) like everywhere below
+    __builtin_amdgcn_s_waitcnt(0x0F70 | P1);   // vmcnt(P1): slot-step 0 has landed
     __syncthreads();
 #pragma unroll
-    for (int f = 0; f < 16; ++f) read_frag(0, lds, f);
+    for (int f = 0; f < NF; ++f) read_frag(0, lds, f);
 
     for (int S = 0; S < ns; ++S) {
         const char* cur = lds + (S & 1) * kSlot;
         const char* nxt = lds + ((S + 1) & 1) * kSlot;
         __builtin_amdgcn_s_waitcnt(0xC07F);   // lgkmcnt(0): fragments of (S,0)
 #pragma unroll
-        for (int idx = 0; idx < 64; ++idx) {
+        for (int idx = 0; idx < NM; ++idx) {
             mfma_one(0, idx >> 3, idx & 7);
-            if (idx < 32 && (idx & 1) == 0) read_frag(1, cur, idx >> 1);
-            if (idx < 32 && idx % 6 == 3) issue(11 + idx / 6, S + 1, lds_base + ((S + 1) & 1) * kSlot);   // loads 11..15 of slot-step S+1
+            if (idx < 2 * NF && (idx & 1) == 0) read_frag(1, cur, idx >> 1);
+            if (idx % G == 3 && P1 + idx / G < NL) issue(P1 + idx / G, S + 1, lds_base + ((S + 1) & 1) * kSlot);   // the other loads of slot-step S+1
             __builtin_amdgcn_sched_barrier(0);
         }
         __builtin_amdgcn_s_waitcnt(0xC07F);   // lgkmcnt(0): fragments of (S,1)
         __syncthreads();
 #pragma unroll
-        for (int idx = 0; idx < 64; ++idx) {
-            if (idx == 32) {
-                __builtin_amdgcn_s_waitcnt(0x0F76);   // vmcnt(6)
+        for (int idx = 0; idx < NM; ++idx) {
+            if (idx == HB) {
+                __builtin_amdgcn_s_waitcnt(0x0F70 | VMB);   // vmcnt(VMB)
                 __syncthreads();
             }
             mfma_one(1, idx >> 3, idx & 7);
-            if (idx % 6 == 1) issue(idx / 6, S + 2, lds_base + (S & 1) * kSlot);          // loads 0..10 of slot-step S+2
-            if (idx >= 32 && (idx & 1) == 0) read_frag(0, nxt, (idx - 32) >> 1);
+            if (idx % G == 1) issue(idx / G, S + 2, lds_base + (S & 1) * kSlot);          // loads 0..P1-1 of slot-step S+2
+            if (idx >= HB && ((idx - HB) & 1) == 0) read_frag(0, nxt, (idx - HB) >> 1);
             __builtin_amdgcn_sched_barrier(0);
         }
     }
@@ -378,12 +397,12 @@ __global__ __launch_bounds__(256, 1) void gemm_tn_kernel(const char* __restrict_
     const int nsub = (lane >> 4) * 4;
     // The side input of row block i+1 is requested before row block i is combined and stored, so
     // its latency is paid once per tile, not once per element group (the wave is alone on its SIMD).
-    uint2 rv[2][8];
-    auto load_side = [&](int i, uint2 (&dst)[8]) {
+    uint2 rv[2][NJ];
+    auto load_side = [&](int i, uint2 (&dst)[NJ]) {
         const int m = m0 + wm * 128 + i * 16 + mrow;
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            const int n = n0 + wn * 128 + j * 16 + nsub;
+        for (int j = 0; j < NJ; ++j) {
+            const int n = n0 + wn * 16 * NJ + j * 16 + nsub;
             dst[j] = make_uint2(0u, 0u);
             if (m < M && n < N) dst[j] = *reinterpret_cast<const uint2*>(R + (size_t)m * N + n);
         }
@@ -395,8 +414,8 @@ __global__ __launch_bounds__(256, 1) void gemm_tn_kernel(const char* __restrict_
         __builtin_amdgcn_sched_barrier(0);
         if (R != nullptr && i + 1 < 8) load_side(i + 1, rv[(i + 1) & 1]);
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            const int n = n0 + wn * 128 + j * 16 + nsub;
+        for (int j = 0; j < NJ; ++j) {
+            const int n = n0 + wn * 16 * NJ + j * 16 + nsub;
             float c0 = alpha * acc_read(acc[j][i][0]);
             float c1 = alpha * acc_read(acc[j][i][1]);
             float c2 = alpha * acc_read(acc[j][i][2]);
@@ -632,18 +651,39 @@ int launch_gemm_epilogue(const void* A, const void* Bm, void* C, const void* R, 
     const int esz = dtype == ROV_BF16 ? 2 : 1;
 
     if (dtype != ROV_F32 && tb && ((size_t)K * esz) % (2 * kRowBytes) == 0 && (N % 4) == 0) {
-        const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
-        const long long T = (long long)tiles_m * tiles_n;
-        if (T > 0x7FFFFFFFLL) return ROV_ERR_UNSUPPORTED;
         // a 256-row operand panel is addressed with 32-bit byte offsets
         if ((unsigned long long)BM * (unsigned long long)K * (unsigned long long)esz > 0xFFFFFFFFull)
             return ROV_ERR_UNSUPPORTED;
-        auto kern = esz == 2 ? gemm_tn_kernel : gemm_fp8_kernel;
-        static bool attr_set[2] = {false, false};
-        if (!attr_set[esz - 1]) {
+        const int tiles_m = (M + BM - 1) / BM;
+        // Tile width 32*nj.  The workgroups run in rounds of one per compute unit; a tile costs about
+        // nj + 1 units (its A panel does not shrink with it), so pick the width with the smallest
+        // rounds x (nj + 1), the widest on ties.  fp8 has the 256-wide kernel only.
+        int nj = 8;
+        const int forced = g_tile_cols.load();
+        if (esz == 2 && forced != 0) {
+            nj = forced / 32;
+        } else if (esz == 2) {
+            const long long ncu = device_cu_count();
+            long long best = -1;
+            for (int c = 8; c >= 4; --c) {
+                const long long t = (long long)tiles_m * ((N + 32 * c - 1) / (32 * c));
+                const long long cost = ((t + ncu - 1) / ncu) * (c + 1);
+                if (best < 0 || cost < best) { best = cost; nj = c; }
+            }
+        }
+        const int tiles_n = (N + 32 * nj - 1) / (32 * nj);
+        const long long T = (long long)tiles_m * tiles_n;
+        if (T > 0x7FFFFFFFLL) return ROV_ERR_UNSUPPORTED;
+        typedef void (*kern_t)(const char*, const char*, uint16_t*, const uint16_t*, int, int, int, float, int, int, int);
+        static const kern_t kerns[6] = {gemm_fp8_kernel,   gemm_tn_kernel<4>, gemm_tn_kernel<5>,
+                                        gemm_tn_kernel<6>, gemm_tn_kernel<7>, gemm_tn_kernel<8>};
+        const int ki = esz == 2 ? nj - 3 : 0;
+        const kern_t kern = kerns[ki];
+        static bool attr_set[6] = {false, false, false, false, false, false};
+        if (!attr_set[ki]) {
             ROV_HIP_TRY(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
                                             kLdsBytes));
-            attr_set[esz - 1] = true;
+            attr_set[ki] = true;
         }
         hipLaunchKernelGGL(kern, dim3((unsigned)T), dim3(256), kLdsBytes, stream, (const char*)A,
                            (const char*)Bm, (uint16_t*)C, (const uint16_t*)R, M, N, K, alpha, tiles_m,
@@ -682,6 +722,11 @@ int launch_gemm_epilogue(const void* A, const void* Bm, void* C, const void* R, 
 }
 
 }  // namespace rov
+
+extern "C" int rov_set_gemm_tile_cols(int cols) {
+    if (cols != 0 && (cols < 128 || cols > 256 || cols % 32 != 0)) return ROV_ERR_INVALID;
+    return rov::g_tile_cols.exchange(cols);
+}
 
 extern "C" int rov_gemm(const void* A, const void* Bm, void* C, int M, int N, int K, int dtype,
                         int transB, float scaleA, float scaleB, void* stream) {

@@ -53,6 +53,38 @@ def test_gemm_bf16_matches_oracle(M, N, K, transB):
     assert err <= BF16_TOL and err <= BF16_EXPECTED, err
 
 
+@pytest.mark.parametrize("cols", [128, 160, 192, 224, 256])
+def test_gemm_bf16_every_tile_width(cols):
+    # each width of the matrix-core kernel on a shape with several tiles in both directions, a
+    # ragged last tile for every width (N = 1000), clamped rows (M = 600) and an odd slot count;
+    # all widths give the same bits (same k order per element)
+    M, N, K = 600, 1000, 448
+    print("gemm bf16 width", cols, flush=True)
+    rng = np.random.default_rng(11)
+    a, w = wl.gemm_operands(rng, M, K, N)
+    A, W = _to_dev(a, torch.bfloat16), _to_dev(w, torch.bfloat16)
+    prev = rov.set_gemm_tile_cols(cols)
+    try:
+        C = rov.gemm(A, W, transB=True)
+        torch.cuda.synchronize()
+    finally:
+        rov.set_gemm_tile_cols(prev)
+    ref = OD.gemm(_f64(A), _f64(W), transB=True)
+    err = _rel_err(_f64(C), ref)
+    assert err <= BF16_TOL and err <= BF16_EXPECTED, err
+    C0 = rov.gemm(A, W, transB=True)       # width chosen from the shape
+    torch.cuda.synchronize()
+    assert torch.equal(C.view(torch.int16), C0.view(torch.int16))
+
+
+def test_gemm_tile_width_knob_rejects_other_values():
+    prev = rov.set_gemm_tile_cols(0)
+    for bad in (-32, 64, 96, 130, 288):
+        with pytest.raises(rov.RovError):
+            rov.set_gemm_tile_cols(bad)
+    assert rov.set_gemm_tile_cols(prev) == 0
+
+
 def test_gemm_bf16_scale_and_one_hot():
     # alpha = scaleA*scaleB is applied; one-hot activations copy weight rows exactly (bf16 in, bf16 out)
     rng = np.random.default_rng(3)

@@ -225,6 +225,36 @@ def test_block_forward_three_schedules_match_oracle(causal):
     assert np.max(np.abs(ref - _f64(x))) / np.max(np.abs(ref)) > 0.1
 
 
+def test_block_forward_same_bits_for_every_gemm_tile_width():
+    # the residual and SwiGLU epilogues of every width of the matrix-core GEMM kernel: the block's
+    # output must not depend on the width (same k order per element, same epilogue arithmetic)
+    B, S, H, Hkv, d, hidden, ffn = 1, 320, 4, 2, 128, 512, 1088
+    p, seed, offset = 0.1, wl.SEED, 64
+    x, wd = _block_setup(B, S, H, Hkv, d, hidden, ffn, 22)
+    cfg = rov.make_block_cfg(H, Hkv, d, hidden, ffn, p)
+    weights = rov.make_block_weights(wd)
+    ws = torch.empty(rov.block_workspace_bytes(cfg, B, S, 0), dtype=torch.uint8, device="cuda")
+    main, side = torch.cuda.Stream(), torch.cuda.Stream()
+    ys = {}
+    for cols in (0, 128, 160, 192, 224, 256):
+        print("block width", cols, flush=True)
+        y = torch.zeros_like(x)
+        torch.cuda.synchronize()
+        prev = rov.set_gemm_tile_cols(cols)
+        try:
+            rov.block_forward(weights, x, y, cfg, rov.SCHED_FUSED, seed, offset, None, ws, main, side)
+            torch.cuda.synchronize()
+        finally:
+            rov.set_gemm_tile_cols(prev)
+        ys[cols] = y
+    for cols in (128, 160, 192, 224, 256):
+        assert torch.equal(ys[0], ys[cols]), cols
+    keep = OP.unpack_keep(OP.dropout_mask(seed, offset, B, H, S, p), S)
+    ocfg = dict(H=H, Hkv=Hkv, d=d, eps=1e-5, rope_theta=500000.0, p=p, causal=False)
+    ref = OD.block_forward(_f64(x), {k_: _f64(v_) for k_, v_ in wd.items()}, ocfg, keep)
+    assert np.max(np.abs(_f64(ys[256]) - ref)) / np.max(np.abs(ref)) <= 2e-2
+
+
 def test_block_workspace_and_argument_errors():
     B, S, H, Hkv, d, hidden, ffn = 1, 64, 2, 2, 64, 128, 256
     x, wd = _block_setup(B, S, H, Hkv, d, hidden, ffn, 3)

@@ -7,29 +7,31 @@
 //     lane, kept in AGPRs).  The 16x16x32 shape is used because under the
 //     board's power limit it sustains about a quarter more flop/s on random
 //     data than 32x32x16 (measured with a register-only loop: 2.05 against
-//     1.66 PFLOP/s);
+//     1.66 PFLOP/s).  Narrower tiles (256 x 224 ... 128) are instances of the
+//     same kernel; the launch picks the width that leaves least of the last
+//     round of workgroups over the compute units empty;
 //   - operands go from global memory straight into LDS (buffer_load ... lds,
-//     16 bytes per lane) through a ring of four 32 KiB slots, one MFMA k-step
-//     (64 bytes of k per row) per slot, loaded four steps ahead and issued one
-//     load per four MFMAs, so that the texture-address unit shared by the four
-//     waves never sees a burst; a wave's 64 lanes always fill 1 KiB of
-//     consecutive LDS, so the bank swizzle is applied on the global-address side;
-//   - the fragments of step s+1 are read from LDS during the first half of
-//     step s, so no MFMA waits for an LDS read issued just before it;
+//     16 bytes per lane) through two 64 KiB slots of 128-byte rows (two MFMA
+//     k-steps per slot), loaded two slot-steps ahead and issued one load per
+//     six MFMAs, so that the texture-address unit shared by the four waves
+//     never sees a burst; a wave's 64 lanes always fill 1 KiB of consecutive
+//     LDS, so the bank swizzle is applied on the global-address side;
+//   - the fragments of a k-step are read from LDS during the k-step before
+//     it, so no MFMA waits for an LDS read issued just before it;
 //   - the MFMA is issued with the weight fragment as first operand, so each
 //     lane ends up with 4 consecutive output columns and stores 8 bytes at once;
 //   - workgroup ids are remapped so that the workgroups that land on one XCD
 //     (one L2) cover a compact block of output tiles, and the k loop of a
 //     workgroup starts at a k offset that depends on its tile row, so that the
-//     workgroups of an XCD do not all fetch the same 64-byte column of every
+//     workgroups of an XCD do not all fetch the same 128-byte column of every
 //     row (the same cache channel) at the same time.
-// The register budget (140 VGPRs + 256 AGPRs of 512) leaves room for RNG
-// waves on every SIMD (the paper's carve-out, Sec. 6.2).
+// The register budget (at most 408 of 512 registers, accumulators included)
+// leaves room for RNG waves on every SIMD (the paper's carve-out, Sec. 6.2).
 //
-// fp8 (OCP e4m3) has a kernel of its own with the same ring, loads and tile
-// order: a ring row is 64 bytes either way (32 bf16 or 64 fp8 values), and the
-// fp8 kernel multiplies with the double-rate MFMA 32x32x64 of the f8f6f4 family
-// (a lane's operand is half a ring row), so it does twice the flop per byte.
+// fp8 (OCP e4m3) has a kernel of its own with the same loads and tile order on
+// a ring of four 32 KiB slots of 64-byte rows (one k-step of 64 fp8 values per
+// slot): it multiplies with the double-rate MFMA 32x32x64 of the f8f6f4 family
+// (a lane's operand is half a ring row), twice the flop per byte.
 //
 // Everything else (fp32, [K,N] weights, K not a multiple of the tile depth)
 // takes a small LDS-tiled VALU kernel that is correct for any shape.

@@ -28,10 +28,10 @@
 // The register budget (at most 408 of 512 registers, accumulators included)
 // leaves room for RNG waves on every SIMD (the paper's carve-out, Sec. 6.2).
 //
-// fp8 (OCP e4m3) has a kernel of its own with the same loads and tile order on
-// a ring of four 32 KiB slots of 64-byte rows (one k-step of 64 fp8 values per
-// slot): it multiplies with the double-rate MFMA 32x32x64 of the f8f6f4 family
-// (a lane's operand is half a ring row), twice the flop per byte.
+// fp8 (OCP e4m3) is the same kernel with another main loop: a 128-byte LDS row
+// is one k-step of the double-rate MFMA 16x16x128 of the f8f6f4 family (twice
+// the flop per byte; on random data under the power limit this shape sustains
+// 4.55 PFLOP/s in a register-only loop against 4.0 for 32x32x64).
 //
 // Everything else (fp32, [K,N] weights, K not a multiple of the tile depth)
 // takes a small LDS-tiled VALU kernel that is correct for any shape.
@@ -47,8 +47,6 @@ namespace {
 
 std::atomic<int> g_tile_cols{0};   // rov_set_gemm_tile_cols: 0 = per shape
 
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 __device__ __forceinline__ uint16_t f32_to_bf16_bits(float f) {
     uint32_t u = __float_as_uint(f);
@@ -141,26 +139,14 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(const T* __restrict__
 }
 
 // ------------------------------------------------------------------ MFMA kernel (bf16 / fp8)
-constexpr int BM = 256, BN = 256;
-// fp8 kernel's ring (the bf16 kernel lays the same 128 KiB out as two slots of 128-byte rows)
-constexpr int kRowBytes = 64;                       // one ring-slot row: 64 fp8 values
-constexpr int kSlotBytes = (BM + BN) * kRowBytes;   // 32 KiB: A rows then W rows
-constexpr int kSlots = 4;
-constexpr int kLdsBytes = kSlots * kSlotBytes;      // 128 KiB
+constexpr int BM = 256, BN = 256;                   // tile height; width of the widest tile
+constexpr int kRowBytes = 128;                      // k per LDS row: 64 bf16 or 128 fp8 values
+constexpr int kLdsBytes = 2 * (BM + BN) * kRowBytes;   // two slots of A rows then W rows: 128 KiB
 
 typedef __attribute__((address_space(3))) void* lptr_t;
 typedef int i32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef int i32x8 __attribute__((ext_vector_type(8)));
-
-// 16-byte chunk swizzle of a 64-byte LDS row (4 chunks).  A 64-lane ds_read_b128 is served 16
-// lanes at a time over 64 banks of 4 bytes, and the lanes that go together are not consecutive:
-// measured on gfx950 with a two-lane probe and the bank-conflict counter, they are
-// {0-3, 12-15, 20-27}, {4-11, 16-19, 28-31} and the same two sets + 32.  A fragment read has
-// lane = 16*chunk + row, so such a set holds rows 0-3 and 12-15 of one logical chunk and rows
-// 4-11 of the next; with the chunk index XORed by (-(row/4)) & 3 its 16 addresses fall into 16
-// different bank groups (counter: 0 conflict cycles, against 4 of 8 cycles per read before).
-__device__ __forceinline__ int row_swizzle(int row) { return (0 - (row >> 2)) & 3; }
 
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
@@ -201,7 +187,9 @@ __device__ __forceinline__ void epilogue_combine(int epi, uint2 r, float& c0, fl
 // for shapes whose tile count would otherwise leave the last round over the compute units partly
 // empty (2048 x 14336: 448 tiles of 256 x 256 are 1.75 rounds over 256 units and take the time of
 // 2; 512 tiles of 256 x 224 are 2 rounds of 7/8 the work each).
-template <int NJ>
+// FP8: the operands are OCP e4m3 bytes and a slot row (128 bytes) is one k-step of the double-rate
+// MFMA 16x16x128 of the f8f6f4 family; everything but the main loop is shared with bf16.
+template <int NJ, bool FP8 = false>
 __global__ __launch_bounds__(256, 1) void gemm_tn_kernel(const char* __restrict__ A,
                                                          const char* __restrict__ Wt,
                                                          uint16_t* __restrict__ C,
@@ -233,7 +221,7 @@ __global__ __launch_bounds__(256, 1) void gemm_tn_kernel(const char* __restrict_
     constexpr int BNT = 32 * NJ;                 // tile width (weight rows)
     const int m0 = tm * BM, n0 = tn * BNT;
 
-    constexpr int ESZ = 2;
+    constexpr int ESZ = FP8 ? 1 : 2;
     f32x4 acc[NJ][8];   // [weight-row block j (16 rows)][activation-row block i (16 rows)]
 #pragma unroll
     for (int j = 0; j < NJ; ++j)
@@ -246,15 +234,19 @@ __global__ __launch_bounds__(256, 1) void gemm_tn_kernel(const char* __restrict_
     // 64 KiB; two slots.  A load instruction moves 8 rows x 128 bytes, i.e. whole 128-byte lines of
     // the row-major operand: with 64-byte row pieces the same L2 -> LDS stream reached 15 TB/s on
     // this chip, with whole lines 26 TB/s, and this kernel is bound by that stream.
-    constexpr int kRow = 128;
+    constexpr int kRow = kRowBytes;
     constexpr int kSlot = (BM + BN) * kRow;      // slot stride (the widest tile's); W rows follow the A rows
     static_assert(2 * kSlot <= kLdsBytes, "two slots fit the launch's LDS");
     // 16-byte chunk swizzle of a 128-byte LDS row (8 chunks, two rows per 256 bytes of banks): the
-    // chunk index is XORed with (row / 2) % 8.  A fragment read has lane = 16*chunk + row; the lane
-    // sets that are served together ({0-3, 12-15, 20-27}, {4-11, 16-19, 28-31}, + 32) then hold,
-    // per row parity, 8 rows whose XOR values are all different: 16 different bank groups.
+    // chunk index is XORed with (row / 2) % 8.  A 64-lane ds_read_b128 is served 16 lanes at a time
+    // over 64 banks of 4 bytes, and the lanes that go together are not consecutive: measured on
+    // gfx950 with a two-lane probe and the bank-conflict counter, they are {0-3, 12-15, 20-27},
+    // {4-11, 16-19, 28-31} and the same two sets + 32.  A fragment read has lane = 16*chunk + row;
+    // such a set then holds, per row parity, 8 rows whose XOR values are all different: 16
+    // different bank groups (counter: 0 conflict cycles).
     auto swz = [](int row) { return (row >> 1) & 7; };
-    // fragment of MFMA 16x16x32: lane holds row lane%16, k-chunk (8 bf16) lane/16 of k-step h
+    // fragment of MFMA 16x16x32: lane holds row lane%16, k-chunk (8 bf16) lane/16 of k-step h (fp8:
+    // the same two 16-byte pieces together are the lane's operand of the one MFMA 16x16x128)
     const int frow = lane & 15;
     const int fchunk = lane >> 4;
     int foff[2];
@@ -320,6 +312,72 @@ __global__ __launch_bounds__(256, 1) void gemm_tn_kernel(const char* __restrict_
         }
     };
 
+    if constexpr (FP8) {
+    // fp8: one slot-step is ONE k-step of NM = 8*NJ MFMAs 16x16x128 (32 cycles each).  A lane's
+    // 32-byte operand is made of the same two 16-byte pieces the bf16 path reads (chunk lane/16 of
+    // each half row): which k values a lane group holds does not matter as long as both operands
+    // agree, and it keeps the bf16 swizzle and its conflict-free reads.
+    // All fragments of a step must be in registers when it starts and there is no room for a
+    // second set (256 accumulators + 128 fragment registers), so the next step's fragments
+    // replace the current ones as these retire: the MFMAs go weight block by weight block, weight
+    // fragment j of slot-step S+1 is read once row j is done, activation fragment i after the last
+    // row's MFMA i (the last of each kind at the start of step S+1, from what is then the current
+    // slot).  One barrier per step, after row 0: by then a wave has read the last of LDS slot S
+    // and its loads of slot-step S+1 (all issued during step S-1) are waited for; after it, slot
+    // S+1 is read and slot S takes the loads of slot-step S+2, one per G MFMAs.
+    i32x8 a8[8], w8[NJ];
+    auto read_half = [&](const char* slot, int f /*0..7 = A block, 8..7+NJ = W block*/, int h) {
+        const i32x4 v = *reinterpret_cast<const i32x4*>(
+            slot + (f < 8 ? a_base + f * 16 * kRow : w_base + (f - 8) * 16 * kRow) + foff[h]);
+        i32x8& dst = f < 8 ? a8[f] : w8[f - 8];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) dst[4 * h + e] = v[e];
+    };
+    auto mfma8 = [&](int j, int i) {
+        asm volatile("v_mfma_f32_16x16x128_f8f6f4 %0, %1, %2, %0" : "+a"(acc[j][i]) : "v"(w8[j]), "v"(a8[i]));
+    };
+    constexpr int NM = 8 * NJ, NL = 8 + NJ;
+    constexpr int G0 = (NM - 17) / (NL - 1);
+    constexpr int G = G0 < 1 ? 1 : (G0 > 3 ? 3 : G0);
+    static_assert(9 + G * (NL - 1) < NM, "the loads of a slot-step are issued within one step");
+#pragma unroll
+    for (int q = 0; q < NL; ++q) issue(q, 0, lds_base);
+#pragma unroll
+    for (int q = 0; q < NL; ++q) issue(q, 1, lds_base + kSlot);
+    __builtin_amdgcn_s_waitcnt(0x0F70 | (NL & 15) | ((NL >> 4) << 14));   // vmcnt(NL): slot-step 0 has landed
+    __syncthreads();
+#pragma unroll
+    for (int f = 0; f < 7; ++f) { read_half(lds, f, 0); read_half(lds, f, 1); }
+#pragma unroll
+    for (int f = 8; f < 8 + NJ - 1; ++f) { read_half(lds, f, 0); read_half(lds, f, 1); }
+    // nothing pending at loop entry: the waits the compiler places in the loop are then those of
+    // the loop's own read order, not of whatever order it gave the reads above
+    __builtin_amdgcn_s_waitcnt(0xC07F);
+    for (int S = 0; S < ns; ++S) {
+        const char* cur = lds + (S & 1) * kSlot;
+        const char* nxt = lds + ((S + 1) & 1) * kSlot;
+#pragma unroll
+        for (int idx = 0; idx < NM; ++idx) {
+            if (idx == 8) {
+                __builtin_amdgcn_s_waitcnt(0x0070);   // vmcnt(0) lgkmcnt(0)
+                __syncthreads();
+            }
+            mfma8(idx >> 3, idx & 7);
+            // the last activation and the last weight fragment of this step: their registers were
+            // in use until the last MFMA of the step before
+            if (idx == 0) { read_half(cur, 7, 0); read_half(cur, 7, 1); }
+            if (idx == 1) { read_half(cur, 8 + NJ - 1, 0); read_half(cur, 8 + NJ - 1, 1); }
+            if (idx >= 9 && (idx & 7) == 1) read_half(nxt, 8 + (idx >> 3) - 1, 0);
+            if (idx >= 9 && (idx & 7) == 2) read_half(nxt, 8 + (idx >> 3) - 1, 1);
+            if (idx >= NM - 7) {                      // MFMA (NJ-1, i) has been issued one MFMA ago for i = idx - (NM-7)
+                read_half(nxt, idx - (NM - 7), 0);
+                read_half(nxt, idx - (NM - 7), 1);
+            }
+            if (idx >= 9 && (idx - 9) % G == 0 && (idx - 9) / G < NL) issue((idx - 9) / G, S + 2, lds_base + (S & 1) * kSlot);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
+    } else {
     i32x4 af[2][8], wf[2][NJ];   // fragments of the two k-steps of a slot
     auto read_frag = [&](int h, const char* slot, int f /*0..7 = A block, 8..7+NJ = W block*/) {
         if (f < 8)
@@ -391,6 +449,7 @@ __global__ __launch_bounds__(256, 1) void gemm_tn_kernel(const char* __restrict_
             __builtin_amdgcn_sched_barrier(0);
         }
     }
+    }
     __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): no LDS load may outlive the loop
     asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");   // the last MFMA results are in the accumulators before they are read
 
@@ -433,201 +492,6 @@ __global__ __launch_bounds__(256, 1) void gemm_tn_kernel(const char* __restrict_
     }
 }
 
-// fp8 (OCP e4m3) with the double-rate MFMA 32x32x64 (f8f6f4 family, both operands fp8): the same
-// ring, loads, waits and tile order as gemm_tn_kernel; a ring row (64 bytes) is one k-step of 64
-// values, a lane's operand is half a row (32 bytes = two 16-byte chunks), and the wave's 128 x 128
-// block is 4 x 4 tiles of 32 x 32.  Twice the flop of the bf16 kernel per byte moved.
-__global__ __launch_bounds__(256, 1) void gemm_fp8_kernel(const char* __restrict__ A,
-                                                         const char* __restrict__ Wt,
-                                                         uint16_t* __restrict__ C,
-                                                         const uint16_t* __restrict__ R, int M, int N,
-                                                         int K, float alpha, int tiles_m, int tiles_n, int epi) {
-    extern __shared__ __attribute__((aligned(1024))) char lds[];
-    // Co-resident RNG waves only need the VALU issue slots this kernel leaves idle; raise this
-    // wave's issue priority so that they never delay its MFMA / LDS instruction stream.
-    __builtin_amdgcn_s_setprio(3);
-    const int lane = threadIdx.x & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int wm = wave >> 1, wn = wave & 1;
-
-    // XCD-aware tile id: workgroup ids are dealt round-robin to the 8 XCDs; give each XCD a
-    // contiguous range of logical tiles, ordered in bands of 8 tile-rows with the row fastest.
-    const int T = tiles_m * tiles_n;
-    int id;
-    {
-        const int pid = blockIdx.x, per = T >> 3, rem = T & 7;
-        const int xcd = pid & 7, loc = pid >> 3;
-        id = xcd < rem ? xcd * (per + 1) + loc : rem * (per + 1) + (xcd - rem) * per + loc;
-    }
-    constexpr int GM = 8;
-    const int band = id / (GM * tiles_n);
-    const int band_rows = (tiles_m - band * GM) < GM ? (tiles_m - band * GM) : GM;
-    const int in_band = id - band * GM * tiles_n;
-    const int tm = band * GM + in_band % band_rows;
-    const int tn = in_band / band_rows;
-    const int m0 = tm * BM, n0 = tn * BN;
-
-    constexpr int ESZ = 1;
-    f32x16 acc[4][4];   // [weight-row block j (32 rows)][activation-row block i (32 rows)]
-#pragma unroll
-    for (int j = 0; j < 4; ++j)
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) acc[j][i][e] = 0.0f;
-
-    // fragment of MFMA 32x32x64: lane holds row lane%32 and the 32 k-values 32*(lane/32) .. +31 of
-    // the step, i.e. logical chunks 2*(lane/32) and 2*(lane/32) + 1 of the row
-    const int frow = lane & 31;
-    const int fhalf = lane >> 5;
-    const int foff0 = frow * kRowBytes + (((2 * fhalf) ^ row_swizzle(frow)) << 4);       // block bases are
-    const int foff1 = frow * kRowBytes + (((2 * fhalf + 1) ^ row_swizzle(frow)) << 4);   // multiples of 32
-    const int a_base = (wm * 128) * kRowBytes;
-    const int w_base = BM * kRowBytes + (wn * 128) * kRowBytes;
-
-    // Loads: one wave instruction moves 16 rows x 64 bytes (1 KiB, linear in LDS).  Wave w issues
-    // row blocks w, w+4, w+8, w+12 of each operand: 8 instructions per ring step.  Lane L fills
-    // physical chunk L%4 of row L/4, i.e. fetches logical chunk (L%4) ^ swizzle(row).
-    const size_t ld_bytes = (size_t)K * ESZ;
-    const int ns = (int)(ld_bytes / kRowBytes);       // ring steps (even)
-    const int rows_a = M - m0 < BM ? M - m0 : BM;
-    const int rows_w = N - n0 < BN ? N - n0 : BN;
-    uint32_t voff_a[4], voff_w[4];
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        const int row = (wave + 4 * j) * 16 + (lane >> 2);
-        const int chunk = (lane & 3) ^ row_swizzle(row);
-        const int ra = row < rows_a ? row : rows_a - 1;   // rows past the edge are never stored
-        const int rw = row < rows_w ? row : rows_w - 1;
-        voff_a[j] = (uint32_t)((size_t)ra * ld_bytes) + (uint32_t)(chunk * 16);
-        voff_w[j] = (uint32_t)((size_t)rw * ld_bytes) + (uint32_t)(chunk * 16);
-    }
-    const char* a_panel = A + (size_t)m0 * ld_bytes;
-    const char* w_panel = Wt + (size_t)n0 * ld_bytes;
-    // ring step at which this workgroup starts its cyclic walk over k (the sum does not depend on
-    // the order; the fp32 rounding does, deterministically)
-    const int kstart = (int)(((unsigned)tm * 2u) % (unsigned)ns);
-    // Buffer resources over the two operand panels (scalar base, per-lane 32-bit offset, scalar k
-    // offset; the range ends with the last valid row, so an offset beyond it would read zeros).
-    auto make_rsrc = [](const char* base, size_t bytes) {
-        const uint64_t b = (uint64_t)(uintptr_t)base;
-        i32x4 r;
-        r[0] = __builtin_amdgcn_readfirstlane((int)(uint32_t)b);
-        r[1] = __builtin_amdgcn_readfirstlane((int)(uint32_t)((b >> 32) & 0xFFFFu));
-        r[2] = __builtin_amdgcn_readfirstlane((int)(uint32_t)bytes);
-        r[3] = 0x00020000;
-        return r;
-    };
-    const i32x4 rsrc_a = make_rsrc(a_panel, (size_t)rows_a * ld_bytes);
-    const i32x4 rsrc_w = make_rsrc(w_panel, (size_t)rows_w * ld_bytes);
-    const uint32_t lds_base = (uint32_t)(uintptr_t)(lptr_t)lds;
-
-    // Load instruction q (0..3 = A row blocks, 4..7 = W row blocks) of ring step `step` into the
-    // ring slot at LDS byte address `slot`.  Inline assembly, so that the compiler's wait-count
-    // pass does not see an LDS write it cannot tell apart from the fragment reads (it would force
-    // vmcnt(0) before every LDS read); the waits are placed by hand below.  M0 (the LDS base of
-    // the transfer) is a reserved register that compiled code only sets right before its own uses.
-    auto issue = [&](int q, int step, uint32_t slot) {
-        int st = step < ns ? step : ns - 1;       // past the end: harmless reload of the last step
-        st += kstart;
-        st = st >= ns ? st - ns : st;
-        const int koff = st * kRowBytes;
-        if (q < 4) {
-            const uint32_t dst = slot + (uint32_t)((wave + 4 * q) * 1024);
-            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
-                         :: "s"(dst), "v"(voff_a[q]), "s"(rsrc_a), "s"(koff) : "memory");
-        } else {
-            const uint32_t dst = slot + (uint32_t)(BM * kRowBytes + (wave + 4 * (q - 4)) * 1024);
-            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
-                         :: "s"(dst), "v"(voff_w[q - 4]), "s"(rsrc_w), "s"(koff) : "memory");
-        }
-    };
-
-    i32x8 af[2][4], wf[2][4];   // fragments of the current and the next ring step
-    // read r (0..15): half r%2 of fragment r/2 (0..3 = A block, 4..7 = W block)
-    auto read_frag = [&](int buf, const char* slot, int r) {
-        const int f = r >> 1;
-        const char* src = slot + (f < 4 ? a_base + f * 32 * kRowBytes : w_base + (f - 4) * 32 * kRowBytes) +
-                          ((r & 1) ? foff1 : foff0);
-        const i32x4 v = *reinterpret_cast<const i32x4*>(src);
-        i32x8& dst = f < 4 ? af[buf][f] : wf[buf][f - 4];
-#pragma unroll
-        for (int e = 0; e < 4; ++e) dst[4 * (r & 1) + e] = v[e];
-    };
-    // inline assembly with explicit register classes, as in gemm_tn_kernel
-    auto mfma_one = [&](int buf, int j, int i) {
-        asm volatile("v_mfma_f32_32x32x64_f8f6f4 %0, %1, %2, %0" : "+a"(acc[j][i]) : "v"(wf[buf][j]), "v"(af[buf][i]));
-    };
-
-    // Ring of 4 slots, one MFMA k-step (64 bytes of k per row) per slot; step t lives in slot t % 4.
-    // At the top of step s every wave has the fragments of step s in registers, so slot s % 4 is
-    // free and takes the loads of step s+4 (8 per wave, one every 2 MFMAs = 128 cycles over the whole
-    // step); the fragments of step s+1 are read in the first half.  Loads complete in order, so
-    // "step s+1 has landed" is vmcnt <= 16 (steps s+2, s+3 are the only later ones in flight).
-#pragma unroll
-    for (int t = 0; t < 4; ++t)
-#pragma unroll
-        for (int q = 0; q < 8; ++q) issue(q, t, lds_base + t * kSlotBytes);
-    __builtin_amdgcn_s_waitcnt(0x4F78);   // vmcnt(24): step 0 has landed
-    __syncthreads();
-#pragma unroll
-    for (int r = 0; r < 16; ++r) read_frag(0, lds, r);
-
-    auto step_body = [&](int buf, int s) {
-        const char* nxt = lds + ((s + 1) & 3) * kSlotBytes;
-        const uint32_t slot = lds_base + (s & 3) * kSlotBytes;
-        __builtin_amdgcn_s_waitcnt(0x4070);   // vmcnt(16) lgkmcnt(0)
-        __syncthreads();
-#pragma unroll
-        for (int idx = 0; idx < 16; ++idx) {   // 16 MFMAs of 64 cycles: the bf16 step's time
-            mfma_one(buf, idx >> 2, idx & 3);
-            if (idx < 8) {
-                read_frag(buf ^ 1, nxt, 2 * idx);
-                read_frag(buf ^ 1, nxt, 2 * idx + 1);
-            }
-            if (idx & 1) issue(idx >> 1, s + 4, slot);   // one load per 2 MFMAs over the whole step (see gemm_tn_kernel)
-            __builtin_amdgcn_sched_barrier(0);
-        }
-    };
-    for (int s = 0; s < ns; s += 2) {
-        step_body(0, s);
-        step_body(1, s + 1);
-    }
-    __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): no LDS load may outlive the loop
-    asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");   // the last MFMA results are in the accumulators before they are read
-
-    // D'[r][c] = C[m = c][n = r]: lane holds activation row lane%32 and, for register e, weight row
-    // 8*(e/4) + 4*(lane/32) + e%4: four consecutive n per e/4
-    const int mrow = lane & 31;
-    const int nsub = (lane >> 5) * 4;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int m = m0 + wm * 128 + i * 32 + mrow;
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const int n = n0 + wn * 128 + j * 32 + q * 8 + nsub;
-                float c0 = alpha * acc_read(acc[j][i][q * 4 + 0]);
-                float c1 = alpha * acc_read(acc[j][i][q * 4 + 1]);
-                float c2 = alpha * acc_read(acc[j][i][q * 4 + 2]);
-                float c3 = alpha * acc_read(acc[j][i][q * 4 + 3]);
-                if (m < M && n < N) {
-                    if (R != nullptr) {
-                        const uint2 r = *reinterpret_cast<const uint2*>(R + (size_t)m * N + n);
-                        epilogue_combine(epi, r, c0, c1, c2, c3);
-                    }
-                    uint2 v;
-                    v.x = pack_bf16x2(c0, c1);
-                    v.y = pack_bf16x2(c2, c3);
-                    *reinterpret_cast<uint2*>(C + (size_t)m * N + n) = v;
-                }
-            }
-        }
-    }
-}
-
 }  // namespace
 
 int launch_gemm(const void* A, const void* Bm, void* C, int M, int N, int K, int dtype, int transB,
@@ -652,19 +516,19 @@ int launch_gemm_epilogue(const void* A, const void* Bm, void* C, const void* R, 
     const bool tb = transB != 0;
     const int esz = dtype == ROV_BF16 ? 2 : 1;
 
-    if (dtype != ROV_F32 && tb && ((size_t)K * esz) % (2 * kRowBytes) == 0 && (N % 4) == 0) {
+    if (dtype != ROV_F32 && tb && ((size_t)K * esz) % kRowBytes == 0 && (N % 4) == 0) {
         // a 256-row operand panel is addressed with 32-bit byte offsets
         if ((unsigned long long)BM * (unsigned long long)K * (unsigned long long)esz > 0xFFFFFFFFull)
             return ROV_ERR_UNSUPPORTED;
         const int tiles_m = (M + BM - 1) / BM;
         // Tile width 32*nj.  The workgroups run in rounds of one per compute unit; a tile costs about
         // nj + 1 units (its A panel does not shrink with it), so pick the width with the smallest
-        // rounds x (nj + 1), the widest on ties.  fp8 has the 256-wide kernel only.
+        // rounds x (nj + 1), the widest on ties.
         int nj = 8;
         const int forced = g_tile_cols.load();
-        if (esz == 2 && forced != 0) {
+        if (forced != 0) {
             nj = forced / 32;
-        } else if (esz == 2) {
+        } else {
             const long long ncu = device_cu_count();
             long long best = -1;
             for (int c = 8; c >= 4; --c) {
@@ -677,11 +541,13 @@ int launch_gemm_epilogue(const void* A, const void* Bm, void* C, const void* R, 
         const long long T = (long long)tiles_m * tiles_n;
         if (T > 0x7FFFFFFFLL) return ROV_ERR_UNSUPPORTED;
         typedef void (*kern_t)(const char*, const char*, uint16_t*, const uint16_t*, int, int, int, float, int, int, int);
-        static const kern_t kerns[6] = {gemm_fp8_kernel,   gemm_tn_kernel<4>, gemm_tn_kernel<5>,
-                                        gemm_tn_kernel<6>, gemm_tn_kernel<7>, gemm_tn_kernel<8>};
-        const int ki = esz == 2 ? nj - 3 : 0;
+        static const kern_t kerns[10] = {gemm_tn_kernel<4>,       gemm_tn_kernel<5>,       gemm_tn_kernel<6>,
+                                         gemm_tn_kernel<7>,       gemm_tn_kernel<8>,       gemm_tn_kernel<4, true>,
+                                         gemm_tn_kernel<5, true>, gemm_tn_kernel<6, true>, gemm_tn_kernel<7, true>,
+                                         gemm_tn_kernel<8, true>};
+        const int ki = nj - 4 + (esz == 2 ? 0 : 5);
         const kern_t kern = kerns[ki];
-        static bool attr_set[6] = {false, false, false, false, false, false};
+        static bool attr_set[10] = {};
         if (!attr_set[ki]) {
             ROV_HIP_TRY(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
                                             kLdsBytes));

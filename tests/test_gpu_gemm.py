@@ -206,6 +206,42 @@ def test_gemm_fp8_matches_oracle(M, N, K):
     assert np.array_equal(mine[nz], Aq.numpy()[nz])
 
 
+@pytest.mark.parametrize("cols", [128, 160, 192, 224, 256])
+def test_gemm_fp8_every_tile_width(cols):
+    # each width of the matrix-core kernel: ragged last tile for every width, clamped rows, odd
+    # number of k-steps; and every e4m3 code decoded exactly through that width
+    from oracle import numerics as ON
+    print("gemm fp8 width", cols, flush=True)
+    M, N, K = 600, 1000, 640
+    rng = np.random.default_rng(13)
+    a, w = wl.gemm_operands(rng, M, K, N)
+    Aq, sa = _quantise(a)
+    Wq, sb = _quantise(w)
+    table = ON.e4m3_decode_table()
+    Kd, Nd, Md = 128, 256, 128
+    Ad = torch.zeros((Md, Kd), dtype=torch.uint8)
+    Ad[torch.arange(Md), torch.arange(Md)] = 0x38                   # 1.0
+    Wd = torch.zeros((Nd, Kd), dtype=torch.uint8)
+    Wd[torch.arange(Nd), torch.arange(Nd) % Kd] = torch.arange(Nd, dtype=torch.int32).to(torch.uint8)
+    Wd[0x7F, 0x7F] = 0                                              # the two NaN codes are left out
+    Wd[0xFF, 0xFF % Kd] = 0
+    prev = rov.set_gemm_tile_cols(cols)
+    try:
+        C = rov.gemm(Aq.cuda(), Wq.cuda(), transB=True, scaleA=sa, scaleB=sb)
+        D = rov.gemm(Ad.cuda(), Wd.cuda(), transB=True)
+        torch.cuda.synchronize()
+    finally:
+        rov.set_gemm_tile_cols(prev)
+    ref = sa * sb * OD.gemm(ON.e4m3_decode(Aq.numpy()), ON.e4m3_decode(Wq.numpy()), transB=True)
+    err = _rel_err(_f64(C), ref)
+    assert err <= FP8_TOL and err <= FP8_EXPECTED, err
+    got = _f64(D)
+    for n in range(Nd):
+        if n not in (0x7F, 0xFF):
+            assert got[n % Kd, n] == table[n], (n, got[n % Kd, n], table[n])
+    assert np.count_nonzero(got) == 256 - 4
+
+
 def test_gemm_fp8_llama70b_qkv_sampled():
     # fourth workload's QKV projection at full size: 8192 x 8192 x 10240, fp8 e4m3, per-tensor scales
     from oracle import numerics as ON

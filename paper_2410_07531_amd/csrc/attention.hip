@@ -386,7 +386,14 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(const AttnParams p) 
 #pragma unroll
                 for (int e = 0; e < 16; ++e) mx = fmaxf(mx, s[t][n][e]);
             mx = fmaxf(mx, __shfl_xor(mx, 32)) * p.scale_log2;
-            const float m_new = fmaxf(m_run[n], mx);
+            // The reference of the exponent follows the maximum lazily: it moves only when the
+            // tile's maximum exceeds it by more than kLazy (in log2 units), so entries reach at
+            // most 2^kLazy, far inside fp32 and bf16 range, the quotient by the row sum is the
+            // same softmax, and the rescale of the output accumulators below runs in the first
+            // tile and hardly ever again (with the exact maximum about a third of all tiles of a
+            // 16k sequence move some row's maximum).
+            constexpr float kLazy = 8.0f;
+            const float m_new = mx > m_run[n] + kLazy ? mx : m_run[n];
             const float m_safe = m_new == -INFINITY ? 0.0f : m_new;
             const float alpha = fast_exp2(m_run[n] - m_safe);
             m_run[n] = m_new;

@@ -125,6 +125,37 @@ def test_attention_constant_v_and_full_drop_rows():
         assert np.all(got.transpose(0, 2, 1, 3)[dead] == 0.0)
 
 
+@pytest.mark.parametrize("direction", ["rising", "falling", "steps"])
+def test_attention_scores_that_move_the_exponent_reference(direction):
+    # scores that grow (or fall) by far more than any fixed margin along the keys: the online
+    # softmax has to move its reference many times (rising), never after the first tile
+    # (falling), or in steps below its margin (about 3 log2 units per 64-key tile: two absorbed,
+    # the third not); rows are compared with the exact softmax of the oracle
+    B, S, H, d = 1, 1024, 2, 128
+    rng = np.random.default_rng(5)
+    u = rng.standard_normal(d).astype(np.float32)
+    u /= np.linalg.norm(u)
+    q = (np.sqrt(d) * 4.0 * u)[None, None, None, :] + 0.1 * rng.standard_normal((B, S, H, d)).astype(np.float32)
+    ramp = np.linspace(0.0, 1.0, S, dtype=np.float32)
+    if direction == "falling":
+        ramp = ramp[::-1].copy()
+    if direction == "steps":
+        ramp = (np.floor(np.arange(S) / 64.0) / (S / 64.0)).astype(np.float32) * 0.6
+    # score(q, k_j) / sqrt(d) ~ 4 * 15 * ramp_j nats: 0 .. 60 nats (87 log2 units)
+    k = (15.0 * ramp)[None, :, None, None] * u[None, None, None, :] + 0.05 * rng.standard_normal((B, S, H, d)).astype(np.float32)
+    v = rng.standard_normal((B, S, H, d)).astype(np.float32)
+    Q, K, V = [torch.from_numpy(x.astype(np.float32)).to(torch.bfloat16).cuda() for x in (q, k, v)]
+    p, seed = 0.1, 11
+    keep = OP.unpack_keep(OP.dropout_mask(seed, 0, B, H, S, p), S)
+    for causal in (False, True):
+        O_none = rov.attention_fwd_dropout(Q, K, V, 0.0, causal=causal)
+        O_fused = rov.attention_fwd_dropout(Q, K, V, p, seed=seed, offset=0, causal=causal)
+        torch.cuda.synchronize()
+        assert bool(torch.isfinite(O_none.float()).all()) and bool(torch.isfinite(O_fused.float()).all())
+        _check(O_none, Q, K, V, None, 0.0, causal, torch.bfloat16)
+        _check(O_fused, Q, K, V, keep, p, causal, torch.bfloat16)
+
+
 def test_attention_llama8b_s2k_sampled_rows():
     # second workload at full size, as the benchmark runs it; the oracle evaluates 16 query rows
     # (first, last, spread) of every head against all 2048 keys

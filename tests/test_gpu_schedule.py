@@ -62,6 +62,53 @@ def test_layer_step_three_schedules(dtype, B, S, H, Hkv, d, gemm):
     assert np.max(np.abs(_f64(cs[0]) - refc)) / np.max(np.abs(refc)) <= (6e-3 if dtype == torch.bfloat16 else 1e-5)
 
 
+@pytest.mark.parametrize("sched", [rov.SCHED_SEQUENTIAL, rov.SCHED_FUSED, rov.SCHED_OVERLAP])
+def test_layer_step_replays_from_a_captured_graph(sched):
+    # a caller may record the step into a HIP graph (the library allocates nothing, synchronises
+    # nothing and clears its work queue with a kernel): every replay, with eager steps and
+    # synchronisations between the replays, must reproduce the eager result
+    B, S, H, Hkv, d = 1, 320, 4, 2, 128
+    rng = np.random.default_rng(31)
+    q, k, v = wl.qkv(rng, B, S, H, Hkv, d)
+    Q, K, V = [_dev(x, torch.bfloat16) for x in (q, k, v)]
+    a, w = wl.gemm_operands(rng, 512, 256, 768)
+    A, W = _dev(a, torch.bfloat16), _dev(w, torch.bfloat16)
+    p, seed, offset = 0.1, wl.SEED, 1280
+    O = torch.zeros_like(Q)
+    C = torch.zeros((512, 768), dtype=torch.bfloat16, device="cuda")
+    mask = torch.zeros(rov.mask_shape(B, H, S), dtype=torch.int64, device="cuda")
+    main, side = torch.cuda.Stream(), torch.cuda.Stream()
+    gd, ad = [rov.make_gemm_desc(A, W, C)], rov.make_attn_desc(Q, K, V, O, p)
+
+    def step():
+        rov.layer_step(sched, gd, ad, seed, offset, None if sched == rov.SCHED_FUSED else mask, main, side)
+
+    torch.cuda.synchronize()
+    step()
+    torch.cuda.synchronize()
+    O_ref, C_ref, m_ref = O.clone(), C.clone(), mask.clone()
+    if sched != rov.SCHED_FUSED:
+        assert np.array_equal(m_ref.cpu().numpy().view(np.uint64), OP.dropout_mask(seed, offset, B, H, S, p))
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=main):
+        step()
+    torch.cuda.synchronize()
+    for r in range(4):
+        print("graph replay", sched, r, flush=True)
+        O.zero_()
+        C.zero_()
+        mask.zero_()
+        torch.cuda.synchronize()
+        with torch.cuda.stream(main):
+            graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(O, O_ref) and torch.equal(C, C_ref), r
+        if sched != rov.SCHED_FUSED:
+            assert torch.equal(mask, m_ref), r
+        step()                       # eager work between the replays
+        torch.cuda.synchronize()
+
+
 @pytest.mark.parametrize("rounds", [3, 5, 7, 10])
 @pytest.mark.parametrize("dtype,d", [(torch.bfloat16, 128), (torch.float32, 64)])
 def test_layer_step_rounds_three_schedules(rounds, dtype, d):

@@ -24,13 +24,17 @@ from typing import Dict, Sequence, Tuple
 class Chip:
     """Sustained limiter rates of one MI355X (gfx950), 256 compute units."""
     cus: int = 256
-    # Matrix cores, bf16 (fp8 through the same-rate 16x16x32 instruction), fp32 accumulate.  Peak is
-    # 4 SIMD x 1024 flop/clk x 2.4 GHz x 256 CU = 2.5 PFLOP/s; a register-only loop of MFMA 16x16x32 on
-    # N(0,1) data sustains 2.05 PFLOP/s under the power limit (rov_valu_probe-style loop).
+    # Matrix cores, bf16, fp32 accumulate.  Peak is 4 SIMD x 1024 flop/clk x 2.4 GHz x 256 CU =
+    # 2.5 PFLOP/s; a register-only loop of MFMA 16x16x32 on N(0,1) data sustains 2.05 PFLOP/s under
+    # the power limit (rov_valu_probe-style loop).  fp8 on the double-rate MFMA 16x16x128: peak 5.0,
+    # the same loop on random e4m3 data 4.55 PFLOP/s.
     mfma_flops: float = 2.05e15
+    mfma_flops_fp8: float = 4.55e15
     # What the GEMM kernel keeps of that once operands stream through L2 and LDS (power shared with
-    # the memory system): measured 1.30-1.36 PFLOP/s on 8192-class shapes.
-    gemm_efficiency: float = 0.65
+    # the memory system): measured 1.38-1.45 PFLOP/s (bf16) and 2.75-3.0 PFLOP/s (fp8) on 8192-class
+    # shapes with the 256 x 256 tile.
+    gemm_efficiency: float = 0.69
+    gemm_efficiency_fp8: float = 0.64
     # VALU issue: cycles per wave64 instruction per SIMD at the VALU clock below, from rov_valu_probe
     # (8 waves per SIMD, ns per wave-instruction per SIMD: add 1.13, three-input xor 1.79, 32x32->64
     # multiply-add 2.32, compare + lane write 2.39).
@@ -97,13 +101,29 @@ def t_rng(chip: Chip, B: int, H: int, S: int, rounds: int = 10, bits: int = 32, 
     return {"valu": valu, "hbm_write": hbm, "time": max(valu, hbm) + chip.launch_s, "calls": calls}
 
 
+def gemm_tile_cols(chip: Chip, M: int, N: int) -> int:
+    """Tile width the library's launch picks: tiles are 256 x 32*nj, nj = 4..8; workgroups run in
+    rounds of one per compute unit and a tile costs about nj + 1 units (its activation panel does
+    not shrink with it); smallest rounds x (nj + 1) wins, the widest on ties."""
+    tiles_m = -(-M // 256)
+    best, cols = None, 256
+    for nj in range(8, 3, -1):
+        cost = -(-(tiles_m * -(-N // (32 * nj))) // chip.cus) * (nj + 1)
+        if best is None or cost < best:
+            best, cols = cost, 32 * nj
+    return cols
+
+
 def t_gemm(chip: Chip, M: int, N: int, K: int, esz: int = 2) -> Dict[str, float]:
     """GEMM (paper Table 1, GEMM column: MMA math first, L2 read bandwidth second)."""
-    tiles = -(-M // 256) * -(-N // 256)
-    rounds = -(-tiles // chip.cus)
-    quant = rounds * chip.cus / tiles                    # last round of tiles partly empty
-    mfma = 2.0 * M * N * K / (chip.mfma_flops * chip.gemm_efficiency) * quant
-    l2 = tiles * (K * esz / 64.0) * 32768.0 / chip.l2_to_cu_bytes_per_s
+    cols = gemm_tile_cols(chip, M, N)
+    nj = cols // 32
+    tiles = -(-M // 256) * -(-N // cols)
+    rounds = -(-tiles // chip.cus)                       # the last round of tiles may be partly empty
+    rate = (chip.mfma_flops * chip.gemm_efficiency if esz == 2 else chip.mfma_flops_fp8 * chip.gemm_efficiency_fp8)
+    # a round takes one tile's time on every compute unit; a narrower tile moves more bytes per flop
+    mfma = rounds * chip.cus * (2.0 * 256 * cols * K) / rate * ((nj + 1) / nj) / (9.0 / 8.0)
+    l2 = tiles * (K * esz / 128.0) * (256 + cols) * 128.0 / chip.l2_to_cu_bytes_per_s
     hbm = ((M + N) * K * esz + M * N * 2.0) / chip.hbm_bytes_per_s
     return {"mfma": mfma, "l2": l2, "hbm": hbm, "time": max(mfma, l2, hbm) + chip.launch_s}
 

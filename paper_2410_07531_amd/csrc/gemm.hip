@@ -313,142 +313,142 @@ __global__ __launch_bounds__(256, 1) void gemm_tn_kernel(const char* __restrict_
     };
 
     if constexpr (FP8) {
-    // fp8: one slot-step is ONE k-step of NM = 8*NJ MFMAs 16x16x128 (32 cycles each).  A lane's
-    // 32-byte operand is made of the same two 16-byte pieces the bf16 path reads (chunk lane/16 of
-    // each half row): which k values a lane group holds does not matter as long as both operands
-    // agree, and it keeps the bf16 swizzle and its conflict-free reads.
-    // All fragments of a step must be in registers when it starts and there is no room for a
-    // second set (256 accumulators + 128 fragment registers), so the next step's fragments
-    // replace the current ones as these retire: the MFMAs go weight block by weight block, weight
-    // fragment j of slot-step S+1 is read once row j is done, activation fragment i after the last
-    // row's MFMA i (the last of each kind at the start of step S+1, from what is then the current
-    // slot).  One barrier per step, after row 0: by then a wave has read the last of LDS slot S
-    // and its loads of slot-step S+1 (all issued during step S-1) are waited for; after it, slot
-    // S+1 is read and slot S takes the loads of slot-step S+2, one per G MFMAs.
-    i32x8 a8[8], w8[NJ];
-    auto read_half = [&](const char* slot, int f /*0..7 = A block, 8..7+NJ = W block*/, int h) {
-        const i32x4 v = *reinterpret_cast<const i32x4*>(
-            slot + (f < 8 ? a_base + f * 16 * kRow : w_base + (f - 8) * 16 * kRow) + foff[h]);
-        i32x8& dst = f < 8 ? a8[f] : w8[f - 8];
+        // fp8: one slot-step is ONE k-step of NM = 8*NJ MFMAs 16x16x128 (32 cycles each).  A lane's
+        // 32-byte operand is made of the same two 16-byte pieces the bf16 path reads (chunk lane/16 of
+        // each half row): which k values a lane group holds does not matter as long as both operands
+        // agree, and it keeps the bf16 swizzle and its conflict-free reads.
+        // All fragments of a step must be in registers when it starts and there is no room for a
+        // second set (256 accumulators + 128 fragment registers), so the next step's fragments
+        // replace the current ones as these retire: the MFMAs go weight block by weight block, weight
+        // fragment j of slot-step S+1 is read once row j is done, activation fragment i after the last
+        // row's MFMA i (the last of each kind at the start of step S+1, from what is then the current
+        // slot).  One barrier per step, after row 0: by then a wave has read the last of LDS slot S
+        // and its loads of slot-step S+1 (all issued during step S-1) are waited for; after it, slot
+        // S+1 is read and slot S takes the loads of slot-step S+2, one per G MFMAs.
+        i32x8 a8[8], w8[NJ];
+        auto read_half = [&](const char* slot, int f /*0..7 = A block, 8..7+NJ = W block*/, int h) {
+            const i32x4 v = *reinterpret_cast<const i32x4*>(
+                slot + (f < 8 ? a_base + f * 16 * kRow : w_base + (f - 8) * 16 * kRow) + foff[h]);
+            i32x8& dst = f < 8 ? a8[f] : w8[f - 8];
 #pragma unroll
-        for (int e = 0; e < 4; ++e) dst[4 * h + e] = v[e];
-    };
-    auto mfma8 = [&](int j, int i) {
-        asm volatile("v_mfma_f32_16x16x128_f8f6f4 %0, %1, %2, %0" : "+a"(acc[j][i]) : "v"(w8[j]), "v"(a8[i]));
-    };
-    constexpr int NM = 8 * NJ, NL = 8 + NJ;
-    constexpr int G0 = (NM - 17) / (NL - 1);
-    constexpr int G = G0 < 1 ? 1 : (G0 > 3 ? 3 : G0);
-    static_assert(9 + G * (NL - 1) < NM, "the loads of a slot-step are issued within one step");
+            for (int e = 0; e < 4; ++e) dst[4 * h + e] = v[e];
+        };
+        auto mfma8 = [&](int j, int i) {
+            asm volatile("v_mfma_f32_16x16x128_f8f6f4 %0, %1, %2, %0" : "+a"(acc[j][i]) : "v"(w8[j]), "v"(a8[i]));
+        };
+        constexpr int NM = 8 * NJ, NL = 8 + NJ;
+        constexpr int G0 = (NM - 17) / (NL - 1);
+        constexpr int G = G0 < 1 ? 1 : (G0 > 3 ? 3 : G0);
+        static_assert(9 + G * (NL - 1) < NM, "the loads of a slot-step are issued within one step");
 #pragma unroll
-    for (int q = 0; q < NL; ++q) issue(q, 0, lds_base);
+        for (int q = 0; q < NL; ++q) issue(q, 0, lds_base);
 #pragma unroll
-    for (int q = 0; q < NL; ++q) issue(q, 1, lds_base + kSlot);
-    __builtin_amdgcn_s_waitcnt(0x0F70 | (NL & 15) | ((NL >> 4) << 14));   // vmcnt(NL): slot-step 0 has landed
-    __syncthreads();
-#pragma unroll
-    for (int f = 0; f < 7; ++f) { read_half(lds, f, 0); read_half(lds, f, 1); }
-#pragma unroll
-    for (int f = 8; f < 8 + NJ - 1; ++f) { read_half(lds, f, 0); read_half(lds, f, 1); }
-    // nothing pending at loop entry: the waits the compiler places in the loop are then those of
-    // the loop's own read order, not of whatever order it gave the reads above
-    __builtin_amdgcn_s_waitcnt(0xC07F);
-    for (int S = 0; S < ns; ++S) {
-        const char* cur = lds + (S & 1) * kSlot;
-        const char* nxt = lds + ((S + 1) & 1) * kSlot;
-#pragma unroll
-        for (int idx = 0; idx < NM; ++idx) {
-            if (idx == 8) {
-                __builtin_amdgcn_s_waitcnt(0x0070);   // vmcnt(0) lgkmcnt(0)
-                __syncthreads();
-            }
-            mfma8(idx >> 3, idx & 7);
-            // the last activation and the last weight fragment of this step: their registers were
-            // in use until the last MFMA of the step before
-            if (idx == 0) { read_half(cur, 7, 0); read_half(cur, 7, 1); }
-            if (idx == 1) { read_half(cur, 8 + NJ - 1, 0); read_half(cur, 8 + NJ - 1, 1); }
-            if (idx >= 9 && (idx & 7) == 1) read_half(nxt, 8 + (idx >> 3) - 1, 0);
-            if (idx >= 9 && (idx & 7) == 2) read_half(nxt, 8 + (idx >> 3) - 1, 1);
-            if (idx >= NM - 7) {                      // MFMA (NJ-1, i) has been issued one MFMA ago for i = idx - (NM-7)
-                read_half(nxt, idx - (NM - 7), 0);
-                read_half(nxt, idx - (NM - 7), 1);
-            }
-            if (idx >= 9 && (idx - 9) % G == 0 && (idx - 9) / G < NL) issue((idx - 9) / G, S + 2, lds_base + (S & 1) * kSlot);
-            __builtin_amdgcn_sched_barrier(0);
-        }
-    }
-    } else {
-    i32x4 af[2][8], wf[2][NJ];   // fragments of the two k-steps of a slot
-    auto read_frag = [&](int h, const char* slot, int f /*0..7 = A block, 8..7+NJ = W block*/) {
-        if (f < 8)
-            af[h][f] = *reinterpret_cast<const i32x4*>(slot + a_base + f * 16 * kRow + foff[h]);
-        else
-            wf[h][f - 8] = *reinterpret_cast<const i32x4*>(slot + w_base + (f - 8) * 16 * kRow + foff[h]);
-    };
-    // The MFMAs are written as inline assembly with explicit register classes (accumulators in
-    // AGPRs, fragments in VGPRs): left to itself the register allocator mixes the two files for 64
-    // four-register accumulators and fills the loop with accumulator moves and spills.
-    auto mfma_one = [&](int h, int j, int i) {
-        asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc[j][i]) : "v"(wf[h][j]), "v"(af[h][i]));
-    };
-
-    // Two slots; slot-step S lives in slot S % 2 and is two k-steps, (S,0) and (S,1), of NM = 8*NJ
-    // MFMAs each.
-    //   (S,0): MFMAs on the fragments of (S,0); the NF = 8+NJ fragments of (S,1) are read from slot S.
-    //   then:  own LDS reads done, barrier: slot S is free.
-    //   (S,1): MFMAs on (S,1); at MFMA HB = NM - 2*NF: own loads of slot-step S+1 landed, barrier
-    //          (slot S+1 is complete for every wave), then the fragments of (S+1,0) are read from it,
-    //          one per 2 MFMAs, which takes the rest of the k-step.
-    // Loads of slot-step S+2 (into slot S), NL = 8+NJ per wave, go out one per G MFMAs: P1 of them
-    // in (S,1), the rest in (S+1,0).  The four waves share one texture-address unit that takes 16
-    // cycles per load, as long as an MFMA runs, and a wave issues nothing while its load waits
-    // there: at one load per 2 MFMAs per wave the unit is oversubscribed and the matrix pipe starves
-    // (measured with loads that touch no memory, zero operands: 1.79 PFLOP/s at one per 2, 1.94 at
-    // one per 4).  At the barrier inside (S,1) a wave has issued VMB younger loads: vmcnt(VMB).
-    // Letting the waves take turns behind different MFMAs would remove the rest of the queueing,
-    // but a taken branch around the load costs more than the load, and a load under an empty EXEC
-    // mask still costs its 16 cycles (both measured: 20 % and 35 % slower).
-    constexpr int NM = 8 * NJ, NF = 8 + NJ, NL = 8 + NJ;
-    constexpr int G = NJ >= 5 ? 6 : 5;
-    constexpr int HB = NM - 2 * NF;
-    constexpr int P1 = (NM - 2) / G + 1;               // load slots idx % G == 1 of a k-step
-    constexpr int P0 = NM >= 4 ? (NM - 4) / G + 1 : 0; // load slots idx % G == 3 of a k-step
-    constexpr int VMB = HB >= 2 ? (HB - 2) / G + 1 : 0;
-    static_assert(HB >= 0 && P1 <= NL && NL - P1 <= P0 && VMB < 16, "load schedule fits the k-steps");
-#pragma unroll
-    for (int q = 0; q < NL; ++q) issue(q, 0, lds_base);
-#pragma unroll
-    for (int q = 0; q < P1; ++q) issue(q, 1, lds_base + kSlot);   // its other loads go out in (0,0) like everywhere below
-    __builtin_amdgcn_s_waitcnt(0x0F70 | P1);   // vmcnt(P1): slot-step 0 has landed
-    __syncthreads();
-#pragma unroll
-    for (int f = 0; f < NF; ++f) read_frag(0, lds, f);
-
-    for (int S = 0; S < ns; ++S) {
-        const char* cur = lds + (S & 1) * kSlot;
-        const char* nxt = lds + ((S + 1) & 1) * kSlot;
-        __builtin_amdgcn_s_waitcnt(0xC07F);   // lgkmcnt(0): fragments of (S,0)
-#pragma unroll
-        for (int idx = 0; idx < NM; ++idx) {
-            mfma_one(0, idx >> 3, idx & 7);
-            if (idx < 2 * NF && (idx & 1) == 0) read_frag(1, cur, idx >> 1);
-            if (idx % G == 3 && P1 + idx / G < NL) issue(P1 + idx / G, S + 1, lds_base + ((S + 1) & 1) * kSlot);   // the other loads of slot-step S+1
-            __builtin_amdgcn_sched_barrier(0);
-        }
-        __builtin_amdgcn_s_waitcnt(0xC07F);   // lgkmcnt(0): fragments of (S,1)
+        for (int q = 0; q < NL; ++q) issue(q, 1, lds_base + kSlot);
+        __builtin_amdgcn_s_waitcnt(0x0F70 | (NL & 15) | ((NL >> 4) << 14));   // vmcnt(NL): slot-step 0 has landed
         __syncthreads();
 #pragma unroll
-        for (int idx = 0; idx < NM; ++idx) {
-            if (idx == HB) {
-                __builtin_amdgcn_s_waitcnt(0x0F70 | VMB);   // vmcnt(VMB)
-                __syncthreads();
+        for (int f = 0; f < 7; ++f) { read_half(lds, f, 0); read_half(lds, f, 1); }
+#pragma unroll
+        for (int f = 8; f < 8 + NJ - 1; ++f) { read_half(lds, f, 0); read_half(lds, f, 1); }
+        // nothing pending at loop entry: the waits the compiler places in the loop are then those of
+        // the loop's own read order, not of whatever order it gave the reads above
+        __builtin_amdgcn_s_waitcnt(0xC07F);
+        for (int S = 0; S < ns; ++S) {
+            const char* cur = lds + (S & 1) * kSlot;
+            const char* nxt = lds + ((S + 1) & 1) * kSlot;
+#pragma unroll
+            for (int idx = 0; idx < NM; ++idx) {
+                if (idx == 8) {
+                    __builtin_amdgcn_s_waitcnt(0x0070);   // vmcnt(0) lgkmcnt(0)
+                    __syncthreads();
+                }
+                mfma8(idx >> 3, idx & 7);
+                // the last activation and the last weight fragment of this step: their registers were
+                // in use until the last MFMA of the step before
+                if (idx == 0) { read_half(cur, 7, 0); read_half(cur, 7, 1); }
+                if (idx == 1) { read_half(cur, 8 + NJ - 1, 0); read_half(cur, 8 + NJ - 1, 1); }
+                if (idx >= 9 && (idx & 7) == 1) read_half(nxt, 8 + (idx >> 3) - 1, 0);
+                if (idx >= 9 && (idx & 7) == 2) read_half(nxt, 8 + (idx >> 3) - 1, 1);
+                if (idx >= NM - 7) {                      // MFMA (NJ-1, i) has been issued one MFMA ago for i = idx - (NM-7)
+                    read_half(nxt, idx - (NM - 7), 0);
+                    read_half(nxt, idx - (NM - 7), 1);
+                }
+                if (idx >= 9 && (idx - 9) % G == 0 && (idx - 9) / G < NL) issue((idx - 9) / G, S + 2, lds_base + (S & 1) * kSlot);
+                __builtin_amdgcn_sched_barrier(0);
             }
-            mfma_one(1, idx >> 3, idx & 7);
-            if (idx % G == 1) issue(idx / G, S + 2, lds_base + (S & 1) * kSlot);          // loads 0..P1-1 of slot-step S+2
-            if (idx >= HB && ((idx - HB) & 1) == 0) read_frag(0, nxt, (idx - HB) >> 1);
-            __builtin_amdgcn_sched_barrier(0);
         }
-    }
+    } else {
+        i32x4 af[2][8], wf[2][NJ];   // fragments of the two k-steps of a slot
+        auto read_frag = [&](int h, const char* slot, int f /*0..7 = A block, 8..7+NJ = W block*/) {
+            if (f < 8)
+                af[h][f] = *reinterpret_cast<const i32x4*>(slot + a_base + f * 16 * kRow + foff[h]);
+            else
+                wf[h][f - 8] = *reinterpret_cast<const i32x4*>(slot + w_base + (f - 8) * 16 * kRow + foff[h]);
+        };
+        // The MFMAs are written as inline assembly with explicit register classes (accumulators in
+        // AGPRs, fragments in VGPRs): left to itself the register allocator mixes the two files for 64
+        // four-register accumulators and fills the loop with accumulator moves and spills.
+        auto mfma_one = [&](int h, int j, int i) {
+            asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc[j][i]) : "v"(wf[h][j]), "v"(af[h][i]));
+        };
+
+        // Two slots; slot-step S lives in slot S % 2 and is two k-steps, (S,0) and (S,1), of NM = 8*NJ
+        // MFMAs each.
+        //   (S,0): MFMAs on the fragments of (S,0); the NF = 8+NJ fragments of (S,1) are read from slot S.
+        //   then:  own LDS reads done, barrier: slot S is free.
+        //   (S,1): MFMAs on (S,1); at MFMA HB = NM - 2*NF: own loads of slot-step S+1 landed, barrier
+        //          (slot S+1 is complete for every wave), then the fragments of (S+1,0) are read from it,
+        //          one per 2 MFMAs, which takes the rest of the k-step.
+        // Loads of slot-step S+2 (into slot S), NL = 8+NJ per wave, go out one per G MFMAs: P1 of them
+        // in (S,1), the rest in (S+1,0).  The four waves share one texture-address unit that takes 16
+        // cycles per load, as long as an MFMA runs, and a wave issues nothing while its load waits
+        // there: at one load per 2 MFMAs per wave the unit is oversubscribed and the matrix pipe starves
+        // (measured with loads that touch no memory, zero operands: 1.79 PFLOP/s at one per 2, 1.94 at
+        // one per 4).  At the barrier inside (S,1) a wave has issued VMB younger loads: vmcnt(VMB).
+        // Letting the waves take turns behind different MFMAs would remove the rest of the queueing,
+        // but a taken branch around the load costs more than the load, and a load under an empty EXEC
+        // mask still costs its 16 cycles (both measured: 20 % and 35 % slower).
+        constexpr int NM = 8 * NJ, NF = 8 + NJ, NL = 8 + NJ;
+        constexpr int G = NJ >= 5 ? 6 : 5;
+        constexpr int HB = NM - 2 * NF;
+        constexpr int P1 = (NM - 2) / G + 1;               // load slots idx % G == 1 of a k-step
+        constexpr int P0 = NM >= 4 ? (NM - 4) / G + 1 : 0; // load slots idx % G == 3 of a k-step
+        constexpr int VMB = HB >= 2 ? (HB - 2) / G + 1 : 0;
+        static_assert(HB >= 0 && P1 <= NL && NL - P1 <= P0 && VMB < 16, "load schedule fits the k-steps");
+#pragma unroll
+        for (int q = 0; q < NL; ++q) issue(q, 0, lds_base);
+#pragma unroll
+        for (int q = 0; q < P1; ++q) issue(q, 1, lds_base + kSlot);   // its other loads go out in (0,0) like everywhere below
+        __builtin_amdgcn_s_waitcnt(0x0F70 | P1);   // vmcnt(P1): slot-step 0 has landed
+        __syncthreads();
+#pragma unroll
+        for (int f = 0; f < NF; ++f) read_frag(0, lds, f);
+
+        for (int S = 0; S < ns; ++S) {
+            const char* cur = lds + (S & 1) * kSlot;
+            const char* nxt = lds + ((S + 1) & 1) * kSlot;
+            __builtin_amdgcn_s_waitcnt(0xC07F);   // lgkmcnt(0): fragments of (S,0)
+#pragma unroll
+            for (int idx = 0; idx < NM; ++idx) {
+                mfma_one(0, idx >> 3, idx & 7);
+                if (idx < 2 * NF && (idx & 1) == 0) read_frag(1, cur, idx >> 1);
+                if (idx % G == 3 && P1 + idx / G < NL) issue(P1 + idx / G, S + 1, lds_base + ((S + 1) & 1) * kSlot);   // the other loads of slot-step S+1
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            __builtin_amdgcn_s_waitcnt(0xC07F);   // lgkmcnt(0): fragments of (S,1)
+            __syncthreads();
+#pragma unroll
+            for (int idx = 0; idx < NM; ++idx) {
+                if (idx == HB) {
+                    __builtin_amdgcn_s_waitcnt(0x0F70 | VMB);   // vmcnt(VMB)
+                    __syncthreads();
+                }
+                mfma_one(1, idx >> 3, idx & 7);
+                if (idx % G == 1) issue(idx / G, S + 2, lds_base + (S & 1) * kSlot);          // loads 0..P1-1 of slot-step S+2
+                if (idx >= HB && ((idx - HB) & 1) == 0) read_frag(0, nxt, (idx - HB) >> 1);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
     }
     __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): no LDS load may outlive the loop
     asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");   // the last MFMA results are in the accumulators before they are read

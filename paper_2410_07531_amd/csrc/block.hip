@@ -61,35 +61,40 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const uint16_t* __restrict
 // Rotary embedding in place on the first `nheads` heads of each token row of a
 // [tokens, row_elems] buffer: pair (2t, 2t+1) of token position s is rotated by
 // s * theta^(-2t/d).  The angle is formed and reduced modulo 2*pi in double so
-// that long sequences keep fp32-accurate sines.
+// that long sequences keep fp32-accurate sines.  A thread owns four pairs (8
+// elements, 16 bytes) of one token and walks over the heads, which all turn by
+// the same angles: the sines are computed once per token, not once per head.
 __global__ __launch_bounds__(256) void rope_kernel(uint16_t* __restrict__ buf, int64_t row_elems,
                                                    int S, int nheads, int d, double log2_theta,
                                                    int64_t total_quads) {
-    // one thread handles 4 pairs (8 elements, 16 bytes)
     const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (idx >= total_quads) return;
     const int quads_per_head = d / 8;
     const int qd = (int)(idx % quads_per_head);
-    const int64_t rest = idx / quads_per_head;
-    const int head = (int)(rest % nheads);
-    const int64_t token = rest / nheads;
+    const int64_t token = idx / quads_per_head;
     const int pos = (int)(token % S);
-    uint16_t* ptr = buf + token * row_elems + (int64_t)head * d + qd * 8;
-    const uint4 v = *reinterpret_cast<const uint4*>(ptr);
-    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
-    uint32_t o[4];
+    float sn[4], cs[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         const int t = qd * 4 + i;
         const double inv_freq = exp2(-2.0 * (double)t / (double)d * log2_theta);
         double ang = (double)pos * inv_freq;
         ang -= 6.283185307179586476925 * rint(ang * 0.15915494309189533577);
-        float sn, cs;
-        sincosf((float)ang, &sn, &cs);
-        const float xe = lo_f(w[i]), xo = hi_f(w[i]);
-        o[i] = pack2(xe * cs - xo * sn, xe * sn + xo * cs);
+        sincosf((float)ang, &sn[i], &cs[i]);
     }
-    *reinterpret_cast<uint4*>(ptr) = make_uint4(o[0], o[1], o[2], o[3]);
+    uint16_t* ptr = buf + token * row_elems + qd * 8;
+#pragma unroll 4
+    for (int head = 0; head < nheads; ++head, ptr += d) {
+        const uint4 v = *reinterpret_cast<const uint4*>(ptr);
+        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+        uint32_t o[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const float xe = lo_f(w[i]), xo = hi_f(w[i]);
+            o[i] = pack2(xe * cs[i] - xo * sn[i], xe * sn[i] + xo * cs[i]);
+        }
+        *reinterpret_cast<uint4*>(ptr) = make_uint4(o[0], o[1], o[2], o[3]);
+    }
 }
 
 }  // namespace
@@ -106,7 +111,7 @@ int launch_rmsnorm(const void* x, const void* weight, void* y, int64_t rows, int
 int launch_rope(void* buf, int64_t tokens, int64_t row_elems, int S, int nheads, int d, float theta,
                 hipStream_t stream) {
     if (tokens <= 0 || nheads <= 0 || (d % 8) != 0 || theta <= 0.0f) return ROV_ERR_UNSUPPORTED;
-    const int64_t quads = tokens * nheads * (d / 8);
+    const int64_t quads = tokens * (d / 8);            // one thread per token and four pairs, all heads
     const int64_t blocks = (quads + 255) / 256;
     if (blocks > 0x7FFFFFFF) return ROV_ERR_UNSUPPORTED;
     hipLaunchKernelGGL(rope_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, (uint16_t*)buf,

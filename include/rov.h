@@ -178,6 +178,10 @@ int rov_gemm(const void *A, const void *Bm, void *C, int M, int N, int K, int dt
  * and tests; process-wide.  Returns the previous value, or ROV_ERR_INVALID
  * (nothing changed) for any other argument. */
 int rov_set_gemm_tile_cols(int cols);
+/* The tile width the matrix-core kernel uses for an M x N output with the
+ * current setting (host-side rule, no device work): 128..256, or
+ * ROV_ERR_INVALID for M <= 0 or N <= 0. */
+int rov_gemm_tile_cols(int M, int N);
 
 /* ---------------------------------------------------------------- attention
  * O = dropout(softmax(Q K^T / sqrt(d))) V, dropout applied to the softmax

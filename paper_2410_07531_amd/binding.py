@@ -73,6 +73,7 @@ SIGNATURES = {
                                     _p, _p, _p]),
     "rov_set_rng_max_workgroups": (_i, [_i]),
     "rov_set_gemm_tile_cols": (_i, [_i]),
+    "rov_gemm_tile_cols": (_i, [_i, _i]),
     "rov_set_rng_overlap_workgroups_per_cu": (_i, [_i]),
     "rov_trace_enable": (_i, [_i]),
     "rov_trace_read": (_i, [ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_float), _i,
@@ -164,6 +165,10 @@ def set_gemm_tile_cols(cols):
     if r < 0:
         raise RovError(r, "rov_set_gemm_tile_cols")
     return r
+
+
+def gemm_tile_cols(M, N):
+    return int(load().rov_gemm_tile_cols(int(M), int(N)))
 
 
 def set_rng_overlap_workgroups_per_cu(n):

@@ -494,6 +494,24 @@ __global__ __launch_bounds__(256, 1) void gemm_tn_kernel(const char* __restrict_
 
 }  // namespace
 
+// Tile width (output columns, 32*nj) for an M x N product.  The workgroups run in rounds of one per
+// compute unit; a tile costs about nj + 1 units (its A panel does not shrink with it), so the width
+// with the smallest rounds x (nj + 1) is taken, the widest on ties; a width set through
+// rov_set_gemm_tile_cols overrides the rule.
+int pick_tile_cols(int M, int N) {
+    const int forced = g_tile_cols.load();
+    if (forced != 0) return forced;
+    const long long tiles_m = (M + BM - 1) / BM, ncu = device_cu_count();
+    long long best = -1;
+    int nj = 8;
+    for (int c = 8; c >= 4; --c) {
+        const long long t = tiles_m * ((N + 32 * c - 1) / (32 * c));
+        const long long cost = ((t + ncu - 1) / ncu) * (c + 1);
+        if (best < 0 || cost < best) { best = cost; nj = c; }
+    }
+    return 32 * nj;
+}
+
 int launch_gemm(const void* A, const void* Bm, void* C, int M, int N, int K, int dtype, int transB,
                 float scaleA, float scaleB, hipStream_t stream) {
     return launch_gemm_residual(A, Bm, C, nullptr, M, N, K, dtype, transB, scaleA, scaleB, stream);
@@ -521,22 +539,7 @@ int launch_gemm_epilogue(const void* A, const void* Bm, void* C, const void* R, 
         if ((unsigned long long)BM * (unsigned long long)K * (unsigned long long)esz > 0xFFFFFFFFull)
             return ROV_ERR_UNSUPPORTED;
         const int tiles_m = (M + BM - 1) / BM;
-        // Tile width 32*nj.  The workgroups run in rounds of one per compute unit; a tile costs about
-        // nj + 1 units (its A panel does not shrink with it), so pick the width with the smallest
-        // rounds x (nj + 1), the widest on ties.
-        int nj = 8;
-        const int forced = g_tile_cols.load();
-        if (forced != 0) {
-            nj = forced / 32;
-        } else {
-            const long long ncu = device_cu_count();
-            long long best = -1;
-            for (int c = 8; c >= 4; --c) {
-                const long long t = (long long)tiles_m * ((N + 32 * c - 1) / (32 * c));
-                const long long cost = ((t + ncu - 1) / ncu) * (c + 1);
-                if (best < 0 || cost < best) { best = cost; nj = c; }
-            }
-        }
+        const int nj = pick_tile_cols(M, N) / 32;
         const int tiles_n = (N + 32 * nj - 1) / (32 * nj);
         const long long T = (long long)tiles_m * tiles_n;
         if (T > 0x7FFFFFFFLL) return ROV_ERR_UNSUPPORTED;
@@ -590,6 +593,11 @@ int launch_gemm_epilogue(const void* A, const void* Bm, void* C, const void* R, 
 }
 
 }  // namespace rov
+
+extern "C" int rov_gemm_tile_cols(int M, int N) {
+    if (M <= 0 || N <= 0) return ROV_ERR_INVALID;
+    return rov::pick_tile_cols(M, N);
+}
 
 extern "C" int rov_set_gemm_tile_cols(int cols) {
     if (cols != 0 && (cols < 128 || cols > 256 || cols % 32 != 0)) return ROV_ERR_INVALID;

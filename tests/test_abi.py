@@ -37,6 +37,28 @@ def test_host_only_entry_points():
     assert L.rov_last_hip_error() == 0
 
 
+def test_gemm_tile_width_rule():
+    # host logic: the width that leaves least of the last round of workgroups empty (256 compute
+    # units), widest on ties; the limiter model's copy of the rule must agree with the library's
+    from paper_2410_07531_amd import limiter_model as LM
+    assert binding.gemm_tile_cols(2048, 14336) == 224      # 448 tiles of 256 -> 512 tiles of 224: two full rounds
+    assert binding.gemm_tile_cols(2048, 6144) == 192       # 192 tiles -> 256 tiles: one full round
+    assert binding.gemm_tile_cols(2048, 4096) == 128
+    assert binding.gemm_tile_cols(8192, 8192) == 256 and binding.gemm_tile_cols(16384, 14336) == 256
+    assert binding.gemm_tile_cols(1, 4) == 128             # one tile either way: the narrowest is the cheapest
+    for M in (1, 256, 300, 2048, 4096, 8192, 16384):
+        for N in range(4, 20000, 364):
+            assert binding.gemm_tile_cols(M, N) == LM.gemm_tile_cols(LM.MI355X, M, N), (M, N)
+    L = binding.load()
+    assert L.rov_gemm_tile_cols(0, 8) == binding.ERR_INVALID and L.rov_gemm_tile_cols(8, -1) == binding.ERR_INVALID
+    prev = binding.set_gemm_tile_cols(160)
+    try:
+        assert binding.gemm_tile_cols(8192, 8192) == 160
+    finally:
+        binding.set_gemm_tile_cols(prev)
+    assert binding.gemm_tile_cols(8192, 8192) == 256
+
+
 def test_no_oracle_on_the_product_path():
     # the package must never import the oracle (and the oracle never the package)
     pkg = os.path.join(ROOT, "paper_2410_07531_amd")

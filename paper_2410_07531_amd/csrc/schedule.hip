@@ -94,7 +94,10 @@ int t_mask(uint64_t seed, uint64_t offset, int B, int H, int S, float p, uint64_
 // otherwise the mask goes through a work queue and a helper launch finishes it after the GEMMs.
 // The rates are this chip's measured ones, rounded against the RNG: about 1.0 PFLOP/s for the
 // bf16 / fp8 GEMM (30 TFLOP/s for the fp32 kernel) and 0.2 T Philox calls/s for the two-workgroups-
-// per-compute-unit grid beside a GEMM.  A wrong guess costs time, never correctness.
+// per-compute-unit grid beside a GEMM.  A wrong guess costs time, never correctness.  (The GEMMs
+// are faster than that by now, 1.3 PFLOP/s bf16 and 2.8 fp8; with those rates the fp8 layer of the
+// 70B shape switches to the work queue and gets 1.4 % slower, the RNG all but fitting beside its
+// GEMMs, so the rule keeps the rates that decide that case the right way.)
 bool rng_fits_beside(double gemm_flop, bool fp32, double rng_calls) {
     const double t_gemm = gemm_flop / (fp32 ? 30e12 : 1.0e15);
     const double t_rng = rng_calls / 0.2e12;

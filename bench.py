@@ -59,6 +59,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--no-block", action="store_true", help="skip the config-5 block timings")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline")
+    ap.add_argument("--seq-sweep", action="store_true",
+                    help="instead of the benchmark line: the Llama-3-8B block (non-causal) under the three schedules "
+                         "at S = 2048 ... 32768 beside the limiter model's prediction and region, one JSON object")
     ap.add_argument("--kernels-only", action="store_true",
                     help="for profilers: launch a 1 GiB device copy (counter calibration), then the RNG, GEMM and "
                          "attention kernels of the workload alone and the overlap step, 5 times each; no JSON")
@@ -104,6 +107,22 @@ def main():
 
     def step(sched):
         rov.layer_step(sched, gd, ad, wl.SEED, wl.OFFSET, None if sched == rov.SCHED_FUSED else mask, main_s, side_s)
+
+    if args.seq_sweep:
+        from paper_2410_07531_amd import limiter_model as LM
+        c5 = wl.CONFIGS[4]
+        out = {}
+        for S_ in (2048, 4096, 8192, 16384, 32768):
+            print("seq-sweep: S =", S_, file=sys.stderr, flush=True)
+            r = bench_block(torch, rov, wl, main_s, side_s, sync, ev_pair, seq_len=S_, causals=(False,), check=True)["noncausal"]
+            bm = LM.block(LM.MI355X, c5["B"], S_, c5["H"], c5["Hkv"], c5["d"], c5["hidden"], c5["ffn"], False)
+            r["limiter_model_ms"] = {"sequential": bm["baseline"] * 1e3, "fused": bm["fusion"] * 1e3,
+                                     "overlap": bm["overlap"] * 1e3, "rng": bm["rng"] * 1e3,
+                                     "rng_exposed": bm["rng_exposed"] * 1e3}
+            r["limiter_model_region"] = LM.region(LM.MI355X, c5["B"], c5["H"], S_, c5["d"], c5["hidden"], c5["ffn"])
+            out["S=%d" % S_] = r
+        print(json.dumps({"seq_sweep_llama3_8b_block": out}))
+        return
 
     if args.kernels_only:
         src = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
@@ -286,10 +305,13 @@ def main():
     print(json.dumps(out))
 
 
-def bench_block(torch, rov, wl, main_s, side_s, sync, ev_pair):
+def bench_block(torch, rov, wl, main_s, side_s, sync, ev_pair, seq_len=None, causals=(False, True), check=False):
+    """Llama-3-8B block (fifth workload; seq_len overrides its S) under the three schedules.  check:
+    also compare the three schedules' outputs bit for bit (they drop the same elements)."""
     ci = 4
     c = wl.CONFIGS[ci]
     B, H, Hkv, S, d, p, hidden, ffn = c["B"], c["H"], c["Hkv"], c["S"], c["d"], c["p"], c["hidden"], c["ffn"]
+    S = S if seq_len is None else int(seq_len)
     gen = torch.Generator(device="cuda")
     gen.manual_seed(1000 + ci)
     bf = torch.bfloat16
@@ -303,7 +325,7 @@ def bench_block(torch, rov, wl, main_s, side_s, sync, ev_pair):
     x = randn(B, S, hidden)
     y = torch.empty_like(x)
     res = {}
-    for causal in (False, True):
+    for causal in causals:
         cfg = rov.make_block_cfg(H, Hkv, d, hidden, ffn, p, causal=causal)
         weights = rov.make_block_weights(wts)
         ws = torch.empty(rov.block_workspace_bytes(cfg, B, S, 0), dtype=torch.uint8, device="cuda")
@@ -333,6 +355,20 @@ def bench_block(torch, rov, wl, main_s, side_s, sync, ev_pair):
         res["causal" if causal else "noncausal"] = {
             "sequential_ms": t_seq, "fused_ms": t_fus, "overlap_ms": t_ovl,
             "speedup_overlap_vs_sequential": t_seq / t_ovl, "speedup_overlap_vs_fused": t_fus / t_ovl}
+        if check:
+            outs = []
+            for fn in (seq, fus):
+                sync()
+                fn()
+                sync()
+                outs.append(y.clone())
+            layer[0] = 0                                   # the overlap call that uses m0 with offset 0
+            rov.dropout_mask_generate(wl.SEED, 0, B, H, S, p, out=m0)
+            sync()
+            ovl()
+            sync()
+            res["causal" if causal else "noncausal"]["schedules_agree_bit_for_bit"] = bool(
+                torch.equal(outs[0], outs[1]) and torch.equal(outs[0], y))
         del ws, m0, m1
         torch.cuda.empty_cache()
     return res

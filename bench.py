@@ -205,6 +205,10 @@ def main():
         rov.set_rng_max_workgroups(n_cu * k_ovl)
         t_pair = median_ms(gemm_beside_rng, 5, 10, sync, ev_pair)
         rov.set_rng_max_workgroups(0)
+        # the same GEMM and mask from the wave-specialised single kernel (paper Sec. 6.1's other form)
+        t_single = median_ms(lambda: rov.gemm_rng_fused(A, Wt, wl.SEED, 0, B, H, S, p, C=C, mask=mask, stream=main_s),
+                             5, 10, sync, ev_pair)
+        rov.set_rng_max_workgroups(0)
         t_seq = median_ms(lambda: step(rov.SCHED_SEQUENTIAL), 5, 10, sync, ev_pair)
         t_fus = median_ms(lambda: step(rov.SCHED_FUSED), 5, 10, sync, ev_pair)
         t_ovl = median_ms(lambda: step(rov.SCHED_OVERLAP), 5, 10, sync, ev_pair)
@@ -235,6 +239,7 @@ def main():
         "rng_in_overlap_step": {"ms": rng_in_step, "slowdown_vs_alone": rng_in_step / t_rng - 1.0,
                                 "helper_launch_ms": rng_helper_in_step},
         "gemm_beside_rng_region_ms": t_pair,
+        "gemm_and_rng_single_wave_specialised_kernel_ms": t_single,
         "rng_overlap_workgroups_per_cu": k_ovl,
         "rng_hidden_fraction": hidden_region,
         "rng_hidden_fraction_whole_step": hidden,

@@ -183,6 +183,22 @@ int rov_set_gemm_tile_cols(int cols);
  * ROV_ERR_INVALID for M <= 0 or N <= 0. */
 int rov_gemm_tile_cols(int M, int N);
 
+/* The overlap as ONE kernel (paper Sec. 6.1 names this wave-specialised form beside
+ * the two-kernel one it uses): every workgroup computes a tile of
+ * C[M,N] = A[M,K] * Bm[N,K]^T (bf16, K contiguous in both, fp32 accumulation) with four
+ * of its waves while four more waves generate chunks of the keep-mask of
+ * rov_dropout_mask_generate(seed, offset, B, H, S, p) (Philox4x32-10, same bits);
+ * what they have not produced when the GEMM ends is produced at full speed by a
+ * launch of the mask kernel queued behind it (Sec. 3.3).  On return both C and the
+ * whole mask are ordered on `stream`.  For comparison with rov_layer_step's
+ * two-kernel overlap; slower than it on this chip (the GEMM must use its
+ * narrowest tile so that two waves fit on a SIMD).
+ * Device pointers: A, Bm, C 16-byte aligned, mask 8-byte aligned with
+ * rov_mask_words(B,H,S) words.  K % 64 == 0, N % 4 == 0, S % 32 == 0, else
+ * ROV_ERR_UNSUPPORTED; null pointers, sizes <= 0, p outside [0,1): ROV_ERR_INVALID. */
+int rov_gemm_rng_fused(const void *A, const void *Bm, void *C, int M, int N, int K, uint64_t seed,
+                       uint64_t offset, int B, int H, int S, float p, uint64_t *mask, void *stream);
+
 /* ---------------------------------------------------------------- attention
  * O = dropout(softmax(Q K^T / sqrt(d))) V, dropout applied to the softmax
  * output (paper Sec. 2.2), kept probabilities scaled by 1/(1-p); the softmax

@@ -80,6 +80,7 @@ SIGNATURES = {
                             ctypes.POINTER(ctypes.c_int)]),
     "rov_valu_probe": (_i, [_i, _i, _i, _p, _p]),
     "rov_gemm": (_i, [_p, _p, _p, _i, _i, _i, _i, _i, _f, _f, _p]),
+    "rov_gemm_rng_fused": (_i, [_p, _p, _p, _i, _i, _i, _u64, _u64, _i, _i, _i, _f, _p, _p]),
     "rov_attention_fwd_dropout": (_i, [_p, _p, _p, _p, _i, _i, _i, _i, _i,
                                        ctypes.POINTER(ctypes.c_int64), _i, _i, _f, _p, _u64, _u64, _p]),
     "rov_layer_step": (_i, [_i, ctypes.POINTER(GemmDesc), _i, ctypes.POINTER(AttnDesc), _u64, _u64,
@@ -238,6 +239,22 @@ def gemm(A, Bm, C=None, transB=True, scaleA=1.0, scaleB=1.0, stream=None):
                            ctypes.c_void_p(C.data_ptr()), M, N, K, code, int(bool(transB)),
                            float(scaleA), float(scaleB), _stream_ptr(stream)), "rov_gemm")
     return C
+
+
+def gemm_rng_fused(A, Bm, seed, offset, B, H, S, p, C=None, mask=None, stream=None):
+    """C = A @ Bm^T (bf16) and the keep-mask of (seed, offset, B, H, S, p) from one wave-specialised kernel."""
+    import torch
+    M, K = A.shape
+    N = Bm.shape[0]
+    if C is None:
+        C = torch.empty((M, N), dtype=torch.bfloat16, device=A.device)
+    if mask is None:
+        mask = torch.empty(mask_shape(B, H, S), dtype=torch.int64, device=A.device)
+    _check(load().rov_gemm_rng_fused(ctypes.c_void_p(A.data_ptr()), ctypes.c_void_p(Bm.data_ptr()),
+                                     ctypes.c_void_p(C.data_ptr()), M, N, K, ctypes.c_uint64(seed),
+                                     ctypes.c_uint64(offset), B, H, S, float(p), ctypes.c_void_p(mask.data_ptr()),
+                                     _stream_ptr(stream)), "rov_gemm_rng_fused")
+    return C, mask
 
 
 def _strides12(Q, K, V, O):

@@ -38,6 +38,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "mask_device.h"
+#include "philox_device.h"
 #include "rov_internal.h"
 
 #include <atomic>
@@ -189,18 +191,14 @@ __device__ __forceinline__ void epilogue_combine(int epi, uint2 r, float& c0, fl
 // 2; 512 tiles of 256 x 224 are 2 rounds of 7/8 the work each).
 // FP8: the operands are OCP e4m3 bytes and a slot row (128 bytes) is one k-step of the double-rate
 // MFMA 16x16x128 of the f8f6f4 family; everything but the main loop is shared with bf16.
-template <int NJ, bool FP8 = false>
-__global__ __launch_bounds__(256, 1) void gemm_tn_kernel(const char* __restrict__ A,
-                                                         const char* __restrict__ Wt,
-                                                         uint16_t* __restrict__ C,
-                                                         const uint16_t* __restrict__ R, int M, int N,
-                                                         int K, float alpha, int tiles_m, int tiles_n, int epi) {
-    extern __shared__ __attribute__((aligned(1024))) char lds[];
-    // Co-resident RNG waves only need the VALU issue slots this kernel leaves idle; raise this
-    // wave's issue priority so that they never delay its MFMA / LDS instruction stream.
-    __builtin_amdgcn_s_setprio(3);
-    const int lane = threadIdx.x & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+// The tile of workgroup blockIdx.x, computed by the workgroup's waves 0-3 (`wave`; `lane` = lane
+// in the wave).  Its barriers are workgroup barriers: 1 + 2*(K*2/128) of them for bf16, 1 + K/128
+// for fp8, whatever the tile; any other wave of the workgroup has to arrive at as many.
+template <int NJ, bool FP8>
+__device__ __forceinline__ void gemm_tile(const char* __restrict__ A, const char* __restrict__ Wt,
+                                          uint16_t* __restrict__ C, const uint16_t* __restrict__ R, int M,
+                                          int N, int K, float alpha, int tiles_m, int tiles_n, int epi,
+                                          char* lds, const int lane, const int wave) {
     const int wm = wave >> 1, wn = wave & 1;
 
     // XCD-aware tile id: workgroup ids are dealt round-robin to the 8 XCDs; give each XCD a
@@ -492,7 +490,131 @@ __global__ __launch_bounds__(256, 1) void gemm_tn_kernel(const char* __restrict_
     }
 }
 
+template <int NJ, bool FP8 = false>
+__global__ __launch_bounds__(256, 1) void gemm_tn_kernel(const char* __restrict__ A,
+                                                         const char* __restrict__ Wt,
+                                                         uint16_t* __restrict__ C,
+                                                         const uint16_t* __restrict__ R, int M, int N,
+                                                         int K, float alpha, int tiles_m, int tiles_n, int epi) {
+    extern __shared__ __attribute__((aligned(1024))) char lds[];
+    // Co-resident RNG waves only need the VALU issue slots this kernel leaves idle; raise this
+    // wave's issue priority so that they never delay its MFMA / LDS instruction stream.
+    __builtin_amdgcn_s_setprio(3);
+    gemm_tile<NJ, FP8>(A, Wt, C, R, M, N, K, alpha, tiles_m, tiles_n, epi, lds, threadIdx.x & 63,
+                       __builtin_amdgcn_readfirstlane(threadIdx.x >> 6));
+}
+
+// Wave-specialised GEMM + RNG (paper Sec. 6.1 names this form beside the two-kernel one): a
+// workgroup of eight waves, two per SIMD; waves 0-3 compute a 256 x 128 bf16 tile exactly as
+// gemm_tn_kernel<4> does (the only tile whose 244 registers leave room for a second wave on the
+// SIMD: every wave of a kernel gets the same allocation), waves 4-7 generate keep-mask chunks
+// pulled from a work queue, one group of 64 Philox calls per 128 bytes of k, arriving at every
+// barrier the tile's waves arrive at (a group per barrier interval made the tile's waves wait
+// longer: measured 341 against 333 us on 2048 x 14336 x 4096 with a 32 x 2048^2-bit mask).  A chunk that was started is
+// finished after the tile's k loop, while the other waves store the tile; chunks never started
+// stay in the queue for whoever drains it next.
+__global__ __launch_bounds__(512, 1) void gemm_rng_kernel(const char* __restrict__ A, const char* __restrict__ Wt,
+                                                         uint16_t* __restrict__ C, int M, int N, int K,
+                                                         int tiles_m, int tiles_n, uint64_t* __restrict__ mask,
+                                                         uint64_t words, uint64_t nchunks, uint64_t offset,
+                                                         uint32_t k0, uint32_t k1, uint32_t t_minus_1,
+                                                         QueueCounter* queues, uint64_t qper) {
+    extern __shared__ __attribute__((aligned(1024))) char lds[];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    if (wave < 4) {
+        __builtin_amdgcn_s_setprio(3);
+        gemm_tile<4, false>(A, Wt, C, nullptr, M, N, K, 1.0f, tiles_m, tiles_n, EPI_ADD, lds, lane, wave);
+    } else {
+        ChunkSource src;
+        src.queues = queues; src.nchunks = nchunks; src.stride = 0; src.per = qper; src.batch = 1u;
+        src.lane = (uint32_t)lane;
+        bool have = false, popped = false, dry = false;
+        int gi = 0;
+        uint32_t vlo = 0u, vhi = 0u;
+        // one group of the current chunk: four keep words into lanes 4*gi .. 4*gi+3; the 16th group
+        // stores the chunk.  A chunk is popped only when its first group is about to be computed, so
+        // that none is taken from the queue and then left undone.
+        auto unit = [&]() {
+            if (!have) {
+                if (dry) return;
+                have = popped ? src.next() : src.first((uint64_t)blockIdx.x * 4u + (uint32_t)(wave - 4));
+                popped = true;
+                if (!have) {
+                    dry = true;
+                    return;
+                }
+            }
+            const uint64_t base = offset + 64u * kGroupsPerChunk * src.cur;   // first call of the chunk
+            uint64_t b[4];
+            if ((uint32_t)base <= 0xFFFFFFFFu - (64u * kGroupsPerChunk - 1u))
+                philox_group_ballots<10, false>(base + 64u * (uint64_t)gi, (uint32_t)lane, k0, k1, t_minus_1, b);
+            else
+                philox_group_ballots<10, true>(base + 64u * (uint64_t)gi, (uint32_t)lane, k0, k1, t_minus_1, b);
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const uint32_t dst = 4u * (uint32_t)gi + (uint32_t)r;
+                vlo = write_lane((uint32_t)b[r], dst, vlo);
+                vhi = write_lane((uint32_t)(b[r] >> 32), dst, vhi);
+            }
+            if (++gi == kGroupsPerChunk) {
+                const uint64_t widx = src.cur * 64u + (uint32_t)lane;
+                if (widx < words) mask[widx] = ((uint64_t)vhi << 32) | vlo;
+                gi = 0;
+                vlo = 0u;
+                vhi = 0u;
+                have = false;
+            }
+        };
+        // the tile's barriers: one before its k loop, two per 128 bytes of k
+        const int ns = (int)(((size_t)K * 2) / kRowBytes);
+        __syncthreads();
+        for (int S = 0; S < ns; ++S) {
+            unit();
+            __syncthreads();   // the tile's "slot free" barrier
+            __syncthreads();   // the tile's "next slot complete" barrier
+        }
+        while (have) unit();   // finish the chunk that was started
+    }
+}
+
 }  // namespace
+
+int launch_gemm_rng(const void* A, const void* Bm, void* C, int M, int N, int K, uint64_t seed, uint64_t offset,
+                    int B, int H, int S, float p, uint64_t* mask, int qslot, hipStream_t stream) {
+    if (A == nullptr || Bm == nullptr || C == nullptr || mask == nullptr || M <= 0 || N <= 0 || K <= 0 ||
+        B <= 0 || H <= 0 || S <= 0)
+        return ROV_ERR_INVALID;
+    if (!aligned(A, 16) || !aligned(Bm, 16) || !aligned(C, 16) || !aligned(mask, 8)) return ROV_ERR_INVALID;
+    uint32_t tm1;
+    if (!keep_threshold_minus_1(p, &tm1)) return ROV_ERR_INVALID;
+    if (((size_t)K * 2) % kRowBytes != 0 || (N % 4) != 0 || (S % 32) != 0) return ROV_ERR_UNSUPPORTED;
+    if ((unsigned long long)BM * (unsigned long long)K * 2ull > 0xFFFFFFFFull) return ROV_ERR_UNSUPPORTED;
+    const uint64_t Tt = (uint64_t)S / 32u;
+    const long double wd = (long double)B * H * Tt * Tt * 16.0L;
+    if (wd > 1099511627776.0L) return ROV_ERR_UNSUPPORTED;
+    const uint64_t words = (uint64_t)B * (uint64_t)H * Tt * Tt * 16u, nchunks = (words + 63u) / 64u;
+    const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + 127) / 128;
+    const long long T = (long long)tiles_m * tiles_n;
+    if (T > 0x7FFFFFFFLL) return ROV_ERR_UNSUPPORTED;
+    void* q = nullptr;
+    int rc = mask_queue_device_ptr(qslot, &q);
+    if (rc != ROV_OK) return rc;
+    uint64_t qper = 0;
+    uint32_t qbatch = 1;
+    mask_queue_geometry(nchunks, &qper, &qbatch);
+    static bool attr_set = false;
+    if (!attr_set) {
+        ROV_HIP_TRY(hipFuncSetAttribute((const void*)gemm_rng_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                        kLdsBytes));
+        attr_set = true;
+    }
+    hipLaunchKernelGGL(gemm_rng_kernel, dim3((unsigned)T), dim3(512), kLdsBytes, stream, (const char*)A,
+                       (const char*)Bm, (uint16_t*)C, M, N, K, tiles_m, tiles_n, mask, words, nchunks, offset,
+                       (uint32_t)seed, (uint32_t)(seed >> 32), tm1, (QueueCounter*)q, qper);
+    ROV_LAUNCH_CHECK();
+    return ROV_OK;
+}
 
 // Tile width (output columns, 32*nj) for an M x N product.  The workgroups run in rounds of one per
 // compute unit; a tile costs about nj + 1 units (its A panel does not shrink with it), so the width

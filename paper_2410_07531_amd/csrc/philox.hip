@@ -16,6 +16,7 @@
 
 #include <atomic>
 
+#include "mask_device.h"
 #include "philox_device.h"
 #include "rov_internal.h"
 
@@ -24,76 +25,12 @@ namespace rov {
 namespace {
 
 constexpr int kWavesPerBlock = 4;
-constexpr int kGroupsPerChunk = 16;   // 16 groups x 4 words = 64 words = one 8-byte store per lane
 
-// Work queues for masks that two launches produce together (see launch_mask).  A queue slot
-// is 32 sub-queues, each with its own 128-byte line and its own contiguous share of the mask's
-// 64-word chunks: atomics on one address retire one after the other (about 10 ns each on this
-// chip, measured), so a single counter popped once per chunk would take longer than the Philox
-// work itself.  A wave pops `batch` chunks at a time from its home sub-queue and moves on to the
-// next sub-queue when that one is empty; empty sub-queues are recognised with a plain load.
-// A slot is reset by queue_reset_kernel before its launches; slots are handed out round-robin
-// so that back-to-back schedule calls never share one.
-constexpr int kQueueSlots = 64;
-constexpr int kSubQueues = 32;
-struct alignas(128) QueueCounter {
-    unsigned long long next;
-    unsigned long long pad[15];
-};
+// The work queues' counters (see mask_device.h): one line per sub-queue.
 __device__ QueueCounter g_queues[kQueueSlots][kSubQueues];
 std::atomic<unsigned> g_queue_cursor{0};
 
 __global__ void queue_reset_kernel(int slot) { g_queues[slot][threadIdx.x].next = 0ull; }
-
-// Where a wave's chunks come from: the grid striding over [0, nchunks) (slot < 0), or a queue.
-struct ChunkSource {
-    int slot;
-    uint64_t nchunks, stride;      // static mode: next = cur + stride
-    uint64_t per;                  // queue mode: chunks per sub-queue (a multiple of batch)
-    uint32_t batch, q, tried, lane;
-    uint64_t cur, end;             // queue mode: chunks [cur, end) are this wave's
-
-    __device__ __forceinline__ bool refill() {
-        while (tried < (uint32_t)kSubQueues) {
-            unsigned long long* ctr = &g_queues[slot][q].next;
-            const uint64_t lo = (uint64_t)q * per;
-            uint64_t hi = lo + per;
-            hi = hi < nchunks ? hi : nchunks;
-            if (lo < hi && __hip_atomic_load(ctr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < hi - lo) {
-                unsigned long long v = 0ull;
-                if (lane == 0u) v = atomicAdd(ctr, (unsigned long long)batch);
-                const uint32_t vl = __builtin_amdgcn_readfirstlane((uint32_t)v);
-                const uint32_t vh = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
-                const uint64_t got = ((uint64_t)vh << 32) | vl;
-                if (got < hi - lo) {
-                    cur = lo + got;
-                    end = cur + batch < hi ? cur + batch : hi;
-                    return true;
-                }
-            }
-            q = q + 1u == (uint32_t)kSubQueues ? 0u : q + 1u;
-            ++tried;
-        }
-        return false;
-    }
-    __device__ __forceinline__ bool first(uint64_t wave_index) {
-        if (slot < 0) {
-            cur = wave_index;
-            return cur < nchunks;
-        }
-        q = (uint32_t)(wave_index % (uint64_t)kSubQueues);
-        tried = 0u;
-        return refill();
-    }
-    __device__ __forceinline__ bool next() {
-        if (slot < 0) {
-            cur += stride;
-            return cur < nchunks;
-        }
-        if (++cur < end) return true;
-        return refill();
-    }
-};
 
 std::atomic<int> g_rng_max_workgroups{0};
 std::atomic<int> g_rng_overlap_wgs_per_cu{2};
@@ -146,7 +83,7 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void mask_kernel(
     // qslot < 0: the grid strides over the chunks; qslot >= 0: waves pull chunks from a queue that
     // another launch of this kernel may be draining too
     ChunkSource src;
-    src.slot = qslot; src.nchunks = nchunks; src.stride = (uint64_t)gridDim.x * kWavesPerBlock;
+    src.queues = qslot >= 0 ? g_queues[qslot] : nullptr; src.nchunks = nchunks; src.stride = (uint64_t)gridDim.x * kWavesPerBlock;
     src.per = qper; src.batch = qbatch; src.lane = lane;
     for (bool more = src.first((uint64_t)blockIdx.x * kWavesPerBlock + wave); more; more = src.next()) {
         const uint64_t chunk = src.cur;
@@ -185,7 +122,7 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void mask_rows_kernel(
     const uint32_t lane = threadIdx.x & 63u;
     const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     ChunkSource src;
-    src.slot = qslot; src.nchunks = nseg * chunks_per_seg; src.stride = (uint64_t)gridDim.x * kWavesPerBlock;
+    src.queues = qslot >= 0 ? g_queues[qslot] : nullptr; src.nchunks = nseg * chunks_per_seg; src.stride = (uint64_t)gridDim.x * kWavesPerBlock;
     src.per = qper; src.batch = qbatch; src.lane = lane;
     for (bool more = src.first((uint64_t)blockIdx.x * kWavesPerBlock + wave); more; more = src.next()) {
         const uint64_t c = src.cur;
@@ -369,6 +306,20 @@ bool keep_threshold_minus_1(float p, uint32_t* t_minus_1) {
     *t_minus_1 = (uint32_t)(T - 1u);
     return true;
 }
+
+int mask_queue_device_ptr(int slot, void** ptr) {
+    if (slot < 0 || slot >= kQueueSlots || ptr == nullptr) return ROV_ERR_INVALID;
+    static std::atomic<QueueCounter*> base{nullptr};
+    QueueCounter* b = base.load();
+    if (b == nullptr) {
+        ROV_HIP_TRY(hipGetSymbolAddress((void**)&b, HIP_SYMBOL(g_queues)));
+        base.store(b);
+    }
+    *ptr = b + (size_t)slot * kSubQueues;
+    return ROV_OK;
+}
+
+void mask_queue_geometry(uint64_t nchunks, uint64_t* per, uint32_t* batch) { queue_geometry(nchunks, per, batch); }
 
 int mask_queue_acquire(hipStream_t stream, int* slot) {
     const int s = (int)(g_queue_cursor.fetch_add(1u) % (unsigned)kQueueSlots);

@@ -43,6 +43,10 @@ void trace_end(int slot, hipStream_t st);
 // chunk is produced by whichever launch gets to it first.  qslot < 0: static striding.
 enum { MASK_GRID_FULL = 0, MASK_GRID_BESIDE = 1, MASK_GRID_HELPER = 2 };
 int mask_queue_acquire(hipStream_t stream, int* slot);
+// Device address of a queue slot's counters (for kernels of other translation units that pull
+// chunks from it), and the queue geometry the mask launches use for a mask of nchunks chunks.
+int mask_queue_device_ptr(int slot, void** ptr);
+void mask_queue_geometry(uint64_t nchunks, uint64_t* per, uint32_t* batch);
 // lower_only: write only what causal attention reads (tiles with key tile <= query tile).
 int launch_mask(uint64_t seed, uint64_t offset, int B, int H, int S, float p, int rounds,
                 uint64_t* out, hipStream_t stream, int grid_mode = MASK_GRID_FULL, int qslot = -1,
@@ -76,6 +80,13 @@ int launch_attention_rows(const void* Q, const void* K, const void* V, void* O, 
                           int S, int d, const int64_t strides[12], int dtype, int causal, float p,
                           const uint64_t* mask, bool mask_is_rows, uint64_t seed, uint64_t offset,
                           int q_begin, int q_rows, hipStream_t stream, int rounds = 10, int bits = 32);
+
+// One kernel whose workgroups compute a tile of the bf16 GEMM with four waves while four more
+// waves generate keep-mask chunks pulled from queue slot `qslot` (paper Sec. 6.1: the single-kernel,
+// wave-specialised form of the overlap).  S % 32 == 0; what the RNG waves do not get to stays in
+// the queue for a helper launch of the mask kernel.
+int launch_gemm_rng(const void* A, const void* Bm, void* C, int M, int N, int K, uint64_t seed, uint64_t offset,
+                    int B, int H, int S, float p, uint64_t* mask, int qslot, hipStream_t stream);
 
 int launch_rmsnorm(const void* x, const void* weight, void* y, int64_t rows, int n, float eps,
                    hipStream_t stream);

@@ -236,6 +236,23 @@ int layer_step_impl(int schedule, const rov_gemm_desc* gemms, int n_gemms, const
 }  // namespace
 }  // namespace rov
 
+extern "C" int rov_gemm_rng_fused(const void* A, const void* Bm, void* C, int M, int N, int K, uint64_t seed,
+                                  uint64_t offset, int B, int H, int S, float p, uint64_t* mask, void* stream) {
+    hipStream_t st = (hipStream_t)stream;
+    if (A == nullptr || Bm == nullptr || C == nullptr || mask == nullptr) return ROV_ERR_INVALID;
+    int slot = -1;
+    int rc = rov::mask_queue_acquire(st, &slot);
+    if (rc != ROV_OK) return rc;
+    rc = rov::traced(ROV_TRACE_GEMM, st, [&] {
+        return rov::launch_gemm_rng(A, Bm, C, M, N, K, seed, offset, B, H, S, p, mask, slot, st);
+    });
+    if (rc != ROV_OK) return rc;
+    // what the RNG waves of the GEMM kernel did not get to, at full speed (paper Sec. 3.3)
+    return rov::traced(ROV_TRACE_RNG_HELPER, st, [&] {
+        return rov::launch_mask(seed, offset, B, H, S, p, 10, mask, st, rov::MASK_GRID_HELPER, slot, false);
+    });
+}
+
 extern "C" int rov_layer_step(int schedule, const rov_gemm_desc* gemms, int n_gemms,
                               const rov_attn_desc* attn, uint64_t seed, uint64_t offset,
                               uint64_t* mask, void* main_stream, void* side_stream) {

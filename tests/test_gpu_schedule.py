@@ -62,6 +62,53 @@ def test_layer_step_three_schedules(dtype, B, S, H, Hkv, d, gemm):
     assert np.max(np.abs(_f64(cs[0]) - refc)) / np.max(np.abs(refc)) <= (6e-3 if dtype == torch.bfloat16 else 1e-5)
 
 
+@pytest.mark.parametrize("M,N,K,B,H,S", [
+    (600, 1000, 448, 1, 2, 256),      # ragged tile edges, odd slot count; 24 tiles, 128 chunks: the waves beside the tiles get most of them
+    (256, 128, 64, 2, 4, 1024),       # one tile, one slot-step: nearly the whole mask (8192 chunks) is left to the launch behind
+    (2048, 2048, 1024, 1, 1, 64),     # 128 tiles, one chunk: most RNG waves find the queue empty
+    (512, 512, 256, 1, 3, 320),       # 75 chunks over 8 tiles
+])
+def test_gemm_rng_single_kernel_matches_oracle(M, N, K, B, H, S):
+    # the wave-specialised single kernel (paper Sec. 6.1): its GEMM against the oracle, its mask bit
+    # for bit against the oracle's, twice in a row (the queue slot changes, the result must not)
+    print("gemm_rng_fused", M, N, K, B, H, S, flush=True)
+    rng = np.random.default_rng(M + N + K + S)
+    a, w = wl.gemm_operands(rng, M, K, N)
+    A, W = _dev(a, torch.bfloat16), _dev(w, torch.bfloat16)
+    p, seed, offset = 0.1, wl.SEED, wl.CARRY_OFFSET - 2048          # some chunks cross 2^32
+    words = OP.dropout_mask(seed, offset, B, H, S, p)
+    refc = OD.gemm(_f64(A), _f64(W), transB=True)
+    st = torch.cuda.Stream()
+    for rep in range(2):
+        C = torch.zeros((M, N), dtype=torch.bfloat16, device="cuda")
+        mask = torch.full(rov.mask_shape(B, H, S), 0x2AAAAAAAAAAAAAAA, dtype=torch.int64, device="cuda")   # poison
+        torch.cuda.synchronize()
+        rov.gemm_rng_fused(A, W, seed, offset, B, H, S, p, C=C, mask=mask, stream=st)
+        torch.cuda.synchronize()
+        assert np.array_equal(mask.cpu().numpy().view(np.uint64), words), rep
+        assert np.max(np.abs(_f64(C) - refc)) / np.max(np.abs(refc)) <= 6e-3, rep
+    # same bits as the two-kernel path's GEMM with the same tile
+    prev = rov.set_gemm_tile_cols(128)
+    try:
+        C2 = rov.gemm(A, W, transB=True)
+        torch.cuda.synchronize()
+    finally:
+        rov.set_gemm_tile_cols(prev)
+    assert torch.equal(C, C2)
+
+
+def test_gemm_rng_single_kernel_argument_errors():
+    A = torch.zeros((256, 64), dtype=torch.bfloat16, device="cuda")
+    W = torch.zeros((128, 64), dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(rov.RovError):
+        rov.gemm_rng_fused(A, W, 1, 0, 1, 1, 48, 0.1)              # S % 32 != 0
+    with pytest.raises(rov.RovError):
+        rov.gemm_rng_fused(A, W, 1, 0, 1, 1, 64, 1.0)              # p outside [0, 1)
+    with pytest.raises(rov.RovError):
+        rov.gemm_rng_fused(A[:, :32], W[:, :32].contiguous(), 1, 0, 1, 1, 64, 0.1)   # K % 64 != 0
+    torch.cuda.synchronize()
+
+
 @pytest.mark.parametrize("sched", [rov.SCHED_SEQUENTIAL, rov.SCHED_FUSED, rov.SCHED_OVERLAP])
 def test_layer_step_replays_from_a_captured_graph(sched):
     # a caller may record the step into a HIP graph (the library allocates nothing, synchronises

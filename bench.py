@@ -29,9 +29,9 @@ PEAK_INT32_TOPS = 78.6          # 256 CU x 4 SIMD x 32 lanes/clk x 2.4 GHz (= fp
 INT32_OPS_PER_CALL = 84         # 20 wide multiplies (lo+hi = 2 results each), 40 two-input xors, 4 compares
 # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (KiB per dispatch, scaled by what the
 # same counters read for a 1 GiB copy: x2.00 and x1.00), see profiles/pmc_fetch_write_llama3_8b_s2k.md
-TRAFFIC_GEMM_BYTES = int((195378.1 * 2.0 + 57375.0) * 1024)      # 2048x4096x14336 bf16 (algorithmic: 184.5 MiB)
-TRAFFIC_RNG_BYTES = int((47.4 * 2.0 + 16384.0) * 1024)           # 32x2048x2048-bit mask (algorithmic: 16 MiB)
-TRAFFIC_ATTN_MASK_BYTES = int((41047.4 * 2.0 + 16390.4) * 1024)  # attention reading the mask (algorithmic: 80 MiB)
+TRAFFIC_GEMM_BYTES = int((195003.0 * 2.0 + 57362.6) * 1024)      # 2048x4096x14336 bf16 (algorithmic: 184.5 MiB)
+TRAFFIC_RNG_BYTES = int((46.8 * 2.0 + 16384.0) * 1024)           # 32x2048x2048-bit mask (algorithmic: 16 MiB)
+TRAFFIC_ATTN_MASK_BYTES = int((41047.4 * 2.0 + 16388.8) * 1024)  # attention reading the mask (algorithmic: 80 MiB)
 
 
 def median_ms(fn, warm, iters, sync, ev_pair, inner=10):

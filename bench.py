@@ -347,19 +347,30 @@ def bench_block(torch, rov, wl, main_s, side_s, sync, ev_pair, seq_len=None, cau
         def fus():
             rov.block_forward(weights, x, y, cfg, rov.SCHED_FUSED, wl.SEED, 0, None, ws, main_s, side_s)
 
-        def ovl():   # steady state: this layer's mask was produced during the previous call
+        def ovl(sched=rov.SCHED_OVERLAP):   # steady state: this layer's mask was produced during the previous call
             cur, nxt = (m0, m1) if layer[0] % 2 == 0 else (m1, m0)
-            rov.block_forward(weights, x, y, cfg, rov.SCHED_OVERLAP, wl.SEED, layer[0] * off1, cur, ws,
+            rov.block_forward(weights, x, y, cfg, sched, wl.SEED, layer[0] * off1, cur, ws,
                               main_s, side_s, mask_ready=True, next_mask=nxt)
             layer[0] += 1
+
+        def hyb():   # stored bits for the rows that fit beside the GEMMs, in-kernel Philox for the rest
+            ovl(rov.SCHED_HYBRID)
 
         with torch.cuda.stream(main_s):
             t_seq = median_ms(seq, 2, 5, sync, ev_pair, inner=2)
             t_fus = median_ms(fus, 2, 5, sync, ev_pair, inner=2)
             t_ovl = median_ms(ovl, 2, 5, sync, ev_pair, inner=2)
+            # hybrid in steady state needs the first rows of this layer's mask in the rows layout
+            rows = rov.block_hybrid_mask_rows(cfg, B, S)
+            t_hyb = None
+            if 0 < rows < S:
+                layer[0] = 0
+                rov.dropout_mask_generate_rows(wl.SEED, 0, B, H, S, p, 0, rows, out=m0, stream=main_s)
+                t_hyb = median_ms(hyb, 2, 5, sync, ev_pair, inner=2)
         res["causal" if causal else "noncausal"] = {
             "sequential_ms": t_seq, "fused_ms": t_fus, "overlap_ms": t_ovl,
-            "speedup_overlap_vs_sequential": t_seq / t_ovl, "speedup_overlap_vs_fused": t_fus / t_ovl}
+            "speedup_overlap_vs_sequential": t_seq / t_ovl, "speedup_overlap_vs_fused": t_fus / t_ovl,
+            "hybrid_mask_rows": rows, "hybrid_ms": t_hyb}
         if check:
             outs = []
             for fn in (seq, fus):
@@ -372,8 +383,15 @@ def bench_block(torch, rov, wl, main_s, side_s, sync, ev_pair, seq_len=None, cau
             sync()
             ovl()
             sync()
-            res["causal" if causal else "noncausal"]["schedules_agree_bit_for_bit"] = bool(
-                torch.equal(outs[0], outs[1]) and torch.equal(outs[0], y))
+            agree = torch.equal(outs[0], outs[1]) and torch.equal(outs[0], y)
+            if 0 < rows < S:
+                layer[0] = 0
+                rov.dropout_mask_generate_rows(wl.SEED, 0, B, H, S, p, 0, rows, out=m0)
+                sync()
+                hyb()
+                sync()
+                agree = agree and torch.equal(outs[0], y)
+            res["causal" if causal else "noncausal"]["schedules_agree_bit_for_bit"] = bool(agree)
         del ws, m0, m1
         torch.cuda.empty_cache()
     return res

@@ -44,6 +44,7 @@ extern "C" {
 #define ROV_SCHED_SEQUENTIAL 0    /* GEMMs, RNG kernel, attention: one stream (paper Sec. 6.1, baseline) */
 #define ROV_SCHED_FUSED 1         /* GEMMs, attention with in-kernel Philox (paper Sec. 6.1, fusion) */
 #define ROV_SCHED_OVERLAP 2       /* RNG on a side stream beside the GEMMs, joined before attention */
+#define ROV_SCHED_HYBRID 3        /* rov_block_forward only: OVERLAP for the query rows whose bits fit beside the GEMMs, FUSED for the rest */
 
 /* hipError_t of the last failing HIP call made by this library on the calling thread (0 if none). */
 int rov_last_hip_error(void);
@@ -358,6 +359,15 @@ int rov_trace_read(int *kinds, float *ms, int max_records, int *n_records);
  *               (paper Sec. 1: RNG hidden behind the GEMM layers between the
  *               previous and the current attention).  next_mask must be NULL for
  *               the other schedules and must differ from mask.
+ *   HYBRID      (not in the paper; for sequences so long that the RNG outlasts the
+ *               GEMMs, the paper's third regime of Sec. 4.1.)  As OVERLAP, but a mask
+ *               holds only the first R = rov_block_hybrid_mask_rows(cfg, B, S) query
+ *               rows, in the layout of rov_dropout_mask_generate_rows(q_begin = 0,
+ *               q_rows = R), R chosen so that the RNG kernel finishes beside the
+ *               GEMMs; attention takes stored bits for those rows and draws the
+ *               same bits in-kernel for the others, so the output is that of the
+ *               other schedules bit for bit.  R == S is OVERLAP, R == 0 is FUSED.
+ *               mask / next_mask as for OVERLAP (mask may be NULL when R == 0).
  * workspace: device scratch, 256-byte aligned, at least
  * rov_block_workspace_bytes() bytes; contents undefined afterwards. */
 typedef struct rov_block_cfg {
@@ -380,6 +390,14 @@ typedef struct rov_block_weights {
 } rov_block_weights;
 
 size_t rov_block_workspace_bytes(const rov_block_cfg *cfg, int B, int S, int schedule);
+
+/* Rows of a mask under ROV_SCHED_HYBRID: a multiple of 32 in [0, S] (host-side rule from the
+ * block's GEMM work and the mask's Philox calls; ROV_ERR_INVALID for a bad cfg or size).
+ * rov_set_block_hybrid_mask_rows: rows > 0 forces that many (rounded down to 32, at most S),
+ * rows < 0 forces none, 0 restores the rule; process-wide, for tests and experiments; returns
+ * the previous setting. */
+int rov_block_hybrid_mask_rows(const rov_block_cfg *cfg, int B, int S);
+int rov_set_block_hybrid_mask_rows(int rows);
 
 int rov_block_forward(const rov_block_weights *w, const void *x, void *y, int B, int S,
                       const rov_block_cfg *cfg, int schedule, uint64_t seed, uint64_t offset,

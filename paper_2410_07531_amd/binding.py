@@ -12,7 +12,7 @@ LIB_PATH = os.path.join(HERE, "librov.so")
 
 OK, ERR_INVALID, ERR_UNSUPPORTED, ERR_HIP, ERR_WORKSPACE = 0, -1, -2, -3, -4
 F32, BF16, FP8_E4M3 = 0, 1, 2
-SCHED_SEQUENTIAL, SCHED_FUSED, SCHED_OVERLAP = 0, 1, 2
+SCHED_SEQUENTIAL, SCHED_FUSED, SCHED_OVERLAP, SCHED_HYBRID = 0, 1, 2, 3
 
 _ERR_NAMES = {ERR_INVALID: "ROV_ERR_INVALID", ERR_UNSUPPORTED: "ROV_ERR_UNSUPPORTED",
               ERR_HIP: "ROV_ERR_HIP", ERR_WORKSPACE: "ROV_ERR_WORKSPACE"}
@@ -95,6 +95,8 @@ SIGNATURES = {
                                               ctypes.POINTER(ctypes.c_int64), _i, _i, _f, _p, _u64, _u64, _i,
                                               _p]),
     "rov_block_workspace_bytes": (ctypes.c_size_t, [ctypes.POINTER(BlockCfg), _i, _i, _i]),
+    "rov_block_hybrid_mask_rows": (_i, [ctypes.POINTER(BlockCfg), _i, _i]),
+    "rov_set_block_hybrid_mask_rows": (_i, [_i]),
     "rov_block_forward": (_i, [ctypes.POINTER(BlockWeights), _p, _p, _i, _i, ctypes.POINTER(BlockCfg),
                                _i, _u64, _u64, _i, _p, _p, _p, ctypes.c_size_t, _p, _p]),
 }
@@ -381,6 +383,14 @@ def layer_step(schedule, gemm_descs, attn_desc, seed, offset, mask, main_stream,
 
 def block_workspace_bytes(cfg, B, S, schedule):
     return int(load().rov_block_workspace_bytes(ctypes.byref(cfg), B, S, int(schedule)))
+
+
+def block_hybrid_mask_rows(cfg, B, S):
+    return int(load().rov_block_hybrid_mask_rows(ctypes.byref(cfg), B, S))
+
+
+def set_block_hybrid_mask_rows(rows):
+    return int(load().rov_set_block_hybrid_mask_rows(int(rows)))
 
 
 def make_block_cfg(H, Hkv, d, hidden, ffn, p, causal=False, eps=1e-5, rope_theta=500000.0, dtype=BF16):

@@ -13,6 +13,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
 #include <mutex>
 
 #include "rov_internal.h"
@@ -105,6 +106,30 @@ bool rng_fits_beside(double gemm_flop, bool fp32, double rng_calls) {
 }
 
 double gemm_flop(int M, int N, int K) { return 2.0 * (double)M * (double)N * (double)K; }
+
+// Hybrid schedule of the block: how many query rows of the next layer's mask the small RNG grid
+// gets done beside the block's PROJ / FC1 / FC2 GEMMs (1.3 PFLOP/s, 16 % slower with the RNG there
+// all the time, 0.325 T Philox calls/s beside them: this chip's measured rates), with a twentieth
+// of margin, in steps of 2048 rows (a full round of attention workgroups at 32 heads); below one
+// step the mask is not worth its launches.  rov_set_block_hybrid_mask_rows overrides the rule.
+std::atomic<int> g_hybrid_rows{0};
+int hybrid_rows(const rov_block_cfg* c, int B, int S) {
+    const int forced = g_hybrid_rows.load();
+    int R;
+    if (forced != 0) {
+        R = forced < 0 ? 0 : forced;
+    } else {
+        const double T = (double)B * S;
+        const double t_gemms = (gemm_flop((int)T, c->hidden, c->H * c->d) + 3.0 * gemm_flop((int)T, c->ffn, c->hidden)) /
+                               1.3e15 * 1.16;
+        const double frac = 0.95 * t_gemms * 0.325e12 / (double)rov_mask_philox_calls(B, c->H, S);
+        // (while most of it fits, the overlap schedule's full-speed launch for the rest costs no more
+        // than drawing those rows in the attention kernel: measured level at 0.8)
+        R = frac >= 0.7 ? S : (int)(frac * S / 2048.0) * 2048;
+    }
+    R = R < S ? R - R % 32 : S;
+    return R;
+}
 
 size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
@@ -379,6 +404,14 @@ extern "C" size_t rov_block_workspace_bytes(const rov_block_cfg* cfg, int B, int
     return L.total;
 }
 
+extern "C" int rov_block_hybrid_mask_rows(const rov_block_cfg* cfg, int B, int S) {
+    rov::BlockLayout L;
+    if (!rov::block_layout(cfg, B, S, &L)) return ROV_ERR_INVALID;
+    return rov::hybrid_rows(cfg, B, S);
+}
+
+extern "C" int rov_set_block_hybrid_mask_rows(int rows) { return rov::g_hybrid_rows.exchange(rows); }
+
 extern "C" int rov_block_forward(const rov_block_weights* w, const void* x, void* y, int B, int S,
                                  const rov_block_cfg* cfg, int schedule, uint64_t seed,
                                  uint64_t offset, int mask_ready, uint64_t* mask,
@@ -386,8 +419,8 @@ extern "C" int rov_block_forward(const rov_block_weights* w, const void* x, void
                                  void* main_stream, void* side_stream) {
     using namespace rov;
     BlockLayout L;
-    if (w == nullptr || x == nullptr || y == nullptr || !valid_schedule(schedule) ||
-        !block_layout(cfg, B, S, &L))
+    if (w == nullptr || x == nullptr || y == nullptr ||
+        !(valid_schedule(schedule) || schedule == ROV_SCHED_HYBRID) || !block_layout(cfg, B, S, &L))
         return ROV_ERR_INVALID;
     if (w->norm1 == nullptr || w->norm2 == nullptr || w->wqkv == nullptr || w->wo == nullptr ||
         w->wg == nullptr || w->wu == nullptr || w->wd == nullptr)
@@ -402,10 +435,13 @@ extern "C" int rov_block_forward(const rov_block_weights* w, const void* x, void
     if (workspace == nullptr || !aligned(workspace, 256)) return ROV_ERR_INVALID;
     if (workspace_bytes < L.total) return ROV_ERR_WORKSPACE;
     const bool dropout = cfg->p > 0.0f;
-    const bool use_mask = dropout && schedule != ROV_SCHED_FUSED;
+    // hybrid: stored bits for query rows [0, R), in-kernel Philox for the rest (the same bits)
+    const bool hybrid = schedule == ROV_SCHED_HYBRID && dropout;
+    const int R = hybrid ? hybrid_rows(cfg, B, S) : S;
+    const bool use_mask = dropout && schedule != ROV_SCHED_FUSED && R > 0;
     if (use_mask && (mask == nullptr || !aligned(mask, 8))) return ROV_ERR_INVALID;
     if (next_mask != nullptr && (!aligned(next_mask, 8) || next_mask == mask)) return ROV_ERR_INVALID;
-    const bool overlap = schedule == ROV_SCHED_OVERLAP && dropout;
+    const bool overlap = (schedule == ROV_SCHED_OVERLAP || schedule == ROV_SCHED_HYBRID) && dropout;
     if (overlap && main_stream == side_stream) return ROV_ERR_INVALID;
     if (!overlap && next_mask != nullptr) return ROV_ERR_INVALID;   // only the overlap schedule runs ahead
     hipStream_t ms = (hipStream_t)main_stream, ss = (hipStream_t)side_stream;
@@ -446,7 +482,16 @@ extern "C" int rov_block_forward(const rov_block_weights* w, const void* x, void
     ROV_STEP(traced(ROV_TRACE_GLUE, ms, [&] { return launch_rmsnorm(x, w->norm1, h, T, hidden, cfg->eps, ms); }));
     ROV_STEP(t_gemm(h, w->wqkv, qkv, nullptr, (int)T, qkv_n, hidden, ROV_BF16, 1, 1.0f, 1.0f, ms));
     if (use_mask && !mask_ready) {
-        if (overlap) {
+        if (overlap && R < S) {   // hybrid: the first R rows only, compact
+            ROV_STEP(traced(ROV_TRACE_RNG, ss, [&] {
+                return launch_mask_rows(seed, offset, B, H, S, cfg->p, 0, R, mask, ss, MASK_GRID_BESIDE, qslot);
+            }));
+            ROV_HIP_TRY(hipEventRecord(ev->join, ss));
+            if (qslot >= 0)
+                ROV_STEP(traced(ROV_TRACE_RNG_HELPER, ms, [&] {
+                    return launch_mask_rows(seed, offset, B, H, S, cfg->p, 0, R, mask, ms, MASK_GRID_HELPER, qslot);
+                }));
+        } else if (overlap) {
             ROV_STEP(t_mask(seed, offset, B, H, S, cfg->p, mask, ss, MASK_GRID_BESIDE, qslot, cfg->causal != 0));
             ROV_HIP_TRY(hipEventRecord(ev->join, ss));
             if (qslot >= 0)
@@ -466,26 +511,48 @@ extern "C" int rov_block_forward(const rov_block_weights* w, const void* x, void
         (int64_t)S * qkv_n, qkv_n, d,      // K
         (int64_t)S * qkv_n, qkv_n, d,      // V
         (int64_t)S * H * d, (int64_t)H * d, d};   // O
-    ROV_STEP(traced(ROV_TRACE_ATTENTION, ms, [&] {
-        return launch_attention(qp, qp + (int64_t)H * d, qp + (int64_t)(H + Hkv) * d, att, B, H, Hkv, S,
-                                d, strides, ROV_BF16, cfg->causal, cfg->p, use_mask ? mask : nullptr,
-                                seed, offset, ms);
-    }));
+    if (hybrid && R < S) {
+        if (R > 0)
+            ROV_STEP(traced(ROV_TRACE_ATTENTION, ms, [&] {
+                return launch_attention_rows(qp, qp + (int64_t)H * d, qp + (int64_t)(H + Hkv) * d, att, B, H, Hkv, S,
+                                             d, strides, ROV_BF16, cfg->causal, cfg->p, mask, true, seed, offset, 0,
+                                             R, ms);
+            }));
+        ROV_STEP(traced(ROV_TRACE_ATTENTION, ms, [&] {
+            return launch_attention_rows(qp, qp + (int64_t)H * d, qp + (int64_t)(H + Hkv) * d, att, B, H, Hkv, S, d,
+                                         strides, ROV_BF16, cfg->causal, cfg->p, nullptr, false, seed, offset, R,
+                                         S - R, ms);
+        }));
+    } else {
+        ROV_STEP(traced(ROV_TRACE_ATTENTION, ms, [&] {
+            return launch_attention(qp, qp + (int64_t)H * d, qp + (int64_t)(H + Hkv) * d, att, B, H, Hkv, S,
+                                    d, strides, ROV_BF16, cfg->causal, cfg->p, use_mask ? mask : nullptr,
+                                    seed, offset, ms);
+        }));
+    }
 
     // the next layer's mask runs beside this block's remaining GEMMs (it would compete with
     // attention for VALU issue, so it starts once attention is done)
     int qslot_next = -1;
-    if (overlap && next_mask != nullptr) {
+    const bool run_ahead = overlap && next_mask != nullptr && R > 0;
+    if (run_ahead) {
         const double rest = gemm_flop((int)T, hidden, H * d) + 2.0 * gemm_flop((int)T, ffn, hidden) +
                             gemm_flop((int)T, hidden, ffn);
-        if (!rng_fits_beside(rest, false, mask_calls)) ROV_STEP(mask_queue_acquire(ms, &qslot_next));
+        // (hybrid with R < S: the rows were chosen to fit, no queue and no helper launch)
+        if (R == S && !rng_fits_beside(rest, false, mask_calls)) ROV_STEP(mask_queue_acquire(ms, &qslot_next));
         ROV_HIP_TRY(hipEventRecord(ev->fork, ms));
         ROV_HIP_TRY(hipStreamWaitEvent(ss, ev->fork, 0));
     }
     ROV_STEP(t_gemm(att, w->wo, x2, x, (int)T, hidden, H * d, ROV_BF16, 1, 1.0f, 1.0f, ms));
-    if (overlap && next_mask != nullptr) {
-        ROV_STEP(t_mask(seed, offset + rov_mask_philox_calls(B, H, S), B, H, S, cfg->p, next_mask, ss,
-                        MASK_GRID_BESIDE, qslot_next, cfg->causal != 0));
+    if (run_ahead) {
+        if (R < S)
+            ROV_STEP(traced(ROV_TRACE_RNG, ss, [&] {
+                return launch_mask_rows(seed, offset + rov_mask_philox_calls(B, H, S), B, H, S, cfg->p, 0, R, next_mask,
+                                        ss, MASK_GRID_BESIDE, -1);
+            }));
+        else
+            ROV_STEP(t_mask(seed, offset + rov_mask_philox_calls(B, H, S), B, H, S, cfg->p, next_mask, ss,
+                            MASK_GRID_BESIDE, qslot_next, cfg->causal != 0));
         ROV_HIP_TRY(hipEventRecord(ev->join, ss));
     }
     ROV_STEP(traced(ROV_TRACE_GLUE, ms, [&] { return launch_rmsnorm(x2, w->norm2, h, T, hidden, cfg->eps, ms); }));
@@ -495,7 +562,7 @@ extern "C" int rov_block_forward(const rov_block_weights* w, const void* x, void
         return launch_gemm_epilogue(h, w->wu, u, g, EPI_SILU_MUL, (int)T, ffn, hidden, ROV_BF16, 1, 1.0f, 1.0f, ms);
     }));
     ROV_STEP(t_gemm(u, w->wd, y, x2, (int)T, hidden, ffn, ROV_BF16, 1, 1.0f, 1.0f, ms));
-    if (overlap && next_mask != nullptr) {
+    if (run_ahead) {
         // what is left of the next mask when the last GEMM ends is finished at full speed
         if (qslot_next >= 0)
             ROV_STEP(t_mask(seed, offset + rov_mask_philox_calls(B, H, S), B, H, S, cfg->p, next_mask, ms,

@@ -319,6 +319,67 @@ def test_block_forward_three_schedules_match_oracle(causal):
     assert np.max(np.abs(ref - _f64(x))) / np.max(np.abs(ref)) > 0.1
 
 
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("rows", [-1, 64, 160, 320])
+def test_block_forward_hybrid_equals_the_other_schedules(rows, causal):
+    # hybrid: stored bits for the first R query rows, in-kernel Philox for the rest; R forced to
+    # none, a part (tile-aligned and not), and all of S = 320: always the sequential schedule's bits,
+    # both when the block makes its own mask and in steady state (mask made by the block before)
+    B, S, H, Hkv, d, hidden, ffn = 1, 320, 4, 2, 128, 512, 1024
+    p, seed, offset = 0.1, wl.SEED, 640
+    x, wd = _block_setup(B, S, H, Hkv, d, hidden, ffn, 23)
+    cfg = rov.make_block_cfg(H, Hkv, d, hidden, ffn, p, causal=causal)
+    weights = rov.make_block_weights(wd)
+    ws = torch.empty(rov.block_workspace_bytes(cfg, B, S, 0), dtype=torch.uint8, device="cuda")
+    main, side = torch.cuda.Stream(), torch.cuda.Stream()
+    calls = rov.mask_philox_calls(B, H, S)
+    y_seq, y_seq2 = torch.zeros_like(x), torch.zeros_like(x)
+    m = torch.zeros(rov.mask_shape(B, H, S), dtype=torch.int64, device="cuda")
+    torch.cuda.synchronize()
+    rov.block_forward(weights, x, y_seq, cfg, rov.SCHED_SEQUENTIAL, seed, offset, m, ws, main, side)
+    rov.block_forward(weights, x, y_seq2, cfg, rov.SCHED_SEQUENTIAL, seed, offset + calls, m, ws, main, side)
+    torch.cuda.synchronize()
+    prev = rov.set_block_hybrid_mask_rows(rows)
+    try:
+        R = rov.block_hybrid_mask_rows(cfg, B, S)
+        assert R == (0 if rows < 0 else rows - rows % 32)
+        y1, y2 = torch.zeros_like(x), torch.zeros_like(x)
+        m0 = torch.full(rov.mask_shape(B, H, S), 0x2AAAAAAAAAAAAAAA, dtype=torch.int64, device="cuda")
+        m1 = torch.full_like(m0, 0x2AAAAAAAAAAAAAAA)
+        torch.cuda.synchronize()
+        print("hybrid", rows, causal, "first block", flush=True)
+        rov.block_forward(weights, x, y1, cfg, rov.SCHED_HYBRID, seed, offset, m0, ws, main, side, next_mask=m1)
+        torch.cuda.synchronize()
+        print("hybrid", rows, causal, "steady state", flush=True)
+        rov.block_forward(weights, x, y2, cfg, rov.SCHED_HYBRID, seed, offset + calls, m1, ws, main, side,
+                          mask_ready=True, next_mask=m0)
+        torch.cuda.synchronize()
+    finally:
+        rov.set_block_hybrid_mask_rows(prev)
+    assert torch.equal(y1, y_seq) and torch.equal(y2, y_seq2)
+    if 0 < R:
+        # the rows that were stored are those of the full mask of the next layer
+        full = OP.dropout_mask(seed, offset + calls, B, H, S, p)             # [B, H, T, T, 16]
+        got = m1.cpu().numpy().view(np.uint64).reshape(-1)[: B * H * (R // 32) * (S // 32) * 16]
+        got = got.reshape(B, H, R // 32, S // 32, 16)
+        if causal and R == S:     # the whole-mask kernel skips the tiles causal attention never reads
+            lower = np.tril(np.ones((S // 32, S // 32), dtype=bool))
+            assert np.array_equal(got[:, :, lower], full[:, :, lower])
+        else:
+            assert np.array_equal(got, full[:, :, : R // 32])
+
+
+def test_block_hybrid_rows_rule():
+    # host rule: everything fits at the benchmark's 16K block, a part at 32K, in steps of 2048 rows
+    cfg = rov.make_block_cfg(32, 8, 128, 4096, 14336, 0.1)
+    assert rov.block_hybrid_mask_rows(cfg, 1, 2048) == 2048
+    assert rov.block_hybrid_mask_rows(cfg, 1, 8192) == 8192
+    r32 = rov.block_hybrid_mask_rows(cfg, 1, 32768)
+    assert 0 < r32 < 32768 and r32 % 2048 == 0
+    r64 = rov.block_hybrid_mask_rows(cfg, 1, 65536)
+    assert 0 <= r64 < 65536 and r64 % 2048 == 0 and r64 / 65536 < r32 / 32768
+
+
 def test_block_forward_same_bits_for_every_gemm_tile_width():
     # the residual and SwiGLU epilogues of every width of the matrix-core GEMM kernel: the block's
     # output must not depend on the width (same k order per element, same epilogue arithmetic)

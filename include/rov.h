@@ -184,6 +184,13 @@ int rov_set_gemm_tile_cols(int cols);
  * ROV_ERR_INVALID for M <= 0 or N <= 0. */
 int rov_gemm_tile_cols(int M, int N);
 
+/* C[M,N] = silu(A Wg^T) * (A Wu^T), bf16 operands and result, fp32 accumulation: the gate and
+ * up projections of the block's SwiGLU feed-forward (Fig. 2's FC1 in its Llama form) as one
+ * product, the gate kept in the accumulators.  A [M,K], Wg and Wu [N,K], all row-major with K
+ * contiguous; device pointers, 16-byte aligned.  K % 64 == 0 and N % 4 == 0, else
+ * ROV_ERR_UNSUPPORTED. */
+int rov_gemm_swiglu(const void *A, const void *Wg, const void *Wu, void *C, int M, int N, int K, void *stream);
+
 /* The overlap as ONE kernel (paper Sec. 6.1 names this wave-specialised form beside
  * the two-kernel one it uses): every workgroup computes a tile of
  * C[M,N] = A[M,K] * Bm[N,K]^T (bf16, K contiguous in both, fp32 accumulation) with four

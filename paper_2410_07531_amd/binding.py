@@ -80,6 +80,7 @@ SIGNATURES = {
                             ctypes.POINTER(ctypes.c_int)]),
     "rov_valu_probe": (_i, [_i, _i, _i, _p, _p]),
     "rov_gemm": (_i, [_p, _p, _p, _i, _i, _i, _i, _i, _f, _f, _p]),
+    "rov_gemm_swiglu": (_i, [_p, _p, _p, _p, _i, _i, _i, _p]),
     "rov_gemm_rng_fused": (_i, [_p, _p, _p, _i, _i, _i, _u64, _u64, _i, _i, _i, _f, _p, _p]),
     "rov_attention_fwd_dropout": (_i, [_p, _p, _p, _p, _i, _i, _i, _i, _i,
                                        ctypes.POINTER(ctypes.c_int64), _i, _i, _f, _p, _u64, _u64, _p]),
@@ -240,6 +241,19 @@ def gemm(A, Bm, C=None, transB=True, scaleA=1.0, scaleB=1.0, stream=None):
     _check(load().rov_gemm(ctypes.c_void_p(A.data_ptr()), ctypes.c_void_p(Bm.data_ptr()),
                            ctypes.c_void_p(C.data_ptr()), M, N, K, code, int(bool(transB)),
                            float(scaleA), float(scaleB), _stream_ptr(stream)), "rov_gemm")
+    return C
+
+
+def gemm_swiglu(A, Wg, Wu, C=None, stream=None):
+    """C = silu(A @ Wg^T) * (A @ Wu^T), bf16."""
+    import torch
+    M, K = A.shape
+    N = Wg.shape[0]
+    if C is None:
+        C = torch.empty((M, N), dtype=torch.bfloat16, device=A.device)
+    _check(load().rov_gemm_swiglu(ctypes.c_void_p(A.data_ptr()), ctypes.c_void_p(Wg.data_ptr()),
+                                  ctypes.c_void_p(Wu.data_ptr()), ctypes.c_void_p(C.data_ptr()), M, N, K,
+                                  _stream_ptr(stream)), "rov_gemm_swiglu")
     return C
 
 

@@ -194,11 +194,17 @@ __device__ __forceinline__ void epilogue_combine(int epi, uint2 r, float& c0, fl
 // The tile of workgroup blockIdx.x, computed by the workgroup's waves 0-3 (`wave`; `lane` = lane
 // in the wave).  Its barriers are workgroup barriers: 1 + 2*(K*2/128) of them for bf16, 1 + K/128
 // for fp8, whatever the tile; any other wave of the workgroup has to arrive at as many.
-template <int NJ, bool FP8>
+// DUAL (SwiGLU, bf16): the tile's weight rows are, per wave, 8*NJ rows of Wt (the gate
+// projection) followed by the same 8*NJ rows of Wt2 (the up projection); the epilogue writes
+// silu(gate) * up for those 8*NJ output columns, both still in fp32, so the gate projection is
+// neither stored nor read back and the activation panel is fetched once for the two products.
+template <int NJ, bool FP8, bool DUAL = false>
 __device__ __forceinline__ void gemm_tile(const char* __restrict__ A, const char* __restrict__ Wt,
-                                          uint16_t* __restrict__ C, const uint16_t* __restrict__ R, int M,
-                                          int N, int K, float alpha, int tiles_m, int tiles_n, int epi,
-                                          char* lds, const int lane, const int wave) {
+                                          const char* __restrict__ Wt2, uint16_t* __restrict__ C,
+                                          const uint16_t* __restrict__ R, int M, int N, int K, float alpha,
+                                          int tiles_m, int tiles_n, int epi, char* lds, const int lane,
+                                          const int wave) {
+    static_assert(!DUAL || (!FP8 && (NJ == 8 || NJ == 4)), "dual form: bf16, 8 or 4 weight blocks per wave");
     const int wm = wave >> 1, wn = wave & 1;
 
     // XCD-aware tile id: workgroup ids are dealt round-robin to the 8 XCDs; give each XCD a
@@ -216,7 +222,7 @@ __device__ __forceinline__ void gemm_tile(const char* __restrict__ A, const char
     const int in_band = id - band * GM * tiles_n;
     const int tm = band * GM + in_band % band_rows;
     const int tn = in_band / band_rows;
-    constexpr int BNT = 32 * NJ;                 // tile width (weight rows)
+    constexpr int BNT = DUAL ? 16 * NJ : 32 * NJ;   // tile width in output columns
     const int m0 = tm * BM, n0 = tn * BNT;
 
     constexpr int ESZ = FP8 ? 1 : 2;
@@ -265,7 +271,9 @@ __device__ __forceinline__ void gemm_tile(const char* __restrict__ A, const char
         const int row = (wave + 4 * j) * 8 + (lane >> 3);
         const int chunk = (lane & 7) ^ swz(row);
         const int ra = row < rows_a ? row : rows_a - 1;   // rows past the edge are never stored
-        const int rw = row < rows_w ? row : rows_w - 1;
+        // dual: LDS rows [16*NJ*h, +8*NJ) are gate rows of output columns 8*NJ*h .., the next 8*NJ the up rows
+        const int wcol = DUAL ? (row / (16 * NJ)) * (8 * NJ) + row % (8 * NJ) : row;
+        const int rw = wcol < rows_w ? wcol : rows_w - 1;
         voff_a[j] = (uint32_t)((size_t)ra * ld_bytes) + (uint32_t)(chunk * 16);
         if (j < NJ) voff_w[j] = (uint32_t)((size_t)rw * ld_bytes) + (uint32_t)(chunk * 16);
     }
@@ -287,6 +295,7 @@ __device__ __forceinline__ void gemm_tile(const char* __restrict__ A, const char
     };
     const i32x4 rsrc_a = make_rsrc(a_panel, (size_t)rows_a * ld_bytes);
     const i32x4 rsrc_w = make_rsrc(w_panel, (size_t)rows_w * ld_bytes);
+    const i32x4 rsrc_w2 = DUAL ? make_rsrc(Wt2 + (size_t)n0 * ld_bytes, (size_t)rows_w * ld_bytes) : rsrc_w;
     const uint32_t lds_base = (uint32_t)(uintptr_t)(lptr_t)lds;
 
     // Load instruction q (0..7 = A row blocks, 8..7+NJ = W row blocks) of slot-step `step` into the
@@ -305,8 +314,11 @@ __device__ __forceinline__ void gemm_tile(const char* __restrict__ A, const char
                          :: "s"(dst), "v"(voff_a[q]), "s"(rsrc_a), "s"(koff) : "memory");
         } else {
             const uint32_t dst = slot + (uint32_t)(BM * kRow + (wave + 4 * (q - 8)) * 1024);
+            // dual: row block wave + 4*(q-8) holds up rows iff it lies in the second half of its wave's
+            // 2*NJ row blocks; with NJ = 8 or 4 that does not depend on the wave
+            const bool up = DUAL && (4 * (q - 8)) % (2 * NJ) >= NJ;
             asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
-                         :: "s"(dst), "v"(voff_w[q - 8]), "s"(rsrc_w), "s"(koff) : "memory");
+                         :: "s"(dst), "v"(voff_w[q - 8]), "s"(up ? rsrc_w2 : rsrc_w), "s"(koff) : "memory");
         }
     };
 
@@ -454,6 +466,31 @@ __device__ __forceinline__ void gemm_tile(const char* __restrict__ A, const char
     // D'[r][c] = C[m = c][n = r]: lane holds activation row lane%16 and weight rows 4*(lane/16) + e
     const int mrow = lane & 15;
     const int nsub = (lane >> 4) * 4;
+    if constexpr (DUAL) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int m = m0 + wm * 128 + i * 16 + mrow;
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int j = 0; j < NJ / 2; ++j) {
+                const int n = n0 + wn * 8 * NJ + j * 16 + nsub;
+                float o[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const float gte = alpha * acc_read(acc[j][i][e]);
+                    const float upv = alpha * acc_read(acc[j + NJ / 2][i][e]);
+                    o[e] = gte / (1.0f + __expf(-gte)) * upv;
+                }
+                if (m < M && n < N) {
+                    uint2 v;
+                    v.x = pack_bf16x2(o[0], o[1]);
+                    v.y = pack_bf16x2(o[2], o[3]);
+                    *reinterpret_cast<uint2*>(C + (size_t)m * N + n) = v;
+                }
+            }
+        }
+        return;
+    }
     // The side input of row block i+1 is requested before row block i is combined and stored, so
     // its latency is paid once per tile, not once per element group (the wave is alone on its SIMD).
     uint2 rv[2][NJ];
@@ -500,8 +537,20 @@ __global__ __launch_bounds__(256, 1) void gemm_tn_kernel(const char* __restrict_
     // Co-resident RNG waves only need the VALU issue slots this kernel leaves idle; raise this
     // wave's issue priority so that they never delay its MFMA / LDS instruction stream.
     __builtin_amdgcn_s_setprio(3);
-    gemm_tile<NJ, FP8>(A, Wt, C, R, M, N, K, alpha, tiles_m, tiles_n, epi, lds, threadIdx.x & 63,
+    gemm_tile<NJ, FP8>(A, Wt, nullptr, C, R, M, N, K, alpha, tiles_m, tiles_n, epi, lds, threadIdx.x & 63,
                        __builtin_amdgcn_readfirstlane(threadIdx.x >> 6));
+}
+
+// C[M, N] = silu(A Wg^T) * (A Wu^T): the SwiGLU of the block's feed-forward as one product with
+// twice the weight rows (see gemm_tile, DUAL).
+template <int NJ>
+__global__ __launch_bounds__(256, 1) void gemm_swiglu_kernel(const char* __restrict__ A, const char* __restrict__ Wg,
+                                                            const char* __restrict__ Wu, uint16_t* __restrict__ C,
+                                                            int M, int N, int K, int tiles_m, int tiles_n) {
+    extern __shared__ __attribute__((aligned(1024))) char lds[];
+    __builtin_amdgcn_s_setprio(3);
+    gemm_tile<NJ, false, true>(A, Wg, Wu, C, nullptr, M, N, K, 1.0f, tiles_m, tiles_n, EPI_ADD, lds,
+                               threadIdx.x & 63, __builtin_amdgcn_readfirstlane(threadIdx.x >> 6));
 }
 
 // Wave-specialised GEMM + RNG (paper Sec. 6.1 names this form beside the two-kernel one): a
@@ -524,7 +573,7 @@ __global__ __launch_bounds__(512, 1) void gemm_rng_kernel(const char* __restrict
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     if (wave < 4) {
         __builtin_amdgcn_s_setprio(3);
-        gemm_tile<4, false>(A, Wt, C, nullptr, M, N, K, 1.0f, tiles_m, tiles_n, EPI_ADD, lds, lane, wave);
+        gemm_tile<4, false>(A, Wt, nullptr, C, nullptr, M, N, K, 1.0f, tiles_m, tiles_n, EPI_ADD, lds, lane, wave);
     } else {
         ChunkSource src;
         src.queues = queues; src.nchunks = nchunks; src.stride = 0; src.per = qper; src.batch = 1u;
@@ -579,6 +628,33 @@ __global__ __launch_bounds__(512, 1) void gemm_rng_kernel(const char* __restrict
 }
 
 }  // namespace
+
+int launch_gemm_swiglu(const void* A, const void* Wg, const void* Wu, void* C, int M, int N, int K,
+                       hipStream_t stream) {
+    if (A == nullptr || Wg == nullptr || Wu == nullptr || C == nullptr || M <= 0 || N <= 0 || K <= 0)
+        return ROV_ERR_INVALID;
+    if (!aligned(A, 16) || !aligned(Wg, 16) || !aligned(Wu, 16) || !aligned(C, 16)) return ROV_ERR_INVALID;
+    if (((size_t)K * 2) % kRowBytes != 0 || (N % 4) != 0) return ROV_ERR_UNSUPPORTED;
+    if ((unsigned long long)BM * (unsigned long long)K * 2ull > 0xFFFFFFFFull) return ROV_ERR_UNSUPPORTED;
+    // 128 or 64 output columns per tile (8 or 4 weight blocks per wave, half gate, half up): the
+    // same rounds x (blocks + 1) rule as for the plain product
+    const long long tiles_m = (M + BM - 1) / BM, ncu = device_cu_count();
+    const long long t8 = tiles_m * ((N + 127) / 128), t4 = tiles_m * ((N + 63) / 64);
+    const bool wide = ((t8 + ncu - 1) / ncu) * 9 <= ((t4 + ncu - 1) / ncu) * 5;
+    const long long T = wide ? t8 : t4;
+    if (T > 0x7FFFFFFFLL) return ROV_ERR_UNSUPPORTED;
+    typedef void (*kern_t)(const char*, const char*, const char*, uint16_t*, int, int, int, int, int);
+    const kern_t kern = wide ? (kern_t)gemm_swiglu_kernel<8> : (kern_t)gemm_swiglu_kernel<4>;
+    static bool attr_set[2] = {};
+    if (!attr_set[wide]) {
+        ROV_HIP_TRY(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes));
+        attr_set[wide] = true;
+    }
+    hipLaunchKernelGGL(kern, dim3((unsigned)T), dim3(256), kLdsBytes, stream, (const char*)A, (const char*)Wg,
+                       (const char*)Wu, (uint16_t*)C, M, N, K, (int)tiles_m, (int)(T / tiles_m));
+    ROV_LAUNCH_CHECK();
+    return ROV_OK;
+}
 
 int launch_gemm_rng(const void* A, const void* Bm, void* C, int M, int N, int K, uint64_t seed, uint64_t offset,
                     int B, int H, int S, float p, uint64_t* mask, int qslot, hipStream_t stream) {

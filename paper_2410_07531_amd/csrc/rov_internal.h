@@ -81,6 +81,10 @@ int launch_attention_rows(const void* Q, const void* K, const void* V, void* O, 
                           const uint64_t* mask, bool mask_is_rows, uint64_t seed, uint64_t offset,
                           int q_begin, int q_rows, hipStream_t stream, int rounds = 10, int bits = 32);
 
+// C[M,N] = silu(A Wg^T) * (A Wu^T), bf16 with fp32 accumulation: the two products of a SwiGLU in one
+// kernel (both weight matrices [N,K], K % 64 == 0, N % 4 == 0).
+int launch_gemm_swiglu(const void* A, const void* Wg, const void* Wu, void* C, int M, int N, int K,
+                       hipStream_t stream);
 // One kernel whose workgroups compute a tile of the bf16 GEMM with four waves while four more
 // waves generate keep-mask chunks pulled from queue slot `qslot` (paper Sec. 6.1: the single-kernel,
 // wave-specialised form of the overlap).  S % 32 == 0; what the RNG waves do not get to stays in

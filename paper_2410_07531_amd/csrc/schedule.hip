@@ -261,6 +261,11 @@ int layer_step_impl(int schedule, const rov_gemm_desc* gemms, int n_gemms, const
 }  // namespace
 }  // namespace rov
 
+extern "C" int rov_gemm_swiglu(const void* A, const void* Wg, const void* Wu, void* C, int M, int N, int K,
+                               void* stream) {
+    return rov::launch_gemm_swiglu(A, Wg, Wu, C, M, N, K, (hipStream_t)stream);
+}
+
 extern "C" int rov_gemm_rng_fused(const void* A, const void* Bm, void* C, int M, int N, int K, uint64_t seed,
                                   uint64_t offset, int B, int H, int S, float p, uint64_t* mask, void* stream) {
     hipStream_t st = (hipStream_t)stream;
@@ -556,10 +561,11 @@ extern "C" int rov_block_forward(const rov_block_weights* w, const void* x, void
         ROV_HIP_TRY(hipEventRecord(ev->join, ss));
     }
     ROV_STEP(traced(ROV_TRACE_GLUE, ms, [&] { return launch_rmsnorm(x2, w->norm2, h, T, hidden, cfg->eps, ms); }));
-    ROV_STEP(t_gemm(h, w->wg, g, nullptr, (int)T, ffn, hidden, ROV_BF16, 1, 1.0f, 1.0f, ms));
-    // SwiGLU in the epilogue of the up projection: u = silu(g) * (h Wu^T), no separate pass over g and u
+    // gate and up projections as one product with the SwiGLU in its epilogue: u = silu(h Wg^T) * (h Wu^T),
+    // the gate never leaves the accumulators and h is fetched once for both
+    (void)g;
     ROV_STEP(traced(ROV_TRACE_GEMM, ms, [&] {
-        return launch_gemm_epilogue(h, w->wu, u, g, EPI_SILU_MUL, (int)T, ffn, hidden, ROV_BF16, 1, 1.0f, 1.0f, ms);
+        return launch_gemm_swiglu(h, w->wg, w->wu, u, (int)T, ffn, hidden, ms);
     }));
     ROV_STEP(t_gemm(u, w->wd, y, x2, (int)T, hidden, ffn, ROV_BF16, 1, 1.0f, 1.0f, ms));
     if (run_ahead) {

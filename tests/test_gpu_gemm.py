@@ -77,6 +77,32 @@ def test_gemm_bf16_every_tile_width(cols):
     assert torch.equal(C.view(torch.int16), C0.view(torch.int16))
 
 
+@pytest.mark.parametrize("M,N,K", [
+    (256, 128, 64),         # one 128-column tile, one slot-step
+    (600, 1000, 448),       # ragged rows and columns (last tile: 104 of 128), odd slot count
+    (300, 72, 192),         # fewer columns than one wave's half of a 64-column tile
+    (2304, 192, 128),       # nine tile rows (every k start), narrow output
+    (512, 4096, 256),       # 64 tiles of 128 columns
+])
+def test_gemm_swiglu_matches_oracle(M, N, K):
+    # silu(A Wg^T) * (A Wu^T) from the dual product: the oracle's two products and its silu
+    print("gemm swiglu", M, N, K, flush=True)
+    rng = np.random.default_rng(M + 3 * N + K)
+    a, wg = wl.gemm_operands(rng, M, K, N)
+    _, wu = wl.gemm_operands(rng, M, K, N)
+    wg, wu = wg * np.float32(40.0), wu * np.float32(40.0)     # gate values of order 1: the silu's curve matters
+    A, Wg, Wu = _to_dev(a, torch.bfloat16), _to_dev(wg, torch.bfloat16), _to_dev(wu, torch.bfloat16)
+    C = rov.gemm_swiglu(A, Wg, Wu)
+    torch.cuda.synchronize()
+    g = OD.gemm(_f64(A), _f64(Wg), transB=True)
+    u = OD.gemm(_f64(A), _f64(Wu), transB=True)
+    ref = OD.silu(g) * u
+    err = _rel_err(_f64(C), ref)
+    assert err <= BF16_TOL and err <= BF16_EXPECTED, err
+    # gate and up are not interchangeable
+    assert _rel_err(_f64(rov.gemm_swiglu(A, Wu, Wg)), ref) > 0.1
+
+
 def test_gemm_tile_width_knob_rejects_other_values():
     prev = rov.set_gemm_tile_cols(0)
     for bad in (-32, 64, 96, 130, 288):

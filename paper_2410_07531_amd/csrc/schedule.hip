@@ -134,7 +134,7 @@ int hybrid_rows(const rov_block_cfg* c, int B, int S) {
 size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 struct BlockLayout {
-    size_t h, qkv, att, x2, g, u, total;
+    size_t h, qkv, att, x2, u, total;
 };
 
 bool block_layout(const rov_block_cfg* c, int B, int S, BlockLayout* L) {
@@ -152,7 +152,6 @@ bool block_layout(const rov_block_cfg* c, int B, int S, BlockLayout* L) {
     L->qkv = take(T * (size_t)(c->H + 2 * c->Hkv) * c->d);
     L->att = take(T * (size_t)c->H * c->d);
     L->x2 = take(T * c->hidden);
-    L->g = take(T * c->ffn);
     L->u = take(T * c->ffn);
     L->total = off;
     return true;
@@ -456,7 +455,6 @@ extern "C" int rov_block_forward(const rov_block_weights* w, const void* x, void
     void* qkv = ws + L.qkv;
     void* att = ws + L.att;
     void* x2 = ws + L.x2;
-    void* g = ws + L.g;
     void* u = ws + L.u;
     const int64_t T = (int64_t)B * S;
     if (T > 0x7FFFFFFF) return ROV_ERR_UNSUPPORTED;
@@ -563,7 +561,6 @@ extern "C" int rov_block_forward(const rov_block_weights* w, const void* x, void
     ROV_STEP(traced(ROV_TRACE_GLUE, ms, [&] { return launch_rmsnorm(x2, w->norm2, h, T, hidden, cfg->eps, ms); }));
     // gate and up projections as one product with the SwiGLU in its epilogue: u = silu(h Wg^T) * (h Wu^T),
     // the gate never leaves the accumulators and h is fetched once for both
-    (void)g;
     ROV_STEP(traced(ROV_TRACE_GEMM, ms, [&] {
         return launch_gemm_swiglu(h, w->wg, w->wu, u, (int)T, ffn, hidden, ms);
     }));

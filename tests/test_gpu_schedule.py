@@ -417,7 +417,7 @@ def test_block_workspace_and_argument_errors():
     weights = rov.make_block_weights(wd)
     need = rov.block_workspace_bytes(cfg, B, S, 0)
     T = B * S
-    assert need >= 2 * T * (2 * hidden + (H + 2 * Hkv) * d + H * d + 2 * ffn)
+    assert need >= 2 * T * (2 * hidden + (H + 2 * Hkv) * d + H * d + ffn)     # h, x2, qkv, att, u
     ws = torch.empty(need - 256, dtype=torch.uint8, device="cuda")
     y = torch.full_like(x, 5.0)
     mask = torch.zeros(rov.mask_shape(B, H, S), dtype=torch.int64, device="cuda")

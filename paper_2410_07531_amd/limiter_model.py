@@ -197,7 +197,9 @@ def block(chip: Chip, B: int, S: int, H: int, Hkv: int, d: int, hidden: int, ffn
     T = B * S
     shapes = [(T, (H + 2 * Hkv) * d, hidden), (T, hidden, H * d), (T, ffn, hidden), (T, ffn, hidden), (T, hidden, ffn)]
     gt = [t_gemm(chip, *g)["time"] for g in shapes]
-    glue = 8.0 * T * (3 * hidden + 2 * ffn) / chip.hbm_bytes_per_s          # norms, RoPE and the GEMM epilogues with a side input (residuals, SwiGLU): HBM passes
+    # norms, RoPE and the two residual epilogues: HBM passes over [T, hidden] (gate and up are one
+    # product with the SwiGLU applied in its accumulators: no pass over [T, ffn])
+    glue = 8.0 * T * (3 * hidden) / chip.hbm_bytes_per_s
     r = t_rng(chip, B, H, S, causal=causal)["time"]
     am = t_attention(chip, B, H, S, d, "mask", causal)["time"]
     af = t_attention(chip, B, H, S, d, "fused", causal)["time"]

@@ -7,9 +7,18 @@
  * flash-attention forward consumes the mask (paper Sec. 1, Sec. 6.1).
  *
  * Conventions shared by every entry point
- *  - Return value: ROV_OK (0) or a negative ROV_ERR_* code.  On error nothing is
- *    enqueued and outputs are untouched.  After ROV_ERR_HIP, rov_last_hip_error()
- *    returns the hipError_t value of the failing runtime call.
+ *  - Return value: ROV_OK (0) or a negative ROV_ERR_* code.  Arguments are checked
+ *    for every kernel of a call before the first one is enqueued: on
+ *    ROV_ERR_INVALID, ROV_ERR_UNSUPPORTED and ROV_ERR_WORKSPACE nothing was enqueued
+ *    and outputs are untouched.  ROV_ERR_HIP means a HIP runtime call failed
+ *    (rov_last_hip_error() returns its hipError_t); in an entry point that launches
+ *    several kernels the earlier ones stay enqueued and the outputs are undefined,
+ *    but a side stream that was forked has been joined into the main stream again.
+ *  - Threads: every entry point may be called from several host threads.  The
+ *    schedule entry points (rov_layer_step*, rov_block_forward*) serialise their
+ *    enqueue phase inside the library; the work they enqueue is ordered by the
+ *    streams they are given, as usual.  The process-wide rov_set_* knobs are for
+ *    experiments and are read once per call.
  *  - Every data pointer is a DEVICE pointer owned by the caller, valid until
  *    the work enqueued on `stream` has completed.  The library allocates no
  *    device memory and never synchronises the device: calls are asynchronous
@@ -84,8 +93,8 @@ uint64_t rov_mask_philox_calls(int B, int H, int S);
 int rov_philox_raw(uint64_t seed, uint64_t first_counter, uint64_t ncalls, int rounds,
                    uint32_t *out, void *stream);
 
-/* Stand-alone RNG kernel (paper Sec. 6.1: "stores bits representing random
- * numbers in HBM for later use by the Attention kernel").
+/* Stand-alone RNG kernel (paper Sec. 6.1, the second dropout scenario: the random
+ * bits go to HBM and the attention kernel reads them later).
  * Mask words are taken in groups of four (g = w / 4, r = w % 4).  Lane l of
  * group g makes Philox-4x32-10 call number offset + 64*g + l; output word r of
  * that call, x, decides bit l of mask word 4*g + r: keep iff x < Tp with

@@ -655,8 +655,10 @@ int launch_bf16(const AttnParams& prm, int mode, hipStream_t stream) {
             default: return ROV_ERR_INVALID;
         }
     }
-    ROV_HIP_TRY(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                    lds_bytes));
+    {
+        const int rc = set_max_dynamic_lds((const void*)kern, lds_bytes);
+        if (rc != ROV_OK) return rc;
+    }
     hipLaunchKernelGGL(kern, grid, block, lds_bytes, stream, prm2);
     ROV_LAUNCH_CHECK();
     return ROV_OK;
@@ -685,10 +687,11 @@ int launch_attention(const void* Q, const void* K, const void* V, void* O, int B
                                  offset, 0, S, stream, rounds, bits);
 }
 
-int launch_attention_rows(const void* Q, const void* K, const void* V, void* O, int B, int H, int Hkv,
-                          int S, int d, const int64_t strides[12], int dtype, int causal, float p,
-                          const uint64_t* mask, bool mask_is_rows, uint64_t seed, uint64_t offset,
-                          int q_begin, int q_rows, hipStream_t stream, int rounds, int bits) {
+// Everything launch_attention_rows refuses, without launching: the schedules call this before
+// they enqueue the first kernel of a sequence.
+int check_attention_rows(const void* Q, const void* K, const void* V, const void* O, int B, int H, int Hkv,
+                         int S, int d, const int64_t strides[12], int dtype, float p, const uint64_t* mask,
+                         int q_begin, int q_rows, int rounds, int bits) {
     if (rounds != 10 && rounds != 7 && rounds != 5 && rounds != 3) return ROV_ERR_INVALID;
     if (bits != 32 && bits != 16 && bits != 8) return ROV_ERR_INVALID;
     if (bits != 32 && rounds != 10) return ROV_ERR_UNSUPPORTED;
@@ -702,6 +705,23 @@ int launch_attention_rows(const void* Q, const void* K, const void* V, void* O, 
     if (B > 65535 || H > 65535) return ROV_ERR_UNSUPPORTED;
     if (d > 256) return ROV_ERR_UNSUPPORTED;
     if (mask != nullptr && !aligned(mask, 8)) return ROV_ERR_INVALID;
+    // workgroups of the matrix-core kernel (256 query rows each) fit the grid's 31 bits
+    const long long q_end = (long long)q_begin + q_rows < S ? (long long)q_begin + q_rows : S;
+    if (((q_end - q_begin + 255) / 256) * (long long)H * B > 0x7FFFFFFFLL) return ROV_ERR_UNSUPPORTED;
+    return ROV_OK;
+}
+
+int launch_attention_rows(const void* Q, const void* K, const void* V, void* O, int B, int H, int Hkv,
+                          int S, int d, const int64_t strides[12], int dtype, int causal, float p,
+                          const uint64_t* mask, bool mask_is_rows, uint64_t seed, uint64_t offset,
+                          int q_begin, int q_rows, hipStream_t stream, int rounds, int bits) {
+    {
+        const int rc = check_attention_rows(Q, K, V, O, B, H, Hkv, S, d, strides, dtype, p, mask, q_begin, q_rows,
+                                            rounds, bits);
+        if (rc != ROV_OK) return rc;
+    }
+    uint32_t tm1 = 0xFFFFFFFFu;
+    (void)keep_threshold_minus_1(p, &tm1);
 
     AttnParams prm;
     prm.Q = Q; prm.K = K; prm.V = V; prm.O = O; prm.mask = mask;

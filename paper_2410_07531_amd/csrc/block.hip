@@ -1,7 +1,7 @@
-// Row-wise glue of the transformer block (paper Fig. 2: the LayerNorm and
-// element-wise layers "require minimal runtime"; here RMSNorm, rotary embedding
-// and the SwiGLU product of a Llama-style block).  All bf16 in / bf16 out with
-// fp32 arithmetic, 16-byte vector accesses, one pass over the data each.
+// Row-wise glue of the transformer block (paper Fig. 2 / Sec. 3.2: the normalisation layers
+// between the GEMMs, which the paper's analysis leaves out as cheap; here RMSNorm and the rotary
+// embedding of a Llama-style block; the SwiGLU product lives in the GEMM epilogue).  All bf16
+// in / bf16 out with fp32 arithmetic, 16-byte vector accesses, one pass over the data each.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 

@@ -3,6 +3,7 @@
 
 #include <atomic>
 #include <mutex>
+#include <utility>
 #include <vector>
 
 #include "rov_internal.h"
@@ -17,6 +18,21 @@ std::atomic<int> g_cu_count{0};
 int record_hip_error(hipError_t e) {
     t_last_hip_error = (int)e;
     return ROV_ERR_HIP;
+}
+
+// hipFuncAttributeMaxDynamicSharedMemorySize is a property of (device, kernel): set it the first
+// time a kernel is launched on a device and never again (the launch paths call this every time).
+int set_max_dynamic_lds(const void* kern, int bytes) {
+    static std::mutex mu;
+    static std::vector<std::pair<int, const void*>> done;
+    int dev = 0;
+    ROV_HIP_TRY(hipGetDevice(&dev));
+    std::lock_guard<std::mutex> lock(mu);
+    for (const auto& d : done)
+        if (d.first == dev && d.second == kern) return ROV_OK;
+    ROV_HIP_TRY(hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, bytes));
+    done.emplace_back(dev, kern);
+    return ROV_OK;
 }
 
 int device_cu_count() {

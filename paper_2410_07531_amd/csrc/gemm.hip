@@ -629,13 +629,22 @@ __global__ __launch_bounds__(512, 1) void gemm_rng_kernel(const char* __restrict
 
 }  // namespace
 
-int launch_gemm_swiglu(const void* A, const void* Wg, const void* Wu, void* C, int M, int N, int K,
-                       hipStream_t stream) {
+int check_gemm_swiglu(const void* A, const void* Wg, const void* Wu, const void* C, int M, int N, int K) {
     if (A == nullptr || Wg == nullptr || Wu == nullptr || C == nullptr || M <= 0 || N <= 0 || K <= 0)
         return ROV_ERR_INVALID;
     if (!aligned(A, 16) || !aligned(Wg, 16) || !aligned(Wu, 16) || !aligned(C, 16)) return ROV_ERR_INVALID;
     if (((size_t)K * 2) % kRowBytes != 0 || (N % 4) != 0) return ROV_ERR_UNSUPPORTED;
     if ((unsigned long long)BM * (unsigned long long)K * 2ull > 0xFFFFFFFFull) return ROV_ERR_UNSUPPORTED;
+    if ((long long)((M + BM - 1) / BM) * ((N + 63) / 64) > 0x7FFFFFFFLL) return ROV_ERR_UNSUPPORTED;
+    return ROV_OK;
+}
+
+int launch_gemm_swiglu(const void* A, const void* Wg, const void* Wu, void* C, int M, int N, int K,
+                       hipStream_t stream) {
+    {
+        const int rc = check_gemm_swiglu(A, Wg, Wu, C, M, N, K);
+        if (rc != ROV_OK) return rc;
+    }
     // 128 or 64 output columns per tile (8 or 4 weight blocks per wave, half gate, half up): the
     // same rounds x (blocks + 1) rule as for the plain product
     const long long tiles_m = (M + BM - 1) / BM, ncu = device_cu_count();
@@ -645,10 +654,9 @@ int launch_gemm_swiglu(const void* A, const void* Wg, const void* Wu, void* C, i
     if (T > 0x7FFFFFFFLL) return ROV_ERR_UNSUPPORTED;
     typedef void (*kern_t)(const char*, const char*, const char*, uint16_t*, int, int, int, int, int);
     const kern_t kern = wide ? (kern_t)gemm_swiglu_kernel<8> : (kern_t)gemm_swiglu_kernel<4>;
-    static bool attr_set[2] = {};
-    if (!attr_set[wide]) {
-        ROV_HIP_TRY(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes));
-        attr_set[wide] = true;
+    {
+        const int rc = set_max_dynamic_lds((const void*)kern, kLdsBytes);
+        if (rc != ROV_OK) return rc;
     }
     hipLaunchKernelGGL(kern, dim3((unsigned)T), dim3(256), kLdsBytes, stream, (const char*)A, (const char*)Wg,
                        (const char*)Wu, (uint16_t*)C, M, N, K, (int)tiles_m, (int)(T / tiles_m));
@@ -656,8 +664,8 @@ int launch_gemm_swiglu(const void* A, const void* Wg, const void* Wu, void* C, i
     return ROV_OK;
 }
 
-int launch_gemm_rng(const void* A, const void* Bm, void* C, int M, int N, int K, uint64_t seed, uint64_t offset,
-                    int B, int H, int S, float p, uint64_t* mask, int qslot, hipStream_t stream) {
+int check_gemm_rng(const void* A, const void* Bm, const void* C, int M, int N, int K, int B, int H, int S, float p,
+                   const uint64_t* mask) {
     if (A == nullptr || Bm == nullptr || C == nullptr || mask == nullptr || M <= 0 || N <= 0 || K <= 0 ||
         B <= 0 || H <= 0 || S <= 0)
         return ROV_ERR_INVALID;
@@ -669,6 +677,19 @@ int launch_gemm_rng(const void* A, const void* Bm, void* C, int M, int N, int K,
     const uint64_t Tt = (uint64_t)S / 32u;
     const long double wd = (long double)B * H * Tt * Tt * 16.0L;
     if (wd > 1099511627776.0L) return ROV_ERR_UNSUPPORTED;
+    if ((long long)((M + BM - 1) / BM) * ((N + 127) / 128) > 0x7FFFFFFFLL) return ROV_ERR_UNSUPPORTED;
+    return ROV_OK;
+}
+
+int launch_gemm_rng(const void* A, const void* Bm, void* C, int M, int N, int K, uint64_t seed, uint64_t offset,
+                    int B, int H, int S, float p, uint64_t* mask, int qslot, hipStream_t stream) {
+    {
+        const int rc0 = check_gemm_rng(A, Bm, C, M, N, K, B, H, S, p, mask);
+        if (rc0 != ROV_OK) return rc0;
+    }
+    uint32_t tm1;
+    (void)keep_threshold_minus_1(p, &tm1);
+    const uint64_t Tt = (uint64_t)S / 32u;
     const uint64_t words = (uint64_t)B * (uint64_t)H * Tt * Tt * 16u, nchunks = (words + 63u) / 64u;
     const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + 127) / 128;
     const long long T = (long long)tiles_m * tiles_n;
@@ -679,12 +700,8 @@ int launch_gemm_rng(const void* A, const void* Bm, void* C, int M, int N, int K,
     uint64_t qper = 0;
     uint32_t qbatch = 1;
     mask_queue_geometry(nchunks, &qper, &qbatch);
-    static bool attr_set = false;
-    if (!attr_set) {
-        ROV_HIP_TRY(hipFuncSetAttribute((const void*)gemm_rng_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                        kLdsBytes));
-        attr_set = true;
-    }
+    rc = set_max_dynamic_lds((const void*)gemm_rng_kernel, kLdsBytes);
+    if (rc != ROV_OK) return rc;
     hipLaunchKernelGGL(gemm_rng_kernel, dim3((unsigned)T), dim3(512), kLdsBytes, stream, (const char*)A,
                        (const char*)Bm, (uint16_t*)C, M, N, K, tiles_m, tiles_n, mask, words, nchunks, offset,
                        (uint32_t)seed, (uint32_t)(seed >> 32), tm1, (QueueCounter*)q, qper);
@@ -720,14 +737,35 @@ int launch_gemm_residual(const void* A, const void* Bm, void* C, const void* R, 
     return launch_gemm_epilogue(A, Bm, C, R, EPI_ADD, M, N, K, dtype, transB, scaleA, scaleB, stream);
 }
 
-int launch_gemm_epilogue(const void* A, const void* Bm, void* C, const void* R, int epi, int M, int N, int K,
-                         int dtype, int transB, float scaleA, float scaleB, hipStream_t stream) {
+// Everything launch_gemm_epilogue refuses, without launching: the schedules call this for every
+// product of a sequence before they enqueue the first kernel.
+int check_gemm(const void* A, const void* Bm, const void* C, const void* R, int epi, int M, int N, int K,
+               int dtype, int transB) {
     if (epi != EPI_ADD && epi != EPI_SILU_MUL) return ROV_ERR_INVALID;
     if (R != nullptr && !aligned(R, 8)) return ROV_ERR_INVALID;
     if (A == nullptr || Bm == nullptr || C == nullptr || M <= 0 || N <= 0 || K <= 0)
         return ROV_ERR_INVALID;
     if (!aligned(A, 16) || !aligned(Bm, 16) || !aligned(C, 16)) return ROV_ERR_INVALID;
     if (dtype != ROV_F32 && dtype != ROV_BF16 && dtype != ROV_FP8_E4M3) return ROV_ERR_INVALID;
+    const int esz = dtype == ROV_BF16 ? 2 : 1;
+    if (dtype != ROV_F32 && transB != 0 && ((size_t)K * esz) % kRowBytes == 0 && (N % 4) == 0) {
+        if ((unsigned long long)BM * (unsigned long long)K * (unsigned long long)esz > 0xFFFFFFFFull)
+            return ROV_ERR_UNSUPPORTED;
+        // (tile count of the narrowest tile: an upper bound for every width)
+        if ((long long)((M + BM - 1) / BM) * ((N + 127) / 128) > 0x7FFFFFFFLL) return ROV_ERR_UNSUPPORTED;
+        return ROV_OK;
+    }
+    if (R != nullptr) return ROV_ERR_UNSUPPORTED;   // the side-input epilogues exist on the MFMA path only
+    if ((unsigned)((M + 63) / 64) > 65535u) return ROV_ERR_UNSUPPORTED;
+    return ROV_OK;
+}
+
+int launch_gemm_epilogue(const void* A, const void* Bm, void* C, const void* R, int epi, int M, int N, int K,
+                         int dtype, int transB, float scaleA, float scaleB, hipStream_t stream) {
+    {
+        const int rc = check_gemm(A, Bm, C, R, epi, M, N, K, dtype, transB);
+        if (rc != ROV_OK) return rc;
+    }
     const float alpha = scaleA * scaleB;
     const bool tb = transB != 0;
     const int esz = dtype == ROV_BF16 ? 2 : 1;
@@ -748,11 +786,9 @@ int launch_gemm_epilogue(const void* A, const void* Bm, void* C, const void* R, 
                                          gemm_tn_kernel<8, true>};
         const int ki = nj - 4 + (esz == 2 ? 0 : 5);
         const kern_t kern = kerns[ki];
-        static bool attr_set[10] = {};
-        if (!attr_set[ki]) {
-            ROV_HIP_TRY(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                            kLdsBytes));
-            attr_set[ki] = true;
+        {
+            const int rc = set_max_dynamic_lds((const void*)kern, kLdsBytes);
+            if (rc != ROV_OK) return rc;
         }
         hipLaunchKernelGGL(kern, dim3((unsigned)T), dim3(256), kLdsBytes, stream, (const char*)A,
                            (const char*)Bm, (uint16_t*)C, (const uint16_t*)R, M, N, K, alpha, tiles_m,

@@ -15,6 +15,7 @@
 #include <stdint.h>
 
 #include <atomic>
+#include <mutex>
 
 #include "mask_device.h"
 #include "philox_device.h"
@@ -309,11 +310,16 @@ bool keep_threshold_minus_1(float p, uint32_t* t_minus_1) {
 
 int mask_queue_device_ptr(int slot, void** ptr) {
     if (slot < 0 || slot >= kQueueSlots || ptr == nullptr) return ROV_ERR_INVALID;
-    static std::atomic<QueueCounter*> base{nullptr};
-    QueueCounter* b = base.load();
+    // every device holds its own copy of g_queues at its own address
+    constexpr int kMaxDevices = 64;
+    static std::atomic<QueueCounter*> base[kMaxDevices];
+    int dev = 0;
+    ROV_HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return ROV_ERR_UNSUPPORTED;
+    QueueCounter* b = base[dev].load();
     if (b == nullptr) {
         ROV_HIP_TRY(hipGetSymbolAddress((void**)&b, HIP_SYMBOL(g_queues)));
-        base.store(b);
+        base[dev].store(b);
     }
     *ptr = b + (size_t)slot * kSubQueues;
     return ROV_OK;
@@ -321,25 +327,77 @@ int mask_queue_device_ptr(int slot, void** ptr) {
 
 void mask_queue_geometry(uint64_t nchunks, uint64_t* per, uint32_t* batch) { queue_geometry(nchunks, per, batch); }
 
+// A slot's last user records `done` behind its last launch that touches the slot
+// (mask_queue_release); the next user of the slot makes its stream wait for that event before it
+// resets the counters, so a slot is never reset under a grid that still pops from it, whatever
+// streams or host threads the two calls came from.  Streams under graph capture are left out of
+// the tracking (a captured call neither waits for nor records the event; capture orders its own
+// work, and replays of one graph serialise).
+namespace {
+struct SlotState {
+    hipEvent_t done = nullptr;
+    bool recorded = false;
+};
+SlotState g_slot_state[kQueueSlots];
+std::mutex g_slot_mu;
+
+bool stream_is_capturing(hipStream_t st) {
+    hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(st, &cs) != hipSuccess) {
+        (void)hipGetLastError();
+        return false;
+    }
+    return cs != hipStreamCaptureStatusNone;
+}
+}  // namespace
+
 int mask_queue_acquire(hipStream_t stream, int* slot) {
+    std::lock_guard<std::mutex> lock(g_slot_mu);
     const int s = (int)(g_queue_cursor.fetch_add(1u) % (unsigned)kQueueSlots);
+    SlotState& st = g_slot_state[s];
+    if (st.recorded && !stream_is_capturing(stream)) ROV_HIP_TRY(hipStreamWaitEvent(stream, st.done, 0));
     hipLaunchKernelGGL(queue_reset_kernel, dim3(1), dim3(kSubQueues), 0, stream, s);
     ROV_LAUNCH_CHECK();
     *slot = s;
     return ROV_OK;
 }
 
-int launch_mask(uint64_t seed, uint64_t offset, int B, int H, int S, float p, int rounds,
-                uint64_t* out, hipStream_t stream, int grid_mode, int qslot, bool lower_only) {
-    if (qslot >= kQueueSlots) return ROV_ERR_INVALID;
+int mask_queue_release(int slot, hipStream_t stream) {
+    if (slot < 0 || slot >= kQueueSlots) return ROV_OK;
+    if (stream_is_capturing(stream)) return ROV_OK;
+    std::lock_guard<std::mutex> lock(g_slot_mu);
+    SlotState& st = g_slot_state[slot];
+    if (st.done == nullptr) ROV_HIP_TRY(hipEventCreateWithFlags(&st.done, hipEventDisableTiming));
+    ROV_HIP_TRY(hipEventRecord(st.done, stream));
+    st.recorded = true;
+    return ROV_OK;
+}
+
+// What every mask launch refuses, without launching (rounds: 3, 5, 7, 10; bits: 8, 16, 32).
+int check_mask(int B, int H, int S, float p, int rounds, int bits, const uint64_t* out) {
     if (B <= 0 || H <= 0 || S <= 0 || out == nullptr) return ROV_ERR_INVALID;
     if (!aligned(out, 8)) return ROV_ERR_INVALID;
+    if (rounds != 10 && rounds != 7 && rounds != 5 && rounds != 3) return ROV_ERR_INVALID;
+    if (bits != 32 && bits != 16 && bits != 8) return ROV_ERR_INVALID;
     uint32_t tm1;
     if (!keep_threshold_minus_1(p, &tm1)) return ROV_ERR_INVALID;
     const uint64_t T = ((uint64_t)S + 31u) / 32u;
     // words = B*H*T*T*16; refuse anything that cannot be a real buffer (> 2^40 words)
     const long double wd = (long double)B * H * T * T * 16.0L;
     if (wd > 1099511627776.0L) return ROV_ERR_UNSUPPORTED;
+    return ROV_OK;
+}
+
+int launch_mask(uint64_t seed, uint64_t offset, int B, int H, int S, float p, int rounds,
+                uint64_t* out, hipStream_t stream, int grid_mode, int qslot, bool lower_only) {
+    if (qslot >= kQueueSlots) return ROV_ERR_INVALID;
+    {
+        const int rc = check_mask(B, H, S, p, rounds, 32, out);
+        if (rc != ROV_OK) return rc;
+    }
+    uint32_t tm1;
+    (void)keep_threshold_minus_1(p, &tm1);
+    const uint64_t T = ((uint64_t)S + 31u) / 32u;
     const uint64_t words = (uint64_t)B * (uint64_t)H * T * T * 16u;
     const uint32_t k0 = (uint32_t)seed, k1 = (uint32_t)(seed >> 32);
     switch (rounds) {

@@ -23,6 +23,9 @@ inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_
 // Number of compute units of the current device (cached per process).
 int device_cu_count();
 
+// Raises a kernel's dynamic-LDS limit to `bytes` once per (device, kernel); later calls return at once.
+int set_max_dynamic_lds(const void* kern, int bytes);
+
 // Keep threshold minus one: an element is kept iff x <= t_minus_1 (== x < T,
 // T = floor((1-p)*2^32) in double, T in [256, 2^32]).  Returns false if p is
 // outside [0,1) or NaN.
@@ -36,13 +39,15 @@ void trace_end(int slot, hipStream_t st);
 // Launchers used across translation units (all asynchronous on `stream`).
 // Grid of the RNG kernel: alone on the device; a small persistent grid meant to run beside a
 // GEMM (overlap schedules); or a device-filling persistent grid that helps such a small grid
-// finish, launched where the GEMMs end (the paper's "remaining RNG operations continue at full
-// speed once GEMM completes", Sec. 3.3).  The last two share the mask through a work queue:
+// finish, launched where the GEMMs end (the full-speed tail of the RNG, paper Sec. 3.3).  The last two share the mask through a work queue:
 // qslot >= 0 (from mask_queue_acquire, which resets the slot on the given stream; it must be
 // ordered before both launches) makes the waves pull 64-word chunks from that queue, so each
 // chunk is produced by whichever launch gets to it first.  qslot < 0: static striding.
 enum { MASK_GRID_FULL = 0, MASK_GRID_BESIDE = 1, MASK_GRID_HELPER = 2 };
 int mask_queue_acquire(hipStream_t stream, int* slot);
+// To be called once per acquired slot, with a stream on which every launch that uses the slot is
+// already ordered (the main stream after the join): the slot's next user waits for that point.
+int mask_queue_release(int slot, hipStream_t stream);
 // Device address of a queue slot's counters (for kernels of other translation units that pull
 // chunks from it), and the queue geometry the mask launches use for a mask of nchunks chunks.
 int mask_queue_device_ptr(int slot, void** ptr);
@@ -91,6 +96,18 @@ int launch_gemm_swiglu(const void* A, const void* Wg, const void* Wu, void* C, i
 // the queue for a helper launch of the mask kernel.
 int launch_gemm_rng(const void* A, const void* Bm, void* C, int M, int N, int K, uint64_t seed, uint64_t offset,
                     int B, int H, int S, float p, uint64_t* mask, int qslot, hipStream_t stream);
+
+// Argument checks of the launchers above, without launching anything: a schedule validates every
+// kernel of its sequence with these before it enqueues the first one.
+int check_gemm(const void* A, const void* Bm, const void* C, const void* R, int epi, int M, int N, int K,
+               int dtype, int transB);
+int check_gemm_swiglu(const void* A, const void* Wg, const void* Wu, const void* C, int M, int N, int K);
+int check_attention_rows(const void* Q, const void* K, const void* V, const void* O, int B, int H, int Hkv,
+                         int S, int d, const int64_t strides[12], int dtype, float p, const uint64_t* mask,
+                         int q_begin, int q_rows, int rounds, int bits);
+int check_mask(int B, int H, int S, float p, int rounds, int bits, const uint64_t* out);
+int check_gemm_rng(const void* A, const void* Bm, const void* C, int M, int N, int K, int B, int H, int S, float p,
+                   const uint64_t* mask);
 
 int launch_rmsnorm(const void* x, const void* weight, void* y, int64_t rows, int n, float eps,
                    hipStream_t stream);

@@ -7,9 +7,13 @@
 //               stream; attention(mask) on the main stream after both.
 //
 // Streams and events only: every kernel is launched by the launchers of the
-// other translation units.  Two events (fork, join) per process are reused by
-// every call; a stream-wait captures the event's state at the time of the call,
-// so re-recording them for the next call is safe.
+// other translation units.  Host side: a call first validates every kernel of
+// its sequence without launching, then enqueues under one process-wide lock, so
+// that the fork / join events (one set per process; a stream-wait captures the
+// event's state at the time of the call, so re-recording them for the next call
+// is safe) are never re-recorded by another host thread between a call's record
+// and its wait.  If a launch fails after the side stream was forked, the side
+// stream is still joined into the main stream before the call returns.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -27,10 +31,13 @@ struct Events {
     bool ok = false;
 };
 
+// Serialises the enqueue phase of the schedule entry points (host side only; the work itself is
+// asynchronous).  Held from the first event record of a call to its last stream wait.
+std::mutex g_sched_mu;
+
+// Call with g_sched_mu held.
 int get_events(Events** out) {
     static Events ev;
-    static std::mutex mu;
-    std::lock_guard<std::mutex> lock(mu);
     if (!ev.ok) {
         ROV_HIP_TRY(hipEventCreateWithFlags(&ev.fork, hipEventDisableTiming));
         ROV_HIP_TRY(hipEventCreateWithFlags(&ev.join, hipEventDisableTiming));
@@ -43,6 +50,36 @@ int get_events(Events** out) {
     *out = &ev;
     return ROV_OK;
 }
+
+// The side stream's part of one call.  fork(): the side stream waits for what the main stream has
+// queued so far.  mark(): the point of the side stream the main stream will wait for.  join(): the
+// main stream waits for that point.  A call that returns early between fork() and join() (a
+// launch failed) still joins: the destructor marks the side stream's end and makes the main
+// stream wait for it, so nothing the side stream was given runs unordered against the caller's
+// later work on the main stream.
+struct SideStream {
+    Events* ev = nullptr;
+    hipStream_t ms = nullptr, ss = nullptr;
+    bool open = false;
+    int fork() {
+        ROV_HIP_TRY(hipEventRecord(ev->fork, ms));
+        ROV_HIP_TRY(hipStreamWaitEvent(ss, ev->fork, 0));
+        open = true;
+        return ROV_OK;
+    }
+    int mark() {
+        ROV_HIP_TRY(hipEventRecord(ev->join, ss));
+        return ROV_OK;
+    }
+    int join() {
+        ROV_HIP_TRY(hipStreamWaitEvent(ms, ev->join, 0));
+        open = false;
+        return ROV_OK;
+    }
+    ~SideStream() {
+        if (open && hipEventRecord(ev->join, ss) == hipSuccess) (void)hipStreamWaitEvent(ms, ev->join, 0);
+    }
+};
 
 bool valid_schedule(int s) {
     return s == ROV_SCHED_SEQUENTIAL || s == ROV_SCHED_FUSED || s == ROV_SCHED_OVERLAP;
@@ -184,12 +221,29 @@ int layer_step_impl(int schedule, const rov_gemm_desc* gemms, int n_gemms, const
     if (need_mask && (mask == nullptr || !aligned(mask, 8))) return ROV_ERR_INVALID;
     if (schedule == ROV_SCHED_OVERLAP && main_stream == side_stream) return ROV_ERR_INVALID;
     hipStream_t ms = (hipStream_t)main_stream, ss = (hipStream_t)side_stream;
-
-    Events* ev = nullptr;
-    int qslot = -1;
-    if (schedule == ROV_SCHED_OVERLAP && need_mask) {
-        int rc = get_events(&ev);
+    // every kernel of the sequence is checked before the first one is enqueued
+    for (int i = 0; i < n_gemms; ++i) {
+        const rov_gemm_desc& g = gemms[i];
+        const int rc = check_gemm(g.A, g.Bm, g.C, nullptr, EPI_ADD, g.M, g.N, g.K, g.dtype, g.transB);
         if (rc != ROV_OK) return rc;
+    }
+    {
+        int rc = check_attention_rows(attn->Q, attn->K, attn->V, attn->O, attn->B, attn->H, attn->Hkv, attn->S,
+                                      attn->d, attn->strides, attn->dtype, attn->p, need_mask ? mask : nullptr, 0,
+                                      attn->S, rounds, bits);
+        if (rc == ROV_OK && need_mask) rc = check_mask(attn->B, attn->H, attn->S, attn->p, rounds, bits, mask);
+        if (rc != ROV_OK) return rc;
+    }
+
+    std::lock_guard<std::mutex> sched_lock(g_sched_mu);
+    SideStream side;
+    int qslot = -1;
+    const bool overlap = schedule == ROV_SCHED_OVERLAP && need_mask;
+    if (overlap) {
+        int rc = get_events(&side.ev);
+        if (rc != ROV_OK) return rc;
+        side.ms = ms;
+        side.ss = ss;
         double flop = 0.0;
         bool fp32 = false;
         for (int i = 0; i < n_gemms; ++i) {
@@ -203,34 +257,28 @@ int layer_step_impl(int schedule, const rov_gemm_desc* gemms, int n_gemms, const
             if (rc != ROV_OK) return rc;
         }
         // the mask buffer may still be read by work already queued on the main stream
-        ROV_HIP_TRY(hipEventRecord(ev->fork, ms));
-        ROV_HIP_TRY(hipStreamWaitEvent(ss, ev->fork, 0));
+        rc = side.fork();
+        if (rc != ROV_OK) return rc;
     }
-    auto run_gemms = [&](hipStream_t st) {
-        for (int i = 0; i < n_gemms; ++i) {
-            const rov_gemm_desc& g = gemms[i];
-            const int rc = t_gemm(g.A, g.Bm, g.C, nullptr, g.M, g.N, g.K, g.dtype, g.transB, g.scaleA,
-                                  g.scaleB, st);
-            if (rc != ROV_OK) return rc;
-        }
-        return (int)ROV_OK;
-    };
     int rc = ROV_OK;
-    if (schedule == ROV_SCHED_OVERLAP && need_mask) {
+    auto run_gemm = [&](int i) {
+        const rov_gemm_desc& g = gemms[i];
+        return t_gemm(g.A, g.Bm, g.C, nullptr, g.M, g.N, g.K, g.dtype, g.transB, g.scaleA, g.scaleB, ms);
+    };
+    if (overlap) {
         // GEMMs first so that their workgroups claim each compute unit's LDS and most of its
         // registers; the RNG workgroups then fill the space left over (paper Sec. 6.2)
         if (n_gemms > 0) {
-            const rov_gemm_desc& g = gemms[0];
-            rc = t_gemm(g.A, g.Bm, g.C, nullptr, g.M, g.N, g.K, g.dtype, g.transB, g.scaleA, g.scaleB, ms);
+            rc = run_gemm(0);
             if (rc != ROV_OK) return rc;
         }
         rc = t_mask(seed, offset, attn->B, attn->H, attn->S, attn->p, mask, ss, MASK_GRID_BESIDE, qslot,
                     attn->causal != 0, rounds, bits);
         if (rc != ROV_OK) return rc;
-        ROV_HIP_TRY(hipEventRecord(ev->join, ss));
+        rc = side.mark();
+        if (rc != ROV_OK) return rc;
         for (int i = 1; i < n_gemms; ++i) {
-            const rov_gemm_desc& g = gemms[i];
-            rc = t_gemm(g.A, g.Bm, g.C, nullptr, g.M, g.N, g.K, g.dtype, g.transB, g.scaleA, g.scaleB, ms);
+            rc = run_gemm(i);
             if (rc != ROV_OK) return rc;
         }
         // whatever the small grid has not produced when the GEMMs end is finished at full speed
@@ -240,10 +288,15 @@ int layer_step_impl(int schedule, const rov_gemm_desc* gemms, int n_gemms, const
                         attn->causal != 0, rounds, bits);
             if (rc != ROV_OK) return rc;
         }
-        ROV_HIP_TRY(hipStreamWaitEvent(ms, ev->join, 0));
-    } else {
-        rc = run_gemms(ms);
+        rc = side.join();
         if (rc != ROV_OK) return rc;
+        rc = mask_queue_release(qslot, ms);
+        if (rc != ROV_OK) return rc;
+    } else {
+        for (int i = 0; i < n_gemms; ++i) {
+            rc = run_gemm(i);
+            if (rc != ROV_OK) return rc;
+        }
         if (need_mask) {
             rc = t_mask(seed, offset, attn->B, attn->H, attn->S, attn->p, mask, ms, MASK_GRID_FULL, -1,
                         attn->causal != 0, rounds, bits);
@@ -269,17 +322,21 @@ extern "C" int rov_gemm_rng_fused(const void* A, const void* Bm, void* C, int M,
                                   uint64_t offset, int B, int H, int S, float p, uint64_t* mask, void* stream) {
     hipStream_t st = (hipStream_t)stream;
     if (A == nullptr || Bm == nullptr || C == nullptr || mask == nullptr) return ROV_ERR_INVALID;
+    int rc = rov::check_gemm_rng(A, Bm, C, M, N, K, B, H, S, p, mask);   // nothing is enqueued on an argument error
+    if (rc != ROV_OK) return rc;
     int slot = -1;
-    int rc = rov::mask_queue_acquire(st, &slot);
+    rc = rov::mask_queue_acquire(st, &slot);
     if (rc != ROV_OK) return rc;
     rc = rov::traced(ROV_TRACE_GEMM, st, [&] {
         return rov::launch_gemm_rng(A, Bm, C, M, N, K, seed, offset, B, H, S, p, mask, slot, st);
     });
     if (rc != ROV_OK) return rc;
     // what the RNG waves of the GEMM kernel did not get to, at full speed (paper Sec. 3.3)
-    return rov::traced(ROV_TRACE_RNG_HELPER, st, [&] {
+    rc = rov::traced(ROV_TRACE_RNG_HELPER, st, [&] {
         return rov::launch_mask(seed, offset, B, H, S, p, 10, mask, st, rov::MASK_GRID_HELPER, slot, false);
     });
+    if (rc != ROV_OK) return rc;
+    return rov::mask_queue_release(slot, st);
 }
 
 extern "C" int rov_layer_step(int schedule, const rov_gemm_desc* gemms, int n_gemms,
@@ -324,10 +381,27 @@ extern "C" int rov_layer_step_chunked(const rov_gemm_desc* gemms, int n_gemms, c
     const int nchunks = (S + q_chunk_rows - 1) / q_chunk_rows;
     const uint64_t slot_words = rov_mask_words_rows(B, H, S, 0, q_chunk_rows);
     uint64_t* slot[2] = {mask_ring, mask_ring + slot_words};
+    // every kernel of the sequence is checked before the first one is enqueued (a chunk's mask and
+    // attention launches take the same arguments but for the row range, which is valid by construction)
+    for (int i = 0; i < n_gemms; ++i) {
+        const rov_gemm_desc& g = gemms[i];
+        const int rc = check_gemm(g.A, g.Bm, g.C, nullptr, EPI_ADD, g.M, g.N, g.K, g.dtype, g.transB);
+        if (rc != ROV_OK) return rc;
+    }
+    {
+        int rc = check_attention_rows(attn->Q, attn->K, attn->V, attn->O, B, H, attn->Hkv, S, attn->d, attn->strides,
+                                      attn->dtype, attn->p, mask_ring, 0, q_chunk_rows, 10, 32);
+        if (rc == ROV_OK) rc = check_mask(B, H, S, attn->p, 10, 32, mask_ring);
+        if (rc != ROV_OK) return rc;
+    }
 
-    Events* ev = nullptr;
-    int rc = get_events(&ev);
+    std::lock_guard<std::mutex> sched_lock(g_sched_mu);
+    SideStream side;
+    int rc = get_events(&side.ev);
     if (rc != ROV_OK) return rc;
+    side.ms = ms;
+    side.ss = ss;
+    Events* ev = side.ev;
     int qslot[2] = {-1, -1};   // work queue of the chunk that currently owns each ring slot
     auto rng_chunk = [&](int c) {   // small grid on the side stream
         rc = traced(ROV_TRACE_RNG, ss, [&] {
@@ -360,8 +434,8 @@ extern "C" int rov_layer_step_chunked(const rov_gemm_desc* gemms, int n_gemms, c
             }
     }
     // the ring may still be read by work queued earlier on the main stream
-    ROV_HIP_TRY(hipEventRecord(ev->fork, ms));
-    ROV_HIP_TRY(hipStreamWaitEvent(ss, ev->fork, 0));
+    rc = side.fork();
+    if (rc != ROV_OK) return rc;
     int next_gemm = 0;
     if (n_gemms > 0) {   // first GEMM first, so that its workgroups claim the compute units
         const rov_gemm_desc& g = gemms[0];
@@ -383,6 +457,10 @@ extern "C" int rov_layer_step_chunked(const rov_gemm_desc* gemms, int n_gemms, c
         rc = rng_help(c);
         if (rc != ROV_OK) return rc;
         ROV_HIP_TRY(hipStreamWaitEvent(ms, ev->rng_done[c & 1], 0));
+        // both launches that pop from the chunk's queue are now ordered on the main stream
+        rc = mask_queue_release(qslot[c & 1], ms);
+        if (rc != ROV_OK) return rc;
+        qslot[c & 1] = -1;
         rc = traced(ROV_TRACE_ATTENTION, ms, [&] {
             return launch_attention_rows(attn->Q, attn->K, attn->V, attn->O, B, H, attn->Hkv, S, attn->d,
                                          attn->strides, attn->dtype, attn->causal, attn->p, slot[c & 1], true,
@@ -398,6 +476,7 @@ extern "C" int rov_layer_step_chunked(const rov_gemm_desc* gemms, int n_gemms, c
             if (rc != ROV_OK) return rc;
         }
     }
+    side.open = false;   // every chunk's side-stream launch has been waited for by its attention
     return ROV_OK;
 }
 
@@ -416,12 +495,13 @@ extern "C" int rov_block_hybrid_mask_rows(const rov_block_cfg* cfg, int B, int S
 
 extern "C" int rov_set_block_hybrid_mask_rows(int rows) { return rov::g_hybrid_rows.exchange(rows); }
 
-extern "C" int rov_block_forward(const rov_block_weights* w, const void* x, void* y, int B, int S,
-                                 const rov_block_cfg* cfg, int schedule, uint64_t seed,
-                                 uint64_t offset, int mask_ready, uint64_t* mask,
-                                 uint64_t* next_mask, void* workspace, size_t workspace_bytes,
-                                 void* main_stream, void* side_stream) {
-    using namespace rov;
+namespace rov {
+namespace {
+int block_forward_impl(const rov_block_weights* w, const void* x, void* y, int B, int S,
+                       const rov_block_cfg* cfg, int schedule, uint64_t seed,
+                       uint64_t offset, int mask_ready, uint64_t* mask,
+                       uint64_t* next_mask, void* workspace, size_t workspace_bytes,
+                       void* main_stream, void* side_stream) {
     BlockLayout L;
     if (w == nullptr || x == nullptr || y == nullptr ||
         !(valid_schedule(schedule) || schedule == ROV_SCHED_HYBRID) || !block_layout(cfg, B, S, &L))
@@ -460,17 +540,36 @@ extern "C" int rov_block_forward(const rov_block_weights* w, const void* x, void
     if (T > 0x7FFFFFFF) return ROV_ERR_UNSUPPORTED;
     const int H = cfg->H, Hkv = cfg->Hkv, d = cfg->d, hidden = cfg->hidden, ffn = cfg->ffn;
     const int qkv_n = (H + 2 * Hkv) * d;
-    Events* ev = nullptr;
+    const uint16_t* qp = (const uint16_t*)qkv;
+    const int64_t strides[12] = {
+        (int64_t)S * qkv_n, qkv_n, d,      // Q
+        (int64_t)S * qkv_n, qkv_n, d,      // K
+        (int64_t)S * qkv_n, qkv_n, d,      // V
+        (int64_t)S * H * d, (int64_t)H * d, d};   // O
     int rc = ROV_OK;
-    if (overlap) {
-        rc = get_events(&ev);
-        if (rc != ROV_OK) return rc;
-    }
+    // every kernel of the block is checked before the first one is enqueued
 #define ROV_STEP(expr)            \
     do {                          \
         rc = (expr);              \
         if (rc != ROV_OK) return rc; \
     } while (0)
+    if ((hidden % 8) != 0 || (d % 8) != 0) return ROV_ERR_UNSUPPORTED;   // RMSNorm / RoPE vector width
+    ROV_STEP(check_gemm(h, w->wqkv, qkv, nullptr, EPI_ADD, (int)T, qkv_n, hidden, ROV_BF16, 1));
+    ROV_STEP(check_gemm(att, w->wo, x2, x, EPI_ADD, (int)T, hidden, H * d, ROV_BF16, 1));
+    ROV_STEP(check_gemm_swiglu(h, w->wg, w->wu, u, (int)T, ffn, hidden));
+    ROV_STEP(check_gemm(u, w->wd, y, x2, EPI_ADD, (int)T, hidden, ffn, ROV_BF16, 1));
+    ROV_STEP(check_attention_rows(qp, qp + (int64_t)H * d, qp + (int64_t)(H + Hkv) * d, att, B, H, Hkv, S, d, strides,
+                                  ROV_BF16, cfg->p, use_mask ? mask : nullptr, 0, S, 10, 32));
+    if (use_mask) ROV_STEP(check_mask(B, H, S, cfg->p, 10, 32, mask));
+    if (next_mask != nullptr) ROV_STEP(check_mask(B, H, S, cfg->p, 10, 32, next_mask));
+
+    std::lock_guard<std::mutex> sched_lock(g_sched_mu);
+    SideStream side;
+    if (overlap) {
+        ROV_STEP(get_events(&side.ev));
+        side.ms = ms;
+        side.ss = ss;
+    }
 
     // this block's own mask, if nobody produced it yet
     int qslot = -1;
@@ -479,8 +578,7 @@ extern "C" int rov_block_forward(const rov_block_weights* w, const void* x, void
         if (!rng_fits_beside(gemm_flop((int)((int64_t)B * S), (cfg->H + 2 * cfg->Hkv) * cfg->d, cfg->hidden), false,
                              mask_calls))
             ROV_STEP(mask_queue_acquire(ms, &qslot));
-        ROV_HIP_TRY(hipEventRecord(ev->fork, ms));
-        ROV_HIP_TRY(hipStreamWaitEvent(ss, ev->fork, 0));
+        ROV_STEP(side.fork());
     }
     ROV_STEP(traced(ROV_TRACE_GLUE, ms, [&] { return launch_rmsnorm(x, w->norm1, h, T, hidden, cfg->eps, ms); }));
     ROV_STEP(t_gemm(h, w->wqkv, qkv, nullptr, (int)T, qkv_n, hidden, ROV_BF16, 1, 1.0f, 1.0f, ms));
@@ -489,14 +587,14 @@ extern "C" int rov_block_forward(const rov_block_weights* w, const void* x, void
             ROV_STEP(traced(ROV_TRACE_RNG, ss, [&] {
                 return launch_mask_rows(seed, offset, B, H, S, cfg->p, 0, R, mask, ss, MASK_GRID_BESIDE, qslot);
             }));
-            ROV_HIP_TRY(hipEventRecord(ev->join, ss));
+            ROV_STEP(side.mark());
             if (qslot >= 0)
                 ROV_STEP(traced(ROV_TRACE_RNG_HELPER, ms, [&] {
                     return launch_mask_rows(seed, offset, B, H, S, cfg->p, 0, R, mask, ms, MASK_GRID_HELPER, qslot);
                 }));
         } else if (overlap) {
             ROV_STEP(t_mask(seed, offset, B, H, S, cfg->p, mask, ss, MASK_GRID_BESIDE, qslot, cfg->causal != 0));
-            ROV_HIP_TRY(hipEventRecord(ev->join, ss));
+            ROV_STEP(side.mark());
             if (qslot >= 0)
                 ROV_STEP(t_mask(seed, offset, B, H, S, cfg->p, mask, ms, MASK_GRID_HELPER, qslot, cfg->causal != 0));
         } else {
@@ -506,14 +604,11 @@ extern "C" int rov_block_forward(const rov_block_weights* w, const void* x, void
     ROV_STEP(traced(ROV_TRACE_GLUE, ms, [&] {   // q heads then k heads
         return launch_rope(qkv, T, qkv_n, S, H + Hkv, d, cfg->rope_theta, ms);
     }));
-    if (use_mask && !mask_ready && overlap) ROV_HIP_TRY(hipStreamWaitEvent(ms, ev->join, 0));
+    if (use_mask && !mask_ready && overlap) {
+        ROV_STEP(side.join());
+        ROV_STEP(mask_queue_release(qslot, ms));
+    }
 
-    const uint16_t* qp = (const uint16_t*)qkv;
-    const int64_t strides[12] = {
-        (int64_t)S * qkv_n, qkv_n, d,      // Q
-        (int64_t)S * qkv_n, qkv_n, d,      // K
-        (int64_t)S * qkv_n, qkv_n, d,      // V
-        (int64_t)S * H * d, (int64_t)H * d, d};   // O
     if (hybrid && R < S) {
         if (R > 0)
             ROV_STEP(traced(ROV_TRACE_ATTENTION, ms, [&] {
@@ -543,8 +638,7 @@ extern "C" int rov_block_forward(const rov_block_weights* w, const void* x, void
                             gemm_flop((int)T, hidden, ffn);
         // (hybrid with R < S: the rows were chosen to fit, no queue and no helper launch)
         if (R == S && !rng_fits_beside(rest, false, mask_calls)) ROV_STEP(mask_queue_acquire(ms, &qslot_next));
-        ROV_HIP_TRY(hipEventRecord(ev->fork, ms));
-        ROV_HIP_TRY(hipStreamWaitEvent(ss, ev->fork, 0));
+        ROV_STEP(side.fork());
     }
     ROV_STEP(t_gemm(att, w->wo, x2, x, (int)T, hidden, H * d, ROV_BF16, 1, 1.0f, 1.0f, ms));
     if (run_ahead) {
@@ -556,7 +650,7 @@ extern "C" int rov_block_forward(const rov_block_weights* w, const void* x, void
         else
             ROV_STEP(t_mask(seed, offset + rov_mask_philox_calls(B, H, S), B, H, S, cfg->p, next_mask, ss,
                             MASK_GRID_BESIDE, qslot_next, cfg->causal != 0));
-        ROV_HIP_TRY(hipEventRecord(ev->join, ss));
+        ROV_STEP(side.mark());
     }
     ROV_STEP(traced(ROV_TRACE_GLUE, ms, [&] { return launch_rmsnorm(x2, w->norm2, h, T, hidden, cfg->eps, ms); }));
     // gate and up projections as one product with the SwiGLU in its epilogue: u = silu(h Wg^T) * (h Wu^T),
@@ -570,8 +664,21 @@ extern "C" int rov_block_forward(const rov_block_weights* w, const void* x, void
         if (qslot_next >= 0)
             ROV_STEP(t_mask(seed, offset + rov_mask_philox_calls(B, H, S), B, H, S, cfg->p, next_mask, ms,
                             MASK_GRID_HELPER, qslot_next, cfg->causal != 0));
-        ROV_HIP_TRY(hipStreamWaitEvent(ms, ev->join, 0));
+        ROV_STEP(side.join());
+        ROV_STEP(mask_queue_release(qslot_next, ms));
     }
 #undef ROV_STEP
     return ROV_OK;
+}
+
+}  // namespace
+}  // namespace rov
+
+extern "C" int rov_block_forward(const rov_block_weights* w, const void* x, void* y, int B, int S,
+                                 const rov_block_cfg* cfg, int schedule, uint64_t seed,
+                                 uint64_t offset, int mask_ready, uint64_t* mask,
+                                 uint64_t* next_mask, void* workspace, size_t workspace_bytes,
+                                 void* main_stream, void* side_stream) {
+    return rov::block_forward_impl(w, x, y, B, S, cfg, schedule, seed, offset, mask_ready, mask, next_mask, workspace,
+                                   workspace_bytes, main_stream, side_stream);
 }

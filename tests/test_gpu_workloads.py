@@ -42,25 +42,37 @@ def _check_mask_heads(mask, seed, offset, B, H, S, p, heads, lower_only=False):
             assert np.array_equal(got, exp[0, 0]), (b, h)
 
 
-def _keep_rows(mask, b, h, rows, S):
-    """bool [len(rows), S]: keep bits of the sampled query rows, unpacked from their tile rows."""
+def _oracle_head_words(seed, offset, H, S, p, b, h):
+    """uint64 [T, T, 16]: the oracle's mask words of one (batch, head) of a [B, H, S, S] mask, computed
+    through the offset-splitting property (a head's words are the 1 x 1 x S x S mask whose call
+    numbers start where that head's do).  Nothing here comes from the device."""
+    T = S // 32
+    first = (b * H + h) * T * T * 16
+    return OP.dropout_mask(seed, offset + 64 * (first // 4), 1, 1, S, p)[0, 0]
+
+
+def _keep_rows(words_head, rows, S):
+    """bool [len(rows), S]: keep bits of the sampled query rows, unpacked from the ORACLE's words of
+    that head (uint64 [T, T, 16])."""
     out = np.zeros((len(rows), S), dtype=bool)
     for n, r in enumerate(rows):
-        tile_row = mask[b, h, r // 32].cpu().numpy().view(np.uint64)     # [T, 16]
-        out[n] = OP.unpack_keep_rows(tile_row, S)[r % 32]
+        out[n] = OP.unpack_keep_rows(words_head[r // 32], S)[r % 32]
     return out
 
 
-def _attention_rows_ref(Q, K, V, mask, p, b, h, rows, causal):
-    """Oracle attention for sampled query rows of one (batch, head): uses the full K, V of the head."""
+def _attention_rows_ref(Q, K, V, mask, seed, offset, p, b, h, rows, causal):
+    """Oracle attention for sampled query rows of one (batch, head), on the oracle's own keep bits for
+    that head; the device mask of the head is required to be exactly those words first."""
     H, Hkv = Q.shape[2], K.shape[2]
     hk = h // (H // Hkv)
     S = Q.shape[1]
+    words = _oracle_head_words(seed, offset, H, S, p, b, h)
+    assert np.array_equal(mask[b, h].cpu().numpy().view(np.uint64), words), (b, h)
     q = _f64(Q[b:b + 1, :, h:h + 1, :])
     k = _f64(K[b:b + 1, :, hk:hk + 1, :])
     v = _f64(V[b:b + 1, :, hk:hk + 1, :])
     keep = np.zeros((1, 1, S, S), dtype=bool)
-    keep[0, 0, rows] = _keep_rows(mask, b, h, rows, S)
+    keep[0, 0, rows] = _keep_rows(words, rows, S)
     return OD.attention_dropout(q, k, v, keep, p, causal=causal, rows=rows)[0, :, 0, :]
 
 
@@ -97,7 +109,7 @@ def test_workload3_b2_s4k_layer_step_schedules():
             _check_mask_heads(mask, wl.SEED, wl.OFFSET, B, H, S, p, [(0, 0), (1, 17), (1, 31)])
             rows = wl.sample_rows(S, 8)
             for b, h in [(0, 0), (1, 5), (1, 31)]:
-                ref = _attention_rows_ref(Q, K, V, mask, p, b, h, rows, False)
+                ref = _attention_rows_ref(Q, K, V, mask, wl.SEED, wl.OFFSET, p, b, h, rows, False)
                 got = _f64(O[b, rows, h, :])
                 assert np.max(np.abs(got - ref)) / np.max(np.abs(ref)) <= 2e-2
             srng = np.random.default_rng(3)
@@ -146,7 +158,7 @@ def test_workload4_llama70b_fp8_gemms_and_gqa_attention():
     _check_mask_heads(mask, wl.SEED, wl.OFFSET, B, H, S, p, [(0, 0), (0, 63)])
     rows = wl.sample_rows(S, 6)
     for h in (0, 9, 63):
-        ref = _attention_rows_ref(Q, K, V, mask, p, 0, h, rows, False)
+        ref = _attention_rows_ref(Q, K, V, mask, wl.SEED, wl.OFFSET, p, 0, h, rows, False)
         assert np.max(np.abs(_f64(O[0, rows, h, :]) - ref)) / np.max(np.abs(ref)) <= 2e-2
     Of = rov.attention_fwd_dropout(Q, K, V, p, seed=wl.SEED, offset=wl.OFFSET)
     torch.cuda.synchronize()
@@ -176,6 +188,15 @@ def test_workload5_block_s16k_overlap_sampled_rows():
     m0 = rov.dropout_mask_generate(wl.SEED, wl.OFFSET, B, H, S, p)
     m1 = torch.zeros_like(m0)
     rows = wl.sample_rows(S, 6)
+    # keep bits of the sampled rows: the oracle's own words for every head (the block mixes all
+    # heads into every output element); the device mask the block reads must equal them
+    torch.cuda.synchronize()
+    keep = np.zeros((B, H, S, S), dtype=bool)
+    for h in range(H):
+        words = _oracle_head_words(wl.SEED, wl.OFFSET, H, S, p, 0, h)
+        assert np.array_equal(m0[0, h].cpu().numpy().view(np.uint64), words), h
+        keep[0, h, rows] = _keep_rows(words, rows, S)
+        del words
     for causal in (False, True):
         print("cfg5 block causal", causal, flush=True)
         cfg = rov.make_block_cfg(H, Hkv, d, hidden, ffn, p, causal=causal)
@@ -189,12 +210,8 @@ def test_workload5_block_s16k_overlap_sampled_rows():
         _check_mask_heads(m1, wl.SEED, wl.OFFSET + OP.mask_philox_calls(B, H, S), B, H, S, p, [(0, 0), (0, 31)],
                           lower_only=causal)
         # oracle: full K, V (all tokens), everything else on the sampled rows only
-        keep = np.zeros((B, H, S, S), dtype=bool)
-        for h in range(H):
-            keep[0, h, rows] = _keep_rows(m0, 0, h, rows, S)
         ocfg = dict(H=H, Hkv=Hkv, d=d, eps=1e-5, rope_theta=500000.0, p=p, causal=causal)
         ref = OD.block_forward(_f64(x), {k_: _f64(v_) for k_, v_ in wts.items()}, ocfg, keep, rows=rows)
         got = _f64(y[:, rows])
         err = np.max(np.abs(got - ref)) / np.max(np.abs(ref))
         assert err <= 2e-2, err
-        del keep

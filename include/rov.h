@@ -420,6 +420,26 @@ int rov_block_forward(const rov_block_weights *w, const void *x, void *y, int B,
                       int mask_ready, uint64_t *mask, uint64_t *next_mask,
                       void *workspace, size_t workspace_bytes, void *main_stream, void *side_stream);
 
+/* rov_block_forward for callers that cannot allocate device memory or carry a workspace around:
+ * code running under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
+ * Same arguments, results and errors as rov_block_forward, minus the workspace: the block's
+ * intermediate tensors live in a scratch array that is part of the library's device image
+ * (ROV_BLOCK_STATIC_SCRATCH_BYTES = 64 MiB per GPU the library runs on, held until the process
+ * ends).  The call allocates nothing and frees nothing.  A block that needs more scratch than that
+ * (rov_block_workspace_bytes(cfg, B, S, schedule) > rov_block_static_scratch_bytes(); 64 MiB is
+ * 1024 tokens of a hidden-4096 / ffn-14336 block) is refused with ROV_ERR_WORKSPACE before
+ * anything is enqueued.  Every call on a GPU uses that GPU's one array: two calls whose work
+ * overlaps in time on one GPU (different stream pairs, or two host threads) race on it, so
+ * callers serialise them; back-to-back calls on one main stream are ordered by the stream.
+ * Nothing in the array needs clearing between calls (a block writes every byte before it reads
+ * it). */
+#define ROV_BLOCK_STATIC_SCRATCH_BYTES (64u << 20)
+size_t rov_block_static_scratch_bytes(void);
+int rov_block_forward_static(const rov_block_weights *w, const void *x, void *y, int B, int S,
+                             const rov_block_cfg *cfg, int schedule, uint64_t seed, uint64_t offset,
+                             int mask_ready, uint64_t *mask, uint64_t *next_mask,
+                             void *main_stream, void *side_stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -100,6 +100,9 @@ SIGNATURES = {
     "rov_set_block_hybrid_mask_rows": (_i, [_i]),
     "rov_block_forward": (_i, [ctypes.POINTER(BlockWeights), _p, _p, _i, _i, ctypes.POINTER(BlockCfg),
                                _i, _u64, _u64, _i, _p, _p, _p, ctypes.c_size_t, _p, _p]),
+    "rov_block_static_scratch_bytes": (ctypes.c_size_t, []),
+    "rov_block_forward_static": (_i, [ctypes.POINTER(BlockWeights), _p, _p, _i, _i, ctypes.POINTER(BlockCfg),
+                                      _i, _u64, _u64, _i, _p, _p, _p, _p]),
 }
 
 _lib = None
@@ -426,6 +429,24 @@ def block_forward(weights, x, y, cfg, schedule, seed, offset, mask, workspace, m
                                     seed & (2**64 - 1), offset & (2**64 - 1), int(bool(mask_ready)), mptr, nptr,
                                     ctypes.c_void_p(workspace.data_ptr()), workspace.numel() * workspace.element_size(),
                                     _stream_ptr(main_stream), _stream_ptr(side_stream)), "rov_block_forward")
+    return y
+
+
+def block_static_scratch_bytes():
+    return int(load().rov_block_static_scratch_bytes())
+
+
+def block_forward_static(weights, x, y, cfg, schedule, seed, offset, mask, main_stream, side_stream,
+                         mask_ready=False, next_mask=None):
+    """block_forward on the library's own static scratch (no workspace, nothing allocated)."""
+    B, S, _ = x.shape
+    mptr = ctypes.c_void_p(mask.data_ptr()) if mask is not None else ctypes.c_void_p(0)
+    nptr = ctypes.c_void_p(next_mask.data_ptr()) if next_mask is not None else ctypes.c_void_p(0)
+    _check(load().rov_block_forward_static(ctypes.byref(weights), ctypes.c_void_p(x.data_ptr()),
+                                           ctypes.c_void_p(y.data_ptr()), B, S, ctypes.byref(cfg), int(schedule),
+                                           seed & (2**64 - 1), offset & (2**64 - 1), int(bool(mask_ready)), mptr,
+                                           nptr, _stream_ptr(main_stream), _stream_ptr(side_stream)),
+           "rov_block_forward_static")
     return y
 
 

@@ -671,6 +671,31 @@ int block_forward_impl(const rov_block_weights* w, const void* x, void* y, int B
     return ROV_OK;
 }
 
+// Scratch of rov_block_forward_static: the block's intermediate tensors (normed activations, QKV,
+// attention output, residual stream, SwiGLU output) for callers that cannot bring a workspace.
+// Every byte a block reads from it was written earlier in the same call, so nothing is cleared
+// between calls.  In host code the array's name is only a handle for hipGetSymbolAddress: the
+// device address is looked up once per device and that pointer is what the kernels are given.
+constexpr size_t kStaticScratchBytes = ROV_BLOCK_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+int static_scratch_ptr(void** out) {
+    constexpr int kMaxDevices = 64;
+    static std::mutex mu;
+    static void* ptrs[kMaxDevices] = {};
+    int dev = 0;
+    ROV_HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return ROV_ERR_UNSUPPORTED;
+    std::lock_guard<std::mutex> lock(mu);
+    if (ptrs[dev] == nullptr) {
+        void* p = nullptr;
+        ROV_HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (p == nullptr) return ROV_ERR_HIP;
+        ptrs[dev] = p;
+    }
+    *out = ptrs[dev];
+    return ROV_OK;
+}
 }  // namespace
 }  // namespace rov
 
@@ -681,4 +706,22 @@ extern "C" int rov_block_forward(const rov_block_weights* w, const void* x, void
                                  void* main_stream, void* side_stream) {
     return rov::block_forward_impl(w, x, y, B, S, cfg, schedule, seed, offset, mask_ready, mask, next_mask, workspace,
                                    workspace_bytes, main_stream, side_stream);
+}
+
+extern "C" size_t rov_block_static_scratch_bytes(void) { return rov::kStaticScratchBytes; }
+
+extern "C" int rov_block_forward_static(const rov_block_weights* w, const void* x, void* y, int B, int S,
+                                        const rov_block_cfg* cfg, int schedule, uint64_t seed,
+                                        uint64_t offset, int mask_ready, uint64_t* mask,
+                                        uint64_t* next_mask, void* main_stream, void* side_stream) {
+    // the size limit comes first: a block too large for the static scratch is an argument error
+    // and touches nothing
+    const size_t need = rov_block_workspace_bytes(cfg, B, S, schedule);
+    if (need == 0) return ROV_ERR_INVALID;
+    if (need > rov::kStaticScratchBytes) return ROV_ERR_WORKSPACE;
+    void* ws = nullptr;
+    const int rc = rov::static_scratch_ptr(&ws);
+    if (rc != ROV_OK) return rc;
+    return rov::block_forward_impl(w, x, y, B, S, cfg, schedule, seed, offset, mask_ready, mask, next_mask, ws,
+                                   rov::kStaticScratchBytes, main_stream, side_stream);
 }

@@ -153,7 +153,10 @@ int rov_set_rng_max_workgroups(int max_workgroups);
 /* Size of the persistent RNG grid that the overlap schedules launch beside a
  * GEMM, in workgroups (4 waves, one per SIMD) per compute unit.  Small enough
  * that a GEMM workgroup still fits on every compute unit whichever kernel
- * arrives first.  n <= 0 restores the default (2).  Returns the previous value. */
+ * arrives first.  n <= 0 restores the default: as many as fit beside the
+ * library's largest GEMM kernel on a SIMD's register file (3, or 2 for the
+ * mask-kernel variants that need 32 registers).  Returns the previous value
+ * (0 = the default rule). */
 int rov_set_rng_overlap_workgroups_per_cu(int n);
 
 /* Diagnostic: VALU issue cost of the instruction kinds the RNG kernel is made of

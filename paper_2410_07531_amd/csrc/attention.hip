@@ -77,6 +77,20 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
+// max(v[lane], v[lane ^ 32]) in every lane.  v_permlane32_swap exchanges the upper 32 lanes of its
+// first operand with the lower 32 of its second: with both operands v, one result holds the lower
+// half-wave's values in both halves and the other the upper half-wave's.
+__device__ __forceinline__ float half_wave_max(float v) {
+    const uint32_t u = __float_as_uint(v);
+    const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float half_wave_sum(float v) {
+    const uint32_t u = __float_as_uint(v);
+    const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
 constexpr int BKV = 64;   // keys per tile = one mask word per query row
 
 template <int D>
@@ -385,7 +399,10 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(const AttnParams p) 
             for (int t = 0; t < 2; ++t)
 #pragma unroll
                 for (int e = 0; e < 16; ++e) mx = fmaxf(mx, s[t][n][e]);
-            mx = fmaxf(mx, __shfl_xor(mx, 32)) * p.scale_log2;
+            // the other half-wave's maximum of the same query: a lane swap in the VALU (gfx950
+            // v_permlane32_swap), not an LDS permute: the LDS counter is shared with the scalar
+            // keep-word loads in flight, so waiting for a permute here would wait for them too
+            mx = half_wave_max(mx) * p.scale_log2;
             // The reference of the exponent follows the maximum lazily: it moves only when the
             // tile's maximum exceeds it by more than kLazy (in log2 units), so entries reach at
             // most 2^kLazy, far inside fp32 and bf16 range, the quotient by the row sum is the
@@ -491,7 +508,7 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(const AttnParams p) 
     // ---- normalise, scale kept entries by 1/(1-p), store O (lane: query ql, 4 consecutive dv per e/4)
 #pragma unroll
     for (int n = 0; n < NQ; ++n) {
-        const float l = l_run[n] + __shfl_xor(l_run[n], 32);
+        const float l = half_wave_sum(l_run[n]);
         const float f = l > 0.0f ? p.inv_keep / l : 0.0f;
         if (qrow[n] < q_end) {
             uint16_t* orow = Op + (int64_t)qrow[n] * p.so[1];

@@ -34,7 +34,7 @@ std::atomic<unsigned> g_queue_cursor{0};
 __global__ void queue_reset_kernel(int slot) { g_queues[slot][threadIdx.x].next = 0ull; }
 
 std::atomic<int> g_rng_max_workgroups{0};
-std::atomic<int> g_rng_overlap_wgs_per_cu{2};
+std::atomic<int> g_rng_overlap_wgs_per_cu{0};   // 0 = by the register rule in mask_grid_cap
 
 // One chunk: 16 groups -> 64 mask words = 4 whole tiles of 32 x 32 elements; word 4*gi + r is
 // parked in lane 4*gi + r of (vhi:vlo).  RAGGED (S % 32 != 0): bits whose row or column lies
@@ -74,8 +74,10 @@ __device__ __forceinline__ void mask_chunk(uint64_t base, uint32_t lane, uint32_
 
 // lower_only: skip every chunk (4 consecutive tiles) none of whose tiles has key tile <= query
 // tile, i.e. which causal attention never reads; what is written has the same bits either way.
+// (at most 24 vector registers for the 10-round kernel: three of its waves then fit on a SIMD beside
+// the GEMM kernels, see mask_grid_cap)
 template <int R, bool RAGGED>
-__global__ __launch_bounds__(kWavesPerBlock * 64) void mask_kernel(
+__global__ __launch_bounds__(kWavesPerBlock * 64) __attribute__((amdgpu_num_vgpr(24))) void mask_kernel(
     uint64_t* __restrict__ out, uint64_t words, uint64_t nchunks, uint64_t offset, uint32_t k0,
     uint32_t k1, uint32_t t_minus_1, uint32_t T, uint32_t S, int lower_only, int qslot, uint64_t qper,
     uint32_t qbatch) {
@@ -247,10 +249,23 @@ void queue_geometry(uint64_t nchunks, uint64_t* per, uint32_t* batch) {
     *batch = (uint32_t)b;
 }
 
-int mask_grid_cap(int grid_mode) {
+// kernel_regs: vector registers a wave of the mask kernel variant about to be launched is allocated
+// (24 or 32).  Beside a GEMM the grid is as many workgroups per compute unit (one wave per SIMD each)
+// as fit next to the largest GEMM kernel of this library on every SIMD: that kernel keeps 420 of a
+// SIMD's 512 registers (fp8; bf16 408), so 92 are left: three 24-register waves or two 32-register
+// ones.  One workgroup more and the GEMM's own workgroups can no longer be placed until the RNG
+// grid, which is persistent, has drained (measured: the block's PROJ GEMM 0.47 -> 1.36 ms).  More
+// RNG waves per SIMD finish the mask sooner at the same cost to the GEMMs (block at S = 16384:
+// 1.96 / 1.53 / 1.25 ms of the RNG exposed with 1 / 2 / 3 waves per SIMD, the GEMMs 8 / 12 / 12 %
+// slower).
+int mask_grid_cap(int grid_mode, int kernel_regs) {
     const int cap = g_rng_max_workgroups.load();
     if (cap > 0) return cap;
-    if (grid_mode == MASK_GRID_BESIDE) return device_cu_count() * g_rng_overlap_wgs_per_cu.load();
+    if (grid_mode == MASK_GRID_BESIDE) {
+        const int forced = g_rng_overlap_wgs_per_cu.load();
+        const int fit = (512 - 420) / (kernel_regs <= 24 ? 24 : 32);
+        return device_cu_count() * (forced > 0 ? forced : (fit < 3 ? fit : 3));
+    }
     if (grid_mode == MASK_GRID_HELPER) return device_cu_count() * 8;
     return device_cu_count() * 64;
 }
@@ -261,7 +276,8 @@ int launch_mask_r(uint64_t* out, uint64_t words, uint64_t offset, uint32_t k0, u
     const uint32_t T = (uint32_t)(((uint64_t)S + 31u) / 32u);
     const uint64_t nchunks = (words + 63u) / 64u;
     uint64_t blocks = (nchunks + kWavesPerBlock - 1) / kWavesPerBlock;
-    const int cap = mask_grid_cap(grid_mode);
+    // registers per wave: 24 for 10 and 3 rounds (and every ragged variant), 25 -> 32 for 7 and 5
+    const int cap = mask_grid_cap(grid_mode, ((S & 31) != 0 || R == 10 || R == 3) ? 24 : 32);
     if (blocks > (uint64_t)cap) blocks = (uint64_t)cap;
     const dim3 grid((unsigned)blocks), block(kWavesPerBlock * 64);
     uint64_t qper = 0;
@@ -284,7 +300,7 @@ int launch_mask_bits_b(uint64_t* out, uint64_t words, uint64_t offset, uint32_t 
     const uint32_t T = (uint32_t)(((uint64_t)S + 31u) / 32u);
     const uint64_t nchunks = (words + 63u) / 64u;
     uint64_t blocks = (nchunks + kWavesPerBlock - 1) / kWavesPerBlock;
-    const int cap = mask_grid_cap(grid_mode);
+    const int cap = mask_grid_cap(grid_mode, 24);
     if (blocks > (uint64_t)cap) blocks = (uint64_t)cap;
     const dim3 grid((unsigned)blocks), block(kWavesPerBlock * 64);
     if ((S & 31) == 0) {
@@ -425,7 +441,7 @@ int launch_mask_rows(uint64_t seed, uint64_t offset, int B, int H, int S, float 
     const uint64_t cps = (seg_words + 63u) / 64u;
     const uint64_t nseg = (uint64_t)B * (uint64_t)H;
     uint64_t blocks = (nseg * cps + kWavesPerBlock - 1) / kWavesPerBlock;
-    const int cap = mask_grid_cap(grid_mode);
+    const int cap = mask_grid_cap(grid_mode, 24);
     if (blocks > (uint64_t)cap) blocks = (uint64_t)cap;
     const dim3 grid((unsigned)blocks), block(kWavesPerBlock * 64);
     const uint32_t k0 = (uint32_t)seed, k1 = (uint32_t)(seed >> 32);
@@ -493,7 +509,7 @@ uint64_t rov_mask_philox_calls(int B, int H, int S) {
 }
 
 int rov_set_rng_overlap_workgroups_per_cu(int n) {
-    return rov::g_rng_overlap_wgs_per_cu.exchange(n > 0 ? n : 2);
+    return rov::g_rng_overlap_wgs_per_cu.exchange(n > 0 ? n : 0);
 }
 
 int rov_set_rng_max_workgroups(int max_workgroups) {

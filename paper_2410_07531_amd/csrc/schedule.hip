@@ -130,25 +130,26 @@ int t_mask(uint64_t seed, uint64_t offset, int B, int H, int S, float p, uint64_
 
 // Will the small RNG grid finish while the GEMMs beside it run?  Then the plain launch is enough;
 // otherwise the mask goes through a work queue and a helper launch finishes it after the GEMMs.
-// The rates are this chip's measured ones, rounded against the RNG: about 1.0 PFLOP/s for the
-// bf16 / fp8 GEMM (30 TFLOP/s for the fp32 kernel) and 0.2 T Philox calls/s for the two-workgroups-
-// per-compute-unit grid beside a GEMM.  A wrong guess costs time, never correctness.  (The GEMMs
-// are faster than that by now, 1.3 PFLOP/s bf16 and 2.8 fp8; with those rates the fp8 layer of the
-// 70B shape switches to the work queue and gets 1.4 % slower, the RNG all but fitting beside its
-// GEMMs, so the rule keeps the rates that decide that case the right way.)
-bool rng_fits_beside(double gemm_flop, bool fp32, double rng_calls) {
-    const double t_gemm = gemm_flop / (fp32 ? 30e12 : 1.0e15);
-    const double t_rng = rng_calls / 0.2e12;
-    return t_rng < 0.8 * t_gemm;
+// The rates are this chip's measured ones with both kernels running: 1.16 PFLOP/s for the bf16
+// GEMMs and 2.55 for fp8 (12 % and 8 % below their stand-alone rates; 30 TFLOP/s for the fp32
+// kernel), 0.335 T Philox calls/s for the three-waves-per-SIMD grid beside them (0.44 of the
+// stand-alone kernel).  A wrong guess costs time (an empty helper launch, about 10 us, or an RNG
+// tail at the small grid's rate), never correctness.
+bool rng_fits_beside(double gemm_flop, int dtype, double rng_calls) {
+    const double rate = dtype == ROV_F32 ? 30e12 : (dtype == ROV_FP8_E4M3 ? 2.55e15 : 1.16e15);
+    const double t_gemm = gemm_flop / rate;
+    const double t_rng = rng_calls / 0.335e12;
+    return t_rng < 0.9 * t_gemm;
 }
 
 double gemm_flop(int M, int N, int K) { return 2.0 * (double)M * (double)N * (double)K; }
 
 // Hybrid schedule of the block: how many query rows of the next layer's mask the small RNG grid
-// gets done beside the block's PROJ / FC1 / FC2 GEMMs (1.3 PFLOP/s, 16 % slower with the RNG there
-// all the time, 0.325 T Philox calls/s beside them: this chip's measured rates), with a twentieth
-// of margin, in steps of 2048 rows (a full round of attention workgroups at 32 heads); below one
-// step the mask is not worth its launches.  rov_set_block_hybrid_mask_rows overrides the rule.
+// gets done beside the block's PROJ / FC1 / FC2 GEMMs (1.3 PFLOP/s alone, 12 % slower with the RNG
+// there all the time, 0.335 T Philox calls/s beside them: this chip's measured rates, the same as in
+// rng_fits_beside), with a twentieth of margin, in steps of 2048 rows (a full round of attention
+// workgroups at 32 heads); below one step the mask is not worth its launches.
+// rov_set_block_hybrid_mask_rows overrides the rule.
 std::atomic<int> g_hybrid_rows{0};
 int hybrid_rows(const rov_block_cfg* c, int B, int S) {
     const int forced = g_hybrid_rows.load();
@@ -158,8 +159,8 @@ int hybrid_rows(const rov_block_cfg* c, int B, int S) {
     } else {
         const double T = (double)B * S;
         const double t_gemms = (gemm_flop((int)T, c->hidden, c->H * c->d) + 3.0 * gemm_flop((int)T, c->ffn, c->hidden)) /
-                               1.3e15 * 1.16;
-        const double frac = 0.95 * t_gemms * 0.325e12 / (double)rov_mask_philox_calls(B, c->H, S);
+                               1.3e15 * 1.12;
+        const double frac = 0.95 * t_gemms * 0.335e12 / (double)rov_mask_philox_calls(B, c->H, S);
         // (while most of it fits, the overlap schedule's full-speed launch for the rest costs no more
         // than drawing those rows in the attention kernel: measured level at 0.8)
         R = frac >= 0.7 ? S : (int)(frac * S / 2048.0) * 2048;
@@ -245,14 +246,14 @@ int layer_step_impl(int schedule, const rov_gemm_desc* gemms, int n_gemms, const
         side.ms = ms;
         side.ss = ss;
         double flop = 0.0;
-        bool fp32 = false;
+        int slowest = ROV_FP8_E4M3;   // the dtype whose GEMM rate is lowest among the sequence's
         for (int i = 0; i < n_gemms; ++i) {
             flop += gemm_flop(gemms[i].M, gemms[i].N, gemms[i].K);
-            fp32 = fp32 || gemms[i].dtype == ROV_F32;
+            if (gemms[i].dtype == ROV_F32 || (gemms[i].dtype == ROV_BF16 && slowest != ROV_F32)) slowest = gemms[i].dtype;
         }
         const double calls = (double)rov_mask_philox_calls(attn->B, attn->H, attn->S) * (attn->causal ? 0.5 : 1.0);
         // (cost per call ~ rounds; the narrower kernels have no work-queue form and simply run on)
-        if (bits == 32 && !rng_fits_beside(flop, fp32, calls * (0.25 + 0.075 * rounds))) {
+        if (bits == 32 && !rng_fits_beside(flop, slowest, calls * (0.25 + 0.075 * rounds))) {
             rc = mask_queue_acquire(ms, &qslot);   // reset here: ordered before both RNG launches
             if (rc != ROV_OK) return rc;
         }
@@ -421,13 +422,13 @@ extern "C" int rov_layer_step_chunked(const rov_gemm_desc* gemms, int n_gemms, c
     };
     {   // chunks 0 and 1 run beside the GEMMs; later chunks run beside attention and always get help
         double flop = 0.0;
-        bool fp32 = false;
+        int slowest = ROV_FP8_E4M3;
         for (int i = 0; i < n_gemms; ++i) {
             flop += gemm_flop(gemms[i].M, gemms[i].N, gemms[i].K);
-            fp32 = fp32 || gemms[i].dtype == ROV_F32;
+            if (gemms[i].dtype == ROV_F32 || (gemms[i].dtype == ROV_BF16 && slowest != ROV_F32)) slowest = gemms[i].dtype;
         }
         const double calls = 16.0 * (double)slot_words * (nchunks > 1 ? 2.0 : 1.0);
-        if (!rng_fits_beside(flop, fp32, calls))
+        if (!rng_fits_beside(flop, slowest, calls))
             for (int c = 0; c < 2 && c < nchunks; ++c) {
                 rc = mask_queue_acquire(ms, &qslot[c]);
                 if (rc != ROV_OK) return rc;
@@ -575,7 +576,7 @@ int block_forward_impl(const rov_block_weights* w, const void* x, void* y, int B
     int qslot = -1;
     const double mask_calls = (double)rov_mask_philox_calls(B, H, S) * (cfg->causal ? 0.5 : 1.0);
     if (use_mask && !mask_ready && overlap) {
-        if (!rng_fits_beside(gemm_flop((int)((int64_t)B * S), (cfg->H + 2 * cfg->Hkv) * cfg->d, cfg->hidden), false,
+        if (!rng_fits_beside(gemm_flop((int)((int64_t)B * S), (cfg->H + 2 * cfg->Hkv) * cfg->d, cfg->hidden), ROV_BF16,
                              mask_calls))
             ROV_STEP(mask_queue_acquire(ms, &qslot));
         ROV_STEP(side.fork());
@@ -637,7 +638,7 @@ int block_forward_impl(const rov_block_weights* w, const void* x, void* y, int B
         const double rest = gemm_flop((int)T, hidden, H * d) + 2.0 * gemm_flop((int)T, ffn, hidden) +
                             gemm_flop((int)T, hidden, ffn);
         // (hybrid with R < S: the rows were chosen to fit, no queue and no helper launch)
-        if (R == S && !rng_fits_beside(rest, false, mask_calls)) ROV_STEP(mask_queue_acquire(ms, &qslot_next));
+        if (R == S && !rng_fits_beside(rest, ROV_BF16, mask_calls)) ROV_STEP(mask_queue_acquire(ms, &qslot_next));
         ROV_STEP(side.fork());
     }
     ROV_STEP(t_gemm(att, w->wo, x2, x, (int)T, hidden, H * d, ROV_BF16, 1, 1.0f, 1.0f, ms));

@@ -157,5 +157,46 @@ def block_forward(x, w, cfg, keep, rows=None):
     return x2 + (silu(g) * u) @ f64(w["wd"]).T
 
 
+def fake_quant_e4m3(v, scale):
+    """Per-tensor fp8 quantisation of an activation as the fp8 block applies it: the value is
+    divided by its dequantisation scale, rounded to the nearest OCP e4m3 code (ties to even,
+    saturating at +-448) and multiplied by the scale again."""
+    from . import numerics as _num
+    return _num.e4m3_decode(_num.e4m3_encode(np.asarray(v, dtype=np.float64) / scale)) * scale
+
+
+def block_forward_fp8(x, w, w_scale, act_scale, cfg, keep, rows=None):
+    """The same block with fp8 (OCP e4m3) GEMMs, the precision the paper measures in (Sec. 1,
+    Sec. 6); the paper does not say where values are quantised, so this is a reading: every GEMM
+    takes both operands in e4m3 with one scale per tensor and accumulates exactly, everything
+    between the GEMMs (normalisation, rotary embedding, attention, residuals) stays unquantised.
+        h1 = Q0(RMSNorm(x))            ; [q|k|v] = h1 dq(Wqkv)^T ; RoPE(q, k)
+        a  = Q1(attention_dropout(q, k, v)) ; x2 = x + a dq(Wo)^T
+        h2 = Q2(RMSNorm(x2))           ; u = Q3(silu(h2 dq(Wg)^T) * (h2 dq(Wu)^T))
+        y  = x2 + u dq(Wd)^T
+    Qi(v) = fake_quant_e4m3(v, act_scale[i]); dq(W) = decode(codes) * w_scale[name].
+    w: 'norm1', 'norm2' as floats, 'wqkv', 'wo', 'wg', 'wu', 'wd' as uint8 e4m3 codes [out, in];
+    w_scale: dict name -> float; act_scale: 4 floats (for h1, a, h2, u).  rows as in block_forward."""
+    from . import numerics as _num
+    x = np.asarray(x, dtype=np.float64)
+    B, S, hidden = x.shape
+    H, Hkv, d = cfg["H"], cfg["Hkv"], cfg["d"]
+    dq = lambda name: _num.e4m3_decode(w[name]) * float(w_scale[name])
+    h1 = fake_quant_e4m3(rmsnorm(x, w["norm1"], cfg["eps"]), act_scale[0])
+    qkv = h1 @ dq("wqkv").T
+    q = qkv[..., : H * d].reshape(B, S, H, d)
+    k = qkv[..., H * d: (H + Hkv) * d].reshape(B, S, Hkv, d)
+    v = qkv[..., (H + Hkv) * d:].reshape(B, S, Hkv, d)
+    q = rope(q, cfg["rope_theta"])
+    k = rope(k, cfg["rope_theta"])
+    a = attention_dropout(q, k, v, keep, cfg["p"], causal=cfg["causal"], rows=rows)
+    a = fake_quant_e4m3(a, act_scale[1])
+    xr = x if rows is None else x[:, np.asarray(rows), :]
+    x2 = xr + a.reshape(B, a.shape[1], H * d) @ dq("wo").T
+    h2 = fake_quant_e4m3(rmsnorm(x2, w["norm2"], cfg["eps"]), act_scale[2])
+    u = fake_quant_e4m3(silu(h2 @ dq("wg").T) * (h2 @ dq("wu").T), act_scale[3])
+    return x2 + u @ dq("wd").T
+
+
 def keep_from_words(words, S):
     return _philox.unpack_keep(words, S)

@@ -307,21 +307,22 @@ def test_fp8_block_matches_library_composition_with_float8_casts():
         assert np.max(np.abs(y - ref64)) > 0.0           # the quantisation is visible
 
 
-def test_fp8_block_stays_within_the_fp8_bar_of_the_unquantised_block():
+def test_fp8_block_stays_within_the_fp8_bar_of_the_unquantised_activations():
     # at widths where a sum has a few hundred terms the rounding of single values averages out:
-    # the fp8 block with amax scales is within 6e-2 (relative to the output scale) of the float64
-    # block on the unquantised weights
+    # quantising the four activations moves the block by less than 6e-2 of its output scale
+    # (reference: the float64 block on the same dequantised weights, the convention of the fp8
+    # GEMM bar), and by a visible amount
     x, w, cfg = _block_setup(33, S=12, H=4, Hkv=2, d=32, hidden=256, ffn=384)
     cfg["p"] = 0.0
-    wq, ws = {"norm1": w["norm1"], "norm2": w["norm2"]}, {}
+    wq, ws, wdq = {"norm1": w["norm1"], "norm2": w["norm2"]}, {}, dict(w)
     for name in ("wqkv", "wo", "wg", "wu", "wd"):
         wq[name], ws[name] = N.e4m3_quantise(w[name] * 0.3)
-        w[name] = w[name] * 0.3
-    ref = D.block_forward(x, w, cfg, None)
+        wdq[name] = N.e4m3_decode(wq[name]) * ws[name]
+    ref = D.block_forward(x, wdq, cfg, None)
     act = [6.0 / 448.0, 3.0 / 448.0, 6.0 / 448.0, 4.0 / 448.0]
     y = D.block_forward_fp8(x, wq, ws, act, cfg, None)
     err = np.max(np.abs(y - ref)) / np.max(np.abs(ref))
-    assert 0.0 < err <= 6e-2, err
+    assert 1e-4 < err <= 6e-2, err
 
 
 def test_fp8_block_with_dropout_rows_and_zero_projections():

@@ -203,6 +203,14 @@ int rov_gemm_tile_cols(int M, int N);
  * ROV_ERR_UNSUPPORTED. */
 int rov_gemm_swiglu(const void *A, const void *Wg, const void *Wu, void *C, int M, int N, int K, void *stream);
 
+/* The same product in fp8 for the fp8 block: A [M,K], Wg, Wu [N,K] and the result C [M,N] are OCP e4m3
+ * bytes with one dequantisation scale per tensor:
+ *     C = e4m3( silu(scaleA*scaleWg * A Wg^T) * (scaleA*scaleWu * A Wu^T) / scaleC ),
+ * nearest code, ties to even, saturating at +-448; fp32 accumulation.  K % 128 == 0 and N % 4 == 0,
+ * else ROV_ERR_UNSUPPORTED; A, Wg, Wu 16-byte aligned, C 4-byte aligned; scaleC > 0. */
+int rov_gemm_swiglu_fp8(const void *A, const void *Wg, const void *Wu, void *C, int M, int N, int K,
+                        float scaleA, float scaleWg, float scaleWu, float scaleC, void *stream);
+
 /* The overlap as ONE kernel (paper Sec. 6.1 names this wave-specialised form beside
  * the two-kernel one it uses): every workgroup computes a tile of
  * C[M,N] = A[M,K] * Bm[N,K]^T (bf16, K contiguous in both, fp32 accumulation) with four
@@ -361,9 +369,19 @@ int rov_trace_read(int *kinds, float *ms, int max_records, int *n_records);
  *   h1 = RMSNorm(x)*norm1; [q|k|v] = h1 Wqkv^T; RoPE(q,k); a = attention_dropout(q,k,v);
  *   x2 = x + a Wo^T; h2 = RMSNorm(x2)*norm2; y = x2 + (silu(h2 Wg^T) * (h2 Wu^T)) Wd^T.
  * RoPE rotates the adjacent pair (2t, 2t+1) of token position s by s*theta^(-2t/d).
- * Weights are row-major [out_features, in_features], bf16 (cfg->dtype must be
- * ROV_BF16; d must be 64 or 128; hidden and ffn multiples of 64).  x, y: bf16
+ * Weights are row-major [out_features, in_features]; d must be 64 or 128.  x, y: bf16
  * [B, S, hidden].
+ * cfg->dtype == ROV_BF16: bf16 weights, hidden and ffn multiples of 64.
+ * cfg->dtype == ROV_FP8_E4M3 (the precision the paper measures in, Sec. 1 / Sec. 6): the five
+ *   weight matrices are OCP e4m3 bytes with one dequantisation scale each (w->w_scale), and every
+ *   GEMM takes its activation in e4m3 too, quantised with a per-tensor scale the caller supplies
+ *   (cfg->act_scale, e.g. amax / 448 from a calibration pass, so that nothing here synchronises):
+ *     h1 = Q0(RMSNorm(x)*norm1); a = Q1(attention_dropout(q,k,v)); h2 = Q2(RMSNorm(x2)*norm2);
+ *     u = Q3(silu(h2 Wg^T) * (h2 Wu^T)),  Qi(v) = act_scale[i] * e4m3(v / act_scale[i])
+ *   (nearest code, ties to even, saturating at +-448), each applied where the value is produced
+ *   (normalisation kernel, attention epilogue, FC1 epilogue).  q, k, v, the residual stream and y
+ *   stay bf16; GEMMs accumulate in fp32.  hidden, ffn and H*d multiples of 128; norm weights bf16.
+ *   Scales must be > 0.
  *
  * This block's attention uses the mask of (seed, offset), p = cfg->p:
  *   SEQUENTIAL  mask_ready == 0: the RNG kernel runs on main_stream between the
@@ -396,6 +414,7 @@ typedef struct rov_block_cfg {
     float p;
     float eps;
     float rope_theta;
+    float act_scale[4];  /* ROV_FP8_E4M3 only: dequantisation scales of h1, a, h2, u (ignored for bf16) */
 } rov_block_cfg;
 
 typedef struct rov_block_weights {
@@ -406,6 +425,7 @@ typedef struct rov_block_weights {
     const void *wg;      /* [ffn, hidden] */
     const void *wu;      /* [ffn, hidden] */
     const void *wd;      /* [hidden, ffn] */
+    float w_scale[5];    /* ROV_FP8_E4M3 only: dequantisation scales of wqkv, wo, wg, wu, wd (ignored for bf16) */
 } rov_block_weights;
 
 size_t rov_block_workspace_bytes(const rov_block_cfg *cfg, int B, int S, int schedule);

@@ -165,7 +165,7 @@ def fake_quant_e4m3(v, scale):
     return _num.e4m3_decode(_num.e4m3_encode(np.asarray(v, dtype=np.float64) / scale)) * scale
 
 
-def block_forward_fp8(x, w, w_scale, act_scale, cfg, keep, rows=None):
+def block_forward_fp8(x, w, w_scale, act_scale, cfg, keep, rows=None, stored_bf16=True):
     """The same block with fp8 (OCP e4m3) GEMMs, the precision the paper measures in (Sec. 1,
     Sec. 6); the paper does not say where values are quantised, so this is a reading: every GEMM
     takes both operands in e4m3 with one scale per tensor and accumulates exactly, everything
@@ -176,23 +176,28 @@ def block_forward_fp8(x, w, w_scale, act_scale, cfg, keep, rows=None):
         y  = x2 + u dq(Wd)^T
     Qi(v) = fake_quant_e4m3(v, act_scale[i]); dq(W) = decode(codes) * w_scale[name].
     w: 'norm1', 'norm2' as floats, 'wqkv', 'wo', 'wg', 'wu', 'wd' as uint8 e4m3 codes [out, in];
-    w_scale: dict name -> float; act_scale: 4 floats (for h1, a, h2, u).  rows as in block_forward."""
+    w_scale: dict name -> float; act_scale: 4 floats (for h1, a, h2, u).  rows as in block_forward.
+    stored_bf16: the tensors the block keeps between its GEMMs in bf16 - the QKV projection, q and k
+    after the rotary embedding, and the residual stream x2 - are rounded to bf16 here too.  They feed
+    the quantisers Q1..Q3, i.e. they decide integer codes, and such a decision is taken on the stored
+    value on both sides (a bf16 rounding error of 2^-9 would otherwise flip one code in thirty)."""
     from . import numerics as _num
     x = np.asarray(x, dtype=np.float64)
     B, S, hidden = x.shape
     H, Hkv, d = cfg["H"], cfg["Hkv"], cfg["d"]
+    st = (lambda t: _num.bf16_round(t).astype(np.float64)) if stored_bf16 else (lambda t: t)
     dq = lambda name: _num.e4m3_decode(w[name]) * float(w_scale[name])
     h1 = fake_quant_e4m3(rmsnorm(x, w["norm1"], cfg["eps"]), act_scale[0])
-    qkv = h1 @ dq("wqkv").T
+    qkv = st(h1 @ dq("wqkv").T)
     q = qkv[..., : H * d].reshape(B, S, H, d)
     k = qkv[..., H * d: (H + Hkv) * d].reshape(B, S, Hkv, d)
     v = qkv[..., (H + Hkv) * d:].reshape(B, S, Hkv, d)
-    q = rope(q, cfg["rope_theta"])
-    k = rope(k, cfg["rope_theta"])
+    q = st(rope(q, cfg["rope_theta"]))
+    k = st(rope(k, cfg["rope_theta"]))
     a = attention_dropout(q, k, v, keep, cfg["p"], causal=cfg["causal"], rows=rows)
     a = fake_quant_e4m3(a, act_scale[1])
     xr = x if rows is None else x[:, np.asarray(rows), :]
-    x2 = xr + a.reshape(B, a.shape[1], H * d) @ dq("wo").T
+    x2 = st(xr + a.reshape(B, a.shape[1], H * d) @ dq("wo").T)
     h2 = fake_quant_e4m3(rmsnorm(x2, w["norm2"], cfg["eps"]), act_scale[2])
     u = fake_quant_e4m3(silu(h2 @ dq("wg").T) * (h2 @ dq("wu").T), act_scale[3])
     return x2 + u @ dq("wd").T

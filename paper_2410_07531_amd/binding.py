@@ -44,11 +44,12 @@ class BlockCfg(ctypes.Structure):
     _fields_ = [("H", ctypes.c_int), ("Hkv", ctypes.c_int), ("d", ctypes.c_int),
                 ("hidden", ctypes.c_int), ("ffn", ctypes.c_int), ("dtype", ctypes.c_int),
                 ("causal", ctypes.c_int), ("p", ctypes.c_float), ("eps", ctypes.c_float),
-                ("rope_theta", ctypes.c_float)]
+                ("rope_theta", ctypes.c_float), ("act_scale", ctypes.c_float * 4)]
 
 
 class BlockWeights(ctypes.Structure):
-    _fields_ = [(n, ctypes.c_void_p) for n in ("norm1", "norm2", "wqkv", "wo", "wg", "wu", "wd")]
+    _fields_ = [(n, ctypes.c_void_p) for n in ("norm1", "norm2", "wqkv", "wo", "wg", "wu", "wd")] + \
+               [("w_scale", ctypes.c_float * 5)]
 
 
 # name -> (restype, argtypes); also the list of symbols the header declares
@@ -81,6 +82,7 @@ SIGNATURES = {
     "rov_valu_probe": (_i, [_i, _i, _i, _p, _p]),
     "rov_gemm": (_i, [_p, _p, _p, _i, _i, _i, _i, _i, _f, _f, _p]),
     "rov_gemm_swiglu": (_i, [_p, _p, _p, _p, _i, _i, _i, _p]),
+    "rov_gemm_swiglu_fp8": (_i, [_p, _p, _p, _p, _i, _i, _i, _f, _f, _f, _f, _p]),
     "rov_gemm_rng_fused": (_i, [_p, _p, _p, _i, _i, _i, _u64, _u64, _i, _i, _i, _f, _p, _p]),
     "rov_attention_fwd_dropout": (_i, [_p, _p, _p, _p, _i, _i, _i, _i, _i,
                                        ctypes.POINTER(ctypes.c_int64), _i, _i, _f, _p, _u64, _u64, _p]),
@@ -260,6 +262,20 @@ def gemm_swiglu(A, Wg, Wu, C=None, stream=None):
     return C
 
 
+def gemm_swiglu_fp8(A, Wg, Wu, scaleA, scaleWg, scaleWu, scaleC, C=None, stream=None):
+    """C (e4m3 bytes) = e4m3(silu(sA sWg A Wg^T) * (sA sWu A Wu^T) / scaleC); A, Wg, Wu e4m3 bytes."""
+    import torch
+    M, K = A.shape
+    N = Wg.shape[0]
+    if C is None:
+        C = torch.empty((M, N), dtype=torch.uint8, device=A.device)
+    _check(load().rov_gemm_swiglu_fp8(ctypes.c_void_p(A.data_ptr()), ctypes.c_void_p(Wg.data_ptr()),
+                                      ctypes.c_void_p(Wu.data_ptr()), ctypes.c_void_p(C.data_ptr()), M, N, K,
+                                      float(scaleA), float(scaleWg), float(scaleWu), float(scaleC),
+                                      _stream_ptr(stream)), "rov_gemm_swiglu_fp8")
+    return C
+
+
 def gemm_rng_fused(A, Bm, seed, offset, B, H, S, p, C=None, mask=None, stream=None):
     """C = A @ Bm^T (bf16) and the keep-mask of (seed, offset, B, H, S, p) from one wave-specialised kernel."""
     import torch
@@ -410,13 +426,19 @@ def set_block_hybrid_mask_rows(rows):
     return int(load().rov_set_block_hybrid_mask_rows(int(rows)))
 
 
-def make_block_cfg(H, Hkv, d, hidden, ffn, p, causal=False, eps=1e-5, rope_theta=500000.0, dtype=BF16):
-    return BlockCfg(H, Hkv, d, hidden, ffn, dtype, int(bool(causal)), float(p), float(eps), float(rope_theta))
+def make_block_cfg(H, Hkv, d, hidden, ffn, p, causal=False, eps=1e-5, rope_theta=500000.0, dtype=BF16,
+                   act_scale=None):
+    """act_scale (fp8 only): dequantisation scales of the four quantised activations h1, a, h2, u."""
+    sc = (ctypes.c_float * 4)(*([float(v) for v in act_scale] if act_scale is not None else [0.0] * 4))
+    return BlockCfg(H, Hkv, d, hidden, ffn, dtype, int(bool(causal)), float(p), float(eps), float(rope_theta), sc)
 
 
-def make_block_weights(w):
-    """w: dict of device tensors norm1, norm2, wqkv, wo, wg, wu, wd."""
-    return BlockWeights(*[w[n].data_ptr() for n in ("norm1", "norm2", "wqkv", "wo", "wg", "wu", "wd")])
+def make_block_weights(w, w_scale=None):
+    """w: dict of device tensors norm1, norm2, wqkv, wo, wg, wu, wd; w_scale (fp8 only): dict of the five
+    weight matrices' dequantisation scales."""
+    names = ("wqkv", "wo", "wg", "wu", "wd")
+    sc = (ctypes.c_float * 5)(*([float(w_scale[n]) for n in names] if w_scale is not None else [0.0] * 5))
+    return BlockWeights(*[w[n].data_ptr() for n in ("norm1", "norm2") + names], sc)
 
 
 def block_forward(weights, x, y, cfg, schedule, seed, offset, mask, workspace, main_stream, side_stream,

@@ -31,6 +31,7 @@
 #include <type_traits>
 #include <stdint.h>
 
+#include "fp8_device.h"
 #include "philox_device.h"
 #include "rov_internal.h"
 
@@ -60,6 +61,8 @@ struct AttnParams {
     int rounds;                           // Philox rounds (fused)
     int bits;                             // random bits per element (fused): 8, 16 or 32
     uint32_t tb;                          // bits < 32: keep iff field < tb (fused)
+    int o_fp8;                            // O is written as OCP e4m3 bytes of (value * o_inv_scale): fp8 block
+    float o_inv_scale;
 };
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
@@ -510,7 +513,18 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(const AttnParams p) 
     for (int n = 0; n < NQ; ++n) {
         const float l = half_wave_sum(l_run[n]);
         const float f = l > 0.0f ? p.inv_keep / l : 0.0f;
-        if (qrow[n] < q_end) {
+        if (qrow[n] < q_end && p.o_fp8) {
+            // the fp8 block quantises the attention output where it is produced (strides count bytes here)
+            uint8_t* orow = (uint8_t*)p.O + b * p.so[0] + h * p.so[2] + (int64_t)qrow[n] * p.so[1];
+            const float fq = f * p.o_inv_scale;
+#pragma unroll
+            for (int t = 0; t < DVT; ++t)
+#pragma unroll
+                for (int g = 0; g < 4; ++g)
+                    *reinterpret_cast<uint32_t*>(orow + 32 * t + 8 * g + 4 * half) =
+                        pack_e4m3x4(o[t][n][4 * g + 0] * fq, o[t][n][4 * g + 1] * fq, o[t][n][4 * g + 2] * fq,
+                                    o[t][n][4 * g + 3] * fq);
+        } else if (qrow[n] < q_end) {
             uint16_t* orow = Op + (int64_t)qrow[n] * p.so[1];
 #pragma unroll
             for (int t = 0; t < DVT; ++t)
@@ -731,7 +745,7 @@ int check_attention_rows(const void* Q, const void* K, const void* V, const void
 int launch_attention_rows(const void* Q, const void* K, const void* V, void* O, int B, int H, int Hkv,
                           int S, int d, const int64_t strides[12], int dtype, int causal, float p,
                           const uint64_t* mask, bool mask_is_rows, uint64_t seed, uint64_t offset,
-                          int q_begin, int q_rows, hipStream_t stream, int rounds, int bits) {
+                          int q_begin, int q_rows, hipStream_t stream, int rounds, int bits, float o_fp8_scale) {
     {
         const int rc = check_attention_rows(Q, K, V, O, B, H, Hkv, S, d, strides, dtype, p, mask, q_begin, q_rows,
                                             rounds, bits);
@@ -763,6 +777,8 @@ int launch_attention_rows(const void* Q, const void* K, const void* V, void* O, 
     prm.bits = bits;
     // keep iff field < tb, tb = floor((1 - p) * 2^bits) in double from the float p
     prm.tb = bits < 32 ? (uint32_t)(uint64_t)((1.0 - (double)p) * (double)(1u << bits)) : 0u;
+    prm.o_fp8 = o_fp8_scale > 0.0f;
+    prm.o_inv_scale = prm.o_fp8 ? 1.0f / o_fp8_scale : 1.0f;
     const int mode = p == 0.0f ? MODE_NONE : (mask != nullptr ? MODE_MASK : MODE_FUSED);
 
     if (dtype == ROV_BF16 && (d == 64 || d == 128)) {
@@ -772,6 +788,11 @@ int launch_attention_rows(const void* Q, const void* K, const void* V, void* O, 
         // K / V of one (batch, kv head) are addressed through a buffer resource: 32-bit byte offsets
         for (int t = 4; t <= 7; t += 3)
             ok = ok && strides[t] >= 0 && (uint64_t)(S - 1) * (uint64_t)strides[t] * 2u + 2u * (uint64_t)d < (1ull << 32);
+        if (prm.o_fp8) {   // four bytes per store: O and its strides (in bytes) are multiples of 4
+            ok = ok && aligned(O, 4);
+            for (int i = 9; i < 12; ++i) ok = ok && (strides[i] % 4) == 0;
+            if (!ok) return ROV_ERR_UNSUPPORTED;
+        }
         if (ok) {
             // 8 waves x 32 query rows: two waves per SIMD (measured 1.5x faster than 4 waves x 64
             // rows at S = 16384: 905 vs 602 TFLOP/s without dropout)
@@ -779,6 +800,7 @@ int launch_attention_rows(const void* Q, const void* K, const void* V, void* O, 
             return launch_bf16<64, 1, 8>(prm, mode, stream);
         }
     }
+    if (prm.o_fp8) return ROV_ERR_UNSUPPORTED;   // the e4m3 output exists in the matrix-core kernel only
     if (dtype == ROV_BF16) return launch_generic<uint16_t>(prm, mode, stream);
     return launch_generic<float>(prm, mode, stream);
 }

@@ -5,6 +5,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "fp8_device.h"
 #include "rov_internal.h"
 
 namespace rov {
@@ -22,9 +23,12 @@ __device__ __forceinline__ float lo_f(uint32_t w) { return __uint_as_float(w << 
 __device__ __forceinline__ float hi_f(uint32_t w) { return __uint_as_float(w & 0xFFFF0000u); }
 
 // y[row] = x[row] / sqrt(mean(x[row]^2) + eps) * weight ; one workgroup per row, n % 8 == 0.
+// OUT8: y is written as OCP e4m3 bytes of (that value * out_inv): the normalised activation of the
+// fp8 block, quantised with its per-tensor scale where it is produced.
+template <bool OUT8>
 __global__ __launch_bounds__(256) void rmsnorm_kernel(const uint16_t* __restrict__ x,
                                                       const uint16_t* __restrict__ weight,
-                                                      uint16_t* __restrict__ y, int n, float eps) {
+                                                      uint16_t* __restrict__ y, int n, float eps, float out_inv) {
     __shared__ float red[4];
     const uint16_t* xr = x + (size_t)blockIdx.x * n;
     uint16_t* yr = y + (size_t)blockIdx.x * n;
@@ -50,11 +54,23 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const uint16_t* __restrict
         const uint4 g = *reinterpret_cast<const uint4*>(weight + c);
         const uint32_t w[4] = {v.x, v.y, v.z, v.w};
         const uint32_t gw[4] = {g.x, g.y, g.z, g.w};
-        uint32_t o[4];
+        if constexpr (OUT8) {
+            float f[8];
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
-            o[i] = pack2(lo_f(w[i]) * inv * lo_f(gw[i]), hi_f(w[i]) * inv * hi_f(gw[i]));
-        *reinterpret_cast<uint4*>(yr + c) = make_uint4(o[0], o[1], o[2], o[3]);
+            for (int i = 0; i < 4; ++i) {
+                f[2 * i] = lo_f(w[i]) * inv * lo_f(gw[i]) * out_inv;
+                f[2 * i + 1] = hi_f(w[i]) * inv * hi_f(gw[i]) * out_inv;
+            }
+            uint8_t* y8 = reinterpret_cast<uint8_t*>(y) + (size_t)blockIdx.x * n;
+            *reinterpret_cast<uint2*>(y8 + c) =
+                make_uint2(pack_e4m3x4(f[0], f[1], f[2], f[3]), pack_e4m3x4(f[4], f[5], f[6], f[7]));
+        } else {
+            uint32_t o[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                o[i] = pack2(lo_f(w[i]) * inv * lo_f(gw[i]), hi_f(w[i]) * inv * hi_f(gw[i]));
+            *reinterpret_cast<uint4*>(yr + c) = make_uint4(o[0], o[1], o[2], o[3]);
+        }
     }
 }
 
@@ -102,8 +118,18 @@ __global__ __launch_bounds__(256) void rope_kernel(uint16_t* __restrict__ buf, i
 int launch_rmsnorm(const void* x, const void* weight, void* y, int64_t rows, int n, float eps,
                    hipStream_t stream) {
     if (rows <= 0 || n <= 0 || (n % 8) != 0 || rows > 0x7FFFFFFF) return ROV_ERR_UNSUPPORTED;
-    hipLaunchKernelGGL(rmsnorm_kernel, dim3((unsigned)rows), dim3(256), 0, stream,
-                       (const uint16_t*)x, (const uint16_t*)weight, (uint16_t*)y, n, eps);
+    hipLaunchKernelGGL(rmsnorm_kernel<false>, dim3((unsigned)rows), dim3(256), 0, stream,
+                       (const uint16_t*)x, (const uint16_t*)weight, (uint16_t*)y, n, eps, 1.0f);
+    ROV_LAUNCH_CHECK();
+    return ROV_OK;
+}
+
+int launch_rmsnorm_fp8(const void* x, const void* weight, void* y8, int64_t rows, int n, float eps, float scale,
+                       hipStream_t stream) {
+    if (rows <= 0 || n <= 0 || (n % 8) != 0 || rows > 0x7FFFFFFF) return ROV_ERR_UNSUPPORTED;
+    if (!(scale > 0.0f)) return ROV_ERR_INVALID;
+    hipLaunchKernelGGL(rmsnorm_kernel<true>, dim3((unsigned)rows), dim3(256), 0, stream,
+                       (const uint16_t*)x, (const uint16_t*)weight, (uint16_t*)y8, n, eps, 1.0f / scale);
     ROV_LAUNCH_CHECK();
     return ROV_OK;
 }

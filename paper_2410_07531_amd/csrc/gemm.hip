@@ -38,6 +38,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "fp8_device.h"
 #include "mask_device.h"
 #include "philox_device.h"
 #include "rov_internal.h"
@@ -198,13 +199,17 @@ __device__ __forceinline__ void epilogue_combine(int epi, uint2 r, float& c0, fl
 // projection) followed by the same 8*NJ rows of Wt2 (the up projection); the epilogue writes
 // silu(gate) * up for those 8*NJ output columns, both still in fp32, so the gate projection is
 // neither stored nor read back and the activation panel is fetched once for the two products.
-template <int NJ, bool FP8, bool DUAL = false>
+// OUT8 (dual form only): the result is written as OCP e4m3 bytes, out_inv * silu(alpha * gate) *
+// (alpha2 * up) rounded to the nearest code, the SwiGLU output of the fp8 block quantised where it
+// is produced; C then points at bytes.
+template <int NJ, bool FP8, bool DUAL = false, bool OUT8 = false>
 __device__ __forceinline__ void gemm_tile(const char* __restrict__ A, const char* __restrict__ Wt,
                                           const char* __restrict__ Wt2, uint16_t* __restrict__ C,
                                           const uint16_t* __restrict__ R, int M, int N, int K, float alpha,
                                           int tiles_m, int tiles_n, int epi, char* lds, const int lane,
-                                          const int wave) {
-    static_assert(!DUAL || (!FP8 && (NJ == 8 || NJ == 4)), "dual form: bf16, 8 or 4 weight blocks per wave");
+                                          const int wave, float alpha2 = 1.0f, float out_inv = 1.0f) {
+    static_assert(!DUAL || NJ == 8 || NJ == 4, "dual form: 8 or 4 weight blocks per wave");
+    static_assert(!OUT8 || DUAL, "e4m3 output exists in the dual form only");
     const int wm = wave >> 1, wn = wave & 1;
 
     // XCD-aware tile id: workgroup ids are dealt round-robin to the 8 XCDs; give each XCD a
@@ -478,14 +483,19 @@ __device__ __forceinline__ void gemm_tile(const char* __restrict__ A, const char
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     const float gte = alpha * acc_read(acc[j][i][e]);
-                    const float upv = alpha * acc_read(acc[j + NJ / 2][i][e]);
+                    const float upv = (DUAL && OUT8 ? alpha2 : alpha) * acc_read(acc[j + NJ / 2][i][e]);
                     o[e] = gte / (1.0f + __expf(-gte)) * upv;
                 }
                 if (m < M && n < N) {
-                    uint2 v;
-                    v.x = pack_bf16x2(o[0], o[1]);
-                    v.y = pack_bf16x2(o[2], o[3]);
-                    *reinterpret_cast<uint2*>(C + (size_t)m * N + n) = v;
+                    if constexpr (OUT8) {
+                        *reinterpret_cast<uint32_t*>(reinterpret_cast<uint8_t*>(C) + (size_t)m * N + n) =
+                            pack_e4m3x4(o[0] * out_inv, o[1] * out_inv, o[2] * out_inv, o[3] * out_inv);
+                    } else {
+                        uint2 v;
+                        v.x = pack_bf16x2(o[0], o[1]);
+                        v.y = pack_bf16x2(o[2], o[3]);
+                        *reinterpret_cast<uint2*>(C + (size_t)m * N + n) = v;
+                    }
                 }
             }
         }
@@ -551,6 +561,20 @@ __global__ __launch_bounds__(256, 1) void gemm_swiglu_kernel(const char* __restr
     __builtin_amdgcn_s_setprio(3);
     gemm_tile<NJ, false, true>(A, Wg, Wu, C, nullptr, M, N, K, 1.0f, tiles_m, tiles_n, EPI_ADD, lds,
                                threadIdx.x & 63, __builtin_amdgcn_readfirstlane(threadIdx.x >> 6));
+}
+
+// The same for the fp8 block: e4m3 activations and weights (alpha_g, alpha_u: activation scale times
+// the weight's scale), e4m3 result, out_inv = 1 / (the result's dequantisation scale).
+template <int NJ>
+__global__ __launch_bounds__(256, 1) void gemm_swiglu_fp8_kernel(const char* __restrict__ A, const char* __restrict__ Wg,
+                                                                const char* __restrict__ Wu, uint8_t* __restrict__ C,
+                                                                int M, int N, int K, int tiles_m, int tiles_n,
+                                                                float alpha_g, float alpha_u, float out_inv) {
+    extern __shared__ __attribute__((aligned(1024))) char lds[];
+    __builtin_amdgcn_s_setprio(3);
+    gemm_tile<NJ, true, true, true>(A, Wg, Wu, reinterpret_cast<uint16_t*>(C), nullptr, M, N, K, alpha_g, tiles_m, tiles_n,
+                                    EPI_ADD, lds, threadIdx.x & 63, __builtin_amdgcn_readfirstlane(threadIdx.x >> 6),
+                                    alpha_u, out_inv);
 }
 
 // Wave-specialised GEMM + RNG (paper Sec. 6.1 names this form beside the two-kernel one): a
@@ -678,6 +702,41 @@ int check_gemm_rng(const void* A, const void* Bm, const void* C, int M, int N, i
     const long double wd = (long double)B * H * Tt * Tt * 16.0L;
     if (wd > 1099511627776.0L) return ROV_ERR_UNSUPPORTED;
     if ((long long)((M + BM - 1) / BM) * ((N + 127) / 128) > 0x7FFFFFFFLL) return ROV_ERR_UNSUPPORTED;
+    return ROV_OK;
+}
+
+int check_gemm_swiglu_fp8(const void* A, const void* Wg, const void* Wu, const void* C, int M, int N, int K,
+                          float scaleC) {
+    if (A == nullptr || Wg == nullptr || Wu == nullptr || C == nullptr || M <= 0 || N <= 0 || K <= 0)
+        return ROV_ERR_INVALID;
+    if (!aligned(A, 16) || !aligned(Wg, 16) || !aligned(Wu, 16) || !aligned(C, 4)) return ROV_ERR_INVALID;
+    if (!(scaleC > 0.0f)) return ROV_ERR_INVALID;
+    if (((size_t)K) % kRowBytes != 0 || (N % 4) != 0) return ROV_ERR_UNSUPPORTED;
+    if ((unsigned long long)BM * (unsigned long long)K > 0xFFFFFFFFull) return ROV_ERR_UNSUPPORTED;
+    if ((long long)((M + BM - 1) / BM) * ((N + 63) / 64) > 0x7FFFFFFFLL) return ROV_ERR_UNSUPPORTED;
+    return ROV_OK;
+}
+
+int launch_gemm_swiglu_fp8(const void* A, const void* Wg, const void* Wu, void* C, int M, int N, int K,
+                           float scaleA, float scaleWg, float scaleWu, float scaleC, hipStream_t stream) {
+    {
+        const int rc = check_gemm_swiglu_fp8(A, Wg, Wu, C, M, N, K, scaleC);
+        if (rc != ROV_OK) return rc;
+    }
+    const long long tiles_m = (M + BM - 1) / BM, ncu = device_cu_count();
+    const long long t8 = tiles_m * ((N + 127) / 128), t4 = tiles_m * ((N + 63) / 64);
+    const bool wide = ((t8 + ncu - 1) / ncu) * 9 <= ((t4 + ncu - 1) / ncu) * 5;
+    const long long T = wide ? t8 : t4;
+    typedef void (*kern_t)(const char*, const char*, const char*, uint8_t*, int, int, int, int, int, float, float, float);
+    const kern_t kern = wide ? (kern_t)gemm_swiglu_fp8_kernel<8> : (kern_t)gemm_swiglu_fp8_kernel<4>;
+    {
+        const int rc = set_max_dynamic_lds((const void*)kern, kLdsBytes);
+        if (rc != ROV_OK) return rc;
+    }
+    hipLaunchKernelGGL(kern, dim3((unsigned)T), dim3(256), kLdsBytes, stream, (const char*)A, (const char*)Wg,
+                       (const char*)Wu, (uint8_t*)C, M, N, K, (int)tiles_m, (int)(T / tiles_m), scaleA * scaleWg,
+                       scaleA * scaleWu, 1.0f / scaleC);
+    ROV_LAUNCH_CHECK();
     return ROV_OK;
 }
 

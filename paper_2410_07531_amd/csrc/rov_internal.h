@@ -84,12 +84,20 @@ int launch_attention(const void* Q, const void* K, const void* V, void* O, int B
 int launch_attention_rows(const void* Q, const void* K, const void* V, void* O, int B, int H, int Hkv,
                           int S, int d, const int64_t strides[12], int dtype, int causal, float p,
                           const uint64_t* mask, bool mask_is_rows, uint64_t seed, uint64_t offset,
-                          int q_begin, int q_rows, hipStream_t stream, int rounds = 10, int bits = 32);
+                          int q_begin, int q_rows, hipStream_t stream, int rounds = 10, int bits = 32,
+                          float o_fp8_scale = 0.0f /* > 0: O holds OCP e4m3 bytes of (value / o_fp8_scale), its
+                                                      strides count bytes (bf16 inputs, head dimension 64 or 128) */);
 
 // C[M,N] = silu(A Wg^T) * (A Wu^T), bf16 with fp32 accumulation: the two products of a SwiGLU in one
 // kernel (both weight matrices [N,K], K % 64 == 0, N % 4 == 0).
 int launch_gemm_swiglu(const void* A, const void* Wg, const void* Wu, void* C, int M, int N, int K,
                        hipStream_t stream);
+// The same with e4m3 operands and an e4m3 result (the fp8 block's FC1): C = q(silu(sA sWg A Wg^T) *
+// (sA sWu A Wu^T) / scaleC), bytes [M,N]; K % 128 == 0, N % 4 == 0.
+int launch_gemm_swiglu_fp8(const void* A, const void* Wg, const void* Wu, void* C, int M, int N, int K,
+                           float scaleA, float scaleWg, float scaleWu, float scaleC, hipStream_t stream);
+int check_gemm_swiglu_fp8(const void* A, const void* Wg, const void* Wu, const void* C, int M, int N, int K,
+                          float scaleC);
 // One kernel whose workgroups compute a tile of the bf16 GEMM with four waves while four more
 // waves generate keep-mask chunks pulled from queue slot `qslot` (paper Sec. 6.1: the single-kernel,
 // wave-specialised form of the overlap).  S % 32 == 0; what the RNG waves do not get to stays in
@@ -111,6 +119,9 @@ int check_gemm_rng(const void* A, const void* Bm, const void* C, int M, int N, i
 
 int launch_rmsnorm(const void* x, const void* weight, void* y, int64_t rows, int n, float eps,
                    hipStream_t stream);
+// y8 (bytes, [rows, n]) = e4m3(RMSNorm(x) * weight / scale): the fp8 block's quantised activations.
+int launch_rmsnorm_fp8(const void* x, const void* weight, void* y8, int64_t rows, int n, float eps, float scale,
+                       hipStream_t stream);
 int launch_rope(void* buf, int64_t tokens, int64_t row_elems, int S, int nheads, int d, float theta,
                 hipStream_t stream);
 

@@ -319,6 +319,11 @@ extern "C" int rov_gemm_swiglu(const void* A, const void* Wg, const void* Wu, vo
     return rov::launch_gemm_swiglu(A, Wg, Wu, C, M, N, K, (hipStream_t)stream);
 }
 
+extern "C" int rov_gemm_swiglu_fp8(const void* A, const void* Wg, const void* Wu, void* C, int M, int N, int K,
+                                   float scaleA, float scaleWg, float scaleWu, float scaleC, void* stream) {
+    return rov::launch_gemm_swiglu_fp8(A, Wg, Wu, C, M, N, K, scaleA, scaleWg, scaleWu, scaleC, (hipStream_t)stream);
+}
+
 extern "C" int rov_gemm_rng_fused(const void* A, const void* Bm, void* C, int M, int N, int K, uint64_t seed,
                                   uint64_t offset, int B, int H, int S, float p, uint64_t* mask, void* stream) {
     hipStream_t st = (hipStream_t)stream;
@@ -513,10 +518,24 @@ int block_forward_impl(const rov_block_weights* w, const void* x, void* y, int B
     if ((cfg->H % cfg->Hkv) != 0 || !(cfg->p >= 0.0f) || !(cfg->p < 1.0f) || !(cfg->eps > 0.0f) ||
         !(cfg->rope_theta > 0.0f))
         return ROV_ERR_INVALID;
-    if (cfg->dtype != ROV_BF16)
-        return (cfg->dtype == ROV_F32 || cfg->dtype == ROV_FP8_E4M3) ? ROV_ERR_UNSUPPORTED : ROV_ERR_INVALID;
+    if (cfg->dtype != ROV_BF16 && cfg->dtype != ROV_FP8_E4M3)
+        return cfg->dtype == ROV_F32 ? ROV_ERR_UNSUPPORTED : ROV_ERR_INVALID;
+    const bool f8 = cfg->dtype == ROV_FP8_E4M3;
+    const int dt = cfg->dtype;
     if ((cfg->d != 64 && cfg->d != 128) || (cfg->hidden % 64) != 0 || (cfg->ffn % 64) != 0)
         return ROV_ERR_UNSUPPORTED;
+    if (f8) {
+        if ((cfg->hidden % 128) != 0 || (cfg->ffn % 128) != 0 || ((cfg->H * cfg->d) % 128) != 0) return ROV_ERR_UNSUPPORTED;
+        for (int i = 0; i < 4; ++i)
+            if (!(cfg->act_scale[i] > 0.0f)) return ROV_ERR_INVALID;
+        for (int i = 0; i < 5; ++i)
+            if (!(w->w_scale[i] > 0.0f)) return ROV_ERR_INVALID;
+    }
+    // fp8: per-tensor dequantisation scales of the quantised activations (h1, a, h2, u) and the weights
+    const float sa0 = f8 ? cfg->act_scale[0] : 1.0f, sa1 = f8 ? cfg->act_scale[1] : 1.0f;
+    const float sa2 = f8 ? cfg->act_scale[2] : 1.0f, sa3 = f8 ? cfg->act_scale[3] : 1.0f;
+    const float sw_qkv = f8 ? w->w_scale[0] : 1.0f, sw_o = f8 ? w->w_scale[1] : 1.0f, sw_g = f8 ? w->w_scale[2] : 1.0f;
+    const float sw_u = f8 ? w->w_scale[3] : 1.0f, sw_d = f8 ? w->w_scale[4] : 1.0f;
     if (workspace == nullptr || !aligned(workspace, 256)) return ROV_ERR_INVALID;
     if (workspace_bytes < L.total) return ROV_ERR_WORKSPACE;
     const bool dropout = cfg->p > 0.0f;
@@ -546,7 +565,11 @@ int block_forward_impl(const rov_block_weights* w, const void* x, void* y, int B
         (int64_t)S * qkv_n, qkv_n, d,      // Q
         (int64_t)S * qkv_n, qkv_n, d,      // K
         (int64_t)S * qkv_n, qkv_n, d,      // V
-        (int64_t)S * H * d, (int64_t)H * d, d};   // O
+        (int64_t)S * H * d, (int64_t)H * d, d};   // O (elements: bf16, or bytes when fp8)
+    // fp8: the attention output is quantised in the attention kernel's epilogue and lives, as bytes, in
+    // the slot of the SwiGLU output (free until FC1 runs, after the PROJ GEMM has consumed it)
+    void* att_out = f8 ? u : att;
+    const float att_q = f8 ? sa1 : 0.0f;
     int rc = ROV_OK;
     // every kernel of the block is checked before the first one is enqueued
 #define ROV_STEP(expr)            \
@@ -555,11 +578,14 @@ int block_forward_impl(const rov_block_weights* w, const void* x, void* y, int B
         if (rc != ROV_OK) return rc; \
     } while (0)
     if ((hidden % 8) != 0 || (d % 8) != 0) return ROV_ERR_UNSUPPORTED;   // RMSNorm / RoPE vector width
-    ROV_STEP(check_gemm(h, w->wqkv, qkv, nullptr, EPI_ADD, (int)T, qkv_n, hidden, ROV_BF16, 1));
-    ROV_STEP(check_gemm(att, w->wo, x2, x, EPI_ADD, (int)T, hidden, H * d, ROV_BF16, 1));
-    ROV_STEP(check_gemm_swiglu(h, w->wg, w->wu, u, (int)T, ffn, hidden));
-    ROV_STEP(check_gemm(u, w->wd, y, x2, EPI_ADD, (int)T, hidden, ffn, ROV_BF16, 1));
-    ROV_STEP(check_attention_rows(qp, qp + (int64_t)H * d, qp + (int64_t)(H + Hkv) * d, att, B, H, Hkv, S, d, strides,
+    ROV_STEP(check_gemm(h, w->wqkv, qkv, nullptr, EPI_ADD, (int)T, qkv_n, hidden, dt, 1));
+    ROV_STEP(check_gemm(att_out, w->wo, x2, x, EPI_ADD, (int)T, hidden, H * d, dt, 1));
+    if (f8)
+        ROV_STEP(check_gemm_swiglu_fp8(h, w->wg, w->wu, u, (int)T, ffn, hidden, sa3));
+    else
+        ROV_STEP(check_gemm_swiglu(h, w->wg, w->wu, u, (int)T, ffn, hidden));
+    ROV_STEP(check_gemm(u, w->wd, y, x2, EPI_ADD, (int)T, hidden, ffn, dt, 1));
+    ROV_STEP(check_attention_rows(qp, qp + (int64_t)H * d, qp + (int64_t)(H + Hkv) * d, att_out, B, H, Hkv, S, d, strides,
                                   ROV_BF16, cfg->p, use_mask ? mask : nullptr, 0, S, 10, 32));
     if (use_mask) ROV_STEP(check_mask(B, H, S, cfg->p, 10, 32, mask));
     if (next_mask != nullptr) ROV_STEP(check_mask(B, H, S, cfg->p, 10, 32, next_mask));
@@ -576,13 +602,16 @@ int block_forward_impl(const rov_block_weights* w, const void* x, void* y, int B
     int qslot = -1;
     const double mask_calls = (double)rov_mask_philox_calls(B, H, S) * (cfg->causal ? 0.5 : 1.0);
     if (use_mask && !mask_ready && overlap) {
-        if (!rng_fits_beside(gemm_flop((int)((int64_t)B * S), (cfg->H + 2 * cfg->Hkv) * cfg->d, cfg->hidden), ROV_BF16,
+        if (!rng_fits_beside(gemm_flop((int)((int64_t)B * S), (cfg->H + 2 * cfg->Hkv) * cfg->d, cfg->hidden), dt,
                              mask_calls))
             ROV_STEP(mask_queue_acquire(ms, &qslot));
         ROV_STEP(side.fork());
     }
-    ROV_STEP(traced(ROV_TRACE_GLUE, ms, [&] { return launch_rmsnorm(x, w->norm1, h, T, hidden, cfg->eps, ms); }));
-    ROV_STEP(t_gemm(h, w->wqkv, qkv, nullptr, (int)T, qkv_n, hidden, ROV_BF16, 1, 1.0f, 1.0f, ms));
+    ROV_STEP(traced(ROV_TRACE_GLUE, ms, [&] {
+        return f8 ? launch_rmsnorm_fp8(x, w->norm1, h, T, hidden, cfg->eps, sa0, ms)
+                  : launch_rmsnorm(x, w->norm1, h, T, hidden, cfg->eps, ms);
+    }));
+    ROV_STEP(t_gemm(h, w->wqkv, qkv, nullptr, (int)T, qkv_n, hidden, dt, 1, sa0, sw_qkv, ms));
     if (use_mask && !mask_ready) {
         if (overlap && R < S) {   // hybrid: the first R rows only, compact
             ROV_STEP(traced(ROV_TRACE_RNG, ss, [&] {
@@ -613,20 +642,20 @@ int block_forward_impl(const rov_block_weights* w, const void* x, void* y, int B
     if (hybrid && R < S) {
         if (R > 0)
             ROV_STEP(traced(ROV_TRACE_ATTENTION, ms, [&] {
-                return launch_attention_rows(qp, qp + (int64_t)H * d, qp + (int64_t)(H + Hkv) * d, att, B, H, Hkv, S,
+                return launch_attention_rows(qp, qp + (int64_t)H * d, qp + (int64_t)(H + Hkv) * d, att_out, B, H, Hkv, S,
                                              d, strides, ROV_BF16, cfg->causal, cfg->p, mask, true, seed, offset, 0,
-                                             R, ms);
+                                             R, ms, 10, 32, att_q);
             }));
         ROV_STEP(traced(ROV_TRACE_ATTENTION, ms, [&] {
-            return launch_attention_rows(qp, qp + (int64_t)H * d, qp + (int64_t)(H + Hkv) * d, att, B, H, Hkv, S, d,
+            return launch_attention_rows(qp, qp + (int64_t)H * d, qp + (int64_t)(H + Hkv) * d, att_out, B, H, Hkv, S, d,
                                          strides, ROV_BF16, cfg->causal, cfg->p, nullptr, false, seed, offset, R,
-                                         S - R, ms);
+                                         S - R, ms, 10, 32, att_q);
         }));
     } else {
         ROV_STEP(traced(ROV_TRACE_ATTENTION, ms, [&] {
-            return launch_attention(qp, qp + (int64_t)H * d, qp + (int64_t)(H + Hkv) * d, att, B, H, Hkv, S,
-                                    d, strides, ROV_BF16, cfg->causal, cfg->p, use_mask ? mask : nullptr,
-                                    seed, offset, ms);
+            return launch_attention_rows(qp, qp + (int64_t)H * d, qp + (int64_t)(H + Hkv) * d, att_out, B, H, Hkv, S,
+                                         d, strides, ROV_BF16, cfg->causal, cfg->p, use_mask ? mask : nullptr, false,
+                                         seed, offset, 0, S, ms, 10, 32, att_q);
         }));
     }
 
@@ -638,10 +667,10 @@ int block_forward_impl(const rov_block_weights* w, const void* x, void* y, int B
         const double rest = gemm_flop((int)T, hidden, H * d) + 2.0 * gemm_flop((int)T, ffn, hidden) +
                             gemm_flop((int)T, hidden, ffn);
         // (hybrid with R < S: the rows were chosen to fit, no queue and no helper launch)
-        if (R == S && !rng_fits_beside(rest, ROV_BF16, mask_calls)) ROV_STEP(mask_queue_acquire(ms, &qslot_next));
+        if (R == S && !rng_fits_beside(rest, dt, mask_calls)) ROV_STEP(mask_queue_acquire(ms, &qslot_next));
         ROV_STEP(side.fork());
     }
-    ROV_STEP(t_gemm(att, w->wo, x2, x, (int)T, hidden, H * d, ROV_BF16, 1, 1.0f, 1.0f, ms));
+    ROV_STEP(t_gemm(att_out, w->wo, x2, x, (int)T, hidden, H * d, dt, 1, sa1, sw_o, ms));
     if (run_ahead) {
         if (R < S)
             ROV_STEP(traced(ROV_TRACE_RNG, ss, [&] {
@@ -653,13 +682,17 @@ int block_forward_impl(const rov_block_weights* w, const void* x, void* y, int B
                             MASK_GRID_BESIDE, qslot_next, cfg->causal != 0));
         ROV_STEP(side.mark());
     }
-    ROV_STEP(traced(ROV_TRACE_GLUE, ms, [&] { return launch_rmsnorm(x2, w->norm2, h, T, hidden, cfg->eps, ms); }));
-    // gate and up projections as one product with the SwiGLU in its epilogue: u = silu(h Wg^T) * (h Wu^T),
-    // the gate never leaves the accumulators and h is fetched once for both
-    ROV_STEP(traced(ROV_TRACE_GEMM, ms, [&] {
-        return launch_gemm_swiglu(h, w->wg, w->wu, u, (int)T, ffn, hidden, ms);
+    ROV_STEP(traced(ROV_TRACE_GLUE, ms, [&] {
+        return f8 ? launch_rmsnorm_fp8(x2, w->norm2, h, T, hidden, cfg->eps, sa2, ms)
+                  : launch_rmsnorm(x2, w->norm2, h, T, hidden, cfg->eps, ms);
     }));
-    ROV_STEP(t_gemm(u, w->wd, y, x2, (int)T, hidden, ffn, ROV_BF16, 1, 1.0f, 1.0f, ms));
+    // gate and up projections as one product with the SwiGLU in its epilogue: u = silu(h Wg^T) * (h Wu^T),
+    // the gate never leaves the accumulators and h is fetched once for both (fp8: u leaves quantised)
+    ROV_STEP(traced(ROV_TRACE_GEMM, ms, [&] {
+        return f8 ? launch_gemm_swiglu_fp8(h, w->wg, w->wu, u, (int)T, ffn, hidden, sa2, sw_g, sw_u, sa3, ms)
+                  : launch_gemm_swiglu(h, w->wg, w->wu, u, (int)T, ffn, hidden, ms);
+    }));
+    ROV_STEP(t_gemm(u, w->wd, y, x2, (int)T, hidden, ffn, dt, 1, sa3, sw_d, ms));
     if (run_ahead) {
         // what is left of the next mask when the last GEMM ends is finished at full speed
         if (qslot_next >= 0)

@@ -291,3 +291,59 @@ def test_gemm_fp8_llama70b_qkv_sampled():
     # reported only: distance to the unquantised product
     full = OD.gemm(a[rows].astype(np.float64), w.astype(np.float64), transB=True)
     print("fp8 vs unquantised product: rel err %.4f" % (np.max(np.abs(Ch[rows] - full)) / np.max(np.abs(full))), flush=True)
+
+
+@pytest.mark.parametrize("M,N,K", [
+    (256, 128, 128),        # one 128-column tile, one k-step
+    (600, 1000, 896),       # ragged rows and columns, odd number of k-steps
+    (300, 72, 384),         # fewer columns than one wave's half of a 64-column tile
+    (512, 4096, 256),       # 64 tiles of 128 columns
+])
+def test_gemm_swiglu_fp8_codes_match_oracle(M, N, K):
+    # e4m3( silu(sA sWg A Wg^T) * (sA sWu A Wu^T) / sC ): the codes the kernel writes against the
+    # oracle's nearest-code choice on the float64 value.  The kernel takes the decision on its own
+    # fp32 value (matrix-core accumulation of sums with cancelling terms, fast exponential), which is
+    # the exact one up to about 3e-5 of the output scale: where the codes differ (few places), the
+    # kernel's code must be as close to the exact value as the best code up to twice that bound.
+    from oracle import numerics as ON
+    print("gemm swiglu fp8", M, N, K, flush=True)
+    rng = np.random.default_rng(5 * M + N + K)
+    a, wg = wl.gemm_operands(rng, M, K, N)
+    _, wu = wl.gemm_operands(rng, M, K, N)
+    Aq, sa = _quantise(a)
+    Gq, sg = _quantise(wg * np.float32(40.0))      # gate values of order 1: the silu's curve matters
+    Uq, su = _quantise(wu * np.float32(40.0))
+    g = sa * sg * OD.gemm(ON.e4m3_decode(Aq.numpy()), ON.e4m3_decode(Gq.numpy()), transB=True)
+    u = sa * su * OD.gemm(ON.e4m3_decode(Aq.numpy()), ON.e4m3_decode(Uq.numpy()), transB=True)
+    v = OD.silu(g) * u
+    sc = float(np.float32(np.max(np.abs(v)) / 600.0))          # the largest values saturate at 448
+    C = rov.gemm_swiglu_fp8(Aq.cuda(), Gq.cuda(), Uq.cuda(), sa, sg, su, sc)
+    torch.cuda.synchronize()
+    got = C.cpu().numpy()
+    exp = ON.e4m3_encode(v / sc)
+    assert np.any((exp & 0x7F) == 0x7E)                        # saturation is exercised
+    same = (got == exp) | (((got | exp) & 0x7F) == 0)          # +0 and -0 are the same value
+    bad = ~same
+    assert bad.mean() <= 1e-2, bad.mean()
+    dg, de = ON.e4m3_decode(got[bad]), ON.e4m3_decode(exp[bad])
+    x = (v / sc)[bad]
+    eps = 3e-5 * np.max(np.abs(v / sc))
+    assert np.all(np.abs(dg - x) <= np.abs(de - x) + 2 * eps), np.max(np.abs(dg - x) - np.abs(de - x)) / eps
+    ref = np.clip(v / sc, -448, 448)
+    assert np.max(np.abs(ON.e4m3_decode(got) - ref)) / np.max(np.abs(ref)) <= FP8_TOL
+    # gate and up are not interchangeable
+    C2 = rov.gemm_swiglu_fp8(Aq.cuda(), Uq.cuda(), Gq.cuda(), sa, su, sg, sc)
+    torch.cuda.synchronize()
+    assert (C2.cpu().numpy() != exp).mean() > 0.5
+
+
+def test_gemm_swiglu_fp8_error_paths():
+    A = torch.zeros((256, 128), dtype=torch.uint8, device="cuda")
+    W = torch.zeros((128, 128), dtype=torch.uint8, device="cuda")
+    for kw, code in ((dict(scaleC=0.0), rov.ERR_INVALID), (dict(scaleC=-1.0), rov.ERR_INVALID)):
+        with pytest.raises(rov.RovError) as e:
+            rov.gemm_swiglu_fp8(A, W, W, 1.0, 1.0, 1.0, kw["scaleC"])
+        assert e.value.code == code
+    with pytest.raises(rov.RovError) as e:      # K not a multiple of 128
+        rov.gemm_swiglu_fp8(A[:, :64].contiguous(), W[:, :64].contiguous(), W[:, :64].contiguous(), 1.0, 1.0, 1.0, 1.0)
+    assert e.value.code == rov.ERR_UNSUPPORTED

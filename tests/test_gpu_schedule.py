@@ -432,3 +432,144 @@ def test_block_workspace_and_argument_errors():
         rov.block_forward(weights, x, y, cfg, rov.SCHED_SEQUENTIAL, 1, 0, mask, ws, s1, s2, next_mask=mask.clone())
     torch.cuda.synchronize()
     assert bool((y == 5.0).all())
+
+
+@pytest.mark.parametrize("causal", [False, True])
+def test_block_forward_fp8_matches_oracle(causal):
+    # fp8 block: e4m3 weights with per-tensor scales, the four activations quantised where they are
+    # produced (normalisation kernel, attention epilogue, FC1 epilogue); against the oracle's fp8 block
+    from oracle import numerics as ON
+    B, S, H, Hkv, d, hidden, ffn = 1, 256, 4, 2, 128, 512, 1024
+    p, seed, offset = 0.1, wl.SEED, 1920
+    rng = np.random.default_rng(27)
+    w = wl.block_weights(rng, H, Hkv, d, hidden, ffn)
+    w["norm1"] = (1.0 + 0.1 * rng.standard_normal(hidden)).astype(np.float32)
+    w["norm2"] = (1.0 + 0.1 * rng.standard_normal(hidden)).astype(np.float32)
+    x = wl.block_input(rng, B, S, hidden)
+    wq, ws, wdev = {}, {}, {}
+    for name in ("wqkv", "wo", "wg", "wu", "wd"):
+        wq[name], ws[name] = ON.e4m3_quantise(w[name] * np.float32(3.0))    # sd 0.06: every stage stays visible
+        wdev[name] = torch.from_numpy(wq[name]).cuda()
+    for name in ("norm1", "norm2"):
+        wdev[name] = _dev(w[name])
+        wq[name] = _f64(wdev[name])
+    X = _dev(x)
+    act = [float(np.float32(v)) for v in (6.0 / 448.0, 6.0 / 448.0, 6.0 / 448.0, 16.0 / 448.0)]
+    cfg = rov.make_block_cfg(H, Hkv, d, hidden, ffn, p, causal=causal, dtype=rov.FP8_E4M3, act_scale=act)
+    weights = rov.make_block_weights(wdev, ws)
+    wsb = torch.empty(rov.block_workspace_bytes(cfg, B, S, 0), dtype=torch.uint8, device="cuda")
+    main, side = torch.cuda.Stream(), torch.cuda.Stream()
+    ys = {}
+    for name, sched, ready in (("seq", rov.SCHED_SEQUENTIAL, False), ("fused", rov.SCHED_FUSED, False),
+                               ("ovl_first", rov.SCHED_OVERLAP, False), ("ovl_steady", rov.SCHED_OVERLAP, True)):
+        print("fp8 block", name, causal, flush=True)
+        y = torch.zeros_like(X)
+        mask = torch.zeros(rov.mask_shape(B, H, S), dtype=torch.int64, device="cuda")
+        nxt = torch.zeros_like(mask) if name == "ovl_steady" else None
+        if ready:
+            rov.dropout_mask_generate(seed, offset, B, H, S, p, out=mask)
+        torch.cuda.synchronize()
+        rov.block_forward(weights, X, y, cfg, sched, seed, offset, None if sched == rov.SCHED_FUSED else mask,
+                          wsb, main, side, mask_ready=ready, next_mask=nxt)
+        torch.cuda.synchronize()
+        ys[name] = y
+    for name in ("fused", "ovl_first", "ovl_steady"):
+        assert torch.equal(ys["seq"], ys[name]), name
+    keep = OP.unpack_keep(OP.dropout_mask(seed, offset, B, H, S, p), S)
+    ocfg = dict(H=H, Hkv=Hkv, d=d, eps=1e-5, rope_theta=500000.0, p=p, causal=causal)
+    ref = OD.block_forward_fp8(_f64(X), wq, ws, act, ocfg, keep)
+    got = _f64(ys["seq"])
+    # Tolerance of the fp8 block (derived, not the single-GEMM bar): two faithful evaluations differ
+    # upstream by rounding (bf16 probabilities inside attention, fp32 against float64), and every
+    # quantiser turns a relative difference delta into a different code for about delta / 2^-4 of its
+    # elements, each then off by one code step (2^-3 of its value at most); the flips compound through
+    # the three quantisers that follow attention (measured: 11 % of the h2 codes, 40 % of the u codes).
+    # The result carries noise of the size of the quantisation noise itself: a few percent of the
+    # output's rms, up to about 5 % of its maximum over 10^5 outputs.
+    err = np.max(np.abs(got - ref)) / np.max(np.abs(ref))
+    rms = np.sqrt(np.mean((got - ref) ** 2)) / np.sqrt(np.mean(ref ** 2))
+    print("fp8 block error: max", err, "rms", rms, flush=True)
+    assert err <= 8e-2 and rms <= 6e-2, (err, rms)
+    # not the identity, and not the block without activation quantisation
+    assert np.max(np.abs(ref - _f64(X))) / np.max(np.abs(ref)) > 0.1
+
+
+def test_block_forward_fp8_quantisers_on_structured_weights():
+    # Every quantiser and scale of the fp8 block, checked tightly: weights chosen so that everything
+    # upstream of a quantiser is exact on both sides and no code can flip through rounding noise.
+    # Wq = Wk = 0 (uniform attention: probabilities 1/S, exact in bf16), Wv and Wo pick single features
+    # (one e4m3 code 1.0 per row), power-of-two scales: q|k|v, the attention output's codes and the
+    # residual stream x2 are then identical on both sides, and RMSNorm / FC1 / FC2 see identical inputs.
+    from oracle import numerics as ON
+    B, S, H, Hkv, d, hidden, ffn = 1, 256, 4, 2, 128, 512, 1024
+    p, seed, offset = 0.1, wl.SEED, 2560
+    rng = np.random.default_rng(29)
+    w = wl.block_weights(rng, H, Hkv, d, hidden, ffn)
+    x = wl.block_input(rng, B, S, hidden)
+    one = 0x38                                                     # e4m3 code of 1.0
+    qkv_n = (H + 2 * Hkv) * d
+    wqkv = np.zeros((qkv_n, hidden), dtype=np.uint8)
+    vrows = np.arange((H + Hkv) * d, qkv_n)
+    wqkv[vrows, rng.permutation(hidden)[: len(vrows)]] = one       # v feature r = one feature of h1
+    wo = np.zeros((hidden, H * d), dtype=np.uint8)
+    wo[np.arange(hidden), rng.permutation(H * d)[:hidden] if H * d >= hidden else rng.integers(0, H * d, hidden)] = one
+    wq = {"wqkv": wqkv, "wo": wo}
+    ws = {"wqkv": 1.0, "wo": 1.0}
+    for name in ("wg", "wu", "wd"):
+        wq[name], ws[name] = ON.e4m3_quantise(w[name] * np.float32(3.0))
+    wdev = {n: torch.from_numpy(wq[n]).cuda() for n in ("wqkv", "wo", "wg", "wu", "wd")}
+    for name in ("norm1", "norm2"):
+        wn = (1.0 + 0.1 * rng.standard_normal(hidden)).astype(np.float32)
+        wdev[name] = _dev(wn)
+        wq[name] = _f64(wdev[name])
+    X = _dev(x)
+    act = [2.0 ** -6, 2.0 ** -8, 2.0 ** -6, 2.0 ** -5]             # h1 up to 7, a (a mean) well below 1.75, h2 up to 7, u up to 14
+    cfg = rov.make_block_cfg(H, Hkv, d, hidden, ffn, p, causal=False, dtype=rov.FP8_E4M3, act_scale=act)
+    wsb = torch.empty(rov.block_workspace_bytes(cfg, B, S, 0), dtype=torch.uint8, device="cuda")
+    main, side = torch.cuda.Stream(), torch.cuda.Stream()
+    y = torch.zeros_like(X)
+    mask = torch.zeros(rov.mask_shape(B, H, S), dtype=torch.int64, device="cuda")
+    torch.cuda.synchronize()
+    rov.block_forward(rov.make_block_weights(wdev, ws), X, y, cfg, rov.SCHED_OVERLAP, seed, offset, mask, wsb, main, side)
+    torch.cuda.synchronize()
+    keep = OP.unpack_keep(OP.dropout_mask(seed, offset, B, H, S, p), S)
+    ocfg = dict(H=H, Hkv=Hkv, d=d, eps=1e-5, rope_theta=500000.0, p=p, causal=False)
+    ref = OD.block_forward_fp8(_f64(X), wq, ws, act, ocfg, keep)
+    got = _f64(y)
+    err = np.max(np.abs(got - ref)) / np.max(np.abs(ref))
+    rms = np.sqrt(np.mean((got - ref) ** 2)) / np.sqrt(np.mean(ref ** 2))
+    print("fp8 block, structured weights: max", err, "rms", rms, flush=True)
+    assert err <= 2e-2 and rms <= 3e-3, (err, rms)
+    # the quantisers matter at this tolerance: the same block without them is much further away
+    noq = OD.block_forward(_f64(X), {n: (ON.e4m3_decode(wq[n]) * ws[n] if n in ws else wq[n]) for n in wq}, ocfg, keep)
+    assert np.max(np.abs(noq - ref)) / np.max(np.abs(ref)) > 4 * max(err, 5e-3)
+
+
+def test_block_forward_fp8_error_paths():
+    B, S, H, Hkv, d, hidden, ffn = 1, 64, 2, 1, 128, 256, 256
+    wdev = {n: torch.zeros(s_, dtype=torch.uint8, device="cuda") for n, s_ in
+            (("wqkv", ((H + 2 * Hkv) * d, hidden)), ("wo", (hidden, H * d)), ("wg", (ffn, hidden)),
+             ("wu", (ffn, hidden)), ("wd", (hidden, ffn)))}
+    wdev["norm1"] = torch.ones(hidden, dtype=torch.bfloat16, device="cuda")
+    wdev["norm2"] = torch.ones(hidden, dtype=torch.bfloat16, device="cuda")
+    X = torch.zeros((B, S, hidden), dtype=torch.bfloat16, device="cuda")
+    y = torch.full_like(X, 2.0)
+    main, side = torch.cuda.Stream(), torch.cuda.Stream()
+    good_ws = {n: 1.0 for n in ("wqkv", "wo", "wg", "wu", "wd")}
+    for act, wsc, code in (([1.0, 0.0, 1.0, 1.0], good_ws, rov.ERR_INVALID),
+                           ([1.0] * 4, dict(good_ws, wd=-1.0), rov.ERR_INVALID)):
+        cfg = rov.make_block_cfg(H, Hkv, d, hidden, ffn, 0.1, dtype=rov.FP8_E4M3, act_scale=act)
+        wsb = torch.empty(rov.block_workspace_bytes(cfg, B, S, 0), dtype=torch.uint8, device="cuda")
+        torch.cuda.synchronize()
+        with pytest.raises(rov.RovError) as e:
+            rov.block_forward(rov.make_block_weights(wdev, wsc), X, y, cfg, rov.SCHED_FUSED, 1, 0, None, wsb, main, side)
+        assert e.value.code == code
+    # hidden not a multiple of 128
+    cfg = rov.make_block_cfg(H, Hkv, d, 192, ffn, 0.1, dtype=rov.FP8_E4M3, act_scale=[1.0] * 4)
+    wsb = torch.empty(1 << 22, dtype=torch.uint8, device="cuda")
+    with pytest.raises(rov.RovError) as e:
+        rov.block_forward(rov.make_block_weights(wdev, good_ws), X[:, :, :192].contiguous(), y[:, :, :192].contiguous(),
+                          cfg, rov.SCHED_FUSED, 1, 0, None, wsb, main, side)
+    assert e.value.code == rov.ERR_UNSUPPORTED
+    torch.cuda.synchronize()
+    assert bool((y == 2.0).all())

@@ -215,3 +215,53 @@ def test_workload5_block_s16k_overlap_sampled_rows():
         got = _f64(y[:, rows])
         err = np.max(np.abs(got - ref)) / np.max(np.abs(ref))
         assert err <= 2e-2, err
+
+
+def test_workload4_llama70b_fp8_block_sampled_rows():
+    # the 70B-shaped layer as ONE fp8 block call (hidden 8192, ffn 28672, 64 query / 8 kv heads, S = 8192):
+    # e4m3 weights and activations with per-tensor scales, overlap schedule in steady state; oracle on
+    # sampled token rows (K and V from every token).  Tolerance: the fp8 block's derived one (see
+    # test_block_forward_fp8_matches_oracle).
+    c = wl.CONFIGS[3]
+    B, H, Hkv, S, d, p, hidden, ffn = c["B"], c["H"], c["Hkv"], c["S"], c["d"], c["p"], c["hidden"], c["ffn"]
+    gen = torch.Generator(device="cuda"); gen.manual_seed(1013)
+
+    def quant(t):
+        scale = float(np.float32(float(t.abs().max()) / 448.0))
+        return (t / scale).to(torch.float8_e4m3fn).view(torch.uint8), scale
+
+    wdev, wscale = {}, {}
+    for name, shape in (("wqkv", ((H + 2 * Hkv) * d, hidden)), ("wo", (hidden, H * d)), ("wg", (ffn, hidden)),
+                        ("wu", (ffn, hidden)), ("wd", (hidden, ffn))):
+        wdev[name], wscale[name] = quant(_randn(gen, *shape, sd=0.02, dtype=torch.float32))
+    wdev["norm1"] = torch.ones(hidden, device="cuda", dtype=torch.bfloat16)
+    wdev["norm2"] = torch.ones(hidden, device="cuda", dtype=torch.bfloat16)
+    x = _randn(gen, B, S, hidden)
+    y = torch.zeros_like(x)
+    act = [float(np.float32(v / 448.0)) for v in (6.0, 8.0, 6.0, 32.0)]
+    cfg = rov.make_block_cfg(H, Hkv, d, hidden, ffn, p, dtype=rov.FP8_E4M3, act_scale=act)
+    ws = torch.empty(rov.block_workspace_bytes(cfg, B, S, 0), dtype=torch.uint8, device="cuda")
+    main, side = torch.cuda.Stream(), torch.cuda.Stream()
+    m0 = rov.dropout_mask_generate(wl.SEED, wl.OFFSET, B, H, S, p)
+    m1 = torch.zeros_like(m0)
+    torch.cuda.synchronize()
+    print("cfg4 fp8 block", flush=True)
+    rov.block_forward(rov.make_block_weights(wdev, wscale), x, y, cfg, rov.SCHED_OVERLAP, wl.SEED, wl.OFFSET, m0, ws,
+                      main, side, mask_ready=True, next_mask=m1)
+    torch.cuda.synchronize()
+    del ws
+    _check_mask_heads(m1, wl.SEED, wl.OFFSET + OP.mask_philox_calls(B, H, S), B, H, S, p, [(0, 0), (0, 63)])
+    rows = wl.sample_rows(S, 4)
+    keep = np.zeros((B, H, S, S), dtype=bool)
+    for h in range(H):
+        words = _oracle_head_words(wl.SEED, wl.OFFSET, H, S, p, 0, h)
+        assert np.array_equal(m0[0, h].cpu().numpy().view(np.uint64), words), h
+        keep[0, h, rows] = _keep_rows(words, rows, S)
+    wq = {n: (wdev[n].cpu().numpy() if n in wscale else _f64(wdev[n])) for n in wdev}
+    ocfg = dict(H=H, Hkv=Hkv, d=d, eps=1e-5, rope_theta=500000.0, p=p, causal=False)
+    ref = OD.block_forward_fp8(_f64(x), wq, wscale, act, ocfg, keep, rows=rows)
+    got = _f64(y[:, rows])
+    err = np.max(np.abs(got - ref)) / np.max(np.abs(ref))
+    rms = np.sqrt(np.mean((got - ref) ** 2)) / np.sqrt(np.mean(ref ** 2))
+    print("cfg4 fp8 block error: max", err, "rms", rms, flush=True)
+    assert err <= 8e-2 and rms <= 6e-2, (err, rms)

@@ -284,7 +284,8 @@ def test_fp8_block_matches_library_composition_with_float8_casts():
         W = {n: torch.from_numpy(wq[n]).view(f8).double() * ws[n] for n in ws}
         def rms(t, g): return t * torch.rsqrt((t * t).mean(-1, keepdim=True) + cfg["eps"]) * torch.from_numpy(g)
         H, Hkv, d = cfg["H"], cfg["Hkv"], cfg["d"]
-        qkv = q(rms(tx, w["norm1"]), act[0]) @ W["wqkv"].T
+        bf = lambda t: t.float().to(torch.bfloat16).double()       # the block's bf16-stored tensors
+        qkv = bf(q(rms(tx, w["norm1"]), act[0]) @ W["wqkv"].T)
         qq, kk, vv = qkv.split([H * d, Hkv * d, Hkv * d], dim=-1)
         def rope(t, nh):
             t = t.reshape(1, -1, nh, d // 2, 2)
@@ -293,12 +294,12 @@ def test_fp8_block_matches_library_composition_with_float8_casts():
             ang = torch.arange(S, dtype=torch.float64)[:, None] * inv[None, :]
             z = torch.view_as_complex(t.contiguous()) * torch.polar(torch.ones_like(ang), ang)[None, :, None, :]
             return torch.view_as_real(z).reshape(1, S, nh, d)
-        qq = rope(qq, H).permute(0, 2, 1, 3)
-        kk = rope(kk, Hkv).permute(0, 2, 1, 3).repeat_interleave(H // Hkv, dim=1)
+        qq = bf(rope(qq, H)).permute(0, 2, 1, 3)
+        kk = bf(rope(kk, Hkv)).permute(0, 2, 1, 3).repeat_interleave(H // Hkv, dim=1)
         vv = vv.reshape(1, -1, Hkv, d).permute(0, 2, 1, 3).repeat_interleave(H // Hkv, dim=1)
         a = torch.nn.functional.scaled_dot_product_attention(qq, kk, vv, is_causal=causal)
         a = q(a.permute(0, 2, 1, 3).reshape(1, -1, H * d), act[1])
-        x2 = tx + a @ W["wo"].T
+        x2 = bf(tx + a @ W["wo"].T)
         h2 = q(rms(x2, w["norm2"]), act[2])
         u = q(torch.nn.functional.silu(h2 @ W["wg"].T) * (h2 @ W["wu"].T), act[3])
         ref = x2 + u @ W["wd"].T
@@ -320,9 +321,13 @@ def test_fp8_block_stays_within_the_fp8_bar_of_the_unquantised_activations():
         wdq[name] = N.e4m3_decode(wq[name]) * ws[name]
     ref = D.block_forward(x, wdq, cfg, None)
     act = [6.0 / 448.0, 3.0 / 448.0, 6.0 / 448.0, 4.0 / 448.0]
-    y = D.block_forward_fp8(x, wq, ws, act, cfg, None)
+    y = D.block_forward_fp8(x, wq, ws, act, cfg, None, stored_bf16=False)
     err = np.max(np.abs(y - ref)) / np.max(np.abs(ref))
     assert 1e-4 < err <= 6e-2, err
+    # storing q, k, v and the residual stream in bf16 flips some of the codes the quantisers pick
+    # downstream (one in about thirty per quantiser): visible, and of the same order as the bar
+    yb = D.block_forward_fp8(x, wq, ws, act, cfg, None)
+    assert 1e-3 < np.max(np.abs(yb - y)) / np.max(np.abs(ref)) <= 6e-2
 
 
 def test_fp8_block_with_dropout_rows_and_zero_projections():
@@ -335,4 +340,6 @@ def test_fp8_block_with_dropout_rows_and_zero_projections():
     # dropout changes the result, and zero output projections still give the identity
     assert np.max(np.abs(full - D.block_forward_fp8(x, wq, ws, act, cfg, None))) > 1e-6
     wz = dict(wq); wz["wo"] = np.zeros_like(wq["wo"]); wz["wd"] = np.zeros_like(wq["wd"])
-    assert np.array_equal(D.block_forward_fp8(x, wz, ws, act, cfg, keep), x)
+    xb = N.bf16_round(x).astype(np.float64)        # the residual stream is a bf16 tensor
+    assert np.array_equal(D.block_forward_fp8(xb, wz, ws, act, cfg, keep), xb)
+    assert np.array_equal(D.block_forward_fp8(x, wz, ws, act, cfg, keep, stored_bf16=False), x)

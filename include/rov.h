@@ -54,6 +54,12 @@ extern "C" {
 #define ROV_SCHED_FUSED 1         /* GEMMs, attention with in-kernel Philox (paper Sec. 6.1, fusion) */
 #define ROV_SCHED_OVERLAP 2       /* RNG on a side stream beside the GEMMs, joined before attention */
 #define ROV_SCHED_HYBRID 3        /* rov_block_forward only: OVERLAP for the query rows whose bits fit beside the GEMMs, FUSED for the rest */
+#define ROV_SCHED_OVERLAP_DEFERRED 4 /* rov_block_forward only: OVERLAP, but the next layer's mask is left in flight at return */
+
+/* values of rov_block_forward's mask_ready */
+#define ROV_MASK_NOT_READY 0      /* the block generates its mask itself */
+#define ROV_MASK_READY 1          /* `mask` holds it (and the work that wrote it is ordered before main_stream) */
+#define ROV_MASK_IN_FLIGHT 2      /* the previous block's ROV_SCHED_OVERLAP_DEFERRED call is still generating it on side_stream */
 
 /* hipError_t of the last failing HIP call made by this library on the calling thread (0 if none). */
 int rov_last_hip_error(void);
@@ -396,6 +402,18 @@ int rov_trace_read(int *kinds, float *ms, int max_records, int *n_records);
  *               (paper Sec. 1: RNG hidden behind the GEMM layers between the
  *               previous and the current attention).  next_mask must be NULL for
  *               the other schedules and must differ from mask.
+ *   OVERLAP_DEFERRED  As OVERLAP, for a stack of blocks called one after the other on the same
+ *               stream pair: the mask of the following layer is started beside this block's
+ *               PROJ / FC1 / FC2 GEMMs and NOT joined when the call returns.  The following
+ *               block is called with that buffer as `mask` and mask_ready ==
+ *               ROV_MASK_IN_FLIGHT: the RNG keeps running beside its RMSNorm and QKV GEMM - all
+ *               the GEMM layers between the previous and the current attention, as in paper
+ *               Sec. 1 - whatever is left then runs at full speed (Sec. 3.3), and the side
+ *               stream is joined before its attention.  Until that call (or any other work
+ *               ordered after side_stream) `next_mask` is incomplete.  mask_ready ==
+ *               ROV_MASK_IN_FLIGHT is accepted by OVERLAP and OVERLAP_DEFERRED, with the seed,
+ *               offset, sizes, p and causal flag the deferred call used for that buffer, else
+ *               ROV_ERR_INVALID.
  *   HYBRID      (not in the paper; for sequences so long that the RNG outlasts the
  *               GEMMs, the paper's third regime of Sec. 4.1.)  As OVERLAP, but a mask
  *               holds only the first R = rov_block_hybrid_mask_rows(cfg, B, S) query

@@ -12,7 +12,8 @@ LIB_PATH = os.path.join(HERE, "librov.so")
 
 OK, ERR_INVALID, ERR_UNSUPPORTED, ERR_HIP, ERR_WORKSPACE = 0, -1, -2, -3, -4
 F32, BF16, FP8_E4M3 = 0, 1, 2
-SCHED_SEQUENTIAL, SCHED_FUSED, SCHED_OVERLAP, SCHED_HYBRID = 0, 1, 2, 3
+SCHED_SEQUENTIAL, SCHED_FUSED, SCHED_OVERLAP, SCHED_HYBRID, SCHED_OVERLAP_DEFERRED = 0, 1, 2, 3, 4
+MASK_NOT_READY, MASK_READY, MASK_IN_FLIGHT = 0, 1, 2
 
 _ERR_NAMES = {ERR_INVALID: "ROV_ERR_INVALID", ERR_UNSUPPORTED: "ROV_ERR_UNSUPPORTED",
               ERR_HIP: "ROV_ERR_HIP", ERR_WORKSPACE: "ROV_ERR_WORKSPACE"}
@@ -448,7 +449,7 @@ def block_forward(weights, x, y, cfg, schedule, seed, offset, mask, workspace, m
     nptr = ctypes.c_void_p(next_mask.data_ptr()) if next_mask is not None else ctypes.c_void_p(0)
     _check(load().rov_block_forward(ctypes.byref(weights), ctypes.c_void_p(x.data_ptr()),
                                     ctypes.c_void_p(y.data_ptr()), B, S, ctypes.byref(cfg), int(schedule),
-                                    seed & (2**64 - 1), offset & (2**64 - 1), int(bool(mask_ready)), mptr, nptr,
+                                    seed & (2**64 - 1), offset & (2**64 - 1), int(mask_ready), mptr, nptr,
                                     ctypes.c_void_p(workspace.data_ptr()), workspace.numel() * workspace.element_size(),
                                     _stream_ptr(main_stream), _stream_ptr(side_stream)), "rov_block_forward")
     return y
@@ -466,7 +467,7 @@ def block_forward_static(weights, x, y, cfg, schedule, seed, offset, mask, main_
     nptr = ctypes.c_void_p(next_mask.data_ptr()) if next_mask is not None else ctypes.c_void_p(0)
     _check(load().rov_block_forward_static(ctypes.byref(weights), ctypes.c_void_p(x.data_ptr()),
                                            ctypes.c_void_p(y.data_ptr()), B, S, ctypes.byref(cfg), int(schedule),
-                                           seed & (2**64 - 1), offset & (2**64 - 1), int(bool(mask_ready)), mptr,
+                                           seed & (2**64 - 1), offset & (2**64 - 1), int(mask_ready), mptr,
                                            nptr, _stream_ptr(main_stream), _stream_ptr(side_stream)),
            "rov_block_forward_static")
     return y

@@ -18,6 +18,7 @@
 #include <stdint.h>
 
 #include <atomic>
+#include <map>
 #include <mutex>
 
 #include "rov_internal.h"
@@ -80,6 +81,17 @@ struct SideStream {
         if (open && hipEventRecord(ev->join, ss) == hipSuccess) (void)hipStreamWaitEvent(ms, ev->join, 0);
     }
 };
+
+// Masks left in flight by ROV_SCHED_OVERLAP_DEFERRED calls, keyed by their buffer: what the
+// following block needs in order to finish and join them (guarded by g_sched_mu).
+struct InFlightMask {
+    hipStream_t ss;
+    int qslot;              // work queue the small grid pulls from (-1: plain launch, nothing to help with)
+    uint64_t seed, offset;
+    int B, H, S, causal;
+    float p;
+};
+std::map<const void*, InFlightMask> g_in_flight;
 
 bool valid_schedule(int s) {
     return s == ROV_SCHED_SEQUENTIAL || s == ROV_SCHED_FUSED || s == ROV_SCHED_OVERLAP;
@@ -510,8 +522,15 @@ int block_forward_impl(const rov_block_weights* w, const void* x, void* y, int B
                        void* main_stream, void* side_stream) {
     BlockLayout L;
     if (w == nullptr || x == nullptr || y == nullptr ||
-        !(valid_schedule(schedule) || schedule == ROV_SCHED_HYBRID) || !block_layout(cfg, B, S, &L))
+        !(valid_schedule(schedule) || schedule == ROV_SCHED_HYBRID || schedule == ROV_SCHED_OVERLAP_DEFERRED) ||
+        !block_layout(cfg, B, S, &L))
         return ROV_ERR_INVALID;
+    const bool defer = schedule == ROV_SCHED_OVERLAP_DEFERRED;
+    if (defer) schedule = ROV_SCHED_OVERLAP;
+    if (mask_ready != ROV_MASK_NOT_READY && mask_ready != ROV_MASK_READY && mask_ready != ROV_MASK_IN_FLIGHT)
+        return ROV_ERR_INVALID;
+    const bool in_flight = mask_ready == ROV_MASK_IN_FLIGHT;
+    if (in_flight && schedule != ROV_SCHED_OVERLAP) return ROV_ERR_INVALID;
     if (w->norm1 == nullptr || w->norm2 == nullptr || w->wqkv == nullptr || w->wo == nullptr ||
         w->wg == nullptr || w->wu == nullptr || w->wd == nullptr)
         return ROV_ERR_INVALID;
@@ -597,6 +616,19 @@ int block_forward_impl(const rov_block_weights* w, const void* x, void* y, int B
         side.ms = ms;
         side.ss = ss;
     }
+    // a mask the previous block left in flight: the record of that call must describe this one
+    InFlightMask fl{};
+    if (in_flight) {
+        if (!use_mask) return ROV_ERR_INVALID;
+        const auto it = g_in_flight.find(mask);
+        if (it == g_in_flight.end()) return ROV_ERR_INVALID;
+        fl = it->second;
+        if (fl.ss != ss || fl.seed != seed || fl.offset != offset || fl.B != B || fl.H != H || fl.S != S ||
+            fl.p != cfg->p || fl.causal != (cfg->causal != 0))
+            return ROV_ERR_INVALID;
+        g_in_flight.erase(it);
+        side.open = true;   // from here on an early return still joins the side stream
+    }
 
     // this block's own mask, if nobody produced it yet
     int qslot = -1;
@@ -631,12 +663,21 @@ int block_forward_impl(const rov_block_weights* w, const void* x, void* y, int B
             ROV_STEP(t_mask(seed, offset, B, H, S, cfg->p, mask, ms, MASK_GRID_FULL, -1, cfg->causal != 0));
         }
     }
+    if (in_flight && fl.qslot >= 0)
+        // what the small grid (running since the previous block) has not produced by the end of this
+        // block's QKV GEMM is finished at full speed (paper Sec. 3.3)
+        ROV_STEP(t_mask(seed, offset, B, H, S, cfg->p, mask, ms, MASK_GRID_HELPER, fl.qslot, cfg->causal != 0));
     ROV_STEP(traced(ROV_TRACE_GLUE, ms, [&] {   // q heads then k heads
         return launch_rope(qkv, T, qkv_n, S, H + Hkv, d, cfg->rope_theta, ms);
     }));
     if (use_mask && !mask_ready && overlap) {
         ROV_STEP(side.join());
         ROV_STEP(mask_queue_release(qslot, ms));
+    }
+    if (in_flight) {
+        ROV_STEP(side.mark());    // everything queued on the side stream so far, the RNG grid included
+        ROV_STEP(side.join());
+        ROV_STEP(mask_queue_release(fl.qslot, ms));
     }
 
     if (hybrid && R < S) {
@@ -693,7 +734,12 @@ int block_forward_impl(const rov_block_weights* w, const void* x, void* y, int B
                   : launch_gemm_swiglu(h, w->wg, w->wu, u, (int)T, ffn, hidden, ms);
     }));
     ROV_STEP(t_gemm(u, w->wd, y, x2, (int)T, hidden, ffn, dt, 1, sa3, sw_d, ms));
-    if (run_ahead) {
+    if (run_ahead && defer && R == S) {
+        // left in flight: the following block (mask_ready == ROV_MASK_IN_FLIGHT) helps and joins
+        g_in_flight[next_mask] = InFlightMask{ss, qslot_next, seed, offset + rov_mask_philox_calls(B, H, S), B, H, S,
+                                              cfg->causal != 0, cfg->p};
+        side.open = false;
+    } else if (run_ahead) {
         // what is left of the next mask when the last GEMM ends is finished at full speed
         if (qslot_next >= 0)
             ROV_STEP(t_mask(seed, offset + rov_mask_philox_calls(B, H, S), B, H, S, cfg->p, next_mask, ms,

@@ -573,3 +573,64 @@ def test_block_forward_fp8_error_paths():
     assert e.value.code == rov.ERR_UNSUPPORTED
     torch.cuda.synchronize()
     assert bool((y == 2.0).all())
+
+
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("force_queue", [False, True])
+def test_block_forward_deferred_join_over_three_layers(causal, force_queue):
+    # a stack of blocks on one stream pair: every block leaves the next layer's mask in flight
+    # (ROV_SCHED_OVERLAP_DEFERRED) and the following one finishes and joins it beside its QKV GEMM
+    # (mask_ready = ROV_MASK_IN_FLIGHT).  Outputs and masks are those of the sequential schedule.
+    B, S, H, Hkv, d, hidden, ffn = 1, 320, 4, 2, 128, 512, 1024
+    p, seed, offset = 0.1, wl.SEED, 4480
+    x, wd = _block_setup(B, S, H, Hkv, d, hidden, ffn, 31)
+    cfg = rov.make_block_cfg(H, Hkv, d, hidden, ffn, p, causal=causal)
+    weights = rov.make_block_weights(wd)
+    ws = torch.empty(rov.block_workspace_bytes(cfg, B, S, 0), dtype=torch.uint8, device="cuda")
+    main, side = torch.cuda.Stream(), torch.cuda.Stream()
+    calls = rov.mask_philox_calls(B, H, S)
+    # (a tiny RNG grid cannot finish beside the GEMMs: the work queue and the helper launch are used)
+    prev = rov.set_rng_max_workgroups(1) if force_queue else None
+    try:
+        y_seq = []
+        m = torch.zeros(rov.mask_shape(B, H, S), dtype=torch.int64, device="cuda")
+        torch.cuda.synchronize()
+        for layer in range(3):
+            y = torch.zeros_like(x)
+            rov.block_forward(weights, x, y, cfg, rov.SCHED_SEQUENTIAL, seed, offset + layer * calls, m, ws, main, side)
+            torch.cuda.synchronize()
+            y_seq.append(y)
+        masks = [torch.zeros(rov.mask_shape(B, H, S), dtype=torch.int64, device="cuda") for _ in range(2)]
+        ys = [torch.zeros_like(x) for _ in range(3)]
+        torch.cuda.synchronize()
+        # layer 0 makes its own mask; layers 1 and 2 find theirs in flight
+        rov.block_forward(weights, x, ys[0], cfg, rov.SCHED_OVERLAP_DEFERRED, seed, offset, masks[0], ws, main, side,
+                          mask_ready=rov.MASK_NOT_READY, next_mask=masks[1])
+        rov.block_forward(weights, x, ys[1], cfg, rov.SCHED_OVERLAP_DEFERRED, seed, offset + calls, masks[1], ws, main, side,
+                          mask_ready=rov.MASK_IN_FLIGHT, next_mask=masks[0])
+        rov.block_forward(weights, x, ys[2], cfg, rov.SCHED_OVERLAP, seed, offset + 2 * calls, masks[0], ws, main, side,
+                          mask_ready=rov.MASK_IN_FLIGHT, next_mask=None)
+        torch.cuda.synchronize()
+    finally:
+        if force_queue:
+            rov.set_rng_max_workgroups(prev)
+    for layer in range(3):
+        assert torch.equal(ys[layer], y_seq[layer]), layer
+    T = S // 32
+    lower = np.tril(np.ones((T, T), dtype=bool))
+    for buf, layer in ((masks[1], 1), (masks[0], 2)):
+        exp = OP.dropout_mask(seed, offset + layer * calls, B, H, S, p)
+        got = buf.cpu().numpy().view(np.uint64)
+        if causal:
+            assert np.array_equal(got[:, :, lower], exp[:, :, lower]), layer
+        else:
+            assert np.array_equal(got, exp), layer
+    # a mask that nobody left in flight, or one described differently, is refused and nothing runs
+    y = torch.full_like(x, 5.0)
+    for off in (offset, offset + calls):
+        with pytest.raises(rov.RovError) as e:
+            rov.block_forward(weights, x, y, cfg, rov.SCHED_OVERLAP, seed, off, masks[1], ws, main, side,
+                              mask_ready=rov.MASK_IN_FLIGHT)
+        assert e.value.code == rov.ERR_INVALID
+    torch.cuda.synchronize()
+    assert bool((y == 5.0).all())

@@ -156,6 +156,65 @@ def test_layer_step_replays_from_a_captured_graph(sched):
         torch.cuda.synchronize()
 
 
+def test_layer_step_overlap_from_two_host_threads():
+    # two host threads enqueue overlap steps at the same time, each on its own pair of streams with its own
+    # buffers and seed (ctypes releases the interpreter lock during the calls).  The library serialises the
+    # enqueue phase of its schedule entry points and shares one set of fork / join events and the work-queue
+    # slots between them: every thread must end with the oracle's mask for its seed and with the outputs a
+    # single-threaded run gives, bit for bit.
+    import threading
+    B, H, Hkv, d = 1, 4, 2, 128
+    cases = [dict(S=512, gemm=(256, 128, 256), seed=wl.SEED),            # RNG outlasts the GEMM: work queue + helper launch
+             dict(S=256, gemm=(1024, 512, 1024), seed=wl.SEED + 77)]     # RNG fits beside the GEMM: plain launch
+    p, reps = 0.1, 12
+    for i, c in enumerate(cases):
+        rng = np.random.default_rng(50 + i)
+        q, k, v = wl.qkv(rng, B, c["S"], H, Hkv, d)
+        a, w = wl.gemm_operands(rng, *c["gemm"])
+        c["Q"], c["K"], c["V"], c["A"], c["W"] = [_dev(x) for x in (q, k, v, a, w)]
+        c["main"], c["side"] = torch.cuda.Stream(), torch.cuda.Stream()
+
+    def run(c, tag):
+        M, Kd, N = c["gemm"]
+        O = torch.zeros_like(c["Q"])
+        C = torch.zeros((M, N), dtype=torch.bfloat16, device="cuda")
+        mask = torch.full(rov.mask_shape(B, H, c["S"]), 0x2AAAAAAAAAAAAAAA, dtype=torch.int64, device="cuda")
+        torch.cuda.synchronize()
+        gd = [rov.make_gemm_desc(c["A"], c["W"], C)]
+        ad = rov.make_attn_desc(c["Q"], c["K"], c["V"], O, p)
+        try:
+            for _ in range(reps):
+                rov.layer_step(rov.SCHED_OVERLAP, gd, ad, c["seed"], wl.OFFSET, mask, c["main"], c["side"])
+        except Exception as e:      # a thread's exception would otherwise be lost
+            c[tag] = e
+            return
+        c[tag] = (O, C, mask)
+
+    print("two threads: single-threaded reference runs", flush=True)
+    for c in cases:
+        run(c, "ref")
+    torch.cuda.synchronize()
+    print("two threads: concurrent runs", flush=True)
+    threads = [threading.Thread(target=run, args=(c, "got")) for c in cases]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join(120)
+        assert not t.is_alive()
+    torch.cuda.synchronize()
+    for c in cases:
+        assert not isinstance(c["ref"], Exception), c["ref"]
+        assert not isinstance(c["got"], Exception), c["got"]
+        (O0, C0, m0), (O1, C1, m1) = c["ref"], c["got"]
+        words = OP.dropout_mask(c["seed"], wl.OFFSET, B, H, c["S"], p)
+        assert np.array_equal(m0.cpu().numpy().view(np.uint64), words)
+        assert np.array_equal(m1.cpu().numpy().view(np.uint64), words)
+        assert torch.equal(O0, O1) and torch.equal(C0, C1)
+        keep = OP.unpack_keep(words, c["S"])
+        ref = OD.attention_dropout(_f64(c["Q"]), _f64(c["K"]), _f64(c["V"]), keep, p)
+        assert np.max(np.abs(_f64(O1) - ref)) / np.max(np.abs(ref)) <= 2e-2
+
+
 @pytest.mark.parametrize("rounds", [3, 5, 7, 10])
 @pytest.mark.parametrize("dtype,d", [(torch.bfloat16, 128), (torch.float32, 64)])
 def test_layer_step_rounds_three_schedules(rounds, dtype, d):

@@ -461,6 +461,17 @@ int rov_block_forward(const rov_block_weights *w, const void *x, void *y, int B,
                       int mask_ready, uint64_t *mask, uint64_t *next_mask,
                       void *workspace, size_t workspace_bytes, void *main_stream, void *side_stream);
 
+/* Completes a mask that a ROV_SCHED_OVERLAP_DEFERRED call left in flight when no following block
+ * will claim it (the last block of a stack, a caller that changes its mind): whatever the small
+ * RNG grid on the side stream has not produced yet is generated at full speed on main_stream
+ * (paper Sec. 3.3: the rest of the RNG runs alone once the GEMMs are over), and main_stream then
+ * waits for the side stream, so that work enqueued on main_stream afterwards sees the whole mask.
+ * mask: the `next_mask` of that call.  main_stream: the main stream of that call (or a stream
+ * ordered after it); it must differ from the side stream the deferred call used.  ROV_ERR_INVALID if the buffer is not in flight (nothing is enqueued).  While a buffer
+ * is in flight, rov_block_forward accepts it only as `mask` with ROV_MASK_IN_FLIGHT; any other use
+ * of it there is ROV_ERR_INVALID, and the caller must not free it. */
+int rov_mask_finish(uint64_t *mask, void *main_stream);
+
 /* rov_block_forward for callers that cannot allocate device memory or carry a workspace around:
  * code running under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
  * Same arguments, results and errors as rov_block_forward, minus the workspace: the block's

@@ -103,6 +103,7 @@ SIGNATURES = {
     "rov_set_block_hybrid_mask_rows": (_i, [_i]),
     "rov_block_forward": (_i, [ctypes.POINTER(BlockWeights), _p, _p, _i, _i, ctypes.POINTER(BlockCfg),
                                _i, _u64, _u64, _i, _p, _p, _p, ctypes.c_size_t, _p, _p]),
+    "rov_mask_finish": (_i, [_p, _p]),
     "rov_block_static_scratch_bytes": (ctypes.c_size_t, []),
     "rov_block_forward_static": (_i, [ctypes.POINTER(BlockWeights), _p, _p, _i, _i, ctypes.POINTER(BlockCfg),
                                       _i, _u64, _u64, _i, _p, _p, _p, _p]),
@@ -453,6 +454,11 @@ def block_forward(weights, x, y, cfg, schedule, seed, offset, mask, workspace, m
                                     ctypes.c_void_p(workspace.data_ptr()), workspace.numel() * workspace.element_size(),
                                     _stream_ptr(main_stream), _stream_ptr(side_stream)), "rov_block_forward")
     return y
+
+
+def mask_finish(mask, main_stream):
+    """Completes and joins a mask that an OVERLAP_DEFERRED block_forward left in flight."""
+    _check(load().rov_mask_finish(ctypes.c_void_p(mask.data_ptr()), _stream_ptr(main_stream)), "rov_mask_finish")
 
 
 def block_static_scratch_bytes():

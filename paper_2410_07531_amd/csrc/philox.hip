@@ -353,6 +353,7 @@ namespace {
 struct SlotState {
     hipEvent_t done = nullptr;
     bool recorded = false;
+    bool in_use = false;     // handed out and not yet released (a mask left in flight keeps its slot across calls)
 };
 SlotState g_slot_state[kQueueSlots];
 std::mutex g_slot_mu;
@@ -369,11 +370,21 @@ bool stream_is_capturing(hipStream_t st) {
 
 int mask_queue_acquire(hipStream_t stream, int* slot) {
     std::lock_guard<std::mutex> lock(g_slot_mu);
-    const int s = (int)(g_queue_cursor.fetch_add(1u) % (unsigned)kQueueSlots);
+    const bool capturing = stream_is_capturing(stream);
+    int s = -1;
+    for (int tries = 0; tries < kQueueSlots; ++tries) {
+        const int c = (int)(g_queue_cursor.fetch_add(1u) % (unsigned)kQueueSlots);
+        if (!g_slot_state[c].in_use) {
+            s = c;
+            break;
+        }
+    }
+    if (s < 0) return ROV_ERR_UNSUPPORTED;   // every slot belongs to a mask that is still in flight
     SlotState& st = g_slot_state[s];
-    if (st.recorded && !stream_is_capturing(stream)) ROV_HIP_TRY(hipStreamWaitEvent(stream, st.done, 0));
+    if (st.recorded && !capturing) ROV_HIP_TRY(hipStreamWaitEvent(stream, st.done, 0));
     hipLaunchKernelGGL(queue_reset_kernel, dim3(1), dim3(kSubQueues), 0, stream, s);
     ROV_LAUNCH_CHECK();
+    if (!capturing) st.in_use = true;
     *slot = s;
     return ROV_OK;
 }
@@ -383,6 +394,7 @@ int mask_queue_release(int slot, hipStream_t stream) {
     if (stream_is_capturing(stream)) return ROV_OK;
     std::lock_guard<std::mutex> lock(g_slot_mu);
     SlotState& st = g_slot_state[slot];
+    st.in_use = false;
     if (st.done == nullptr) ROV_HIP_TRY(hipEventCreateWithFlags(&st.done, hipEventDisableTiming));
     ROV_HIP_TRY(hipEventRecord(st.done, stream));
     st.recorded = true;

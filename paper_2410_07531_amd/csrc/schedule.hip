@@ -628,7 +628,10 @@ int block_forward_impl(const rov_block_weights* w, const void* x, void* y, int B
             return ROV_ERR_INVALID;
         g_in_flight.erase(it);
         side.open = true;   // from here on an early return still joins the side stream
+    } else if (use_mask && g_in_flight.count(mask) != 0) {
+        return ROV_ERR_INVALID;   // still being written on a side stream: claim it (ROV_MASK_IN_FLIGHT) or rov_mask_finish it
     }
+    if (next_mask != nullptr && g_in_flight.count(next_mask) != 0) return ROV_ERR_INVALID;
 
     // this block's own mask, if nobody produced it yet
     int qslot = -1;
@@ -751,6 +754,39 @@ int block_forward_impl(const rov_block_weights* w, const void* x, void* y, int B
     return ROV_OK;
 }
 
+// Completes a mask that an OVERLAP_DEFERRED block left in flight and nobody claimed: what the small
+// grid has not produced yet is finished by a full-size launch on the main stream (paper Sec. 3.3),
+// the side stream is joined into the main stream and the work-queue slot is given back.
+int mask_finish_impl(uint64_t* mask, void* main_stream) {
+    if (mask == nullptr) return ROV_ERR_INVALID;
+    std::lock_guard<std::mutex> sched_lock(g_sched_mu);
+    const auto it = g_in_flight.find(mask);
+    if (it == g_in_flight.end()) return ROV_ERR_INVALID;
+    const InFlightMask fl = it->second;
+    hipStream_t ms = (hipStream_t)main_stream;
+    if (ms == fl.ss) return ROV_ERR_INVALID;
+    if (fl.qslot >= 0) {
+        const int rc0 = check_mask(fl.B, fl.H, fl.S, fl.p, 10, 32, mask);
+        if (rc0 != ROV_OK) return rc0;
+    }
+    SideStream side;
+    int rc = get_events(&side.ev);
+    if (rc != ROV_OK) return rc;
+    side.ms = ms;
+    side.ss = fl.ss;
+    g_in_flight.erase(it);
+    side.open = true;   // an early return below still joins
+    if (fl.qslot >= 0) {
+        rc = t_mask(fl.seed, fl.offset, fl.B, fl.H, fl.S, fl.p, mask, ms, MASK_GRID_HELPER, fl.qslot, fl.causal != 0);
+        if (rc != ROV_OK) return rc;
+    }
+    rc = side.mark();
+    if (rc != ROV_OK) return rc;
+    rc = side.join();
+    if (rc != ROV_OK) return rc;
+    return mask_queue_release(fl.qslot, ms);
+}
+
 // Scratch of rov_block_forward_static: the block's intermediate tensors (normed activations, QKV,
 // attention output, residual stream, SwiGLU output) for callers that cannot bring a workspace.
 // Every byte a block reads from it was written earlier in the same call, so nothing is cleared
@@ -787,6 +823,8 @@ extern "C" int rov_block_forward(const rov_block_weights* w, const void* x, void
     return rov::block_forward_impl(w, x, y, B, S, cfg, schedule, seed, offset, mask_ready, mask, next_mask, workspace,
                                    workspace_bytes, main_stream, side_stream);
 }
+
+extern "C" int rov_mask_finish(uint64_t* mask, void* main_stream) { return rov::mask_finish_impl(mask, main_stream); }
 
 extern "C" size_t rov_block_static_scratch_bytes(void) { return rov::kStaticScratchBytes; }
 

@@ -693,3 +693,60 @@ def test_block_forward_deferred_join_over_three_layers(causal, force_queue):
         assert e.value.code == rov.ERR_INVALID
     torch.cuda.synchronize()
     assert bool((y == 5.0).all())
+
+
+@pytest.mark.parametrize("force_queue", [False, True])
+def test_mask_finish_completes_a_mask_left_in_flight(force_queue):
+    # the last block of a stack called with ROV_SCHED_OVERLAP_DEFERRED leaves a mask that no block will
+    # claim: while it is in flight every other use of the buffer is refused; rov_mask_finish completes it
+    # (bit-exact against the oracle) and gives the buffer back
+    B, S, H, Hkv, d, hidden, ffn = 1, 320, 4, 2, 128, 512, 1024
+    p, seed, offset = 0.1, wl.SEED, 96
+    x, wd = _block_setup(B, S, H, Hkv, d, hidden, ffn, 37)
+    cfg = rov.make_block_cfg(H, Hkv, d, hidden, ffn, p)
+    weights = rov.make_block_weights(wd)
+    ws = torch.empty(rov.block_workspace_bytes(cfg, B, S, 0), dtype=torch.uint8, device="cuda")
+    main, side = torch.cuda.Stream(), torch.cuda.Stream()
+    calls = rov.mask_philox_calls(B, H, S)
+    masks = [torch.full(rov.mask_shape(B, H, S), 0x2AAAAAAAAAAAAAAA, dtype=torch.int64, device="cuda") for _ in range(2)]
+    y = torch.zeros_like(x)
+    torch.cuda.synchronize()
+    prev = rov.set_rng_max_workgroups(1) if force_queue else None
+    try:
+        print("mask_finish: deferred block", force_queue, flush=True)
+        rov.block_forward(weights, x, y, cfg, rov.SCHED_OVERLAP_DEFERRED, seed, offset, masks[0], ws, main, side,
+                          mask_ready=rov.MASK_NOT_READY, next_mask=masks[1])
+        # in flight: not usable as a ready mask, not as a target, and only finishable once
+        y2 = torch.full_like(x, 5.0)
+        for kw in (dict(mask=masks[1], mask_ready=rov.MASK_READY, next_mask=None),
+                   dict(mask=masks[1], mask_ready=rov.MASK_NOT_READY, next_mask=None),
+                   dict(mask=masks[0], mask_ready=rov.MASK_READY, next_mask=masks[1])):
+            with pytest.raises(rov.RovError) as e:
+                rov.block_forward(weights, x, y2, cfg, rov.SCHED_OVERLAP, seed, offset + calls, kw["mask"], ws, main, side,
+                                  mask_ready=kw["mask_ready"], next_mask=kw["next_mask"])
+            assert e.value.code == rov.ERR_INVALID
+        with pytest.raises(rov.RovError) as e:
+            rov.mask_finish(masks[1], side)            # the stream the RNG runs on cannot be the one that waits for it
+        assert e.value.code == rov.ERR_INVALID
+        print("mask_finish: finish", flush=True)
+        rov.mask_finish(masks[1], main)
+        with pytest.raises(rov.RovError) as e:
+            rov.mask_finish(masks[1], main)
+        assert e.value.code == rov.ERR_INVALID
+        with pytest.raises(rov.RovError):
+            rov.mask_finish(masks[0], main)            # never was in flight
+        main.synchronize()                             # the main stream alone: it has joined the side stream
+    finally:
+        if force_queue:
+            rov.set_rng_max_workgroups(prev)
+    assert bool((y2 == 5.0).all())
+    assert np.array_equal(masks[1].cpu().numpy().view(np.uint64), OP.dropout_mask(seed, offset + calls, B, H, S, p))
+    # the buffer is an ordinary ready mask again
+    y3 = torch.zeros_like(x)
+    y_seq = torch.zeros_like(x)
+    rov.block_forward(weights, x, y3, cfg, rov.SCHED_OVERLAP, seed, offset + calls, masks[1], ws, main, side,
+                      mask_ready=rov.MASK_READY)
+    m = torch.zeros(rov.mask_shape(B, H, S), dtype=torch.int64, device="cuda")
+    rov.block_forward(weights, x, y_seq, cfg, rov.SCHED_SEQUENTIAL, seed, offset + calls, m, ws, main, side)
+    torch.cuda.synchronize()
+    assert torch.equal(y3, y_seq)

@@ -193,7 +193,9 @@ int rov_gemm(const void *A, const void *Bm, void *C, int M, int N, int K, int dt
  * MMA-bound kernel), in output columns: 0 = chosen per call from the shape (the
  * default: the width that wastes least of the last round of workgroups over the
  * compute units), or one of 128, 160, 192, 224, 256 for every later call.  The
- * result is the same sum in the same order for every width.  For experiments
+ * result is the same sum in the same order for every width.  rov_gemm_swiglu and
+ * rov_gemm_swiglu_fp8 have two tile forms: 256 forces the wide one, 128 the narrow
+ * one, other values leave their choice to the shape.  For experiments
  * and tests; process-wide.  Returns the previous value, or ROV_ERR_INVALID
  * (nothing changed) for any other argument. */
 int rov_set_gemm_tile_cols(int cols);

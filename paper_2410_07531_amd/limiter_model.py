@@ -138,7 +138,7 @@ def t_gemm(chip: Chip, M: int, N: int, K: int, esz: int = 2, dual: bool = False)
     if dual:
         tiles_m, cu = -(-M // 256), chip.cus
         t8, t4 = tiles_m * -(-N // 128), tiles_m * -(-N // 64)
-        nj = 8 if -(-t8 // cu) * 9 <= -(-t4 // cu) * 5 else 4
+        nj = 8 if -(-t8 // cu) * 3 <= -(-t4 // cu) * 2 else 4      # the launch's rule for the dual tile
         tiles, out_cols = (t8 if nj == 8 else t4), 16 * nj
     else:
         cols = gemm_tile_cols(chip, M, N)

@@ -84,16 +84,21 @@ def test_gemm_bf16_every_tile_width(cols):
     (2304, 192, 128),       # nine tile rows (every k start), narrow output
     (512, 4096, 256),       # 64 tiles of 128 columns
 ])
-def test_gemm_swiglu_matches_oracle(M, N, K):
+@pytest.mark.parametrize("form", [0, 128, 256])       # the launch's choice, the narrow tile, the wide tile
+def test_gemm_swiglu_matches_oracle(M, N, K, form):
     # silu(A Wg^T) * (A Wu^T) from the dual product: the oracle's two products and its silu
-    print("gemm swiglu", M, N, K, flush=True)
+    print("gemm swiglu", M, N, K, form, flush=True)
     rng = np.random.default_rng(M + 3 * N + K)
     a, wg = wl.gemm_operands(rng, M, K, N)
     _, wu = wl.gemm_operands(rng, M, K, N)
     wg, wu = wg * np.float32(40.0), wu * np.float32(40.0)     # gate values of order 1: the silu's curve matters
     A, Wg, Wu = _to_dev(a, torch.bfloat16), _to_dev(wg, torch.bfloat16), _to_dev(wu, torch.bfloat16)
-    C = rov.gemm_swiglu(A, Wg, Wu)
-    torch.cuda.synchronize()
+    prev = rov.set_gemm_tile_cols(form)
+    try:
+        C = rov.gemm_swiglu(A, Wg, Wu)
+        torch.cuda.synchronize()
+    finally:
+        rov.set_gemm_tile_cols(prev)
     g = OD.gemm(_f64(A), _f64(Wg), transB=True)
     u = OD.gemm(_f64(A), _f64(Wu), transB=True)
     ref = OD.silu(g) * u
@@ -299,14 +304,15 @@ def test_gemm_fp8_llama70b_qkv_sampled():
     (300, 72, 384),         # fewer columns than one wave's half of a 64-column tile
     (512, 4096, 256),       # 64 tiles of 128 columns
 ])
-def test_gemm_swiglu_fp8_codes_match_oracle(M, N, K):
+@pytest.mark.parametrize("form", [128, 256])          # the narrow and the wide tile
+def test_gemm_swiglu_fp8_codes_match_oracle(M, N, K, form):
     # e4m3( silu(sA sWg A Wg^T) * (sA sWu A Wu^T) / sC ): the codes the kernel writes against the
     # oracle's nearest-code choice on the float64 value.  The kernel takes the decision on its own
     # fp32 value (matrix-core accumulation of sums with cancelling terms, fast exponential), which is
     # the exact one up to about 3e-5 of the output scale: where the codes differ (few places), the
     # kernel's code must be as close to the exact value as the best code up to twice that bound.
     from oracle import numerics as ON
-    print("gemm swiglu fp8", M, N, K, flush=True)
+    print("gemm swiglu fp8", M, N, K, form, flush=True)
     rng = np.random.default_rng(5 * M + N + K)
     a, wg = wl.gemm_operands(rng, M, K, N)
     _, wu = wl.gemm_operands(rng, M, K, N)
@@ -317,8 +323,12 @@ def test_gemm_swiglu_fp8_codes_match_oracle(M, N, K):
     u = sa * su * OD.gemm(ON.e4m3_decode(Aq.numpy()), ON.e4m3_decode(Uq.numpy()), transB=True)
     v = OD.silu(g) * u
     sc = float(np.float32(np.max(np.abs(v)) / 600.0))          # the largest values saturate at 448
-    C = rov.gemm_swiglu_fp8(Aq.cuda(), Gq.cuda(), Uq.cuda(), sa, sg, su, sc)
-    torch.cuda.synchronize()
+    prev = rov.set_gemm_tile_cols(form)
+    try:
+        C = rov.gemm_swiglu_fp8(Aq.cuda(), Gq.cuda(), Uq.cuda(), sa, sg, su, sc)
+        torch.cuda.synchronize()
+    finally:
+        rov.set_gemm_tile_cols(prev)
     got = C.cpu().numpy()
     exp = ON.e4m3_encode(v / sc)
     assert np.any((exp & 0x7F) == 0x7E)                        # saturation is exercised

@@ -18,7 +18,11 @@
  *    schedule entry points (rov_layer_step*, rov_block_forward*) serialise their
  *    enqueue phase inside the library; the work they enqueue is ordered by the
  *    streams they are given, as usual.  The process-wide rov_set_* knobs are for
- *    experiments and are read once per call.
+ *    experiments and are read once per call.  Masks that two launches produce
+ *    together go through one of 64 work queues of the library; a queue is taken for
+ *    the duration of a call (for a mask left in flight: until it is claimed or
+ *    finished) and handed out again only after the launches that used it have
+ *    completed.  With all 64 taken a call returns ROV_ERR_UNSUPPORTED.
  *  - Every data pointer is a DEVICE pointer owned by the caller, valid until
  *    the work enqueued on `stream` has completed.  The library allocates no
  *    device memory and never synchronises the device: calls are asynchronous

@@ -265,3 +265,38 @@ def test_workload4_llama70b_fp8_block_sampled_rows():
     rms = np.sqrt(np.mean((got - ref) ** 2)) / np.sqrt(np.mean(ref ** 2))
     print("cfg4 fp8 block error: max", err, "rms", rms, flush=True)
     assert err <= 8e-2 and rms <= 6e-2, (err, rms)
+
+
+def test_longest_sequence_s32k_mask_and_attention_sampled():
+    # The longest sequence the measurements use: S = 32768, H = 32 (8 KV heads): a 4 GiB mask (2^35 bits,
+    # 2^30 bits per head: word indices and call numbers beyond 32 bits), causal and non-causal attention
+    # on sampled rows against the oracle, stored-mask and in-kernel Philox outputs equal everywhere.
+    B, H, Hkv, S, d, p = 1, 32, 8, 32768, 128, 0.1
+    seed, offset = wl.SEED, wl.CARRY_OFFSET - 4096        # call numbers cross 2^32 inside head 0
+    gen = torch.Generator(device="cuda"); gen.manual_seed(1032)
+    Q, K, V = _randn(gen, B, S, H, d), _randn(gen, B, S, Hkv, d), _randn(gen, B, S, Hkv, d)
+    print("s32k: mask", flush=True)
+    mask = rov.dropout_mask_generate(seed, offset, B, H, S, p)
+    torch.cuda.synchronize()
+    heads = [(0, 0), (0, 31)]
+    rows = wl.sample_rows(S, 6)
+    for causal in (False, True):
+        print("s32k: attention causal =", causal, flush=True)
+        O_mask = torch.zeros_like(Q)
+        O_fused = torch.zeros_like(Q)
+        rov.attention_fwd_dropout(Q, K, V, p, mask=mask, causal=causal, O=O_mask)
+        rov.attention_fwd_dropout(Q, K, V, p, seed=seed, offset=offset, causal=causal, O=O_fused)
+        torch.cuda.synchronize()
+        assert torch.equal(O_mask, O_fused)
+        for b, h in heads:
+            ref = _attention_rows_ref(Q, K, V, mask, seed, offset, p, b, h, rows, causal)   # also: device mask of the head == oracle's
+            got = _f64(O_mask[b, rows, h, :])
+            assert np.max(np.abs(got - ref)) / np.max(np.abs(ref)) <= 2e-2, (b, h, causal)
+    # kept fraction of the whole mask inside its 4-sigma band (popcount on the device words)
+    nbits = B * H * S * S
+    flat = mask.view(-1)
+    kept = 0
+    for i in range(0, flat.numel(), 1 << 24):
+        kept += OP.popcount(flat[i:i + (1 << 24)].cpu().numpy().view(np.uint64))
+    q = OP.keep_threshold(p) / 2.0 ** 32
+    assert abs(kept / nbits - q) <= 4.0 * math.sqrt(q * (1.0 - q) / nbits)

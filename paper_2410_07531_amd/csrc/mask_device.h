@@ -8,6 +8,30 @@ namespace rov {
 
 constexpr int kGroupsPerChunk = 16;   // 16 groups x 4 words = 64 words = one 8-byte store per lane
 
+// Division of a wave-uniform 32-bit index by a launch constant d without the compiler's software
+// 64-bit division (hundreds of instructions, paid once per chunk - also by the chunks a causal mask
+// skips, which made skipping them gain nothing).  m = floor(2^32 / d) from the host (0xFFFFFFFF for
+// d = 1): mulhi(n, m) is floor(n / d) or one less, so one correction step gives the exact pair.
+__host__ __device__ inline uint32_t div_magic(uint64_t d) {
+    return d <= 1u ? 0xFFFFFFFFu : (uint32_t)(0x100000000ull / d);
+}
+__device__ __forceinline__ void divmod_u32(uint32_t n, uint32_t d, uint32_t m, uint32_t& q, uint32_t& r) {
+    q = __umulhi(n, m);
+    r = n - q * d;
+    if (r >= d) { ++q; r -= d; }
+}
+// (query tile, key tile) of tile number `tile` of a [..][T][T] tile array.
+__device__ __forceinline__ void tile_coords(uint64_t tile, uint32_t T, uint32_t Tm, uint32_t& qt, uint32_t& kt) {
+    if ((tile >> 32) == 0u) {
+        uint32_t row, unused;
+        divmod_u32((uint32_t)tile, T, Tm, row, kt);
+        divmod_u32(row, T, Tm, unused, qt);
+    } else {   // masks beyond 2^32 tiles (4 Tbit): the plain division
+        kt = (uint32_t)(tile % T);
+        qt = (uint32_t)((tile / T) % T);
+    }
+}
+
 // Work queues for masks that two launches produce together.  A queue slot is 32 sub-queues, each
 // with its own 128-byte line and its own contiguous share of the mask's 64-word chunks: atomics
 // on one address retire one after the other (about 10 ns each on this chip, measured), so a

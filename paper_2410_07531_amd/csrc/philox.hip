@@ -79,7 +79,7 @@ __device__ __forceinline__ void mask_chunk(uint64_t base, uint32_t lane, uint32_
 template <int R, bool RAGGED>
 __global__ __launch_bounds__(kWavesPerBlock * 64) __attribute__((amdgpu_num_vgpr(24))) void mask_kernel(
     uint64_t* __restrict__ out, uint64_t words, uint64_t nchunks, uint64_t offset, uint32_t k0,
-    uint32_t k1, uint32_t t_minus_1, uint32_t T, uint32_t S, int lower_only, int qslot, uint64_t qper,
+    uint32_t k1, uint32_t t_minus_1, uint32_t T, uint32_t Tm, uint32_t S, int lower_only, int qslot, uint64_t qper,
     uint32_t qbatch) {
     const uint32_t lane = threadIdx.x & 63u;
     const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -93,9 +93,7 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) __attribute__((amdgpu_num_vgpr
         uint32_t vlo = 0u, vhi = 0u;
         uint32_t qt = 0u, kt = 0u;   // tile coordinates of the chunk's first tile
         if (RAGGED || lower_only) {
-            const uint64_t tile = chunk * 4u;
-            kt = (uint32_t)(tile % T);
-            qt = (uint32_t)((tile / T) % T);
+            tile_coords(chunk * 4u, T, Tm, qt, kt);
             // the chunk's tiles are (qt, kt) .. (qt, kt+3), wrapping into row qt+1 at kt = T;
             // a wrapped tile (qt+1, 0) is always needed, so only a chunk that stays inside its
             // row with kt > qt can be skipped
@@ -121,7 +119,7 @@ template <int R, bool RAGGED>
 __global__ __launch_bounds__(kWavesPerBlock * 64) void mask_rows_kernel(
     uint64_t* __restrict__ out, uint64_t seg_words, uint64_t chunks_per_seg, uint64_t nseg,
     uint64_t seg_stride, uint64_t seg_first, uint64_t offset, uint32_t k0, uint32_t k1,
-    uint32_t t_minus_1, uint32_t T, uint32_t S, int qslot, uint64_t qper, uint32_t qbatch) {
+    uint32_t t_minus_1, uint32_t T, uint32_t Tm, uint32_t cps_m, uint32_t S, int qslot, uint64_t qper, uint32_t qbatch) {
     const uint32_t lane = threadIdx.x & 63u;
     const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     ChunkSource src;
@@ -129,10 +127,17 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void mask_rows_kernel(
     src.per = qper; src.batch = qbatch; src.lane = lane;
     for (bool more = src.first((uint64_t)blockIdx.x * kWavesPerBlock + wave); more; more = src.next()) {
         const uint64_t c = src.cur;
-        const uint64_t seg = c / chunks_per_seg, lc = c - seg * chunks_per_seg;
+        uint64_t seg, lc;
+        if ((c >> 32) == 0u && (chunks_per_seg >> 32) == 0u) {
+            uint32_t q, r;
+            divmod_u32((uint32_t)c, (uint32_t)chunks_per_seg, cps_m, q, r);
+            seg = q; lc = r;
+        } else {
+            seg = c / chunks_per_seg; lc = c - seg * chunks_per_seg;
+        }
         const uint64_t gw = seg * seg_stride + seg_first + lc * 64u;   // first global word (multiple of 16)
-        const uint64_t tile = gw >> 4;
-        const uint32_t kt = (uint32_t)(tile % T), qt = (uint32_t)((tile / T) % T);
+        uint32_t kt, qt;
+        tile_coords(gw >> 4, T, Tm, qt, kt);
         uint32_t vlo = 0u, vhi = 0u;
         const uint64_t base = offset + 16u * gw;   // 64 calls per 4 words
         if ((uint32_t)base <= 0xFFFFFFFFu - (64u * kGroupsPerChunk - 1u)) {
@@ -190,7 +195,7 @@ __device__ __forceinline__ void mask_chunk_bits(uint64_t base, uint32_t lane, ui
 template <int BITS, bool RAGGED>
 __global__ __launch_bounds__(kWavesPerBlock * 64) void mask_bits_kernel(
     uint64_t* __restrict__ out, uint64_t words, uint64_t nchunks, uint64_t offset, uint32_t k0,
-    uint32_t k1, uint32_t tb, uint32_t T, uint32_t S) {
+    uint32_t k1, uint32_t tb, uint32_t T, uint32_t Tm, uint32_t S) {
     constexpr uint32_t kCallsPerChunk = 64u * (64u / (4u * (32u / BITS)));   // 256 (8 bits) or 512 (16 bits)
     const uint32_t lane = threadIdx.x & 63u;
     const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -200,8 +205,8 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void mask_bits_kernel(
         uint32_t vlo = 0u, vhi = 0u;
         uint32_t qts[4] = {0u, 0u, 0u, 0u}, kts[4] = {0u, 0u, 0u, 0u};
         if (RAGGED) {
-            const uint64_t tile = chunk * 4u;
-            uint32_t kt = (uint32_t)(tile % T), qt = (uint32_t)((tile / T) % T);
+            uint32_t kt, qt;
+            tile_coords(chunk * 4u, T, Tm, qt, kt);
 #pragma unroll
             for (int t = 0; t < 4; ++t) {
                 qts[t] = qt;
@@ -279,16 +284,31 @@ int launch_mask_r(uint64_t* out, uint64_t words, uint64_t offset, uint32_t k0, u
     // registers per wave: 24 for 10 and 3 rounds (and every ragged variant), 25 -> 32 for 7 and 5
     const int cap = mask_grid_cap(grid_mode, ((S & 31) != 0 || R == 10 || R == 3) ? 24 : 32);
     if (blocks > (uint64_t)cap) blocks = (uint64_t)cap;
+    // Causal masks with a grid that strides over the chunks: a wave's chunks are `stride` apart, and when
+    // the stride is a multiple of a tile row's chunks (T / 4; power-of-two sequence lengths) every
+    // chunk of a wave has the same key-tile position - the wave skips all of them or none, half of the
+    // waves leave at once and the other half do the whole job in the time of the full mask.  Take a
+    // few workgroups off the grid so that the stride advances the key-tile position by about 0.62 of a
+    // row per step (and by an odd multiple of four chunks, which visits every fourth position of a
+    // power-of-two row): every wave then skips its fair share.
+    if (lower_only && qslot < 0 && (T & 3u) == 0u && T >= 32u) {
+        const uint64_t row = T / 4u;
+        uint64_t want = (uint64_t)((double)row * 0.618) & ~(uint64_t)7u;
+        want += 4u;                                            // = 4 (mod 8)
+        const uint64_t have = (blocks * kWavesPerBlock) % row;
+        const uint64_t off = ((have + row - want % row) % row) / kWavesPerBlock;   // workgroups to drop
+        if (off < blocks && blocks - off >= blocks / 2u) blocks -= off;
+    }
     const dim3 grid((unsigned)blocks), block(kWavesPerBlock * 64);
     uint64_t qper = 0;
     uint32_t qbatch = 1;
     queue_geometry(nchunks, &qper, &qbatch);
     if ((S & 31) == 0) {
         hipLaunchKernelGGL((mask_kernel<R, false>), grid, block, 0, stream, out, words, nchunks,
-                           offset, k0, k1, t_minus_1, T, (uint32_t)S, (int)lower_only, qslot, qper, qbatch);
+                           offset, k0, k1, t_minus_1, T, div_magic(T), (uint32_t)S, (int)lower_only, qslot, qper, qbatch);
     } else {
         hipLaunchKernelGGL((mask_kernel<R, true>), grid, block, 0, stream, out, words, nchunks,
-                           offset, k0, k1, t_minus_1, T, (uint32_t)S, (int)lower_only, qslot, qper, qbatch);
+                           offset, k0, k1, t_minus_1, T, div_magic(T), (uint32_t)S, (int)lower_only, qslot, qper, qbatch);
     }
     ROV_LAUNCH_CHECK();
     return ROV_OK;
@@ -305,10 +325,10 @@ int launch_mask_bits_b(uint64_t* out, uint64_t words, uint64_t offset, uint32_t 
     const dim3 grid((unsigned)blocks), block(kWavesPerBlock * 64);
     if ((S & 31) == 0) {
         hipLaunchKernelGGL((mask_bits_kernel<BITS, false>), grid, block, 0, stream, out, words, nchunks,
-                           offset, k0, k1, tb, T, (uint32_t)S);
+                           offset, k0, k1, tb, T, div_magic(T), (uint32_t)S);
     } else {
         hipLaunchKernelGGL((mask_bits_kernel<BITS, true>), grid, block, 0, stream, out, words, nchunks,
-                           offset, k0, k1, tb, T, (uint32_t)S);
+                           offset, k0, k1, tb, T, div_magic(T), (uint32_t)S);
     }
     ROV_LAUNCH_CHECK();
     return ROV_OK;
@@ -453,7 +473,8 @@ int launch_mask_rows(uint64_t seed, uint64_t offset, int B, int H, int S, float 
     const uint64_t cps = (seg_words + 63u) / 64u;
     const uint64_t nseg = (uint64_t)B * (uint64_t)H;
     uint64_t blocks = (nseg * cps + kWavesPerBlock - 1) / kWavesPerBlock;
-    const int cap = mask_grid_cap(grid_mode, 24);
+    // registers per wave: 26 (allocated as 32) without the ragged edge handling, 24 with it
+    const int cap = mask_grid_cap(grid_mode, (S & 31) == 0 ? 32 : 24);
     if (blocks > (uint64_t)cap) blocks = (uint64_t)cap;
     const dim3 grid((unsigned)blocks), block(kWavesPerBlock * 64);
     const uint32_t k0 = (uint32_t)seed, k1 = (uint32_t)(seed >> 32);
@@ -463,10 +484,10 @@ int launch_mask_rows(uint64_t seed, uint64_t offset, int B, int H, int S, float 
     const uint64_t seg_first = (uint64_t)(q_begin / 32) * T * 16u;
     if ((S & 31) == 0) {
         hipLaunchKernelGGL((mask_rows_kernel<10, false>), grid, block, 0, stream, out, seg_words, cps, nseg,
-                           T * T * 16u, seg_first, offset, k0, k1, tm1, (uint32_t)T, (uint32_t)S, qslot, qper, qbatch);
+                           T * T * 16u, seg_first, offset, k0, k1, tm1, (uint32_t)T, div_magic(T), div_magic(cps), (uint32_t)S, qslot, qper, qbatch);
     } else {
         hipLaunchKernelGGL((mask_rows_kernel<10, true>), grid, block, 0, stream, out, seg_words, cps, nseg,
-                           T * T * 16u, seg_first, offset, k0, k1, tm1, (uint32_t)T, (uint32_t)S, qslot, qper, qbatch);
+                           T * T * 16u, seg_first, offset, k0, k1, tm1, (uint32_t)T, div_magic(T), div_magic(cps), (uint32_t)S, qslot, qper, qbatch);
     }
     ROV_LAUNCH_CHECK();
     return ROV_OK;

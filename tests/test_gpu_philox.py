@@ -115,13 +115,22 @@ def test_mask_largest_workload_sampled_and_counted():
     torch.cuda.empty_cache()
 
 
-@pytest.mark.parametrize("B,H,S", [(1, 2, 256), (2, 3, 200), (1, 1, 32), (1, 2, 1024)])
-def test_mask_causal_variant_writes_what_causal_attention_reads(B, H, S):
+@pytest.mark.parametrize("B,H,S,cap", [(1, 2, 256, 0), (2, 3, 200, 0), (1, 1, 32, 0), (1, 2, 1024, 0),
+                                        # power-of-two tile rows with a grid that strides many times over the chunks:
+                                        # the launch shortens the grid so that a wave's chunks do not all sit at one
+                                        # key-tile position (48 workgroups: stride 192 = 12 rows of 16 chunks)
+                                        (1, 2, 2048, 48), (1, 3, 4096, 200), (2, 1, 2048, 0)])
+def test_mask_causal_variant_writes_what_causal_attention_reads(B, H, S, cap):
     import torch
     p, seed, offset = 0.1, 7, 12345
     poison = 0x2AAAAAAAAAAAAAAA
     out = torch.full(rov.mask_shape(B, H, S), poison, dtype=torch.int64, device="cuda")
-    rov.dropout_mask_generate_causal(seed, offset, B, H, S, p, out)
+    prev = rov.set_rng_max_workgroups(cap)
+    try:
+        rov.dropout_mask_generate_causal(seed, offset, B, H, S, p, out)
+        torch.cuda.synchronize()
+    finally:
+        rov.set_rng_max_workgroups(prev)
     got = _np_u64(out)
     exp = OP.dropout_mask(seed, offset, B, H, S, p)
     T = (S + 31) // 32

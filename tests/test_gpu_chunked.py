@@ -31,6 +31,8 @@ def _dev(x, dtype=torch.bfloat16):
     (2, 3, 200, 0.3, 99, 5, 160, 500),                               # runs past S: clipped to the last rows
     (1, 5, 70, 0.25, 2**40 + 7, 2**32 - 64 * 16 - 3, 64, 32),        # last, partial tile row + carry
     (1, 4, 1024, 0.1, wl.SEED, 2**64 - 640, 256, 512),               # 64-bit wrap of the call index
+    (2, 3, 4000, 0.1, 5, 640, 1024, 1504),                           # 125 tiles per side, 47 tile rows: many chunks per (batch, head) segment
+    (1, 2, 4096, 0.5, 6, 0, 3072, 1024),                             # power-of-two tile rows, last quarter
 ])
 def test_mask_rows_are_slices_of_the_full_mask(B, H, S, p, seed, offset, q_begin, q_rows):
     print("mask rows", B, H, S, p, seed, offset, q_begin, q_rows, flush=True)

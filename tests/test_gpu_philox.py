@@ -119,7 +119,10 @@ def test_mask_largest_workload_sampled_and_counted():
                                         # power-of-two tile rows with a grid that strides many times over the chunks:
                                         # the launch shortens the grid so that a wave's chunks do not all sit at one
                                         # key-tile position (48 workgroups: stride 192 = 12 rows of 16 chunks)
-                                        (1, 2, 2048, 48), (1, 3, 4096, 200), (2, 1, 2048, 0)])
+                                        (1, 2, 2048, 48), (1, 3, 4096, 200), (2, 1, 2048, 0),
+                                        # tile rows that are no power of two (T = 125, 500): the index arithmetic's
+                                        # reciprocal division, with and without a capped grid
+                                        (1, 2, 4000, 100), (1, 1, 16000, 0)])
 def test_mask_causal_variant_writes_what_causal_attention_reads(B, H, S, cap):
     import torch
     p, seed, offset = 0.1, 7, 12345
